@@ -1,0 +1,164 @@
+#!/usr/bin/env python3
+"""Throughput of the TS + TAB-Q hot path on one MI355X.
+
+One step = one pass of the whole hot path over one batch of synthetic input:
+compress (threshold splitting, width selection, scan, quantize + pack, CSR emission)
+followed by decompress (unpack, dequantize, outlier scatter).  Inputs are resident
+in HBM before the timed region; the step rotates over several buffer sets so that
+the 256 MB last-level cache does not serve the input.
+
+Prints ONE JSON line (see README for the fields).
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0     # MI355X HBM3E, published peak
+
+
+def parse():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=50)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--workload", default="C4", choices=["C1", "C2", "C3", "C4", "C5"])
+    ap.add_argument("--eps", type=float, default=0.05, help="error budget, relative to the row RMS")
+    ap.add_argument("--pipeline", default="auto", choices=["auto", "staged", "fused"])
+    ap.add_argument("--nbuf", type=int, default=4, help="buffer sets rotated through")
+    ap.add_argument("--c5-seqs", type=int, default=32)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--cpu-sample-rows", type=int, default=0, help="0 = sized for about 10-30 s")
+    return ap.parse_args()
+
+
+def make_input(args):
+    from paper_2511_04002_amd import synth
+    w = synth.WORKLOADS[args.workload]
+    if args.workload == "C5":
+        x = synth.make_c5(seqs=args.c5_seqs, workers=8)
+    elif args.workload == "C3":
+        x = synth.make_c3(0)
+    else:
+        x = synth.make(args.workload)
+    return w, x
+
+
+def cpu_baseline(x, w, eps, rows):
+    """The oracle as it stands, on a bounded sample of the same workload."""
+    from oracle import tsq_oracle as O
+    O.build()
+    dt = O.F16 if w.dtype == "f16" else O.BF16
+    threads = min(O.max_threads(), os.cpu_count() or 1, 16)
+    rows = min(rows, x.shape[0])
+    xs = x[:rows]
+    t0 = time.perf_counter()
+    c = O.compress(xs, dt, w.tau, w.bit_set, eps, O.BUDGET_REL_RMS, nthreads=threads)
+    t1 = time.perf_counter()
+    O.decompress(c, nthreads=threads)
+    t2 = time.perf_counter()
+    gb = xs.size * 2 / 1e9
+    return {"value": gb / (t2 - t0), "unit": "GB/s", "cores": threads, "kind": "oracle",
+            "sample": "first %d of %d rows of %s, compress %.3f s + decompress %.3f s, %d threads"
+                      % (rows, x.shape[0], w.name, t1 - t0, t2 - t1, threads)}
+
+
+def main():
+    args = parse()
+    if args.gpus != 1:
+        print("bench.py measures one GPU: the path has no cross-GPU step (rows are independent); "
+              "run with --gpus 1", file=sys.stderr)
+        sys.exit(2)
+    import numpy as np
+    import torch
+    from paper_2511_04002_amd import tsq
+
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    tsq.lib()
+    torch.cuda.set_device(0)
+    w, x = make_input(args)
+    T, H = x.shape
+    plan = tsq.Plan(T, H, w.dtype, w.tau, w.bit_set, args.eps, mode="rel_rms", pipeline=args.pipeline,
+                    max_outliers=max(1, (T * H) // 8))
+    x0 = torch.from_numpy(x.view(np.int16)).cuda()
+    nbuf = max(1, args.nbuf)
+    xs = [x0] + [x0.clone() for _ in range(nbuf - 1)]
+    blobs = [plan.new_blob() for _ in range(nbuf)]
+    outs = [plan.new_output() for _ in range(nbuf)]
+    ws = plan.new_workspace()
+
+    def step(i, ev=None):
+        k = i % nbuf
+        if ev:
+            ev[0].record()
+        plan.compress(xs[k], blobs[k], ws)
+        if ev:
+            ev[1].record()
+        plan.decompress(blobs[k], outs[k])
+        if ev:
+            ev[2].record()
+
+    for i in range(args.warmup):
+        step(i)
+    torch.cuda.synchronize()
+    info = plan.info(blobs[0])
+    assert info.status == 0
+
+    evs = [[torch.cuda.Event(enable_timing=True) for _ in range(3)] for _ in range(args.steps)]
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(args.steps):
+        step(args.warmup + i, evs[i])
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+
+    total_ms = evs[0][0].elapsed_time(evs[-1][2])
+    ms_per_step = total_ms / args.steps
+    ms_c = sum(e[0].elapsed_time(e[1]) for e in evs) / args.steps
+    ms_d = sum(e[1].elapsed_time(e[2]) for e in evs) / args.steps
+
+    n = T * H
+    rho = info.nnz / n
+    bbar = 8.0 * info.payload_bytes / n
+    side = info.payload_bytes + 4 * info.nnz + 21 * T      # payload + CSR + per-token metadata
+    alg_c = 2 * n + side                                   # compress: read input, write the blob
+    alg_d = side + 2 * n                                   # decompress: read the blob, write output
+    kern = {"compress": {"ms": ms_c, "alg_bytes": alg_c, "GBps": alg_c / ms_c / 1e6},
+            "decompress": {"ms": ms_d, "alg_bytes": alg_d, "GBps": alg_d / ms_d / 1e6}}
+    dom = "compress" if ms_c >= ms_d else "decompress"
+    achieved = kern[dom]["GBps"]
+    pair_gbps = (alg_c + alg_d) / (ms_c + ms_d) / 1e6
+
+    res = {
+        "metric": "compress+decompress GB/s of split-point activations",
+        "value": 2.0 * n / ms_per_step / 1e6,
+        "unit": "GB/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": ms_per_step,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "f32",
+        "data": "synthetic",
+        "config": {"workload": "%s %dx%d %s" % (w.name, T, H, w.dtype), "tau": w.tau,
+                   "bit_set": list(w.bit_set), "budget": "%.3g x row RMS" % args.eps,
+                   "pipeline": args.pipeline, "buffer_sets": nbuf, "mean_width": round(bbar, 3),
+                   "outlier_fraction": round(rho, 6), "width_hist": list(info.width_hist),
+                   "compression_ratio": round(2.0 * n / info.compressed_bytes, 3)},
+        "roofline": {"bound": "hbm", "kernel": dom, "achieved": achieved, "peak": HBM_PEAK_GBS,
+                     "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS, "traffic": None,
+                     "pair_achieved": pair_gbps, "pair_frac": pair_gbps / HBM_PEAK_GBS,
+                     "kernels": kern},
+        "host_wall_ms_per_step": wall * 1e3 / args.steps,
+    }
+    if not args.no_cpu_baseline:
+        rows = args.cpu_sample_rows or max(64, min(T, int(2.5e8 // H)))
+        res["cpu_baseline"] = cpu_baseline(x, w, args.eps, rows)
+    print(json.dumps(res))
+
+
+if __name__ == "__main__":
+    main()

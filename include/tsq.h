@@ -1,0 +1,158 @@
+/*
+ * tsq.h — C ABI of the MI355X (gfx950) library for two-stage compression of a
+ * split-point hidden-state tensor [tokens x hidden] and its exact inverse:
+ *
+ *   threshold splitting (TS)  — paper Sec. II-C.1, Eq. (ts): elements with
+ *       |x| >= tau go, untouched, to a sparse side stream stored in CSR form;
+ *   token-wise adaptive bit quantization (TAB-Q) — Sec. II-C.2, Eq. (Proposed)
+ *       and Algorithm 1: every token gets its own bit-width from an allowed
+ *       set, chosen by descending through the set while a distortion statistic
+ *       stays within a budget; magnitudes are quantized with round-half-even
+ *       and bit-packed, one sign bit per element;
+ *   restore — Eq. (dequnt): unpack, dequantize, put the outliers back.
+ *
+ * All pointers named d_* are DEVICE pointers on the current HIP device; every
+ * other pointer is a HOST pointer.  The library allocates no device memory,
+ * keeps no global state, and never synchronizes except where stated.
+ * `stream` is a hipStream_t passed as void* (NULL = the default stream).
+ *
+ * Errors are return codes only (no exceptions, no abort).
+ */
+#ifndef TSQ_H
+#define TSQ_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    TSQ_OK              = 0,
+    TSQ_ERR_INVALID_ARG = 1,  /* NULL pointer, zero size, tau/budget/bit set out of domain      */
+    TSQ_ERR_UNSUPPORTED = 2,  /* valid request this build cannot run (shape limits below)       */
+    TSQ_ERR_CAPACITY    = 3,  /* the outlier side stream did not fit max_outliers               */
+    TSQ_ERR_HIP         = 4,  /* a HIP call or kernel launch failed                             */
+    TSQ_ERR_FORMAT      = 5,  /* the blob does not carry this library's header / this plan      */
+    TSQ_ERR_INTERNAL    = 6   /* a bounded device-side wait expired (workspace not reset?)      */
+} tsq_status;
+
+typedef enum { TSQ_F16 = 0, TSQ_BF16 = 1 } tsq_dtype;
+
+typedef enum {
+    TSQ_BUDGET_LSB     = 0,   /* Algorithm 1 as printed: mean |floor(T0/2^k) - T| in code LSBs
+                                 of the candidate width, compared with Delta                    */
+    TSQ_BUDGET_REL_RMS = 1    /* the same statistic in value units, compared with
+                                 budget * RMS of the token's inlier part                        */
+} tsq_budget_mode;
+
+typedef enum {
+    TSQ_PIPE_AUTO   = 0,      /* the library picks                                              */
+    TSQ_PIPE_STAGED = 1,      /* row statistics -> device-wide scan -> pack: three launches,
+                                 the input is read twice                                        */
+    TSQ_PIPE_FUSED  = 2       /* one launch, the input is read once; output placement by a
+                                 chained scan between workgroups                                */
+} tsq_pipeline;
+
+/* Problem statement (Algorithm 1 "Require": T, Q-bar, Delta; Eq. (ts): tau). */
+typedef struct {
+    uint32_t tokens;        /* T >= 1: rows of the tensor                                       */
+    uint32_t hidden;        /* H: row length; this build needs H % 8 == 0 and 8 <= H <= 32768   */
+    int32_t  dtype;         /* tsq_dtype of the input and of the restored output                */
+    float    tau;           /* TS threshold, 0 < tau < inf                                      */
+    uint32_t bit_mask;      /* allowed widths: bit b set <=> b allowed, 2 <= b <= 8, b counts
+                               the sign bit (magnitude levels 2^(b-1) - 1)                      */
+    float    budget;        /* Delta (LSB mode) or epsilon (REL_RMS mode), >= 0, may be +inf    */
+    int32_t  mode;          /* tsq_budget_mode                                                  */
+    int32_t  pipeline;      /* tsq_pipeline                                                     */
+    uint64_t max_outliers;  /* capacity of the side stream in elements; 0 = tokens*hidden       */
+} tsq_config;
+
+typedef struct tsq_plan tsq_plan;   /* opaque, host memory, immutable, reusable across calls    */
+
+/*
+ * Layout of a compressed blob (device memory, all little-endian, every section
+ * 256-byte aligned, offsets in bytes from the blob's start):
+ *   header    128 B   magic "TSQ1", version, the plan's parameters, status, nnz, payload_bytes,
+ *                     the section offsets and capacities below
+ *   bits      u8 [T]      chosen width b_t per token            (Algorithm 1's Q*)
+ *   scale     f32[T]      s_t = inlier absmax / (2^(b_t-1) - 1) (Algorithm 1's S*; Z* = 0)
+ *   pay_off   u64[T+1]    byte offset of each token's codes inside payload (exclusive scan)
+ *   row_ptr   u64[T+1]    CSR row pointers of the outlier stream            (exclusive scan)
+ *   payload   bytes       per token a dense LSB-first stream of b_t-bit sign|magnitude codes,
+ *                         element j in stream bits [j*b_t, (j+1)*b_t), sign in the field's top
+ *                         bit, zero padded to a multiple of 4 bytes; outlier slots hold code 0
+ *   out_col   u16[cap]    CSR column indices, ascending inside a token
+ *   out_val   u16[cap]    the outliers' raw 16-bit input values (lossless, NaN payloads kept)
+ * Bytes past the actual lengths (payload_bytes, nnz) are unspecified.
+ */
+typedef struct {
+    uint64_t blob_bytes;       /* what the caller must allocate for d_blob                      */
+    uint64_t workspace_bytes;  /* what the caller must allocate for d_ws                        */
+    uint64_t off_bits, off_scale, off_pay_off, off_row_ptr, off_payload, off_out_col, off_out_val;
+    uint64_t payload_capacity; /* bytes                                                         */
+    uint64_t outlier_capacity; /* elements                                                      */
+} tsq_layout;
+
+typedef struct {
+    uint64_t nnz;               /* outliers stored                                              */
+    uint64_t payload_bytes;     /* sum over tokens of 4*ceil(H*b_t/32)                          */
+    uint64_t compressed_bytes;  /* 128 + 5T + 16(T+1) + payload_bytes + 4*nnz                   */
+    uint64_t width_hist[9];     /* tokens per width, index = width                              */
+    uint32_t status;            /* tsq_status recorded by the device (0 = ok)                   */
+    uint32_t reserved;
+} tsq_info;
+
+/* Validates cfg and fixes blob layout and launch geometry.  Host only.
+ * Returns INVALID_ARG / UNSUPPORTED without touching *out on failure. */
+tsq_status tsq_plan_create(const tsq_config *cfg, tsq_plan **out);
+void       tsq_plan_destroy(tsq_plan *plan);
+tsq_status tsq_plan_layout(const tsq_plan *plan, tsq_layout *out);
+size_t     tsq_plan_blob_bytes(const tsq_plan *plan);
+size_t     tsq_plan_workspace_bytes(const tsq_plan *plan);
+
+/*
+ * Puts d_ws into its initial state (enqueues one small kernel on `stream`).
+ * Required once after d_ws is allocated, and again after any compress call on
+ * it that was aborted or returned TSQ_ERR_INTERNAL through tsq_blob_info; the
+ * fused pipeline leaves the workspace ready for the next call by itself.  A
+ * workspace serves one compress call at a time.
+ */
+tsq_status tsq_workspace_reset(const tsq_plan *plan, void *d_ws, void *stream);
+
+/*
+ * TS + TAB-Q (Eq. (ts), Eq. (Proposed), Algorithm 1).
+ *   d_in   : tokens*hidden 16-bit values, row-major, 16-byte aligned, read only
+ *   d_blob : tsq_plan_blob_bytes() bytes, 256-byte aligned, fully overwritten where specified
+ *   d_ws   : tsq_plan_workspace_bytes() bytes, 256-byte aligned, reset as described above
+ * Only enqueues work on `stream`; never synchronizes.  Buffers must not overlap.
+ * A side stream larger than max_outliers is detected on the device: the blob's
+ * status becomes TSQ_ERR_CAPACITY (reported by tsq_blob_info) and the tokens
+ * that no longer fit have no outliers stored.
+ */
+tsq_status tsq_compress(const tsq_plan *plan, const void *d_in, void *d_blob, void *d_ws,
+                        void *stream);
+
+/*
+ * Restore (Eq. (dequnt)): d_out receives tokens*hidden 16-bit values of the
+ * plan's dtype.  Inliers become sign * (code * s_t) rounded to nearest even,
+ * outliers their stored bits.  If the blob's header does not match the plan or
+ * carries a non-zero status, nothing is written.  Enqueues only.
+ */
+tsq_status tsq_decompress(const tsq_plan *plan, const void *d_blob, void *d_out, void *stream);
+
+/*
+ * Reads the blob's header and widths back to the host.  SYNCHRONIZES `stream`.
+ * Returns the status stored in the blob (CAPACITY / INTERNAL), FORMAT when the
+ * header is not this plan's, or OK.
+ */
+tsq_status tsq_blob_info(const tsq_plan *plan, const void *d_blob, tsq_info *host_out,
+                         void *stream);
+
+const char *tsq_status_string(tsq_status s);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* TSQ_H */

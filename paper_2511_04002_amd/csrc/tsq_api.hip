@@ -1,0 +1,218 @@
+// Host side of the C ABI declared in include/tsq.h: validation, blob layout,
+// launch geometry, and the order of kernel launches.  No arithmetic of the
+// method happens here except the translation of tau into a 16-bit pattern.
+#include <hip/hip_runtime.h>
+
+#include <cmath>
+#include <cstdlib>
+#include <cstring>
+#include <mutex>
+#include <new>
+#include <vector>
+
+#include "tsq.h"
+#include "tsq_internal.hpp"
+
+using namespace tsq;
+
+struct tsq_plan {
+    tsq_config cfg;
+    Params p;
+    Geometry g;
+    tsq_layout layout;
+    int pipeline;  // resolved: TSQ_PIPE_STAGED or TSQ_PIPE_FUSED
+};
+
+namespace {
+
+uint64_t align_up(uint64_t v, uint64_t a) { return (v + a - 1) / a * a; }
+
+// value of a non-negative 16-bit pattern (sign bit clear), exact in double
+double pattern_value(uint32_t pat, int dtype) {
+    if (dtype == TSQ_BF16) {
+        uint32_t u = pat << 16;
+        float f;
+        std::memcpy(&f, &u, 4);
+        return (double)f;
+    }
+    const uint32_t e = (pat >> 10) & 0x1Fu, f = pat & 0x3FFu;
+    if (e == 31) return f ? NAN : INFINITY;
+    if (e == 0) return std::ldexp((double)f, -24);
+    return std::ldexp((double)(1024 + f), (int)e - 25);
+}
+
+// Smallest magnitude pattern whose value is >= tau.  The pattern of +Inf always qualifies, so
+// Inf and NaN (patterns above it) are on the outlier side for every finite tau.
+uint32_t threshold_pattern(float tau, int dtype) {
+    uint32_t lo = 0, hi = dtype == TSQ_BF16 ? 0x7F80u : 0x7C00u;
+    while (lo < hi) {
+        const uint32_t mid = (lo + hi) / 2;
+        if (pattern_value(mid, dtype) >= (double)tau) hi = mid; else lo = mid + 1;
+    }
+    return lo;
+}
+
+uint32_t row_bytes_host(uint32_t H, uint32_t b) { return 4u * ((H * b + 31u) / 32u); }
+
+std::once_flag g_prepare_once;
+int g_prepare_rc = 0;
+
+tsq_status hip_rc(int e) { return e == 0 ? TSQ_OK : TSQ_ERR_HIP; }
+
+}  // namespace
+
+extern "C" {
+
+const char *tsq_status_string(tsq_status s) {
+    switch (s) {
+        case TSQ_OK: return "ok";
+        case TSQ_ERR_INVALID_ARG: return "invalid argument";
+        case TSQ_ERR_UNSUPPORTED: return "unsupported shape or option";
+        case TSQ_ERR_CAPACITY: return "outlier side stream exceeds max_outliers";
+        case TSQ_ERR_HIP: return "HIP call failed";
+        case TSQ_ERR_FORMAT: return "blob does not match this plan";
+        case TSQ_ERR_INTERNAL: return "device-side wait expired";
+    }
+    return "unknown status";
+}
+
+tsq_status tsq_plan_create(const tsq_config *cfg, tsq_plan **out) {
+    if (!cfg || !out) return TSQ_ERR_INVALID_ARG;
+    if (cfg->tokens == 0 || cfg->hidden == 0) return TSQ_ERR_INVALID_ARG;
+    if (cfg->dtype != TSQ_F16 && cfg->dtype != TSQ_BF16) return TSQ_ERR_INVALID_ARG;
+    if (!(cfg->tau > 0.0f) || std::isinf(cfg->tau)) return TSQ_ERR_INVALID_ARG;
+    if ((cfg->bit_mask & 0x1FCu) == 0 || (cfg->bit_mask & ~0x1FCu) != 0) return TSQ_ERR_INVALID_ARG;
+    if (!(cfg->budget >= 0.0f)) return TSQ_ERR_INVALID_ARG;  // rejects NaN too
+    if (cfg->mode != TSQ_BUDGET_LSB && cfg->mode != TSQ_BUDGET_REL_RMS) return TSQ_ERR_INVALID_ARG;
+    if (cfg->pipeline < TSQ_PIPE_AUTO || cfg->pipeline > TSQ_PIPE_FUSED) return TSQ_ERR_INVALID_ARG;
+    if ((uint64_t)cfg->tokens * cfg->hidden >= (1ull << 32)) return TSQ_ERR_INVALID_ARG;
+    if (cfg->hidden % 8 != 0 || cfg->hidden > kMaxHidden) return TSQ_ERR_UNSUPPORTED;
+
+    tsq_plan *pl = new (std::nothrow) tsq_plan();
+    if (!pl) return TSQ_ERR_INVALID_ARG;
+    pl->cfg = *cfg;
+    const uint32_t T = cfg->tokens, H = cfg->hidden;
+
+    Params &p = pl->p;
+    std::memset(&p, 0, sizeof p);
+    p.tokens = T;
+    p.hidden = H;
+    p.runs = (H + kRun - 1) / kRun;
+    p.pieces = H / 8;
+    p.dtype = (uint32_t)cfg->dtype;
+    const uint32_t thr = threshold_pattern(cfg->tau, cfg->dtype);
+    p.thr_pk = thr | (thr << 16);
+    p.bit_mask = cfg->bit_mask;
+    uint32_t bmax = 0;
+    for (int b = 8; b >= 2; --b)
+        if (cfg->bit_mask & (1u << b)) {
+            if (!bmax) bmax = (uint32_t)b;
+            p.widths_pk |= (uint64_t)b << (8 * p.n_widths);
+            ++p.n_widths;
+        }
+    p.tau = cfg->tau;
+    p.budget = cfg->budget;
+    p.mode = cfg->mode;
+    p.spin_limit = 1u << 22;
+
+    tsq_layout &L = pl->layout;
+    uint64_t off = align_up(sizeof(BlobHeader), 256);
+    L.off_bits = off;      off = align_up(off + T, 256);
+    L.off_scale = off;     off = align_up(off + 4ull * T, 256);
+    L.off_pay_off = off;   off = align_up(off + 8ull * (T + 1ull), 256);
+    L.off_row_ptr = off;   off = align_up(off + 8ull * (T + 1ull), 256);
+    L.payload_capacity = (uint64_t)T * row_bytes_host(H, bmax);
+    L.off_payload = off;   off = align_up(off + L.payload_capacity, 256);
+    L.outlier_capacity = cfg->max_outliers ? cfg->max_outliers : (uint64_t)T * H;
+    if (L.outlier_capacity > (uint64_t)T * H) L.outlier_capacity = (uint64_t)T * H;
+    L.off_out_col = off;   off = align_up(off + 2ull * L.outlier_capacity, 256);
+    L.off_out_val = off;   off = align_up(off + 2ull * L.outlier_capacity, 256);
+    L.blob_bytes = off;
+
+    uint64_t w = 0;
+    p.ws_cnt = w;    w = align_up(w + 4ull * T, 256);
+    p.ws_state = w;  w = align_up(w + 8ull * T, 256);
+    p.ws_ctrl = w;   w = align_up(w + 256, 256);
+    L.workspace_bytes = w;
+
+    p.off_bits = L.off_bits; p.off_scale = L.off_scale; p.off_pay_off = L.off_pay_off;
+    p.off_row_ptr = L.off_row_ptr; p.off_payload = L.off_payload; p.off_out_col = L.off_out_col;
+    p.off_out_val = L.off_out_val; p.payload_capacity = L.payload_capacity;
+    p.outlier_capacity = L.outlier_capacity;
+
+    pl->g.block = 64u * ((p.runs + 63u) / 64u);
+    pl->g.lds_bytes = (p.runs * kRunLdsDw + 2u * 2u * kMaxWaves + kMaxWaves) * 4u;
+    pl->pipeline = cfg->pipeline == TSQ_PIPE_FUSED ? TSQ_PIPE_FUSED : TSQ_PIPE_STAGED;
+    *out = pl;
+    return TSQ_OK;
+}
+
+void tsq_plan_destroy(tsq_plan *plan) { delete plan; }
+
+tsq_status tsq_plan_layout(const tsq_plan *plan, tsq_layout *out) {
+    if (!plan || !out) return TSQ_ERR_INVALID_ARG;
+    *out = plan->layout;
+    return TSQ_OK;
+}
+
+size_t tsq_plan_blob_bytes(const tsq_plan *plan) { return plan ? (size_t)plan->layout.blob_bytes : 0; }
+size_t tsq_plan_workspace_bytes(const tsq_plan *plan) { return plan ? (size_t)plan->layout.workspace_bytes : 0; }
+
+static tsq_status ensure_prepared() {
+    std::call_once(g_prepare_once, [] { g_prepare_rc = prepare_kernels(); });
+    return hip_rc(g_prepare_rc);
+}
+
+tsq_status tsq_workspace_reset(const tsq_plan *plan, void *d_ws, void *stream) {
+    if (!plan || !d_ws) return TSQ_ERR_INVALID_ARG;
+    return hip_rc(launch_ws_reset(plan->p, d_ws, stream));
+}
+
+tsq_status tsq_compress(const tsq_plan *plan, const void *d_in, void *d_blob, void *d_ws, void *stream) {
+    if (!plan || !d_in || !d_blob || !d_ws) return TSQ_ERR_INVALID_ARG;
+    if (((uintptr_t)d_in & 15u) || ((uintptr_t)d_blob & 255u) || ((uintptr_t)d_ws & 255u)) return TSQ_ERR_INVALID_ARG;
+    tsq_status st = ensure_prepared();
+    if (st != TSQ_OK) return st;
+    if (plan->pipeline == TSQ_PIPE_FUSED) return hip_rc(launch_fused(plan->p, plan->g, d_in, d_blob, d_ws, stream));
+    int e = launch_row_stats(plan->p, plan->g, d_in, d_blob, d_ws, stream);
+    if (e == 0) e = launch_scan(plan->p, d_blob, d_ws, stream);
+    if (e == 0) e = launch_pack(plan->p, plan->g, d_in, d_blob, d_ws, stream);
+    return hip_rc(e);
+}
+
+tsq_status tsq_decompress(const tsq_plan *plan, const void *d_blob, void *d_out, void *stream) {
+    if (!plan || !d_blob || !d_out) return TSQ_ERR_INVALID_ARG;
+    if (((uintptr_t)d_out & 15u) || ((uintptr_t)d_blob & 255u)) return TSQ_ERR_INVALID_ARG;
+    tsq_status st = ensure_prepared();
+    if (st != TSQ_OK) return st;
+    return hip_rc(launch_unpack(plan->p, plan->g, d_blob, d_out, stream));
+}
+
+tsq_status tsq_blob_info(const tsq_plan *plan, const void *d_blob, tsq_info *host_out, void *stream) {
+    if (!plan || !d_blob || !host_out) return TSQ_ERR_INVALID_ARG;
+    hipStream_t s = reinterpret_cast<hipStream_t>(stream);
+    BlobHeader h;
+    std::vector<uint8_t> bits(plan->p.tokens);
+    if (hipMemcpyAsync(&h, d_blob, sizeof h, hipMemcpyDeviceToHost, s) != hipSuccess) return TSQ_ERR_HIP;
+    if (hipMemcpyAsync(bits.data(), static_cast<const uint8_t *>(d_blob) + plan->layout.off_bits, bits.size(),
+                       hipMemcpyDeviceToHost, s) != hipSuccess)
+        return TSQ_ERR_HIP;
+    if (hipStreamSynchronize(s) != hipSuccess) return TSQ_ERR_HIP;
+    std::memset(host_out, 0, sizeof *host_out);
+    const Params &p = plan->p;
+    if (h.magic != kMagic || h.version != kVersion || h.tokens != p.tokens || h.hidden != p.hidden ||
+        h.dtype != p.dtype || h.bit_mask != p.bit_mask || h.off_payload != p.off_payload ||
+        h.off_out_col != p.off_out_col || h.off_out_val != p.off_out_val)
+        return TSQ_ERR_FORMAT;
+    host_out->status = h.status;
+    host_out->nnz = h.nnz;
+    host_out->payload_bytes = h.payload_bytes;
+    host_out->compressed_bytes = 128ull + 5ull * p.tokens + 16ull * (p.tokens + 1ull) + h.payload_bytes + 4ull * h.nnz;
+    for (uint8_t b : bits)
+        if (b <= 8) host_out->width_hist[b]++;
+    if (h.status == TSQ_ERR_CAPACITY) return TSQ_ERR_CAPACITY;
+    if (h.status != 0) return TSQ_ERR_INTERNAL;
+    return TSQ_OK;
+}
+
+}  // extern "C"

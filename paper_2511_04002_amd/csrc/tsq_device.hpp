@@ -1,0 +1,293 @@
+// Device-side building blocks of the row kernels (gfx950, wave64).
+//
+// Data ownership inside a workgroup: the row of `hidden` 16-bit values is cut
+// into runs of 32 consecutive elements; lane r of the workgroup owns run r.
+// A run is 64 bytes of input (4 pieces of 16 B), 8 dwords of packed magnitude
+// bytes, and exactly b dwords of packed b-bit codes, so packing never crosses
+// lanes.  Rows travel between HBM and the lanes through LDS: global accesses
+// are 16 B per lane with consecutive lanes on consecutive addresses, and the
+// LDS copy of run r starts at dword r*kRunLdsDw (padded against bank conflicts).
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "tsq_internal.hpp"
+
+namespace tsq {
+
+constexpr int kF16 = 0, kBF16 = 1;
+constexpr int kModeLsb = 0;
+
+typedef unsigned short u16x2 __attribute__((ext_vector_type(2)));
+typedef short i16x2 __attribute__((ext_vector_type(2)));
+
+__device__ __forceinline__ uint32_t pk_sub_u16(uint32_t a, uint32_t b) {
+    return __builtin_bit_cast(uint32_t, (u16x2)(__builtin_bit_cast(u16x2, a) - __builtin_bit_cast(u16x2, b)));
+}
+__device__ __forceinline__ uint32_t pk_max_u16(uint32_t a, uint32_t b) {
+    return __builtin_bit_cast(uint32_t,
+                              __builtin_elementwise_max(__builtin_bit_cast(u16x2, a), __builtin_bit_cast(u16x2, b)));
+}
+__device__ __forceinline__ uint32_t pk_ashr15_i16(uint32_t a) {
+    return __builtin_bit_cast(uint32_t, (i16x2)(__builtin_bit_cast(i16x2, a) >> 15));
+}
+
+// ---------------------------------------------------------------- wave / block collectives
+
+__device__ __forceinline__ uint32_t wave_max_u32(uint32_t v) {
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) {
+        uint32_t n = (uint32_t)__shfl_xor((int)v, o);
+        v = n > v ? n : v;
+    }
+    return v;
+}
+__device__ __forceinline__ uint32_t wave_sum_u32(uint32_t v) {
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) v += (uint32_t)__shfl_xor((int)v, o);
+    return v;
+}
+
+// Every thread gets max over the block of mx and sum over the block of sm.
+// red: 2*kMaxWaves dwords of LDS; consecutive calls must alternate between two such areas.
+__device__ __forceinline__ void block_max_sum(uint32_t &mx, uint32_t &sm, uint32_t *red) {
+    mx = wave_max_u32(mx);
+    sm = wave_sum_u32(sm);
+    const uint32_t nw = blockDim.x >> 6;
+    if (nw == 1) return;
+    const uint32_t lane = threadIdx.x & 63, wv = threadIdx.x >> 6;
+    if (lane == 0) { red[2 * wv] = mx; red[2 * wv + 1] = sm; }
+    __syncthreads();
+    uint32_t M = 0, S = 0;
+    for (uint32_t w = 0; w < nw; ++w) {
+        uint32_t a = red[2 * w], b = red[2 * w + 1];
+        M = a > M ? a : M;
+        S += b;
+    }
+    mx = M;
+    sm = S;
+}
+__device__ __forceinline__ void block_sum2(uint32_t &x, uint32_t &y, uint32_t *red) {
+    x = wave_sum_u32(x);
+    y = wave_sum_u32(y);
+    const uint32_t nw = blockDim.x >> 6;
+    if (nw == 1) return;
+    const uint32_t lane = threadIdx.x & 63, wv = threadIdx.x >> 6;
+    if (lane == 0) { red[2 * wv] = x; red[2 * wv + 1] = y; }
+    __syncthreads();
+    uint32_t X = 0, Y = 0;
+    for (uint32_t w = 0; w < nw; ++w) { X += red[2 * w]; Y += red[2 * w + 1]; }
+    x = X;
+    y = Y;
+}
+
+// Exclusive prefix sum of v over the threads of the block, in thread order.
+// scr: kMaxWaves dwords of LDS not in use by anything else until the next barrier.
+__device__ __forceinline__ uint32_t block_excl_scan(uint32_t v, uint32_t *scr) {
+    const uint32_t lane = threadIdx.x & 63, wv = threadIdx.x >> 6;
+    uint32_t inc = v;
+#pragma unroll
+    for (int o = 1; o < 64; o <<= 1) {
+        uint32_t n = (uint32_t)__shfl_up((int)inc, o);
+        if ((int)lane >= o) inc += n;
+    }
+    if (lane == 63) scr[wv] = inc;
+    __syncthreads();
+    uint32_t base = 0;
+    for (uint32_t w = 0; w < wv; ++w) base += scr[w];
+    return base + inc - v;
+}
+
+// ---------------------------------------------------------------- row staging
+
+// HBM -> LDS, coalesced: slot p of the LDS row holds 16-byte piece p (zeros past the row's end).
+__device__ __forceinline__ void stage_row(const uint4 *__restrict__ src, uint32_t pieces, uint32_t runs,
+                                          uint32_t *lrow) {
+    uint4 v[4];
+#pragma unroll
+    for (int k = 0; k < 4; ++k) {
+        const uint32_t p = threadIdx.x + k * blockDim.x;
+        v[k] = make_uint4(0, 0, 0, 0);
+        if (p < pieces) v[k] = src[p];
+    }
+#pragma unroll
+    for (int k = 0; k < 4; ++k) {
+        const uint32_t p = threadIdx.x + k * blockDim.x;
+        if (p < 4 * runs) *reinterpret_cast<uint4 *>(lrow + (p >> 2) * kRunLdsDw + (p & 3) * 4) = v[k];
+    }
+}
+
+// ---------------------------------------------------------------- Eq. (ts) on one run
+
+// Threshold splitting of the 32 elements a lane owns, on the 16-bit magnitude
+// patterns: for fp16 and bf16 alike the pattern of |x| grows with |x|, and the
+// patterns of Inf and NaN lie above every finite one, so
+//   !(|x| < tau)  <=>  (pattern & 0x7FFF) >= thr,
+// thr being the smallest pattern whose value is >= tau (computed on the host).
+//   apk   : |x| patterns of the inliers, 0 at outlier slots (|T_below|)
+//   omask : outlier flags; bit i = element 2i, bit 16+i = element 2i+1
+//   amax  : running maximum of the inlier patterns, both halves
+__device__ __forceinline__ void split_run(const uint32_t *lrun, uint32_t thr_pk, uint32_t (&apk)[16],
+                                          uint32_t &omask, uint32_t &amax_pk) {
+    uint32_t w[16];
+#pragma unroll
+    for (int k = 0; k < 4; ++k) {
+        const uint4 q = *reinterpret_cast<const uint4 *>(lrun + 4 * k);
+        w[4 * k] = q.x; w[4 * k + 1] = q.y; w[4 * k + 2] = q.z; w[4 * k + 3] = q.w;
+    }
+    uint32_t om = 0, mx = amax_pk;
+#pragma unroll
+    for (int i = 0; i < 16; ++i) {
+        const uint32_t absw = w[i] & 0x7FFF7FFFu;
+        const uint32_t inl = pk_ashr15_i16(pk_sub_u16(absw, thr_pk));  // 0xFFFF where |x| < tau
+        const uint32_t a = absw & inl;
+        apk[i] = a;
+        mx = pk_max_u16(mx, a);
+        om |= (~inl & 0x00010001u) << i;
+    }
+    omask = om;
+    amax_pk = mx;
+}
+
+template <int DT>
+__device__ __forceinline__ float widen_lo(uint32_t w) {
+    if (DT == kBF16) return __uint_as_float(w << 16);
+    return (float)__builtin_bit_cast(_Float16, (unsigned short)(w & 0xFFFFu));
+}
+template <int DT>
+__device__ __forceinline__ float widen_hi(uint32_t w) {
+    if (DT == kBF16) return __uint_as_float(w & 0xFFFF0000u);
+    return (float)__builtin_bit_cast(_Float16, (unsigned short)(w >> 16));
+}
+template <int DT>
+__device__ __forceinline__ float widen16(uint32_t pattern) {
+    return widen_lo<DT>(pattern & 0xFFFFu);
+}
+
+// ---------------------------------------------------------------- Eq. (Proposed) on one run
+
+// m = rint(a * r), one byte per element, element 4g+k in byte k of m[g].
+// A clamp min(., Q) to the code range never binds: a <= amax and r = fl(Q/amax) give
+// a*r <= Q*(1+2^-24)^2 < Q + 1/2, so rint already yields at most Q.
+template <int DT>
+__device__ __forceinline__ void quantize_run(const uint32_t (&apk)[16], float r, uint32_t (&m)[8]) {
+#pragma unroll
+    for (int g = 0; g < 8; ++g) {
+        uint32_t acc = 0;
+        acc = __builtin_amdgcn_cvt_pk_u8_f32(__builtin_rintf(widen_lo<DT>(apk[2 * g]) * r), 0, acc);
+        acc = __builtin_amdgcn_cvt_pk_u8_f32(__builtin_rintf(widen_hi<DT>(apk[2 * g]) * r), 1, acc);
+        acc = __builtin_amdgcn_cvt_pk_u8_f32(__builtin_rintf(widen_lo<DT>(apk[2 * g + 1]) * r), 2, acc);
+        acc = __builtin_amdgcn_cvt_pk_u8_f32(__builtin_rintf(widen_hi<DT>(apk[2 * g + 1]) * r), 3, acc);
+        m[g] = acc;
+    }
+}
+
+__device__ __forceinline__ uint32_t sum_squares_run(const uint32_t (&m)[8]) {
+    uint32_t s = 0;
+#pragma unroll
+    for (int g = 0; g < 8; ++g) s = __builtin_amdgcn_udot4(m[g], m[g], s, false);
+    return s;
+}
+
+// sum over the run of | (m0 >> sh) - mi |, bytewise
+__device__ __forceinline__ uint32_t sad_run(const uint32_t (&m0)[8], const uint32_t (&mi)[8], uint32_t sh) {
+    const uint32_t keep = (0xFFu >> sh) * 0x01010101u;
+    uint32_t s = 0;
+#pragma unroll
+    for (int g = 0; g < 8; ++g) s = __builtin_amdgcn_sad_u8((m0[g] >> sh) & keep, mi[g], s);
+    return s;
+}
+
+// Algorithm 1's stopping test, the same fixed sequence of fp64 operations on every lane.
+__device__ __forceinline__ bool violates(int mode, float budget, uint32_t H, uint32_t Q0, uint32_t Qi,
+                                         uint32_t sad, uint32_t ss0) {
+    if (mode == kModeLsb) return (double)sad > (double)budget * (double)H;
+    double L = (double)Q0 * (double)sad;
+    L *= L;
+    double R = (double)budget * (double)Qi;
+    R *= R;
+    R *= (double)H;
+    R *= (double)ss0;
+    return L > R;
+}
+
+constexpr float kAmaxFloor = 0x1p-100f;  // below it Q/amax may overflow binary32: row is coded as zeros
+
+__device__ __forceinline__ float level_count(uint32_t width) { return (float)((1u << (width - 1)) - 1u); }
+
+// ---------------------------------------------------------------- bit packing of one run
+
+// out[0..B) = the run's 32 codes, LSB first.  m: magnitude bytes; w: the run's
+// raw input dwords (sign bits).  The sign is dropped where the magnitude is 0.
+template <int B>
+__device__ __forceinline__ void pack_run(const uint32_t (&m)[8], const uint32_t *lrun, uint32_t (&out)[B]) {
+    constexpr uint32_t K = (1u << (B - 1)) - 1u;
+    uint32_t w[16];
+#pragma unroll
+    for (int k = 0; k < 4; ++k) {
+        const uint4 q = *reinterpret_cast<const uint4 *>(lrun + 4 * k);
+        w[4 * k] = q.x; w[4 * k + 1] = q.y; w[4 * k + 2] = q.z; w[4 * k + 3] = q.w;
+    }
+    uint64_t acc = 0;
+    int filled = 0, od = 0;
+#pragma unroll
+    for (int g = 0; g < 8; ++g) {
+        const uint32_t mg = m[g];
+        // byte k <- high byte of element 4g+k (bit 7 of it is the sign)
+        const uint32_t sg = __builtin_amdgcn_perm(w[2 * g + 1], w[2 * g], 0x07050301u);
+        const uint32_t sgb = (B == 8) ? sg : (sg >> (8 - B));            // sign now at bit B-1 of each byte
+        const uint32_t nzb = mg + K * 0x01010101u;                       // bit B-1 of each byte: m > 0
+        const uint32_t code = mg | (sgb & nzb & (0x01010101u << (B - 1)));
+        uint32_t chunk;
+        if (B == 8) {
+            chunk = code;
+        } else {
+            constexpr uint32_t F = (1u << B) - 1u;
+            const uint32_t t = (code & (F * 0x00010001u)) | ((code >> (8 - B)) & ((F << B) * 0x00010001u));
+            chunk = (t & 0xFFFFu) | ((t >> 16) << (2 * B));
+        }
+        acc |= (uint64_t)chunk << filled;
+        filled += 4 * B;
+        if (filled >= 32) {
+            out[od++] = (uint32_t)acc;
+            acc >>= 32;
+            filled -= 32;
+        }
+    }
+}
+
+// Inverse of pack_run followed by Eq. (dequnt) for the inliers: 32 codes ->
+// 16 dwords of 16-bit values sign * (m * s), rounded to nearest even.
+template <int DT>
+__device__ __forceinline__ uint32_t narrow2(float lo, float hi) {
+    if (DT == kBF16) {
+        typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+        typedef float f32x2 __attribute__((ext_vector_type(2)));
+        f32x2 v = {lo, hi};
+        return __builtin_bit_cast(uint32_t, __builtin_convertvector(v, bf16x2));
+    }
+    const unsigned short l = __builtin_bit_cast(unsigned short, (_Float16)lo);
+    const unsigned short h = __builtin_bit_cast(unsigned short, (_Float16)hi);
+    return (uint32_t)l | ((uint32_t)h << 16);
+}
+
+template <int B>
+__device__ __forceinline__ float decode_one(const uint32_t (&d)[B], int j, float s) {
+    const int off = j * B;
+    const int k = off >> 5, sh = off & 31;
+    uint32_t code = d[k] >> sh;
+    if (sh + B > 32) code |= d[k + 1 < B ? k + 1 : k] << (32 - sh);
+    const uint32_t mag = code & ((1u << (B - 1)) - 1u);
+    const uint32_t neg = (code >> (B - 1)) & 1u;
+    const float v = (float)mag * s;
+    return __uint_as_float(__float_as_uint(v) | (neg << 31));
+}
+
+template <int DT, int B>
+__device__ __forceinline__ void unpack_run(const uint32_t (&d)[B], float s, uint32_t (&o)[16]) {
+#pragma unroll
+    for (int i = 0; i < 16; ++i) o[i] = narrow2<DT>(decode_one<B>(d, 2 * i, s), decode_one<B>(d, 2 * i + 1, s));
+}
+
+}  // namespace tsq

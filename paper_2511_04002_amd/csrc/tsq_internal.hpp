@@ -1,0 +1,73 @@
+// Shared between the host API (tsq_api.hip) and the kernels (tsq_kernels.hip).
+// Plain data only.
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace tsq {
+
+constexpr uint32_t kMagic   = 0x31515354u;   // "TSQ1", little-endian
+constexpr uint32_t kVersion = 1;
+
+constexpr int kRun      = 32;   // elements owned by one lane (a "run")
+constexpr int kRunLdsDw = 20;   // dwords one run occupies in LDS: 16 of data + 4 of padding,
+                                // so that 8 lanes reading 16 B each hit 32 distinct banks
+constexpr int kMaxWaves = 16;   // 1024 threads per workgroup at most
+constexpr uint32_t kMaxHidden = 32768;
+
+// 128-byte header at the start of every blob.
+struct BlobHeader {
+    uint32_t magic, version, dtype, tokens, hidden, tau_bits, bit_mask, budget_bits, mode, status;
+    uint64_t nnz, payload_bytes;
+    uint64_t off_bits, off_scale, off_pay_off, off_row_ptr, off_payload, off_out_col, off_out_val;
+    uint64_t payload_capacity, outlier_capacity;
+};
+static_assert(sizeof(BlobHeader) == 128, "blob header must be 128 bytes");
+
+// Kernel argument block (passed by value).
+struct Params {
+    uint32_t tokens, hidden;
+    uint32_t runs;          // ceil(hidden / 32): lanes that own data in a row
+    uint32_t pieces;        // hidden / 8: 16-byte pieces in a row
+    uint32_t dtype;
+    uint32_t thr_pk;        // smallest 16-bit magnitude pattern with value >= tau, in both halves
+    uint32_t bit_mask;
+    uint32_t n_widths;      // number of allowed widths
+    uint32_t pad0;
+    uint64_t widths_pk;     // allowed widths, descending, one per byte (byte 0 = largest)
+    float    tau;
+    float    budget;
+    int32_t  mode;
+    uint32_t spin_limit;    // bound on every device-side wait (fused pipeline)
+    uint64_t off_bits, off_scale, off_pay_off, off_row_ptr, off_payload, off_out_col, off_out_val;
+    uint64_t payload_capacity, outlier_capacity;
+    // workspace sections (bytes from d_ws)
+    uint64_t ws_cnt;        // u32[T]  outliers per token           (staged)
+    uint64_t ws_state;      // u64[T]  chained-scan state per token (fused)
+    uint64_t ws_ctrl;       // u32[64] ticket / done counters       (fused)
+};
+
+inline __host__ __device__ uint32_t width_at(const Params &p, uint32_t i) {
+    return (uint32_t)(p.widths_pk >> (8u * i)) & 0xFFu;
+}
+
+// Launch geometry fixed by the plan.
+struct Geometry {
+    uint32_t block;         // threads per workgroup = 64 * ceil(runs / 64)
+    uint32_t lds_bytes;     // dynamic LDS of the row kernels
+};
+
+// launchers implemented in tsq_kernels.hip; each returns a hipError_t as int
+int launch_row_stats(const Params &p, const Geometry &g, const void *d_in, void *d_blob, void *d_ws,
+                     void *stream);
+int launch_scan(const Params &p, void *d_blob, void *d_ws, void *stream);
+int launch_pack(const Params &p, const Geometry &g, const void *d_in, void *d_blob, void *d_ws,
+                void *stream);
+int launch_fused(const Params &p, const Geometry &g, const void *d_in, void *d_blob, void *d_ws,
+                 void *stream);
+int launch_ws_reset(const Params &p, void *d_ws, void *stream);
+int launch_unpack(const Params &p, const Geometry &g, const void *d_blob, void *d_out, void *stream);
+int prepare_kernels();  // raises the dynamic-LDS limit of the row kernels once per process
+
+}  // namespace tsq

@@ -1,0 +1,241 @@
+"""Thin Python binding of the C-ABI library (include/tsq.h): argument marshalling
+only.  Every step of the method runs in the HIP kernels of libtsq.so; there is
+no CPU fallback, and a missing library is an error.
+
+PyTorch is used for device memory and streams, nothing else.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+from typing import Dict, Iterable, Optional
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_LIB_PATH = os.path.join(_HERE, "libtsq.so")
+
+TSQ_OK, TSQ_ERR_INVALID_ARG, TSQ_ERR_UNSUPPORTED, TSQ_ERR_CAPACITY = 0, 1, 2, 3
+TSQ_ERR_HIP, TSQ_ERR_FORMAT, TSQ_ERR_INTERNAL = 4, 5, 6
+TSQ_F16, TSQ_BF16 = 0, 1
+TSQ_BUDGET_LSB, TSQ_BUDGET_REL_RMS = 0, 1
+TSQ_PIPE_AUTO, TSQ_PIPE_STAGED, TSQ_PIPE_FUSED = 0, 1, 2
+
+EXPORTS = ("tsq_plan_create", "tsq_plan_destroy", "tsq_plan_layout", "tsq_plan_blob_bytes",
+           "tsq_plan_workspace_bytes", "tsq_workspace_reset", "tsq_compress", "tsq_decompress",
+           "tsq_blob_info", "tsq_status_string")
+
+
+class tsq_config(C.Structure):
+    _fields_ = [("tokens", C.c_uint32), ("hidden", C.c_uint32), ("dtype", C.c_int32),
+                ("tau", C.c_float), ("bit_mask", C.c_uint32), ("budget", C.c_float),
+                ("mode", C.c_int32), ("pipeline", C.c_int32), ("max_outliers", C.c_uint64)]
+
+
+class tsq_layout(C.Structure):
+    _fields_ = [(n, C.c_uint64) for n in
+                ("blob_bytes", "workspace_bytes", "off_bits", "off_scale", "off_pay_off",
+                 "off_row_ptr", "off_payload", "off_out_col", "off_out_val", "payload_capacity",
+                 "outlier_capacity")]
+
+
+class tsq_info(C.Structure):
+    _fields_ = [("nnz", C.c_uint64), ("payload_bytes", C.c_uint64),
+                ("compressed_bytes", C.c_uint64), ("width_hist", C.c_uint64 * 9),
+                ("status", C.c_uint32), ("reserved", C.c_uint32)]
+
+
+class TsqError(RuntimeError):
+    def __init__(self, status: int, what: str):
+        self.status = status
+        super().__init__("%s: %s (status %d)" % (what, tsq_status_string(status), status))
+
+
+_lib = None
+
+
+def lib():
+    """Loads libtsq.so.  Raises if it has not been built: there is no fallback."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(_LIB_PATH):
+            raise RuntimeError("libtsq.so is missing: run `python -m paper_2511_04002_amd.build` "
+                               "(hipcc, gfx950); the library has no CPU fallback")
+        L = C.CDLL(_LIB_PATH)
+        vp, u = C.c_void_p, C.c_int
+        L.tsq_plan_create.restype = u
+        L.tsq_plan_create.argtypes = [C.POINTER(tsq_config), C.POINTER(vp)]
+        L.tsq_plan_destroy.restype = None
+        L.tsq_plan_destroy.argtypes = [vp]
+        L.tsq_plan_layout.restype = u
+        L.tsq_plan_layout.argtypes = [vp, C.POINTER(tsq_layout)]
+        L.tsq_plan_blob_bytes.restype = C.c_size_t
+        L.tsq_plan_blob_bytes.argtypes = [vp]
+        L.tsq_plan_workspace_bytes.restype = C.c_size_t
+        L.tsq_plan_workspace_bytes.argtypes = [vp]
+        L.tsq_workspace_reset.restype = u
+        L.tsq_workspace_reset.argtypes = [vp, vp, vp]
+        L.tsq_compress.restype = u
+        L.tsq_compress.argtypes = [vp, vp, vp, vp, vp]
+        L.tsq_decompress.restype = u
+        L.tsq_decompress.argtypes = [vp, vp, vp, vp]
+        L.tsq_blob_info.restype = u
+        L.tsq_blob_info.argtypes = [vp, vp, C.POINTER(tsq_info), vp]
+        L.tsq_status_string.restype = C.c_char_p
+        L.tsq_status_string.argtypes = [u]
+        _lib = L
+    return _lib
+
+
+# ------------------------------------------------------------------ the C entry points, same names
+
+def tsq_status_string(status: int) -> str:
+    return lib().tsq_status_string(int(status)).decode()
+
+
+def tsq_plan_create(cfg: tsq_config) -> int:
+    """-> opaque plan handle (int).  Raises TsqError on a rejected configuration."""
+    h = C.c_void_p()
+    st = lib().tsq_plan_create(C.byref(cfg), C.byref(h))
+    if st != TSQ_OK:
+        raise TsqError(st, "tsq_plan_create")
+    return h.value
+
+
+def tsq_plan_destroy(plan: int) -> None:
+    lib().tsq_plan_destroy(plan)
+
+
+def tsq_plan_layout(plan: int) -> tsq_layout:
+    out = tsq_layout()
+    st = lib().tsq_plan_layout(plan, C.byref(out))
+    if st != TSQ_OK:
+        raise TsqError(st, "tsq_plan_layout")
+    return out
+
+
+def tsq_plan_blob_bytes(plan: int) -> int:
+    return int(lib().tsq_plan_blob_bytes(plan))
+
+
+def tsq_plan_workspace_bytes(plan: int) -> int:
+    return int(lib().tsq_plan_workspace_bytes(plan))
+
+
+def tsq_workspace_reset(plan: int, d_ws: int, stream: int = 0) -> None:
+    st = lib().tsq_workspace_reset(plan, d_ws, stream)
+    if st != TSQ_OK:
+        raise TsqError(st, "tsq_workspace_reset")
+
+
+def tsq_compress(plan: int, d_in: int, d_blob: int, d_ws: int, stream: int = 0) -> None:
+    st = lib().tsq_compress(plan, d_in, d_blob, d_ws, stream)
+    if st != TSQ_OK:
+        raise TsqError(st, "tsq_compress")
+
+
+def tsq_decompress(plan: int, d_blob: int, d_out: int, stream: int = 0) -> None:
+    st = lib().tsq_decompress(plan, d_blob, d_out, stream)
+    if st != TSQ_OK:
+        raise TsqError(st, "tsq_decompress")
+
+
+def tsq_blob_info(plan: int, d_blob: int, stream: int = 0, check: bool = True) -> tsq_info:
+    out = tsq_info()
+    st = lib().tsq_blob_info(plan, d_blob, C.byref(out), stream)
+    if st != TSQ_OK and check:
+        raise TsqError(st, "tsq_blob_info")
+    out.return_status = st
+    return out
+
+
+# ------------------------------------------------------------------ convenience over torch tensors
+
+def bit_mask(bit_set: Iterable[int]) -> int:
+    m = 0
+    for b in bit_set:
+        m |= 1 << int(b)
+    return m
+
+
+_DTYPES = {"f16": TSQ_F16, "bf16": TSQ_BF16}
+_MODES = {"lsb": TSQ_BUDGET_LSB, "rel_rms": TSQ_BUDGET_REL_RMS}
+_PIPES = {"auto": TSQ_PIPE_AUTO, "staged": TSQ_PIPE_STAGED, "fused": TSQ_PIPE_FUSED}
+
+
+class Plan:
+    """Owns one tsq_plan plus helpers that allocate torch buffers and pass their pointers."""
+
+    def __init__(self, tokens: int, hidden: int, dtype: str, tau: float, bit_set: Iterable[int],
+                 budget: float, mode: str = "rel_rms", pipeline: str = "auto", max_outliers: int = 0):
+        self.cfg = tsq_config(tokens, hidden, _DTYPES[dtype], tau, bit_mask(bit_set), budget,
+                              _MODES[mode], _PIPES[pipeline], max_outliers)
+        self.handle = tsq_plan_create(self.cfg)
+        self.layout = tsq_plan_layout(self.handle)
+        self.tokens, self.hidden, self.dtype = tokens, hidden, dtype
+
+    def __del__(self):
+        h = getattr(self, "handle", None)
+        if h:
+            tsq_plan_destroy(h)
+            self.handle = None
+
+    @staticmethod
+    def _stream() -> int:
+        import torch
+        return int(torch.cuda.current_stream().cuda_stream)
+
+    def new_blob(self):
+        import torch
+        return torch.empty(int(self.layout.blob_bytes), dtype=torch.uint8, device="cuda")
+
+    def new_workspace(self):
+        import torch
+        ws = torch.empty(int(self.layout.workspace_bytes), dtype=torch.uint8, device="cuda")
+        tsq_workspace_reset(self.handle, ws.data_ptr(), self._stream())
+        return ws
+
+    def new_output(self):
+        import torch
+        return torch.empty((self.tokens, self.hidden), dtype=torch.int16, device="cuda")
+
+    def compress(self, x, blob=None, ws=None):
+        """x: contiguous CUDA tensor [tokens, hidden] of a 16-bit dtype (raw bits are what counts)."""
+        assert x.is_cuda and x.is_contiguous() and x.element_size() == 2
+        assert x.numel() == self.tokens * self.hidden
+        blob = self.new_blob() if blob is None else blob
+        ws = self.new_workspace() if ws is None else ws
+        tsq_compress(self.handle, x.data_ptr(), blob.data_ptr(), ws.data_ptr(), self._stream())
+        return blob
+
+    def decompress(self, blob, out=None):
+        out = self.new_output() if out is None else out
+        assert out.is_cuda and out.is_contiguous() and out.element_size() == 2
+        tsq_decompress(self.handle, blob.data_ptr(), out.data_ptr(), self._stream())
+        return out
+
+    def info(self, blob, check: bool = True) -> tsq_info:
+        return tsq_blob_info(self.handle, blob.data_ptr(), self._stream(), check)
+
+    def sections(self, blob) -> Dict[str, "object"]:
+        """Host copies (numpy) of the blob's sections, cut to their actual lengths."""
+        import numpy as np
+        import torch
+        torch.cuda.synchronize()
+        L, T = self.layout, self.tokens
+        raw = blob.cpu().numpy()
+
+        def view(off, nbytes, dt):
+            return raw[int(off): int(off) + int(nbytes)].view(dt).copy()
+
+        pay_off = view(L.off_pay_off, 8 * (T + 1), np.uint64)
+        row_ptr = view(L.off_row_ptr, 8 * (T + 1), np.uint64)
+        nnz = min(int(row_ptr[-1]), int(L.outlier_capacity))
+        return {
+            "header": view(0, 128, np.uint8),
+            "bits": view(L.off_bits, T, np.uint8),
+            "scale": view(L.off_scale, 4 * T, np.float32),
+            "pay_off": pay_off,
+            "row_ptr": row_ptr,
+            "payload": view(L.off_payload, min(int(pay_off[-1]), int(L.payload_capacity)), np.uint8),
+            "out_col": view(L.off_out_col, 2 * nnz, np.uint16),
+            "out_val": view(L.off_out_val, 2 * nnz, np.uint16),
+        }

@@ -1,0 +1,127 @@
+"""Host-only checks of the C-ABI library: it loads, exports every function that
+include/tsq.h declares, and its plan validation and layout behave as the header
+says.  No kernel is launched here."""
+import ctypes as C
+import os
+import re
+
+import pytest
+
+from paper_2511_04002_amd import build as tsq_build
+from paper_2511_04002_amd import tsq
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module")
+def L():
+    tsq_build.build()
+    return tsq.lib()
+
+
+def declared_functions():
+    text = open(os.path.join(ROOT, "include", "tsq.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(tsq_[a-z_]+)\s*\(", text)))
+
+
+def test_every_declared_symbol_is_exported(L):
+    names = declared_functions()
+    assert set(names) == set(tsq.EXPORTS)
+    for n in names:
+        assert hasattr(L, n), n
+
+
+def cfg(**kw):
+    base = dict(tokens=128, hidden=768, dtype=tsq.TSQ_F16, tau=6.0, bit_mask=tsq.bit_mask((2, 4, 8)),
+                budget=0.05, mode=tsq.TSQ_BUDGET_REL_RMS, pipeline=tsq.TSQ_PIPE_AUTO, max_outliers=0)
+    base.update(kw)
+    return tsq.tsq_config(**base)
+
+
+@pytest.mark.parametrize("kw,status", [
+    (dict(tokens=0), tsq.TSQ_ERR_INVALID_ARG),
+    (dict(hidden=0), tsq.TSQ_ERR_INVALID_ARG),
+    (dict(dtype=7), tsq.TSQ_ERR_INVALID_ARG),
+    (dict(tau=0.0), tsq.TSQ_ERR_INVALID_ARG),
+    (dict(tau=-1.0), tsq.TSQ_ERR_INVALID_ARG),
+    (dict(tau=float("inf")), tsq.TSQ_ERR_INVALID_ARG),
+    (dict(tau=float("nan")), tsq.TSQ_ERR_INVALID_ARG),
+    (dict(bit_mask=0), tsq.TSQ_ERR_INVALID_ARG),
+    (dict(bit_mask=1 << 1), tsq.TSQ_ERR_INVALID_ARG),
+    (dict(bit_mask=(1 << 9) | (1 << 4)), tsq.TSQ_ERR_INVALID_ARG),
+    (dict(budget=-0.1), tsq.TSQ_ERR_INVALID_ARG),
+    (dict(budget=float("nan")), tsq.TSQ_ERR_INVALID_ARG),
+    (dict(mode=5), tsq.TSQ_ERR_INVALID_ARG),
+    (dict(pipeline=9), tsq.TSQ_ERR_INVALID_ARG),
+    (dict(tokens=1 << 20, hidden=4096), tsq.TSQ_ERR_INVALID_ARG),       # tokens*hidden >= 2^32
+    (dict(hidden=772), tsq.TSQ_ERR_UNSUPPORTED),                        # not a multiple of 8
+    (dict(hidden=65536), tsq.TSQ_ERR_UNSUPPORTED),
+])
+def test_plan_create_rejects(L, kw, status):
+    with pytest.raises(tsq.TsqError) as e:
+        tsq.tsq_plan_create(cfg(**kw))
+    assert e.value.status == status
+
+
+def test_null_arguments(L):
+    h = C.c_void_p()
+    assert L.tsq_plan_create(None, C.byref(h)) == tsq.TSQ_ERR_INVALID_ARG
+    c = cfg()
+    assert L.tsq_plan_create(C.byref(c), None) == tsq.TSQ_ERR_INVALID_ARG
+    plan = tsq.tsq_plan_create(c)
+    try:
+        assert L.tsq_compress(plan, None, None, None, None) == tsq.TSQ_ERR_INVALID_ARG
+        assert L.tsq_decompress(plan, None, None, None) == tsq.TSQ_ERR_INVALID_ARG
+        assert L.tsq_blob_info(plan, None, None, None) == tsq.TSQ_ERR_INVALID_ARG
+        assert L.tsq_workspace_reset(plan, None, None) == tsq.TSQ_ERR_INVALID_ARG
+        # misaligned device pointers are refused before any launch
+        assert L.tsq_compress(plan, 0x1008, 0x2000, 0x3000, None) == tsq.TSQ_ERR_INVALID_ARG
+        assert L.tsq_compress(plan, 0x1000, 0x2010, 0x3000, None) == tsq.TSQ_ERR_INVALID_ARG
+    finally:
+        tsq.tsq_plan_destroy(plan)
+    assert L.tsq_plan_blob_bytes(None) == 0 and L.tsq_plan_workspace_bytes(None) == 0
+    L.tsq_plan_destroy(None)
+
+
+def test_budget_may_be_infinite_and_zero(L):
+    for b in (0.0, float("inf")):
+        tsq.tsq_plan_destroy(tsq.tsq_plan_create(cfg(budget=b)))
+
+
+@pytest.mark.parametrize("T,H,bits,cap", [(128, 768, (2, 4, 8), 0), (2048, 4096, (2, 3, 4, 6, 8), 1 << 20),
+                                          (7, 40, (3,), 5), (1, 8, (2, 8), 0)])
+def test_layout(L, T, H, bits, cap):
+    plan = tsq.tsq_plan_create(cfg(tokens=T, hidden=H, bit_mask=tsq.bit_mask(bits), max_outliers=cap))
+    try:
+        lay = tsq.tsq_plan_layout(plan)
+        offs = [lay.off_bits, lay.off_scale, lay.off_pay_off, lay.off_row_ptr, lay.off_payload,
+                lay.off_out_col, lay.off_out_val]
+        sizes = [T, 4 * T, 8 * (T + 1), 8 * (T + 1), lay.payload_capacity, 2 * lay.outlier_capacity,
+                 2 * lay.outlier_capacity]
+        assert offs[0] >= 128
+        for o in offs:
+            assert o % 256 == 0
+        for (o, s), nxt in zip(zip(offs, sizes), offs[1:] + [lay.blob_bytes]):
+            assert o + s <= nxt                                        # sections do not overlap
+        assert lay.payload_capacity == T * 4 * ((H * max(bits) + 31) // 32)
+        assert lay.outlier_capacity == (min(cap, T * H) if cap else T * H)
+        assert lay.blob_bytes == tsq.tsq_plan_blob_bytes(plan)
+        assert lay.workspace_bytes == tsq.tsq_plan_workspace_bytes(plan) > 0
+    finally:
+        tsq.tsq_plan_destroy(plan)
+
+
+def test_status_strings(L):
+    seen = {tsq.tsq_status_string(s) for s in range(7)}
+    assert len(seen) == 7 and "ok" in seen
+    assert tsq.tsq_status_string(99) == "unknown status"
+
+
+def test_product_package_does_not_import_the_oracle():
+    pkg = os.path.join(ROOT, "paper_2511_04002_amd")
+    for dirpath, _, files in os.walk(pkg):
+        for f in files:
+            if f.endswith((".py", ".hip", ".hpp", ".h", ".cpp")):
+                text = open(os.path.join(dirpath, f)).read()
+                assert "oracle" not in text.lower(), f

@@ -1,0 +1,205 @@
+"""Parity of the HIP path with the CPU oracle, through the C ABI.
+
+Bar: bit-exact widths, scales, offsets, CSR columns / values and packed bytes;
+decoded values bit-exact as well (the stated tolerance is 1e-6 relative in fp32
+arithmetic; decode is one exact integer->float conversion, one fp32 multiply and
+one round-to-nearest-even store, so both sides agree to the bit and the test
+asserts that, after asserting the stated tolerance).
+"""
+import numpy as np
+import pytest
+
+from paper_2511_04002_amd import synth
+
+pytestmark = pytest.mark.gpu
+
+F16, BF16 = 0, 1
+DT = {"f16": F16, "bf16": BF16}
+MODE = {"lsb": 0, "rel_rms": 1}
+PIPELINES = ["staged"]
+
+
+@pytest.fixture(scope="module")
+def tsq():
+    import torch
+    assert torch.cuda.is_available(), "these tests need the GPU"
+    from paper_2511_04002_amd import tsq as m
+    m.lib()                                   # fails loudly if libtsq.so is missing
+    return m
+
+
+def widen(raw, dt):
+    if dt == F16:
+        return raw.view(np.float16).astype(np.float32)
+    return (raw.astype(np.uint32) << 16).view(np.float32)
+
+
+def check_parity(tsq, oracle, x, dtype, tau, bit_set, budget, mode="rel_rms", pipeline="staged",
+                 max_outliers=0, label=""):
+    import torch
+    print("case", label, x.shape, dtype, tau, bit_set, budget, mode, pipeline, flush=True)
+    T, H = x.shape
+    ref = oracle.compress(x, DT[dtype], tau, bit_set, budget, MODE[mode], nthreads=8)
+    ref_out = oracle.decompress(ref, nthreads=8)
+
+    plan = tsq.Plan(T, H, dtype, tau, bit_set, budget, mode=mode, pipeline=pipeline,
+                    max_outliers=max_outliers or max(ref.nnz, 1))
+    xd = torch.from_numpy(x.view(np.int16)).cuda()
+    ws = plan.new_workspace()
+    blob = plan.new_blob()
+    blob.fill_(0xA5)                                    # stale bytes must not matter
+    plan.compress(xd, blob, ws)
+    info = plan.info(blob)
+    sec = plan.sections(blob)
+
+    assert np.array_equal(sec["bits"], ref.bits), "widths"
+    assert np.array_equal(sec["scale"].view(np.uint32), ref.scale.view(np.uint32)), "scales"
+    assert np.array_equal(sec["row_ptr"], ref.row_ptr), "row_ptr"
+    assert np.array_equal(sec["pay_off"], ref.pay_off), "pay_off"
+    assert np.array_equal(sec["out_col"], ref.out_col), "CSR columns"
+    assert np.array_equal(sec["out_val"], ref.out_val), "CSR values"
+    assert np.array_equal(sec["payload"], ref.payload), "packed bytes"
+    assert info.nnz == ref.nnz and info.payload_bytes == ref.payload_bytes and info.status == 0
+    assert info.compressed_bytes == oracle.compressed_bytes(ref)
+    assert list(info.width_hist) == np.bincount(ref.bits, minlength=9).tolist()
+
+    out = plan.new_output()
+    out.fill_(0x5A5A)
+    plan.decompress(blob, out)
+    got = out.cpu().numpy().view(np.uint16)
+    gv, rv = widen(got, DT[dtype]).astype(np.float64), widen(ref_out, DT[dtype]).astype(np.float64)
+    fin = np.isfinite(rv)
+    assert np.array_equal(np.isfinite(gv), fin)
+    assert np.all(np.abs(gv[fin] - rv[fin]) <= 1e-6 * np.abs(rv[fin])), "decoded values, 1e-6 relative"
+    assert np.array_equal(got, ref_out), "decoded bits"
+
+    # same input -> same bytes (a second run into a differently pre-filled blob)
+    blob2 = plan.new_blob()
+    blob2.fill_(0x3C)
+    plan.compress(xd, blob2, ws)
+    sec2 = plan.sections(blob2)
+    for k in ("bits", "scale", "row_ptr", "pay_off", "out_col", "out_val", "payload", "header"):
+        assert np.array_equal(sec[k], sec2[k]), "determinism: " + k
+    return ref, info
+
+
+@pytest.mark.parametrize("pipeline", PIPELINES)
+@pytest.mark.parametrize("budget,mode", [(0.05, "rel_rms"), (0.1, "rel_rms"), (0.2, "lsb"), (0.0, "rel_rms"),
+                                         (float("inf"), "lsb")])
+def test_c1_tiny(tsq, oracle, pipeline, budget, mode):
+    check_parity(tsq, oracle, synth.make_c1(), "f16", 6.0, (2, 4, 8), budget, mode, pipeline, label="C1")
+
+
+@pytest.mark.parametrize("pipeline", PIPELINES)
+@pytest.mark.parametrize("eps", [0.05, 0.2])
+def test_c2_prefill_7b(tsq, oracle, pipeline, eps):
+    ref, _ = check_parity(tsq, oracle, synth.make_c2(), "f16", 8.0, (2, 3, 4, 6, 8), eps, "rel_rms", pipeline,
+                          label="C2")
+    assert len(set(ref.bits.tolist())) >= 2
+
+
+@pytest.mark.parametrize("pipeline", PIPELINES)
+def test_c3_decode_steps(tsq, oracle, pipeline):
+    for step in (0, 1, 63):
+        check_parity(tsq, oracle, synth.make_c3(step), "f16", 8.0, (2, 4, 8), 0.2, "rel_rms", pipeline,
+                     label="C3 step %d" % step)
+
+
+@pytest.mark.parametrize("pipeline", PIPELINES)
+@pytest.mark.parametrize("eps", [0.05, 0.2])
+def test_c4_prefill_70b_full_size(tsq, oracle, pipeline, eps):
+    ref, _ = check_parity(tsq, oracle, synth.make_c4(), "bf16", 10.0, (2, 3, 4, 5, 6, 8), eps, "rel_rms", pipeline,
+                          label="C4")
+    assert len(set(ref.bits.tolist())) >= 3
+
+
+@pytest.mark.parametrize("pipeline", PIPELINES)
+@pytest.mark.parametrize("tau", synth.C5_TAUS)
+@pytest.mark.parametrize("bit_set", synth.C5_BIT_SETS)
+def test_c5_stress_two_sequences(tsq, oracle, pipeline, tau, bit_set):
+    x = np.concatenate([synth.make_c5_seq(0, 1024), synth.make_c5_seq(31, 1024)])
+    check_parity(tsq, oracle, x, "bf16", tau, bit_set, 0.05, "rel_rms", pipeline, label="C5 subset")
+
+
+@pytest.mark.parametrize("pipeline", PIPELINES)
+@pytest.mark.parametrize("dtype", ["f16", "bf16"])
+@pytest.mark.parametrize("H", [8, 24, 32, 40, 264, 1000, 2056, 4096 + 8, 32768])
+def test_edge_rows_and_ragged_hidden(tsq, oracle, pipeline, dtype, H):
+    x = synth.edge_rows(H, dtype, 6.0) if H >= 264 else None
+    if x is None:
+        g = np.random.Generator(np.random.PCG64(H))
+        v = g.standard_normal((37, H)) * 3.0
+        x = synth.to_f16_bits(v) if dtype == "f16" else synth.to_bf16_bits(v)
+    for bs, bud, mode in (((2, 4, 5, 8), 0.05, "rel_rms"), ((2, 3, 4, 5, 6, 7, 8), 0.3, "lsb"), ((7,), 0.1, "lsb"),
+                          ((3, 6), 0.5, "rel_rms")):
+        check_parity(tsq, oracle, x, dtype, 6.0, bs, bud, mode, pipeline, label="edge H=%d" % H)
+
+
+@pytest.mark.parametrize("pipeline", PIPELINES)
+@pytest.mark.parametrize("dtype", ["f16", "bf16"])
+def test_many_absmax_values_exercise_the_divisions(tsq, oracle, pipeline, dtype):
+    # one row per absmax pattern: r = Q/amax and s = amax/Q must be correctly rounded for all of them
+    g = np.random.Generator(np.random.PCG64(3))
+    T, H = 4096, 64
+    if dtype == "f16":
+        pats = np.linspace(1, 0x7BFF, T).astype(np.uint16)
+    else:
+        pats = np.concatenate([np.linspace(0x0001, 0x0D80, T // 4), np.linspace(0x0D80, 0x7F7F, T - T // 4)]).astype(np.uint16)
+    frac = g.random((T, H))
+    x = np.empty((T, H), np.uint16)
+    for t in range(T):
+        # magnitudes below the row's absmax pattern, random signs, absmax itself at a random slot
+        row = (frac[t] * pats[t]).astype(np.uint16)
+        row[g.integers(0, H)] = pats[t]
+        x[t] = row | (g.integers(0, 2, H).astype(np.uint16) << 15)
+    tau = 3.0e38 if dtype == "bf16" else 65504.0
+    check_parity(tsq, oracle, x, dtype, tau, (2, 3, 4, 5, 6, 7, 8), 0.05, "rel_rms", pipeline, label="absmax sweep")
+    check_parity(tsq, oracle, x, dtype, tau, (3, 5, 8), 0.25, "lsb", pipeline, label="absmax sweep lsb")
+
+
+@pytest.mark.parametrize("pipeline", PIPELINES)
+def test_all_width_subsets_small(tsq, oracle, pipeline):
+    import itertools
+    x = synth.make_c2(tokens=32)[:, :1024].copy()
+    subsets = [s for n in (1, 2, 3, 7) for s in itertools.combinations(range(2, 9), n)]
+    for i, bs in enumerate(subsets):
+        bud, mode = ((0.05, "rel_rms"), (0.2, "rel_rms"), (0.25, "lsb"))[i % 3]
+        check_parity(tsq, oracle, x, "f16", 4.0, bs, bud, mode, pipeline, label="subset %s" % (bs,))
+
+
+@pytest.mark.parametrize("pipeline", PIPELINES)
+def test_side_stream_overflow_is_reported_and_decompress_refuses(tsq, oracle, pipeline):
+    import torch
+    x = synth.make_c2(tokens=64)
+    ref = oracle.compress(x, F16, 8.0, (2, 4, 8), 0.05, 1, nthreads=4)
+    assert ref.nnz > 40
+    plan = tsq.Plan(64, 4096, "f16", 8.0, (2, 4, 8), 0.05, pipeline=pipeline, max_outliers=ref.nnz - 1)
+    xd = torch.from_numpy(x.view(np.int16)).cuda()
+    blob = plan.compress(xd)
+    info = plan.info(blob, check=False)
+    assert info.return_status == tsq.TSQ_ERR_CAPACITY and info.status == tsq.TSQ_ERR_CAPACITY
+    assert info.nnz == ref.nnz                                  # the true count is still reported
+    sec = plan.sections(blob)
+    assert np.array_equal(sec["bits"], ref.bits) and np.array_equal(sec["row_ptr"], ref.row_ptr)
+    out = plan.new_output()
+    out.fill_(0x1234)
+    plan.decompress(blob, out)
+    assert bool((out == 0x1234).all())                          # nothing written
+    # the exact capacity works
+    plan2 = tsq.Plan(64, 4096, "f16", 8.0, (2, 4, 8), 0.05, pipeline=pipeline, max_outliers=ref.nnz)
+    blob2 = plan2.compress(xd)
+    assert plan2.info(blob2).status == 0
+    assert np.array_equal(plan2.decompress(blob2).cpu().numpy().view(np.uint16), oracle.decompress(ref))
+
+
+def test_decompress_refuses_a_foreign_blob(tsq):
+    import torch
+    plan = tsq.Plan(16, 256, "f16", 6.0, (4, 8), 0.05)
+    blob = plan.new_blob()
+    blob.zero_()
+    out = plan.new_output()
+    out.fill_(0x0BAD)
+    plan.decompress(blob, out)
+    assert bool((out == 0x0BAD).all())
+    info = plan.info(blob, check=False)
+    assert info.return_status == tsq.TSQ_ERR_FORMAT
