@@ -113,7 +113,7 @@ tsq_status tsq_plan_create(const tsq_config *cfg, tsq_plan **out) {
     p.tau = cfg->tau;
     p.budget = cfg->budget;
     p.mode = cfg->mode;
-    p.spin_limit = 1u << 22;
+    p.spin_limit = 1u << 20;
 
     tsq_layout &L = pl->layout;
     uint64_t off = align_up(sizeof(BlobHeader), 256);
@@ -131,7 +131,8 @@ tsq_status tsq_plan_create(const tsq_config *cfg, tsq_plan **out) {
 
     uint64_t w = 0;
     p.ws_cnt = w;    w = align_up(w + 4ull * T, 256);
-    p.ws_state = w;  w = align_up(w + 8ull * T, 256);
+    p.ws_agg = w;    w = align_up(w + 16ull * T, 256);
+    p.ws_pref = w;   w = align_up(w + 16ull * T, 256);
     p.ws_ctrl = w;   w = align_up(w + 256, 256);
     L.workspace_bytes = w;
 
@@ -141,8 +142,9 @@ tsq_status tsq_plan_create(const tsq_config *cfg, tsq_plan **out) {
     p.outlier_capacity = L.outlier_capacity;
 
     pl->g.block = 64u * ((p.runs + 63u) / 64u);
-    pl->g.lds_bytes = (p.runs * kRunLdsDw + 2u * 2u * kMaxWaves + kMaxWaves) * 4u;
-    pl->pipeline = cfg->pipeline == TSQ_PIPE_FUSED ? TSQ_PIPE_FUSED : TSQ_PIPE_STAGED;
+    pl->g.lds_bytes = (p.runs * kRunLdsDw + kScratchDw) * 4u;
+    pl->g.lds_fused_bytes = (2u * p.runs * 16u + kScratchDw) * 4u;
+    pl->pipeline = cfg->pipeline == TSQ_PIPE_STAGED ? TSQ_PIPE_STAGED : TSQ_PIPE_FUSED;
     *out = pl;
     return TSQ_OK;
 }

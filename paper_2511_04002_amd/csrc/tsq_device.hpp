@@ -35,18 +35,47 @@ __device__ __forceinline__ uint32_t pk_ashr15_i16(uint32_t a) {
 
 // ---------------------------------------------------------------- wave / block collectives
 
+// DPP controls (gfx9): quad_perm [1,0,3,2] and [2,3,0,1], mirror inside 8 lanes, mirror inside a
+// row of 16 lanes, shift right inside a row by n.
+constexpr int kDppQuadXor1 = 0xB1, kDppQuadXor2 = 0x4E, kDppHalfMirror = 0x141, kDppRowMirror = 0x140;
+constexpr int kDppRowShr = 0x110;
+
+template <int CTRL>
+__device__ __forceinline__ uint32_t dpp(uint32_t v) {
+    return (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, CTRL, 0xF, 0xF, true);
+}
+__device__ __forceinline__ uint32_t lane_value(uint32_t v, int lane) {
+    return (uint32_t)__builtin_amdgcn_readlane((int)v, lane);
+}
+
+// Reductions over the 64 lanes of a wave; the result is uniform.  Four DPP steps leave the
+// total of each row of 16 lanes in all of its lanes; the four row totals are combined as scalars.
 __device__ __forceinline__ uint32_t wave_max_u32(uint32_t v) {
-#pragma unroll
-    for (int o = 32; o > 0; o >>= 1) {
-        uint32_t n = (uint32_t)__shfl_xor((int)v, o);
-        v = n > v ? n : v;
-    }
-    return v;
+    uint32_t n;
+    n = dpp<kDppQuadXor1>(v);   v = n > v ? n : v;
+    n = dpp<kDppQuadXor2>(v);   v = n > v ? n : v;
+    n = dpp<kDppHalfMirror>(v); v = n > v ? n : v;
+    n = dpp<kDppRowMirror>(v);  v = n > v ? n : v;
+    const uint32_t a = lane_value(v, 0), b = lane_value(v, 16), c = lane_value(v, 32), d = lane_value(v, 48);
+    const uint32_t ab = a > b ? a : b, cd = c > d ? c : d;
+    return ab > cd ? ab : cd;
 }
 __device__ __forceinline__ uint32_t wave_sum_u32(uint32_t v) {
-#pragma unroll
-    for (int o = 32; o > 0; o >>= 1) v += (uint32_t)__shfl_xor((int)v, o);
-    return v;
+    v += dpp<kDppQuadXor1>(v);
+    v += dpp<kDppQuadXor2>(v);
+    v += dpp<kDppHalfMirror>(v);
+    v += dpp<kDppRowMirror>(v);
+    return lane_value(v, 0) + lane_value(v, 16) + lane_value(v, 32) + lane_value(v, 48);
+}
+// Inclusive prefix sum over the lanes of a wave, in lane order.
+__device__ __forceinline__ uint32_t wave_incl_scan_u32(uint32_t v) {
+    v += dpp<kDppRowShr + 1>(v);    // lanes without a source inside their row add 0
+    v += dpp<kDppRowShr + 2>(v);
+    v += dpp<kDppRowShr + 4>(v);
+    v += dpp<kDppRowShr + 8>(v);
+    const uint32_t r0 = lane_value(v, 15), r1 = lane_value(v, 31), r2 = lane_value(v, 47);
+    const uint32_t row = (threadIdx.x & 63) >> 4;
+    return v + (row > 0 ? r0 : 0u) + (row > 1 ? r1 : 0u) + (row > 2 ? r2 : 0u);
 }
 
 // Every thread gets max over the block of mx and sum over the block of sm.
@@ -86,12 +115,7 @@ __device__ __forceinline__ void block_sum2(uint32_t &x, uint32_t &y, uint32_t *r
 // scr: kMaxWaves dwords of LDS not in use by anything else until the next barrier.
 __device__ __forceinline__ uint32_t block_excl_scan(uint32_t v, uint32_t *scr) {
     const uint32_t lane = threadIdx.x & 63, wv = threadIdx.x >> 6;
-    uint32_t inc = v;
-#pragma unroll
-    for (int o = 1; o < 64; o <<= 1) {
-        uint32_t n = (uint32_t)__shfl_up((int)inc, o);
-        if ((int)lane >= o) inc += n;
-    }
+    const uint32_t inc = wave_incl_scan_u32(v);
     if (lane == 63) scr[wv] = inc;
     __syncthreads();
     uint32_t base = 0;
@@ -128,14 +152,8 @@ __device__ __forceinline__ void stage_row(const uint4 *__restrict__ src, uint32_
 //   apk   : |x| patterns of the inliers, 0 at outlier slots (|T_below|)
 //   omask : outlier flags; bit i = element 2i, bit 16+i = element 2i+1
 //   amax  : running maximum of the inlier patterns, both halves
-__device__ __forceinline__ void split_run(const uint32_t *lrun, uint32_t thr_pk, uint32_t (&apk)[16],
-                                          uint32_t &omask, uint32_t &amax_pk) {
-    uint32_t w[16];
-#pragma unroll
-    for (int k = 0; k < 4; ++k) {
-        const uint4 q = *reinterpret_cast<const uint4 *>(lrun + 4 * k);
-        w[4 * k] = q.x; w[4 * k + 1] = q.y; w[4 * k + 2] = q.z; w[4 * k + 3] = q.w;
-    }
+__device__ __forceinline__ void split_regs(const uint32_t (&w)[16], uint32_t thr_pk, uint32_t (&apk)[16],
+                                           uint32_t &omask, uint32_t &amax_pk) {
     uint32_t om = 0, mx = amax_pk;
 #pragma unroll
     for (int i = 0; i < 16; ++i) {
@@ -148,6 +166,46 @@ __device__ __forceinline__ void split_run(const uint32_t *lrun, uint32_t thr_pk,
     }
     omask = om;
     amax_pk = mx;
+}
+
+// A run in the padded LDS row of the staged kernels.
+__device__ __forceinline__ void load_run_padded(const uint32_t *lrun, uint32_t (&w)[16]) {
+#pragma unroll
+    for (int k = 0; k < 4; ++k) {
+        const uint4 q = *reinterpret_cast<const uint4 *>(lrun + 4 * k);
+        w[4 * k] = q.x; w[4 * k + 1] = q.y; w[4 * k + 2] = q.z; w[4 * k + 3] = q.w;
+    }
+}
+__device__ __forceinline__ void split_run(const uint32_t *lrun, uint32_t thr_pk, uint32_t (&apk)[16],
+                                          uint32_t &omask, uint32_t &amax_pk) {
+    uint32_t w[16];
+    load_run_padded(lrun, w);
+    split_regs(w, thr_pk, apk, omask, amax_pk);
+}
+
+// Lane-private copy of a run in LDS, 16 dwords per lane, no padding: the four 16-byte chunks
+// of lane r are stored in the order k ^ ((r >> 1) & 3), which spreads 8 neighbouring lanes
+// over all 32 banks.
+__device__ __forceinline__ void slot_write(uint32_t *slot, uint32_t r, const uint32_t (&w)[16]) {
+    const uint32_t sw = (r >> 1) & 3u;
+    uint32_t *base = slot + r * 16;
+#pragma unroll
+    for (uint32_t k = 0; k < 4; ++k)
+        *reinterpret_cast<uint4 *>(base + ((k ^ sw) << 2)) = make_uint4(w[4 * k], w[4 * k + 1], w[4 * k + 2], w[4 * k + 3]);
+}
+__device__ __forceinline__ void slot_read(const uint32_t *slot, uint32_t r, uint32_t (&w)[16]) {
+    const uint32_t sw = (r >> 1) & 3u;
+    const uint32_t *base = slot + r * 16;
+#pragma unroll
+    for (uint32_t k = 0; k < 4; ++k) {
+        const uint4 q = *reinterpret_cast<const uint4 *>(base + ((k ^ sw) << 2));
+        w[4 * k] = q.x; w[4 * k + 1] = q.y; w[4 * k + 2] = q.z; w[4 * k + 3] = q.w;
+    }
+}
+__device__ __forceinline__ uint16_t slot_raw(const uint32_t *slot, uint32_t r, uint32_t j) {
+    const uint32_t d = j >> 1;
+    const uint32_t pos = r * 16 + ((((d >> 2) ^ ((r >> 1) & 3u)) << 2) | (d & 3u));
+    return reinterpret_cast<const uint16_t *>(slot)[2 * pos + (j & 1u)];
 }
 
 template <int DT>
@@ -167,7 +225,9 @@ __device__ __forceinline__ float widen16(uint32_t pattern) {
 
 // ---------------------------------------------------------------- Eq. (Proposed) on one run
 
-// m = rint(a * r), one byte per element, element 4g+k in byte k of m[g].
+// m = rint(a * r), one byte per element, element 4g+k in byte k of m[g].  The rounding is done by
+// v_cvt_pk_u8_f32 itself, which converts with round-to-nearest-even (checked on gfx950 on exact
+// halves 0.5, 1.5, 2.5, ... and pinned by the tie rows of the parity tests) and saturates at 255.
 // A clamp min(., Q) to the code range never binds: a <= amax and r = fl(Q/amax) give
 // a*r <= Q*(1+2^-24)^2 < Q + 1/2, so rint already yields at most Q.
 template <int DT>
@@ -175,10 +235,10 @@ __device__ __forceinline__ void quantize_run(const uint32_t (&apk)[16], float r,
 #pragma unroll
     for (int g = 0; g < 8; ++g) {
         uint32_t acc = 0;
-        acc = __builtin_amdgcn_cvt_pk_u8_f32(__builtin_rintf(widen_lo<DT>(apk[2 * g]) * r), 0, acc);
-        acc = __builtin_amdgcn_cvt_pk_u8_f32(__builtin_rintf(widen_hi<DT>(apk[2 * g]) * r), 1, acc);
-        acc = __builtin_amdgcn_cvt_pk_u8_f32(__builtin_rintf(widen_lo<DT>(apk[2 * g + 1]) * r), 2, acc);
-        acc = __builtin_amdgcn_cvt_pk_u8_f32(__builtin_rintf(widen_hi<DT>(apk[2 * g + 1]) * r), 3, acc);
+        acc = __builtin_amdgcn_cvt_pk_u8_f32(widen_lo<DT>(apk[2 * g]) * r, 0, acc);
+        acc = __builtin_amdgcn_cvt_pk_u8_f32(widen_hi<DT>(apk[2 * g]) * r, 1, acc);
+        acc = __builtin_amdgcn_cvt_pk_u8_f32(widen_lo<DT>(apk[2 * g + 1]) * r, 2, acc);
+        acc = __builtin_amdgcn_cvt_pk_u8_f32(widen_hi<DT>(apk[2 * g + 1]) * r, 3, acc);
         m[g] = acc;
     }
 }
@@ -221,14 +281,8 @@ __device__ __forceinline__ float level_count(uint32_t width) { return (float)((1
 // out[0..B) = the run's 32 codes, LSB first.  m: magnitude bytes; w: the run's
 // raw input dwords (sign bits).  The sign is dropped where the magnitude is 0.
 template <int B>
-__device__ __forceinline__ void pack_run(const uint32_t (&m)[8], const uint32_t *lrun, uint32_t (&out)[B]) {
+__device__ __forceinline__ void pack_regs(const uint32_t (&m)[8], const uint32_t (&w)[16], uint32_t (&out)[B]) {
     constexpr uint32_t K = (1u << (B - 1)) - 1u;
-    uint32_t w[16];
-#pragma unroll
-    for (int k = 0; k < 4; ++k) {
-        const uint4 q = *reinterpret_cast<const uint4 *>(lrun + 4 * k);
-        w[4 * k] = q.x; w[4 * k + 1] = q.y; w[4 * k + 2] = q.z; w[4 * k + 3] = q.w;
-    }
     uint64_t acc = 0;
     int filled = 0, od = 0;
 #pragma unroll
@@ -255,6 +309,13 @@ __device__ __forceinline__ void pack_run(const uint32_t (&m)[8], const uint32_t 
             filled -= 32;
         }
     }
+}
+
+template <int B>
+__device__ __forceinline__ void pack_run(const uint32_t (&m)[8], const uint32_t *lrun, uint32_t (&out)[B]) {
+    uint32_t w[16];
+    load_run_padded(lrun, w);
+    pack_regs<B>(m, w, out);
 }
 
 // Inverse of pack_run followed by Eq. (dequnt) for the inliers: 32 codes ->

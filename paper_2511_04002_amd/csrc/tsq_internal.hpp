@@ -14,6 +14,9 @@ constexpr int kRun      = 32;   // elements owned by one lane (a "run")
 constexpr int kRunLdsDw = 20;   // dwords one run occupies in LDS: 16 of data + 4 of padding,
                                 // so that 8 lanes reading 16 B each hit 32 distinct banks
 constexpr int kMaxWaves = 16;   // 1024 threads per workgroup at most
+// LDS scratch of the row kernels behind the row: two reduce areas (3 dwords per wave), one scan
+// area, one broadcast area
+constexpr uint32_t kScratchDw = 2 * 3 * kMaxWaves + kMaxWaves + 8;
 constexpr uint32_t kMaxHidden = 32768;
 
 // 128-byte header at the start of every blob.
@@ -44,8 +47,9 @@ struct Params {
     uint64_t payload_capacity, outlier_capacity;
     // workspace sections (bytes from d_ws)
     uint64_t ws_cnt;        // u32[T]  outliers per token           (staged)
-    uint64_t ws_state;      // u64[T]  chained-scan state per token (fused)
-    uint64_t ws_ctrl;       // u32[64] ticket / done counters       (fused)
+    uint64_t ws_agg;        // u64[2][T] per-token (words, count), two generations   (fused)
+    uint64_t ws_pref;       // u64[2][T] per-token exclusive prefix, two generations (fused)
+    uint64_t ws_ctrl;       // u32[64]   generation, error flag                      (fused)
 };
 
 inline __host__ __device__ uint32_t width_at(const Params &p, uint32_t i) {
@@ -55,7 +59,8 @@ inline __host__ __device__ uint32_t width_at(const Params &p, uint32_t i) {
 // Launch geometry fixed by the plan.
 struct Geometry {
     uint32_t block;         // threads per workgroup = 64 * ceil(runs / 64)
-    uint32_t lds_bytes;     // dynamic LDS of the row kernels
+    uint32_t lds_bytes;     // dynamic LDS of the staged row kernels and of unpack
+    uint32_t lds_fused_bytes;  // dynamic LDS of the fused kernel (two lane-private row copies)
 };
 
 // launchers implemented in tsq_kernels.hip; each returns a hipError_t as int

@@ -13,7 +13,9 @@
 namespace tsq {
 
 // LDS map of the row kernels (dynamic):  [ row: runs*kRunLdsDw dwords | scratch: kScratchDw dwords ]
-constexpr uint32_t kScratchDw = 2 * 2 * kMaxWaves + kMaxWaves;  // two reduce areas + one scan area
+//   scratch: reduce area 0 [0,32) | reduce area 1 [32,64) | scan area [64,80) | broadcast area [80,88);
+//   the scan workgroup of the fused kernel uses [0,96) as two areas of 3 dwords per wave
+constexpr uint32_t kScrScan = 4 * kMaxWaves;
 
 __device__ __forceinline__ uint32_t row_bytes(uint32_t H, uint32_t b) { return 4u * ((H * b + 31u) >> 5); }
 
@@ -182,12 +184,7 @@ k_scan(const Params p, uint8_t *__restrict__ blob, const uint8_t *__restrict__ w
             sc += c[k]; sy += y[k];
         }
         // inclusive scan inside the wave
-        uint32_t ic = sc, iy = sy;
-#pragma unroll
-        for (int o = 1; o < 64; o <<= 1) {
-            const uint32_t nc = (uint32_t)__shfl_up((int)ic, o), ny = (uint32_t)__shfl_up((int)iy, o);
-            if ((int)lane >= o) { ic += nc; iy += ny; }
-        }
+        const uint32_t ic = wave_incl_scan_u32(sc), iy = wave_incl_scan_u32(sy);
         uint32_t (*s)[2] = scr[it & 1];
         if (lane == 63) { s[wv][0] = ic; s[wv][1] = iy; }
         __syncthreads();
@@ -268,7 +265,301 @@ k_pack(const Params p, const uint16_t *__restrict__ in, uint8_t *__restrict__ bl
     // side stream: only tokens that fit entirely below the capacity are stored
     if (cnt > 0 && rp1 <= p.outlier_capacity && rp1 - rp0 == cnt) {
         emit_outliers(omask, lrow, run, reinterpret_cast<uint16_t *>(blob + p.off_out_col),
-                      reinterpret_cast<uint16_t *>(blob + p.off_out_val), rp0, scratch + 4 * kMaxWaves);
+                      reinterpret_cast<uint16_t *>(blob + p.off_out_val), rp0, scratch + kScrScan);
+    }
+}
+
+// ---------------------------------------------------------------- k_fused: one pass over the input
+//
+// A persistent grid whose workgroups are all resident at once.  Workgroup 0 is the scan
+// workgroup; workgroup 1+w compresses tokens w, w+G, w+2G, ... (G = grid - 1).
+//
+//   compute workgroup, token t:  load the row (each lane its run, straight into registers; the
+//       next row's loads are already in flight), split, choose the width, publish
+//       agg[t] = (payload words, outlier count), pack the codes into registers.  The token's
+//       output position comes back from the scan workgroup as pref[t]; it is picked up one
+//       iteration later, after the next token's arithmetic, so the round trip is hidden.
+//   scan workgroup:  for every batch of G tokens, waits for their agg words, scans them in
+//       token order on top of a running total, and publishes pref[t] = exclusive prefix.  It
+//       also writes row_ptr / pay_off and, at the end, the blob header.
+//
+// agg and pref words: bit 62 = valid, bit 63 = error, bits 61..32 words, bits 31..0 count; both
+// sums stay below 2^30 / 2^32 because tokens*hidden < 2^32.  They are written and read with
+// device-coherent relaxed atomics (the values are self-contained, nothing else is ordered by
+// them).  Two generations of both arrays alternate between calls: a call fills one and zeroes
+// the other, so no clearing pass is needed.  Every wait is bounded by p.spin_limit.
+constexpr uint64_t kWordValid = 1ull << 62, kWordError = 1ull << 63;
+constexpr int kScanItems = 8;  // tokens per thread and round in the scan workgroup
+
+enum { kCtlGen = 0, kCtlError = 1 };
+
+__device__ __forceinline__ uint64_t word_load(const uint64_t *p) {
+    return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ __forceinline__ void word_store(uint64_t *p, uint64_t v) {
+    __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ __forceinline__ uint64_t wait_word(const uint64_t *p, uint32_t spin_limit) {
+    uint64_t v = word_load(p);
+    uint32_t spins = 0;
+    while (!(v & kWordValid) && spins < spin_limit) {
+        __builtin_amdgcn_s_sleep(1);
+        v = word_load(p);
+        ++spins;
+    }
+    return v;
+}
+
+__device__ __forceinline__ void write_header(const Params &p, uint8_t *blob, uint64_t nnz, uint64_t payload_bytes,
+                                             uint32_t status) {
+    BlobHeader h;
+    h.magic = kMagic; h.version = kVersion; h.dtype = p.dtype; h.tokens = p.tokens; h.hidden = p.hidden;
+    h.tau_bits = __float_as_uint(p.tau); h.bit_mask = p.bit_mask; h.budget_bits = __float_as_uint(p.budget);
+    h.mode = (uint32_t)p.mode;
+    h.status = status;
+    h.nnz = nnz; h.payload_bytes = payload_bytes;
+    h.off_bits = p.off_bits; h.off_scale = p.off_scale; h.off_pay_off = p.off_pay_off;
+    h.off_row_ptr = p.off_row_ptr; h.off_payload = p.off_payload; h.off_out_col = p.off_out_col;
+    h.off_out_val = p.off_out_val; h.payload_capacity = p.payload_capacity;
+    h.outlier_capacity = p.outlier_capacity;
+    *reinterpret_cast<BlobHeader *>(blob) = h;
+}
+
+// The scan workgroup (all of its threads).
+__device__ __forceinline__ void scan_role(const Params &p, uint8_t *blob, uint8_t *ws, uint32_t G, uint32_t gen,
+                                          uint32_t *scr) {
+    const uint64_t *agg = reinterpret_cast<const uint64_t *>(ws + p.ws_agg) + (size_t)gen * p.tokens;
+    uint64_t *pref = reinterpret_cast<uint64_t *>(ws + p.ws_pref) + (size_t)gen * p.tokens;
+    uint64_t *pref_next = reinterpret_cast<uint64_t *>(ws + p.ws_pref) + (size_t)(1u - gen) * p.tokens;
+    uint32_t *ctrl = reinterpret_cast<uint32_t *>(ws + p.ws_ctrl);
+    uint64_t *row_ptr = reinterpret_cast<uint64_t *>(blob + p.off_row_ptr);
+    uint64_t *pay_off = reinterpret_cast<uint64_t *>(blob + p.off_pay_off);
+    const uint32_t tid = threadIdx.x, wv = tid >> 6, nw = blockDim.x >> 6;
+    const uint32_t per_round = blockDim.x * kScanItems;
+
+    uint64_t carry_c = 0, carry_w = 0;
+    uint32_t failed = 0, it = 0;
+    // batches of G tokens become ready together; inside a batch, rounds of per_round tokens
+    for (uint64_t batch = 0; batch < p.tokens; batch += G) {
+        const uint64_t batch_end = batch + G < p.tokens ? batch + G : p.tokens;
+        for (uint64_t base = batch; base < batch_end; base += per_round, ++it) {
+            uint64_t v[kScanItems];
+            uint32_t sc = 0, sw = 0, bad = 0;
+#pragma unroll
+            for (int k = 0; k < kScanItems; ++k) {
+                const uint64_t t = base + (uint64_t)tid * kScanItems + k;
+                v[k] = 0;
+                if (t < batch_end) v[k] = word_load(agg + t);
+            }
+#pragma unroll
+            for (int k = 0; k < kScanItems; ++k) {
+                const uint64_t t = base + (uint64_t)tid * kScanItems + k;
+                if (t < batch_end) {
+                    if (!(v[k] & kWordValid)) v[k] = wait_word(agg + t, p.spin_limit);
+                    if (!(v[k] & kWordValid)) { bad = 1; v[k] = 0; }
+                }
+                sc += (uint32_t)v[k];
+                sw += (uint32_t)(v[k] >> 32) & 0x3FFFFFFFu;
+            }
+            const uint32_t ic = wave_incl_scan_u32(sc), iw = wave_incl_scan_u32(sw);
+            const uint32_t anybad = wave_sum_u32(bad);
+            uint32_t *s3 = scr + (it & 1) * 3 * kMaxWaves;
+            if ((tid & 63) == 63) { s3[3 * wv] = ic; s3[3 * wv + 1] = iw; s3[3 * wv + 2] = anybad; }
+            __syncthreads();
+            uint32_t bc = 0, bw = 0, tc = 0, tw = 0;
+            for (uint32_t w = 0; w < nw; ++w) {
+                const uint32_t a = s3[3 * w], b = s3[3 * w + 1];
+                if (w < wv) { bc += a; bw += b; }
+                tc += a; tw += b;
+                failed |= s3[3 * w + 2];
+            }
+            uint64_t ec = carry_c + bc + ic - sc, ew = carry_w + bw + iw - sw;
+            const uint64_t flags = kWordValid | (failed ? kWordError : 0ull);
+#pragma unroll
+            for (int k = 0; k < kScanItems; ++k) {
+                const uint64_t t = base + (uint64_t)tid * kScanItems + k;
+                if (t < batch_end) {
+                    word_store(pref + t, flags | ((ew & 0x3FFFFFFFull) << 32) | (ec & 0xFFFFFFFFull));
+                    pref_next[t] = 0;
+                    row_ptr[t] = ec;
+                    pay_off[t] = ew << 2;
+                }
+                ec += (uint32_t)v[k];
+                ew += (uint32_t)(v[k] >> 32) & 0x3FFFFFFFu;
+            }
+            carry_c += tc;
+            carry_w += tw;
+        }
+    }
+    if (tid == 0) {
+        row_ptr[p.tokens] = carry_c;
+        pay_off[p.tokens] = carry_w << 2;
+        const uint32_t err = failed | __hip_atomic_load(ctrl + kCtlError, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        write_header(p, blob, carry_c, carry_w << 2, err ? 6u : (carry_c > p.outlier_capacity ? 3u : 0u));
+        // re-arm the workspace: every compute workgroup that owns a token has read the generation
+        // before publishing its first agg word, and all agg words have been consumed by now
+        __hip_atomic_store(ctrl + kCtlError, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        __hip_atomic_store(ctrl + kCtlGen, gen ^ 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    }
+}
+
+template <int B>
+__device__ __forceinline__ void pack_into(const uint32_t (&m)[8], const uint32_t (&w)[16], uint32_t (&out)[8]) {
+    uint32_t o[B];
+    pack_regs<B>(m, w, o);
+#pragma unroll
+    for (int k = 0; k < B; ++k) out[k] = o[k];
+}
+
+// What a compute workgroup keeps of a token between publishing it and storing it.
+struct Pending {
+    uint32_t out[8];   // packed codes of the lane's run (first `width` dwords)
+    uint32_t omask;    // the lane's outlier flags
+    uint32_t loff;     // outliers of the token in lanes before this one
+};
+
+__device__ __forceinline__ void store_pending(const Params &p, uint8_t *blob, uint8_t *ws, const Pending &pd,
+                                              uint32_t t, uint32_t width, uint32_t cnt, const uint32_t *slot,
+                                              uint64_t pv, uint32_t run) {
+    const uint64_t *pref = reinterpret_cast<const uint64_t *>(ws + p.ws_pref);
+    (void)pref;
+    bool ok = (pv & kWordValid) && !(pv & kWordError);
+    const uint32_t ew = (uint32_t)(pv >> 32) & 0x3FFFFFFFu, ec = (uint32_t)pv;
+    const uint32_t words = row_bytes(p.hidden, width) >> 2;
+    if ((uint64_t)ew + words > (p.payload_capacity >> 2)) ok = false;  // never store outside the blob
+    if (!ok) {
+        if (threadIdx.x == 0) {
+            uint32_t *ctrl = reinterpret_cast<uint32_t *>(ws + p.ws_ctrl);
+            __hip_atomic_fetch_or(ctrl + kCtlError, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            // the header may already be final: make the blob unreadable
+            __hip_atomic_store(reinterpret_cast<uint32_t *>(blob), 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        }
+        return;
+    }
+    if (run < p.runs) {
+        const uint32_t left = p.pieces - 4 * run;
+        const uint32_t nd = left >= 4 ? width : ((left * width + 3u) >> 2);
+        uint32_t *dst = reinterpret_cast<uint32_t *>(blob + p.off_payload) + ew + run * width;
+#pragma unroll
+        for (uint32_t k = 0; k < 8; ++k)
+            if (k < nd) dst[k] = pd.out[k];
+        if (pd.omask && (uint64_t)ec + cnt <= p.outlier_capacity) {
+            uint16_t *col = reinterpret_cast<uint16_t *>(blob + p.off_out_col);
+            uint16_t *val = reinterpret_cast<uint16_t *>(blob + p.off_out_val);
+            uint64_t pos = (uint64_t)ec + pd.loff;
+            uint32_t ev = pd.omask & 0xFFFFu, od = pd.omask >> 16;
+            while (ev | od) {
+                const uint32_t je = ev ? 2u * (uint32_t)__builtin_ctz(ev) : 64u;
+                const uint32_t jo = od ? 2u * (uint32_t)__builtin_ctz(od) + 1u : 64u;
+                uint32_t j;
+                if (je < jo) { j = je; ev &= ev - 1u; } else { j = jo; od &= od - 1u; }
+                col[pos] = (uint16_t)(run * kRun + j);
+                val[pos] = slot_raw(slot, run, j);
+                ++pos;
+            }
+        }
+    }
+}
+
+template <int DT>
+__global__ void __launch_bounds__(1024)
+k_fused(const Params p, const uint16_t *__restrict__ in, uint8_t *__restrict__ blob, uint8_t *__restrict__ ws,
+        const uint32_t G) {
+    extern __shared__ __align__(16) uint32_t lds[];
+    const uint32_t slot_dw = p.runs * 16;
+    uint32_t *scratch = lds + 2 * slot_dw;
+    uint32_t *ctrl = reinterpret_cast<uint32_t *>(ws + p.ws_ctrl);
+    const uint32_t gen = ctrl[kCtlGen] & 1u;  // written by the previous call or the reset kernel
+
+    if (blockIdx.x == 0) {
+        scan_role(p, blob, ws, G, gen, scratch);
+        return;
+    }
+
+    uint64_t *agg = reinterpret_cast<uint64_t *>(ws + p.ws_agg) + (size_t)gen * p.tokens;
+    uint64_t *agg_next = reinterpret_cast<uint64_t *>(ws + p.ws_agg) + (size_t)(1u - gen) * p.tokens;
+    const uint64_t *pref = reinterpret_cast<const uint64_t *>(ws + p.ws_pref) + (size_t)gen * p.tokens;
+    const uint32_t run = threadIdx.x;
+    const bool owns = run < p.runs;
+    const uint32_t left = owns ? p.pieces - 4 * run : 0;  // 16-byte pieces of the run inside the row
+
+    auto load_row = [&](uint32_t t, uint4 (&q)[4]) {
+        const uint4 *src = reinterpret_cast<const uint4 *>(in + (size_t)t * p.hidden) + 4 * run;
+#pragma unroll
+        for (uint32_t k = 0; k < 4; ++k) {
+            q[k] = make_uint4(0, 0, 0, 0);
+            if (k < left) q[k] = src[k];
+        }
+    };
+
+    uint32_t t = blockIdx.x - 1;
+    uint4 nxt[4];
+    if (t < p.tokens) load_row(t, nxt);
+
+    Pending pd;
+    uint32_t pd_t = 0, pd_width = 0, pd_cnt = 0, cur = 0;
+    bool have_pd = false;
+
+    for (; t < p.tokens; t += G) {
+        uint32_t w[16];
+#pragma unroll
+        for (int k = 0; k < 4; ++k) { w[4 * k] = nxt[k].x; w[4 * k + 1] = nxt[k].y; w[4 * k + 2] = nxt[k].z; w[4 * k + 3] = nxt[k].w; }
+        if (t + G < p.tokens) load_row(t + G, nxt);               // next row: in flight during this one
+        uint64_t pv = 0;
+        if (have_pd) pv = word_load(pref + pd_t);                 // asked for early, used at the end
+
+        uint32_t *slot = lds + cur * slot_dw;
+        uint32_t apk[16], omask = 0, amax_pk = 0;
+        if (owns) {
+            slot_write(slot, run, w);                             // raw bits: signs now, outlier values later
+            split_regs(w, p.thr_pk, apk, omask, amax_pk);
+        } else {
+#pragma unroll
+            for (int i = 0; i < 16; ++i) apk[i] = 0;
+        }
+        uint32_t m[8];
+        const Choice c = choose_width<DT>(p, apk, omask, amax_pk, scratch, m);
+        if (threadIdx.x == 0) {
+            const uint32_t words = row_bytes(p.hidden, c.width) >> 2;
+            word_store(agg + t, kWordValid | ((uint64_t)words << 32) | c.cnt);
+            agg_next[t] = 0;
+            blob[p.off_bits + t] = (uint8_t)c.width;
+            reinterpret_cast<float *>(blob + p.off_scale)[t] = scale_of(c.amax, c.width);
+        }
+
+        Pending np;
+        np.omask = omask;
+        np.loff = 0;
+#pragma unroll
+        for (int k = 0; k < 8; ++k) np.out[k] = 0;
+        if (owns) {
+            uint32_t wr[16];
+            slot_read(slot, run, wr);
+            switch (c.width) {
+                case 2: pack_into<2>(m, wr, np.out); break;
+                case 3: pack_into<3>(m, wr, np.out); break;
+                case 4: pack_into<4>(m, wr, np.out); break;
+                case 5: pack_into<5>(m, wr, np.out); break;
+                case 6: pack_into<6>(m, wr, np.out); break;
+                case 7: pack_into<7>(m, wr, np.out); break;
+                default: pack_into<8>(m, wr, np.out); break;
+            }
+        }
+        if (c.cnt > 0) np.loff = block_excl_scan((uint32_t)__builtin_popcount(omask), scratch + kScrScan);
+
+        if (have_pd) {
+            if (!(pv & kWordValid)) pv = wait_word(pref + pd_t, p.spin_limit);
+            store_pending(p, blob, ws, pd, pd_t, pd_width, pd_cnt, lds + (cur ^ 1u) * slot_dw, pv, run);
+        }
+        pd = np;
+        pd_t = t; pd_width = c.width; pd_cnt = c.cnt;
+        have_pd = true;
+        cur ^= 1u;
+        __syncthreads();  // the reduce and scan areas of LDS are reused by the next token
+    }
+    if (have_pd) {
+        const uint64_t pv = wait_word(pref + pd_t, p.spin_limit);
+        store_pending(p, blob, ws, pd, pd_t, pd_width, pd_cnt, lds + (cur ^ 1u) * slot_dw, pv, run);
     }
 }
 
@@ -359,7 +650,7 @@ k_unpack(const Params p, const uint8_t *__restrict__ blob, uint16_t *__restrict_
 static hipStream_t as_stream(void *s) { return reinterpret_cast<hipStream_t>(s); }
 
 int prepare_kernels() {
-    const int big = (int)((kMaxHidden / kRun) * kRunLdsDw * 4 + kScratchDw * 4);
+    const int big = (int)((kMaxHidden / kRun) * 2 * 16 * 4 + kScratchDw * 4);  // the fused kernel's two slots
     hipError_t e;
 #define TSQ_RAISE(k)                                                                                     \
     e = hipFuncSetAttribute(reinterpret_cast<const void *>(k), hipFuncAttributeMaxDynamicSharedMemorySize, big); \
@@ -368,6 +659,8 @@ int prepare_kernels() {
     TSQ_RAISE(k_row_stats<kBF16>)
     TSQ_RAISE(k_pack<kF16>)
     TSQ_RAISE(k_pack<kBF16>)
+    TSQ_RAISE(k_fused<kF16>)
+    TSQ_RAISE(k_fused<kBF16>)
     TSQ_RAISE(k_unpack<kF16>)
     TSQ_RAISE(k_unpack<kBF16>)
 #undef TSQ_RAISE
@@ -422,22 +715,48 @@ int launch_unpack(const Params &p, const Geometry &g, const void *d_blob, void *
 // ---------------------------------------------------------------- workspace reset
 
 __global__ void k_ws_reset(const Params p, uint8_t *__restrict__ ws) {
-    uint64_t *state = reinterpret_cast<uint64_t *>(ws + p.ws_state);
+    uint64_t *agg = reinterpret_cast<uint64_t *>(ws + p.ws_agg);
+    uint64_t *pref = reinterpret_cast<uint64_t *>(ws + p.ws_pref);
     uint32_t *ctrl = reinterpret_cast<uint32_t *>(ws + p.ws_ctrl);
     const uint64_t i = (uint64_t)blockIdx.x * blockDim.x + threadIdx.x;
-    if (i < p.tokens) state[i] = 0;
+    if (i < 2ull * p.tokens) { agg[i] = 0; pref[i] = 0; }
     if (i < 64) ctrl[i] = 0;
 }
 
 int launch_ws_reset(const Params &p, void *d_ws, void *stream) {
-    const uint32_t n = p.tokens > 64 ? p.tokens : 64;
-    hipLaunchKernelGGL(k_ws_reset, dim3((n + 255) / 256), dim3(256), 0, as_stream(stream), p,
+    const uint64_t n = 2ull * p.tokens > 64 ? 2ull * p.tokens : 64;
+    hipLaunchKernelGGL(k_ws_reset, dim3((uint32_t)((n + 255) / 256)), dim3(256), 0, as_stream(stream), p,
                        static_cast<uint8_t *>(d_ws));
     return (int)hipGetLastError();
 }
 
-int launch_fused(const Params &, const Geometry &, const void *, void *, void *, void *) {
-    return (int)hipErrorNotSupported;
+// Workgroups of k_fused that can be resident at once on the current device.
+static int fused_capacity(int dtype, uint32_t block, uint32_t lds_bytes) {
+    int dev = 0, cus = 0, per_cu = 0;
+    if (hipGetDevice(&dev) != hipSuccess) return -1;
+    if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess) return -1;
+    const void *fn = dtype == kF16 ? reinterpret_cast<const void *>(k_fused<kF16>)
+                                   : reinterpret_cast<const void *>(k_fused<kBF16>);
+    if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, fn, (int)block, lds_bytes) != hipSuccess) return -1;
+    return per_cu * cus;
+}
+
+int launch_fused(const Params &p, const Geometry &g, const void *d_in, void *d_blob, void *d_ws, void *stream) {
+    const int cap = fused_capacity((int)p.dtype, g.block, g.lds_fused_bytes);
+    if (cap < 2) return (int)hipErrorLaunchOutOfResources;
+    // one scan workgroup plus G compute workgroups, all resident together
+    uint32_t G = (uint32_t)cap - 1;
+    if (G > p.tokens) G = p.tokens;
+    const dim3 grid(G + 1), block(g.block);
+    if (p.dtype == kF16)
+        hipLaunchKernelGGL(k_fused<kF16>, grid, block, g.lds_fused_bytes, as_stream(stream), p,
+                           static_cast<const uint16_t *>(d_in), static_cast<uint8_t *>(d_blob),
+                           static_cast<uint8_t *>(d_ws), G);
+    else
+        hipLaunchKernelGGL(k_fused<kBF16>, grid, block, g.lds_fused_bytes, as_stream(stream), p,
+                           static_cast<const uint16_t *>(d_in), static_cast<uint8_t *>(d_blob),
+                           static_cast<uint8_t *>(d_ws), G);
+    return (int)hipGetLastError();
 }
 
 }  // namespace tsq

@@ -11,7 +11,8 @@ import os
 from typing import Dict, Iterable, Optional
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
-_LIB_PATH = os.path.join(_HERE, "libtsq.so")
+# TSQ_LIBRARY may name another build of the same library (e.g. one with different compile flags)
+_LIB_PATH = os.environ.get("TSQ_LIBRARY") or os.path.join(_HERE, "libtsq.so")
 
 TSQ_OK, TSQ_ERR_INVALID_ARG, TSQ_ERR_UNSUPPORTED, TSQ_ERR_CAPACITY = 0, 1, 2, 3
 TSQ_ERR_HIP, TSQ_ERR_FORMAT, TSQ_ERR_INTERNAL = 4, 5, 6

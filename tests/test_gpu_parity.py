@@ -16,7 +16,7 @@ pytestmark = pytest.mark.gpu
 F16, BF16 = 0, 1
 DT = {"f16": F16, "bf16": BF16}
 MODE = {"lsb": 0, "rel_rms": 1}
-PIPELINES = ["staged"]
+PIPELINES = ["fused", "staged"]
 
 
 @pytest.fixture(scope="module")
@@ -155,6 +155,29 @@ def test_many_absmax_values_exercise_the_divisions(tsq, oracle, pipeline, dtype)
     tau = 3.0e38 if dtype == "bf16" else 65504.0
     check_parity(tsq, oracle, x, dtype, tau, (2, 3, 4, 5, 6, 7, 8), 0.05, "rel_rms", pipeline, label="absmax sweep")
     check_parity(tsq, oracle, x, dtype, tau, (3, 5, 8), 0.25, "lsb", pipeline, label="absmax sweep lsb")
+
+
+@pytest.mark.parametrize("pipeline", PIPELINES)
+@pytest.mark.parametrize("dtype", ["f16", "bf16"])
+def test_exact_halves_round_to_even(tsq, oracle, pipeline, dtype):
+    # rows whose scaled magnitudes a*r are exactly k + 1/2: the code must be the even neighbour
+    for b in range(2, 9):
+        Q = 2 ** (b - 1) - 1
+        p = 3
+        k = np.arange(0, max(Q, 1))
+        vals = np.concatenate([(k + 0.5) * 2.0 ** -p, [Q * 2.0 ** -p]])          # absmax = Q*2^-p: r = 2^p
+        reps = -(-256 // vals.size)
+        row = np.tile(vals, reps)[:256]
+        row[-1] = Q * 2.0 ** -p
+        x = np.stack([row, -row, row[::-1].copy()])
+        bits = synth.to_f16_bits(x) if dtype == "f16" else synth.to_bf16_bits(x)
+        ref, _ = check_parity(tsq, oracle, bits, dtype, 1.0e4, (b,), 0.05, "rel_rms", pipeline,
+                              label="ties b=%d" % b)
+        m, neg = oracle.unpack_row(ref.payload[: 4 * ((256 * b + 31) // 32)], 256, b)
+        kk = np.tile(np.concatenate([k, [Q]]), reps)[:255]
+        tie = kk != Q
+        expect = np.where(kk % 2 == 0, kk, kk + 1)
+        assert np.array_equal(m[:255][tie], expect[tie])
 
 
 @pytest.mark.parametrize("pipeline", PIPELINES)
