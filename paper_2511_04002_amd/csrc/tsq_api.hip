@@ -143,8 +143,8 @@ tsq_status tsq_plan_create(const tsq_config *cfg, tsq_plan **out) {
 
     pl->g.block = 64u * ((p.runs + 63u) / 64u);
     pl->g.lds_bytes = (p.runs * kRunLdsDw + kScratchDw) * 4u;
-    pl->g.lds_fused_bytes = (2u * p.runs * 16u + kScratchDw) * 4u;
-    pl->pipeline = cfg->pipeline == TSQ_PIPE_STAGED ? TSQ_PIPE_STAGED : TSQ_PIPE_FUSED;
+    pl->g.lds_fused_bytes = (p.runs * 16u + kScratchDw) * 4u;
+    pl->pipeline = cfg->pipeline == TSQ_PIPE_FUSED ? TSQ_PIPE_FUSED : TSQ_PIPE_STAGED;
     *out = pl;
     return TSQ_OK;
 }

@@ -60,7 +60,7 @@ inline __host__ __device__ uint32_t width_at(const Params &p, uint32_t i) {
 struct Geometry {
     uint32_t block;         // threads per workgroup = 64 * ceil(runs / 64)
     uint32_t lds_bytes;     // dynamic LDS of the staged row kernels and of unpack
-    uint32_t lds_fused_bytes;  // dynamic LDS of the fused kernel (two lane-private row copies)
+    uint32_t lds_fused_bytes;  // dynamic LDS of the fused kernel (one lane-private row copy)
 };
 
 // launchers implemented in tsq_kernels.hip; each returns a hipError_t as int

@@ -15,7 +15,7 @@ namespace tsq {
 // LDS map of the row kernels (dynamic):  [ row: runs*kRunLdsDw dwords | scratch: kScratchDw dwords ]
 //   scratch: reduce area 0 [0,32) | reduce area 1 [32,64) | scan area [64,80) | broadcast area [80,88);
 //   the scan workgroup of the fused kernel uses [0,96) as two areas of 3 dwords per wave
-constexpr uint32_t kScrScan = 4 * kMaxWaves;
+constexpr uint32_t kScrScan = 4 * kMaxWaves, kScrBcast = 5 * kMaxWaves;
 
 __device__ __forceinline__ uint32_t row_bytes(uint32_t H, uint32_t b) { return 4u * ((H * b + 31u) >> 5); }
 
@@ -271,17 +271,16 @@ k_pack(const Params p, const uint16_t *__restrict__ in, uint8_t *__restrict__ bl
 
 // ---------------------------------------------------------------- k_fused: one pass over the input
 //
-// A persistent grid whose workgroups are all resident at once.  Workgroup 0 is the scan
-// workgroup; workgroup 1+w compresses tokens w, w+G, w+2G, ... (G = grid - 1).
+// Workgroup 1+t compresses token t; workgroup 0 (dispatched first) is the scan workgroup.
 //
-//   compute workgroup, token t:  load the row (each lane its run, straight into registers; the
-//       next row's loads are already in flight), split, choose the width, publish
-//       agg[t] = (payload words, outlier count), pack the codes into registers.  The token's
-//       output position comes back from the scan workgroup as pref[t]; it is picked up one
-//       iteration later, after the next token's arithmetic, so the round trip is hidden.
-//   scan workgroup:  for every batch of G tokens, waits for their agg words, scans them in
-//       token order on top of a running total, and publishes pref[t] = exclusive prefix.  It
-//       also writes row_ptr / pay_off and, at the end, the blob header.
+//   compute workgroup:  load the row (each lane its run, straight into registers), split, choose
+//       the width, publish agg[t] = (payload words, outlier count), pack the codes into
+//       registers, wait for pref[t], store.
+//   scan workgroup:  streams over the tokens in order.  Each round it reads a window of agg words
+//       starting at the first unpublished token, takes the longest run of valid ones, scans it on
+//       top of a running total and publishes pref[t] = exclusive prefix; it also writes row_ptr /
+//       pay_off and, at the end, the blob header.  pref[t] depends on tokens before t only, all of
+//       which were dispatched before t.
 //
 // agg and pref words: bit 62 = valid, bit 63 = error, bits 61..32 words, bits 31..0 count; both
 // sums stay below 2^30 / 2^32 because tokens*hidden < 2^32.  They are written and read with
@@ -323,84 +322,6 @@ __device__ __forceinline__ void write_header(const Params &p, uint8_t *blob, uin
     h.off_out_val = p.off_out_val; h.payload_capacity = p.payload_capacity;
     h.outlier_capacity = p.outlier_capacity;
     *reinterpret_cast<BlobHeader *>(blob) = h;
-}
-
-// The scan workgroup (all of its threads).
-__device__ __forceinline__ void scan_role(const Params &p, uint8_t *blob, uint8_t *ws, uint32_t G, uint32_t gen,
-                                          uint32_t *scr) {
-    const uint64_t *agg = reinterpret_cast<const uint64_t *>(ws + p.ws_agg) + (size_t)gen * p.tokens;
-    uint64_t *pref = reinterpret_cast<uint64_t *>(ws + p.ws_pref) + (size_t)gen * p.tokens;
-    uint64_t *pref_next = reinterpret_cast<uint64_t *>(ws + p.ws_pref) + (size_t)(1u - gen) * p.tokens;
-    uint32_t *ctrl = reinterpret_cast<uint32_t *>(ws + p.ws_ctrl);
-    uint64_t *row_ptr = reinterpret_cast<uint64_t *>(blob + p.off_row_ptr);
-    uint64_t *pay_off = reinterpret_cast<uint64_t *>(blob + p.off_pay_off);
-    const uint32_t tid = threadIdx.x, wv = tid >> 6, nw = blockDim.x >> 6;
-    const uint32_t per_round = blockDim.x * kScanItems;
-
-    uint64_t carry_c = 0, carry_w = 0;
-    uint32_t failed = 0, it = 0;
-    // batches of G tokens become ready together; inside a batch, rounds of per_round tokens
-    for (uint64_t batch = 0; batch < p.tokens; batch += G) {
-        const uint64_t batch_end = batch + G < p.tokens ? batch + G : p.tokens;
-        for (uint64_t base = batch; base < batch_end; base += per_round, ++it) {
-            uint64_t v[kScanItems];
-            uint32_t sc = 0, sw = 0, bad = 0;
-#pragma unroll
-            for (int k = 0; k < kScanItems; ++k) {
-                const uint64_t t = base + (uint64_t)tid * kScanItems + k;
-                v[k] = 0;
-                if (t < batch_end) v[k] = word_load(agg + t);
-            }
-#pragma unroll
-            for (int k = 0; k < kScanItems; ++k) {
-                const uint64_t t = base + (uint64_t)tid * kScanItems + k;
-                if (t < batch_end) {
-                    if (!(v[k] & kWordValid)) v[k] = wait_word(agg + t, p.spin_limit);
-                    if (!(v[k] & kWordValid)) { bad = 1; v[k] = 0; }
-                }
-                sc += (uint32_t)v[k];
-                sw += (uint32_t)(v[k] >> 32) & 0x3FFFFFFFu;
-            }
-            const uint32_t ic = wave_incl_scan_u32(sc), iw = wave_incl_scan_u32(sw);
-            const uint32_t anybad = wave_sum_u32(bad);
-            uint32_t *s3 = scr + (it & 1) * 3 * kMaxWaves;
-            if ((tid & 63) == 63) { s3[3 * wv] = ic; s3[3 * wv + 1] = iw; s3[3 * wv + 2] = anybad; }
-            __syncthreads();
-            uint32_t bc = 0, bw = 0, tc = 0, tw = 0;
-            for (uint32_t w = 0; w < nw; ++w) {
-                const uint32_t a = s3[3 * w], b = s3[3 * w + 1];
-                if (w < wv) { bc += a; bw += b; }
-                tc += a; tw += b;
-                failed |= s3[3 * w + 2];
-            }
-            uint64_t ec = carry_c + bc + ic - sc, ew = carry_w + bw + iw - sw;
-            const uint64_t flags = kWordValid | (failed ? kWordError : 0ull);
-#pragma unroll
-            for (int k = 0; k < kScanItems; ++k) {
-                const uint64_t t = base + (uint64_t)tid * kScanItems + k;
-                if (t < batch_end) {
-                    word_store(pref + t, flags | ((ew & 0x3FFFFFFFull) << 32) | (ec & 0xFFFFFFFFull));
-                    pref_next[t] = 0;
-                    row_ptr[t] = ec;
-                    pay_off[t] = ew << 2;
-                }
-                ec += (uint32_t)v[k];
-                ew += (uint32_t)(v[k] >> 32) & 0x3FFFFFFFu;
-            }
-            carry_c += tc;
-            carry_w += tw;
-        }
-    }
-    if (tid == 0) {
-        row_ptr[p.tokens] = carry_c;
-        pay_off[p.tokens] = carry_w << 2;
-        const uint32_t err = failed | __hip_atomic_load(ctrl + kCtlError, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        write_header(p, blob, carry_c, carry_w << 2, err ? 6u : (carry_c > p.outlier_capacity ? 3u : 0u));
-        // re-arm the workspace: every compute workgroup that owns a token has read the generation
-        // before publishing its first agg word, and all agg words have been consumed by now
-        __hip_atomic_store(ctrl + kCtlError, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        __hip_atomic_store(ctrl + kCtlGen, gen ^ 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-    }
 }
 
 template <int B>
@@ -461,106 +382,181 @@ __device__ __forceinline__ void store_pending(const Params &p, uint8_t *blob, ui
     }
 }
 
+__device__ __forceinline__ uint32_t wave_min_u32(uint32_t v) {
+    uint32_t n;
+    n = dpp<kDppQuadXor1>(v);   v = n < v ? n : v;
+    n = dpp<kDppQuadXor2>(v);   v = n < v ? n : v;
+    n = dpp<kDppHalfMirror>(v); v = n < v ? n : v;
+    n = dpp<kDppRowMirror>(v);  v = n < v ? n : v;
+    const uint32_t a = lane_value(v, 0), b = lane_value(v, 16), c = lane_value(v, 32), d = lane_value(v, 48);
+    const uint32_t ab = a < b ? a : b, cd = c < d ? c : d;
+    return ab < cd ? ab : cd;
+}
+
+__device__ __forceinline__ void scan_stream(const Params &p, uint8_t *blob, uint8_t *ws, uint32_t gen, uint32_t *scr) {
+    const uint64_t *agg = reinterpret_cast<const uint64_t *>(ws + p.ws_agg) + (size_t)gen * p.tokens;
+    uint64_t *pref = reinterpret_cast<uint64_t *>(ws + p.ws_pref) + (size_t)gen * p.tokens;
+    uint64_t *pref_next = reinterpret_cast<uint64_t *>(ws + p.ws_pref) + (size_t)(1u - gen) * p.tokens;
+    uint32_t *ctrl = reinterpret_cast<uint32_t *>(ws + p.ws_ctrl);
+    uint64_t *row_ptr = reinterpret_cast<uint64_t *>(blob + p.off_row_ptr);
+    uint64_t *pay_off = reinterpret_cast<uint64_t *>(blob + p.off_pay_off);
+    const uint32_t tid = threadIdx.x, wv = tid >> 6, nw = blockDim.x >> 6;
+    const uint32_t window = blockDim.x * kScanItems;
+
+    uint64_t carry_c = 0, carry_w = 0, start = 0;
+    uint32_t failed = 0, it = 0, idle = 0;
+    while (start < p.tokens) {
+        uint64_t v[kScanItems];
+        uint32_t first_missing = window;
+#pragma unroll
+        for (int k = 0; k < kScanItems; ++k) {
+            const uint64_t t = start + (uint64_t)tid * kScanItems + k;
+            v[k] = 0;
+            if (t < p.tokens) v[k] = word_load(agg + t);
+        }
+#pragma unroll
+        for (int k = kScanItems - 1; k >= 0; --k)
+            if (!(v[k] & kWordValid)) first_missing = tid * kScanItems + k;
+        // length of the run of valid words at the front of the window
+        uint32_t *s4 = scr + (it & 1) * 4 * kMaxWaves;
+        ++it;
+        uint32_t n = wave_min_u32(first_missing);
+        if (nw > 1) {
+            if ((tid & 63) == 0) s4[4 * wv + 3] = n;
+            __syncthreads();
+            for (uint32_t w = 0; w < nw; ++w) { const uint32_t x = s4[4 * w + 3]; n = x < n ? x : n; }
+        }
+        const uint64_t remaining = p.tokens - start;
+        if (n > remaining) n = (uint32_t)remaining;
+        if (n == 0) {
+            if (++idle > p.spin_limit) { failed = 1; n = remaining < window ? (uint32_t)remaining : window; }
+            else { __builtin_amdgcn_s_sleep(1); continue; }
+        }
+        idle = 0;
+        uint32_t sc = 0, sw = 0;
+#pragma unroll
+        for (int k = 0; k < kScanItems; ++k) {
+            if (tid * kScanItems + k >= n || !(v[k] & kWordValid)) v[k] = 0;
+            sc += (uint32_t)v[k];
+            sw += (uint32_t)(v[k] >> 32) & 0x3FFFFFFFu;
+        }
+        const uint32_t ic = wave_incl_scan_u32(sc), iw = wave_incl_scan_u32(sw);
+        uint32_t bc = 0, bw = 0, tc = ic, tw = iw;
+        if (nw > 1) {
+            uint32_t *s4b = scr + (it & 1) * 4 * kMaxWaves;
+            ++it;
+            if ((tid & 63) == 63) { s4b[4 * wv] = ic; s4b[4 * wv + 1] = iw; }
+            __syncthreads();
+            tc = 0; tw = 0;
+            for (uint32_t w = 0; w < nw; ++w) {
+                const uint32_t a = s4b[4 * w], b = s4b[4 * w + 1];
+                if (w < wv) { bc += a; bw += b; }
+                tc += a; tw += b;
+            }
+        } else {
+            tc = lane_value(ic, 63); tw = lane_value(iw, 63);
+        }
+        uint64_t ec = carry_c + bc + ic - sc, ew = carry_w + bw + iw - sw;
+        const uint64_t flags = kWordValid | (failed ? kWordError : 0ull);
+#pragma unroll
+        for (int k = 0; k < kScanItems; ++k) {
+            if (tid * kScanItems + k < n) {
+                const uint64_t t = start + (uint64_t)tid * kScanItems + k;
+                word_store(pref + t, flags | ((ew & 0x3FFFFFFFull) << 32) | (ec & 0xFFFFFFFFull));
+                pref_next[t] = 0;
+                row_ptr[t] = ec;
+                pay_off[t] = ew << 2;
+            }
+            ec += (uint32_t)v[k];
+            ew += (uint32_t)(v[k] >> 32) & 0x3FFFFFFFu;
+        }
+        carry_c += tc;
+        carry_w += tw;
+        start += n;
+    }
+    if (tid == 0) {
+        row_ptr[p.tokens] = carry_c;
+        pay_off[p.tokens] = carry_w << 2;
+        const uint32_t err = failed | __hip_atomic_load(ctrl + kCtlError, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        write_header(p, blob, carry_c, carry_w << 2, err ? 6u : (carry_c > p.outlier_capacity ? 3u : 0u));
+        __hip_atomic_store(ctrl + kCtlError, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        __hip_atomic_store(ctrl + kCtlGen, gen ^ 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    }
+}
+
 template <int DT>
 __global__ void __launch_bounds__(1024)
-k_fused(const Params p, const uint16_t *__restrict__ in, uint8_t *__restrict__ blob, uint8_t *__restrict__ ws,
-        const uint32_t G) {
+k_fused(const Params p, const uint16_t *__restrict__ in, uint8_t *__restrict__ blob, uint8_t *__restrict__ ws) {
     extern __shared__ __align__(16) uint32_t lds[];
-    const uint32_t slot_dw = p.runs * 16;
-    uint32_t *scratch = lds + 2 * slot_dw;
+    uint32_t *slot = lds;
+    uint32_t *scratch = lds + p.runs * 16;
     uint32_t *ctrl = reinterpret_cast<uint32_t *>(ws + p.ws_ctrl);
-    const uint32_t gen = ctrl[kCtlGen] & 1u;  // written by the previous call or the reset kernel
-
+    const uint32_t gen = ctrl[kCtlGen] & 1u;
     if (blockIdx.x == 0) {
-        scan_role(p, blob, ws, G, gen, scratch);
+        scan_stream(p, blob, ws, gen, scratch);
         return;
     }
-
+    const uint32_t t = blockIdx.x - 1;
     uint64_t *agg = reinterpret_cast<uint64_t *>(ws + p.ws_agg) + (size_t)gen * p.tokens;
     uint64_t *agg_next = reinterpret_cast<uint64_t *>(ws + p.ws_agg) + (size_t)(1u - gen) * p.tokens;
     const uint64_t *pref = reinterpret_cast<const uint64_t *>(ws + p.ws_pref) + (size_t)gen * p.tokens;
     const uint32_t run = threadIdx.x;
     const bool owns = run < p.runs;
-    const uint32_t left = owns ? p.pieces - 4 * run : 0;  // 16-byte pieces of the run inside the row
+    const uint32_t left = owns ? p.pieces - 4 * run : 0;
 
-    auto load_row = [&](uint32_t t, uint4 (&q)[4]) {
+    uint32_t apk[16], omask = 0, amax_pk = 0;
+    if (owns) {
+        uint32_t w[16];
         const uint4 *src = reinterpret_cast<const uint4 *>(in + (size_t)t * p.hidden) + 4 * run;
 #pragma unroll
         for (uint32_t k = 0; k < 4; ++k) {
-            q[k] = make_uint4(0, 0, 0, 0);
-            if (k < left) q[k] = src[k];
+            uint4 q = make_uint4(0, 0, 0, 0);
+            if (k < left) q = src[k];
+            w[4 * k] = q.x; w[4 * k + 1] = q.y; w[4 * k + 2] = q.z; w[4 * k + 3] = q.w;
         }
-    };
-
-    uint32_t t = blockIdx.x - 1;
-    uint4 nxt[4];
-    if (t < p.tokens) load_row(t, nxt);
-
+        slot_write(slot, run, w);
+        split_regs(w, p.thr_pk, apk, omask, amax_pk);
+    } else {
+#pragma unroll
+        for (int i = 0; i < 16; ++i) apk[i] = 0;
+    }
+    uint32_t m[8];
+    const Choice c = choose_width<DT>(p, apk, omask, amax_pk, scratch, m);
+    if (threadIdx.x == 0) {
+        const uint32_t words = row_bytes(p.hidden, c.width) >> 2;
+        word_store(agg + t, kWordValid | ((uint64_t)words << 32) | c.cnt);
+        agg_next[t] = 0;
+        blob[p.off_bits + t] = (uint8_t)c.width;
+        reinterpret_cast<float *>(blob + p.off_scale)[t] = scale_of(c.amax, c.width);
+    }
     Pending pd;
-    uint32_t pd_t = 0, pd_width = 0, pd_cnt = 0, cur = 0;
-    bool have_pd = false;
-
-    for (; t < p.tokens; t += G) {
-        uint32_t w[16];
+    pd.omask = omask;
+    pd.loff = 0;
 #pragma unroll
-        for (int k = 0; k < 4; ++k) { w[4 * k] = nxt[k].x; w[4 * k + 1] = nxt[k].y; w[4 * k + 2] = nxt[k].z; w[4 * k + 3] = nxt[k].w; }
-        if (t + G < p.tokens) load_row(t + G, nxt);               // next row: in flight during this one
-        uint64_t pv = 0;
-        if (have_pd) pv = word_load(pref + pd_t);                 // asked for early, used at the end
-
-        uint32_t *slot = lds + cur * slot_dw;
-        uint32_t apk[16], omask = 0, amax_pk = 0;
-        if (owns) {
-            slot_write(slot, run, w);                             // raw bits: signs now, outlier values later
-            split_regs(w, p.thr_pk, apk, omask, amax_pk);
-        } else {
-#pragma unroll
-            for (int i = 0; i < 16; ++i) apk[i] = 0;
+    for (int k = 0; k < 8; ++k) pd.out[k] = 0;
+    if (owns) {
+        uint32_t wr[16];
+        slot_read(slot, run, wr);
+        switch (c.width) {
+            case 2: pack_into<2>(m, wr, pd.out); break;
+            case 3: pack_into<3>(m, wr, pd.out); break;
+            case 4: pack_into<4>(m, wr, pd.out); break;
+            case 5: pack_into<5>(m, wr, pd.out); break;
+            case 6: pack_into<6>(m, wr, pd.out); break;
+            case 7: pack_into<7>(m, wr, pd.out); break;
+            default: pack_into<8>(m, wr, pd.out); break;
         }
-        uint32_t m[8];
-        const Choice c = choose_width<DT>(p, apk, omask, amax_pk, scratch, m);
-        if (threadIdx.x == 0) {
-            const uint32_t words = row_bytes(p.hidden, c.width) >> 2;
-            word_store(agg + t, kWordValid | ((uint64_t)words << 32) | c.cnt);
-            agg_next[t] = 0;
-            blob[p.off_bits + t] = (uint8_t)c.width;
-            reinterpret_cast<float *>(blob + p.off_scale)[t] = scale_of(c.amax, c.width);
-        }
-
-        Pending np;
-        np.omask = omask;
-        np.loff = 0;
-#pragma unroll
-        for (int k = 0; k < 8; ++k) np.out[k] = 0;
-        if (owns) {
-            uint32_t wr[16];
-            slot_read(slot, run, wr);
-            switch (c.width) {
-                case 2: pack_into<2>(m, wr, np.out); break;
-                case 3: pack_into<3>(m, wr, np.out); break;
-                case 4: pack_into<4>(m, wr, np.out); break;
-                case 5: pack_into<5>(m, wr, np.out); break;
-                case 6: pack_into<6>(m, wr, np.out); break;
-                case 7: pack_into<7>(m, wr, np.out); break;
-                default: pack_into<8>(m, wr, np.out); break;
-            }
-        }
-        if (c.cnt > 0) np.loff = block_excl_scan((uint32_t)__builtin_popcount(omask), scratch + kScrScan);
-
-        if (have_pd) {
-            if (!(pv & kWordValid)) pv = wait_word(pref + pd_t, p.spin_limit);
-            store_pending(p, blob, ws, pd, pd_t, pd_width, pd_cnt, lds + (cur ^ 1u) * slot_dw, pv, run);
-        }
-        pd = np;
-        pd_t = t; pd_width = c.width; pd_cnt = c.cnt;
-        have_pd = true;
-        cur ^= 1u;
-        __syncthreads();  // the reduce and scan areas of LDS are reused by the next token
     }
-    if (have_pd) {
-        const uint64_t pv = wait_word(pref + pd_t, p.spin_limit);
-        store_pending(p, blob, ws, pd, pd_t, pd_width, pd_cnt, lds + (cur ^ 1u) * slot_dw, pv, run);
+    if (c.cnt > 0) pd.loff = block_excl_scan((uint32_t)__builtin_popcount(omask), scratch + kScrScan);
+    // wave 0 waits for the token's position and hands it to the others
+    uint32_t *bc = scratch + kScrBcast;
+    if (threadIdx.x < 64) {
+        const uint64_t pv = wait_word(pref + t, p.spin_limit);
+        if (threadIdx.x == 0) { bc[0] = (uint32_t)pv; bc[1] = (uint32_t)(pv >> 32); }
     }
+    __syncthreads();
+    const uint64_t pv = ((uint64_t)bc[1] << 32) | bc[0];
+    store_pending(p, blob, ws, pd, t, c.width, c.cnt, slot, pv, run);
 }
 
 // ---------------------------------------------------------------- k_unpack
@@ -650,7 +646,7 @@ k_unpack(const Params p, const uint8_t *__restrict__ blob, uint16_t *__restrict_
 static hipStream_t as_stream(void *s) { return reinterpret_cast<hipStream_t>(s); }
 
 int prepare_kernels() {
-    const int big = (int)((kMaxHidden / kRun) * 2 * 16 * 4 + kScratchDw * 4);  // the fused kernel's two slots
+    const int big = (int)((kMaxHidden / kRun) * kRunLdsDw * 4 + kScratchDw * 4);
     hipError_t e;
 #define TSQ_RAISE(k)                                                                                     \
     e = hipFuncSetAttribute(reinterpret_cast<const void *>(k), hipFuncAttributeMaxDynamicSharedMemorySize, big); \
@@ -730,32 +726,16 @@ int launch_ws_reset(const Params &p, void *d_ws, void *stream) {
     return (int)hipGetLastError();
 }
 
-// Workgroups of k_fused that can be resident at once on the current device.
-static int fused_capacity(int dtype, uint32_t block, uint32_t lds_bytes) {
-    int dev = 0, cus = 0, per_cu = 0;
-    if (hipGetDevice(&dev) != hipSuccess) return -1;
-    if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess) return -1;
-    const void *fn = dtype == kF16 ? reinterpret_cast<const void *>(k_fused<kF16>)
-                                   : reinterpret_cast<const void *>(k_fused<kBF16>);
-    if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, fn, (int)block, lds_bytes) != hipSuccess) return -1;
-    return per_cu * cus;
-}
-
 int launch_fused(const Params &p, const Geometry &g, const void *d_in, void *d_blob, void *d_ws, void *stream) {
-    const int cap = fused_capacity((int)p.dtype, g.block, g.lds_fused_bytes);
-    if (cap < 2) return (int)hipErrorLaunchOutOfResources;
-    // one scan workgroup plus G compute workgroups, all resident together
-    uint32_t G = (uint32_t)cap - 1;
-    if (G > p.tokens) G = p.tokens;
-    const dim3 grid(G + 1), block(g.block);
+    const dim3 grid(p.tokens + 1), block(g.block);
     if (p.dtype == kF16)
         hipLaunchKernelGGL(k_fused<kF16>, grid, block, g.lds_fused_bytes, as_stream(stream), p,
                            static_cast<const uint16_t *>(d_in), static_cast<uint8_t *>(d_blob),
-                           static_cast<uint8_t *>(d_ws), G);
+                           static_cast<uint8_t *>(d_ws));
     else
         hipLaunchKernelGGL(k_fused<kBF16>, grid, block, g.lds_fused_bytes, as_stream(stream), p,
                            static_cast<const uint16_t *>(d_in), static_cast<uint8_t *>(d_blob),
-                           static_cast<uint8_t *>(d_ws), G);
+                           static_cast<uint8_t *>(d_ws));
     return (int)hipGetLastError();
 }
 
