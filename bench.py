@@ -21,6 +21,14 @@ if ROOT not in sys.path:
 
 HBM_PEAK_GBS = 8000.0     # MI355X HBM3E, published peak
 
+# HBM bytes per launch from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of this command, scaled by
+# what the same counters read for a plain 128 MiB copy (profiles/C4_staged_hbm_traffic.txt);
+# keyed by (workload, pipeline, eps) -> kernel -> bytes.  None where no such run was made.
+TRAFFIC = {
+    ("C4", "staged", 0.05): {"k_row_stats": 134.3e6 + 0.6e6, "k_pack": 136.6e6 + 62.7e6,
+                             "k_unpack": 67.1e6 + 134.2e6, "k_scan": 0.2e6},
+}
+
 
 def parse():
     ap = argparse.ArgumentParser()
@@ -83,7 +91,8 @@ def main():
     torch.cuda.set_device(0)
     w, x = make_input(args)
     T, H = x.shape
-    plan = tsq.Plan(T, H, w.dtype, w.tau, w.bit_set, args.eps, mode="rel_rms", pipeline=args.pipeline,
+    pipe = "staged" if args.pipeline == "auto" else args.pipeline    # what "auto" resolves to
+    plan = tsq.Plan(T, H, w.dtype, w.tau, w.bit_set, args.eps, mode="rel_rms", pipeline=pipe,
                     max_outliers=max(1, (T * H) // 8))
     x0 = torch.from_numpy(x.view(np.int16)).cuda()
     nbuf = max(1, args.nbuf)
@@ -128,11 +137,30 @@ def main():
     side = info.payload_bytes + 4 * info.nnz + 21 * T      # payload + CSR + per-token metadata
     alg_c = 2 * n + side                                   # compress: read input, write the blob
     alg_d = side + 2 * n                                   # decompress: read the blob, write output
-    kern = {"compress": {"ms": ms_c, "alg_bytes": alg_c, "GBps": alg_c / ms_c / 1e6},
-            "decompress": {"ms": ms_d, "alg_bytes": alg_d, "GBps": alg_d / ms_d / 1e6}}
-    dom = "compress" if ms_c >= ms_d else "decompress"
+
+    # per-kernel durations of the same steps, HIP events around every launch inside the library
+    # (tsq_compress_timed) and around the one decompress kernel
+    names = ["k_fused"] if pipe == "fused" else ["k_row_stats", "k_scan", "k_pack"]
+    acc = [0.0] * len(names)
+    for i in range(args.steps):
+        k = (args.warmup + i) % nbuf
+        ms = tsq.tsq_compress_timed(plan.handle, xs[k].data_ptr(), blobs[k].data_ptr(), ws.data_ptr(),
+                                    plan._stream())
+        for j in range(len(names)):
+            acc[j] += ms[j]
+        plan.decompress(blobs[k], outs[k])
+    torch.cuda.synchronize()
+    # algorithmic bytes of each kernel: what it must read and write once
+    kalg = {"k_fused": alg_c, "k_row_stats": 2 * n + 9 * T, "k_scan": 29 * T, "k_pack": alg_c,
+            "k_unpack": alg_d}
+    kern = {nm: {"ms": acc[j] / args.steps, "alg_bytes": kalg[nm]} for j, nm in enumerate(names)}
+    kern["k_unpack"] = {"ms": ms_d, "alg_bytes": alg_d}
+    for v in kern.values():
+        v["GBps"] = v["alg_bytes"] / v["ms"] / 1e6
+    dom = max(kern, key=lambda nm: kern[nm]["ms"])
     achieved = kern[dom]["GBps"]
     pair_gbps = (alg_c + alg_d) / (ms_c + ms_d) / 1e6
+    traffic = TRAFFIC.get((w.name, pipe, args.eps), {}).get(dom)
 
     res = {
         "metric": "compress+decompress GB/s of split-point activations",
@@ -145,11 +173,12 @@ def main():
         "data": "synthetic",
         "config": {"workload": "%s %dx%d %s" % (w.name, T, H, w.dtype), "tau": w.tau,
                    "bit_set": list(w.bit_set), "budget": "%.3g x row RMS" % args.eps,
-                   "pipeline": args.pipeline, "buffer_sets": nbuf, "mean_width": round(bbar, 3),
+                   "pipeline": pipe, "buffer_sets": nbuf, "mean_width": round(bbar, 3),
                    "outlier_fraction": round(rho, 6), "width_hist": list(info.width_hist),
                    "compression_ratio": round(2.0 * n / info.compressed_bytes, 3)},
         "roofline": {"bound": "hbm", "kernel": dom, "achieved": achieved, "peak": HBM_PEAK_GBS,
-                     "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS, "traffic": None,
+                     "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS, "traffic": traffic,
+                     "compress_ms": ms_c, "decompress_ms": ms_d,
                      "pair_achieved": pair_gbps, "pair_frac": pair_gbps / HBM_PEAK_GBS,
                      "kernels": kern},
         "host_wall_ms_per_step": wall * 1e3 / args.steps,

@@ -135,6 +135,16 @@ tsq_status tsq_compress(const tsq_plan *plan, const void *d_in, void *d_blob, vo
                         void *stream);
 
 /*
+ * Measurement aid: tsq_compress with every kernel of the call bracketed by HIP
+ * events on `stream`.  SYNCHRONIZES `stream`.  ms_out (host, 4 floats) receives
+ * the kernels' durations in milliseconds: staged pipeline {row statistics, scan,
+ * pack, 0}; fused pipeline {fused kernel, 0, 0, 0}.  Same arguments and result
+ * as tsq_compress otherwise.
+ */
+tsq_status tsq_compress_timed(const tsq_plan *plan, const void *d_in, void *d_blob, void *d_ws,
+                              void *stream, float *ms_out);
+
+/*
  * Restore (Eq. (dequnt)): d_out receives tokens*hidden 16-bit values of the
  * plan's dtype.  Inliers become sign * (code * s_t) rounded to nearest even,
  * outliers their stored bits.  If the blob's header does not match the plan or

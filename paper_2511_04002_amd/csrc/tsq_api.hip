@@ -182,6 +182,39 @@ tsq_status tsq_compress(const tsq_plan *plan, const void *d_in, void *d_blob, vo
     return hip_rc(e);
 }
 
+tsq_status tsq_compress_timed(const tsq_plan *plan, const void *d_in, void *d_blob, void *d_ws, void *stream,
+                              float *ms_out) {
+    if (!plan || !d_in || !d_blob || !d_ws || !ms_out) return TSQ_ERR_INVALID_ARG;
+    if (((uintptr_t)d_in & 15u) || ((uintptr_t)d_blob & 255u) || ((uintptr_t)d_ws & 255u)) return TSQ_ERR_INVALID_ARG;
+    tsq_status st = ensure_prepared();
+    if (st != TSQ_OK) return st;
+    hipStream_t s = reinterpret_cast<hipStream_t>(stream);
+    hipEvent_t ev[4];
+    for (auto &e : ev)
+        if (hipEventCreate(&e) != hipSuccess) return TSQ_ERR_HIP;
+    int rc = 0, n = 0;
+    (void)hipEventRecord(ev[0], s);
+    if (plan->pipeline == TSQ_PIPE_FUSED) {
+        rc = launch_fused(plan->p, plan->g, d_in, d_blob, d_ws, stream);
+        (void)hipEventRecord(ev[1], s);
+        n = 1;
+    } else {
+        rc = launch_row_stats(plan->p, plan->g, d_in, d_blob, d_ws, stream);
+        (void)hipEventRecord(ev[1], s);
+        if (rc == 0) rc = launch_scan(plan->p, d_blob, d_ws, stream);
+        (void)hipEventRecord(ev[2], s);
+        if (rc == 0) rc = launch_pack(plan->p, plan->g, d_in, d_blob, d_ws, stream);
+        (void)hipEventRecord(ev[3], s);
+        n = 3;
+    }
+    if (hipEventSynchronize(ev[n]) != hipSuccess) rc = rc ? rc : 1;
+    for (int i = 0; i < 4; ++i) ms_out[i] = 0.0f;
+    for (int i = 0; i < n && rc == 0; ++i)
+        if (hipEventElapsedTime(&ms_out[i], ev[i], ev[i + 1]) != hipSuccess) rc = 1;
+    for (auto &e : ev) (void)hipEventDestroy(e);
+    return hip_rc(rc);
+}
+
 tsq_status tsq_decompress(const tsq_plan *plan, const void *d_blob, void *d_out, void *stream) {
     if (!plan || !d_blob || !d_out) return TSQ_ERR_INVALID_ARG;
     if (((uintptr_t)d_out & 15u) || ((uintptr_t)d_blob & 255u)) return TSQ_ERR_INVALID_ARG;

@@ -21,7 +21,8 @@ TSQ_BUDGET_LSB, TSQ_BUDGET_REL_RMS = 0, 1
 TSQ_PIPE_AUTO, TSQ_PIPE_STAGED, TSQ_PIPE_FUSED = 0, 1, 2
 
 EXPORTS = ("tsq_plan_create", "tsq_plan_destroy", "tsq_plan_layout", "tsq_plan_blob_bytes",
-           "tsq_plan_workspace_bytes", "tsq_workspace_reset", "tsq_compress", "tsq_decompress",
+           "tsq_plan_workspace_bytes", "tsq_workspace_reset", "tsq_compress", "tsq_compress_timed",
+           "tsq_decompress",
            "tsq_blob_info", "tsq_status_string")
 
 
@@ -76,6 +77,8 @@ def lib():
         L.tsq_workspace_reset.argtypes = [vp, vp, vp]
         L.tsq_compress.restype = u
         L.tsq_compress.argtypes = [vp, vp, vp, vp, vp]
+        L.tsq_compress_timed.restype = u
+        L.tsq_compress_timed.argtypes = [vp, vp, vp, vp, vp, C.POINTER(C.c_float)]
         L.tsq_decompress.restype = u
         L.tsq_decompress.argtypes = [vp, vp, vp, vp]
         L.tsq_blob_info.restype = u
@@ -131,6 +134,15 @@ def tsq_compress(plan: int, d_in: int, d_blob: int, d_ws: int, stream: int = 0) 
     st = lib().tsq_compress(plan, d_in, d_blob, d_ws, stream)
     if st != TSQ_OK:
         raise TsqError(st, "tsq_compress")
+
+
+def tsq_compress_timed(plan: int, d_in: int, d_blob: int, d_ws: int, stream: int = 0):
+    """-> per-kernel milliseconds [4] (synchronizes the stream)."""
+    ms = (C.c_float * 4)()
+    st = lib().tsq_compress_timed(plan, d_in, d_blob, d_ws, stream, ms)
+    if st != TSQ_OK:
+        raise TsqError(st, "tsq_compress_timed")
+    return list(ms)
 
 
 def tsq_decompress(plan: int, d_blob: int, d_out: int, stream: int = 0) -> None:
