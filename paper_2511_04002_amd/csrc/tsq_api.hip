@@ -131,6 +131,7 @@ tsq_status tsq_plan_create(const tsq_config *cfg, tsq_plan **out) {
 
     uint64_t w = 0;
     p.ws_cnt = w;    w = align_up(w + 4ull * T, 256);
+    p.ws_amax = w;   w = align_up(w + 4ull * T, 256);
     p.ws_agg = w;    w = align_up(w + 16ull * T, 256);
     p.ws_pref = w;   w = align_up(w + 16ull * T, 256);
     p.ws_ctrl = w;   w = align_up(w + 256, 256);

@@ -78,21 +78,35 @@ __device__ __forceinline__ uint32_t wave_incl_scan_u32(uint32_t v) {
     return v + (row > 0 ? r0 : 0u) + (row > 1 ? r1 : 0u) + (row > 2 ? r2 : 0u);
 }
 
+// Cross-wave step of the block reductions.  A reduce area is 2*kMaxWaves dwords of LDS: slot w
+// holds wave w's first value, slot kMaxWaves + w its second.  Slots of waves that do not exist
+// must hold 0 (clear_reduce_areas), so that whole quads of slots can be read with one 16-byte
+// load each; 0 is the identity of both max and sum on unsigned values.
+__device__ __forceinline__ void clear_reduce_areas(uint32_t *scratch) {
+    if (threadIdx.x < 4 * kMaxWaves) scratch[threadIdx.x] = 0;
+}
+__device__ __forceinline__ uint32_t max4(const uint4 v, uint32_t m) {
+    const uint32_t a = v.x > v.y ? v.x : v.y, b = v.z > v.w ? v.z : v.w;
+    const uint32_t c = a > b ? a : b;
+    return c > m ? c : m;
+}
+
 // Every thread gets max over the block of mx and sum over the block of sm.
-// red: 2*kMaxWaves dwords of LDS; consecutive calls must alternate between two such areas.
+// red: a reduce area; consecutive calls must alternate between two such areas.
 __device__ __forceinline__ void block_max_sum(uint32_t &mx, uint32_t &sm, uint32_t *red) {
     mx = wave_max_u32(mx);
     sm = wave_sum_u32(sm);
     const uint32_t nw = blockDim.x >> 6;
     if (nw == 1) return;
     const uint32_t lane = threadIdx.x & 63, wv = threadIdx.x >> 6;
-    if (lane == 0) { red[2 * wv] = mx; red[2 * wv + 1] = sm; }
+    if (lane == 0) { red[wv] = mx; red[kMaxWaves + wv] = sm; }
     __syncthreads();
     uint32_t M = 0, S = 0;
-    for (uint32_t w = 0; w < nw; ++w) {
-        uint32_t a = red[2 * w], b = red[2 * w + 1];
-        M = a > M ? a : M;
-        S += b;
+    for (uint32_t q = 0; 4 * q < nw; ++q) {
+        const uint4 a = reinterpret_cast<const uint4 *>(red)[q];
+        const uint4 b = reinterpret_cast<const uint4 *>(red + kMaxWaves)[q];
+        M = max4(a, M);
+        S += (b.x + b.y) + (b.z + b.w);
     }
     mx = M;
     sm = S;
@@ -103,12 +117,31 @@ __device__ __forceinline__ void block_sum2(uint32_t &x, uint32_t &y, uint32_t *r
     const uint32_t nw = blockDim.x >> 6;
     if (nw == 1) return;
     const uint32_t lane = threadIdx.x & 63, wv = threadIdx.x >> 6;
-    if (lane == 0) { red[2 * wv] = x; red[2 * wv + 1] = y; }
+    if (lane == 0) { red[wv] = x; red[kMaxWaves + wv] = y; }
     __syncthreads();
     uint32_t X = 0, Y = 0;
-    for (uint32_t w = 0; w < nw; ++w) { X += red[2 * w]; Y += red[2 * w + 1]; }
+    for (uint32_t q = 0; 4 * q < nw; ++q) {
+        const uint4 a = reinterpret_cast<const uint4 *>(red)[q];
+        const uint4 b = reinterpret_cast<const uint4 *>(red + kMaxWaves)[q];
+        X += (a.x + a.y) + (a.z + a.w);
+        Y += (b.x + b.y) + (b.z + b.w);
+    }
     x = X;
     y = Y;
+}
+__device__ __forceinline__ void block_sum1(uint32_t &x, uint32_t *red) {
+    x = wave_sum_u32(x);
+    const uint32_t nw = blockDim.x >> 6;
+    if (nw == 1) return;
+    const uint32_t lane = threadIdx.x & 63, wv = threadIdx.x >> 6;
+    if (lane == 0) red[wv] = x;
+    __syncthreads();
+    uint32_t X = 0;
+    for (uint32_t q = 0; 4 * q < nw; ++q) {
+        const uint4 a = reinterpret_cast<const uint4 *>(red)[q];
+        X += (a.x + a.y) + (a.z + a.w);
+    }
+    x = X;
 }
 
 // Exclusive prefix sum of v over the threads of the block, in thread order.
@@ -151,20 +184,24 @@ __device__ __forceinline__ void stage_row(const uint4 *__restrict__ src, uint32_
 // thr being the smallest pattern whose value is >= tau (computed on the host).
 //   apk   : |x| patterns of the inliers, 0 at outlier slots (|T_below|)
 //   omask : outlier flags; bit i = element 2i, bit 16+i = element 2i+1
-//   amax  : running maximum of the inlier patterns, both halves
+//   amax  : running maximum of the inlier patterns, both halves (only if WANT_MAX)
+// Six instructions per pair of elements: and, packed subtract, packed arithmetic shift
+// (the borrow of pattern - thr marks the inliers), and, packed max, bit-field insert.
+template <bool WANT_MAX>
 __device__ __forceinline__ void split_regs(const uint32_t (&w)[16], uint32_t thr_pk, uint32_t (&apk)[16],
                                            uint32_t &omask, uint32_t &amax_pk) {
-    uint32_t om = 0, mx = amax_pk;
+    uint32_t im = 0, mx = amax_pk;
 #pragma unroll
     for (int i = 0; i < 16; ++i) {
         const uint32_t absw = w[i] & 0x7FFF7FFFu;
         const uint32_t inl = pk_ashr15_i16(pk_sub_u16(absw, thr_pk));  // 0xFFFF where |x| < tau
         const uint32_t a = absw & inl;
         apk[i] = a;
-        mx = pk_max_u16(mx, a);
-        om |= (~inl & 0x00010001u) << i;
+        if (WANT_MAX) mx = pk_max_u16(mx, a);
+        const uint32_t sel = 0x00010001u << i;
+        im = (inl & sel) | (im & ~sel);                                // v_bfi_b32
     }
-    omask = om;
+    omask = ~im;
     amax_pk = mx;
 }
 
@@ -176,11 +213,12 @@ __device__ __forceinline__ void load_run_padded(const uint32_t *lrun, uint32_t (
         w[4 * k] = q.x; w[4 * k + 1] = q.y; w[4 * k + 2] = q.z; w[4 * k + 3] = q.w;
     }
 }
+template <bool WANT_MAX>
 __device__ __forceinline__ void split_run(const uint32_t *lrun, uint32_t thr_pk, uint32_t (&apk)[16],
                                           uint32_t &omask, uint32_t &amax_pk) {
     uint32_t w[16];
     load_run_padded(lrun, w);
-    split_regs(w, thr_pk, apk, omask, amax_pk);
+    split_regs<WANT_MAX>(w, thr_pk, apk, omask, amax_pk);
 }
 
 // Lane-private copy of a run in LDS, 16 dwords per lane, no padding: the four 16-byte chunks
@@ -225,20 +263,30 @@ __device__ __forceinline__ float widen16(uint32_t pattern) {
 
 // ---------------------------------------------------------------- Eq. (Proposed) on one run
 
+// The inlier magnitudes of a run as binary32 (exact for both 16-bit formats); widened once and
+// kept in registers, so that every quantization pass costs one multiply and one convert per element.
+template <int DT>
+__device__ __forceinline__ void widen_run(const uint32_t (&apk)[16], float (&af)[32]) {
+#pragma unroll
+    for (int i = 0; i < 16; ++i) {
+        af[2 * i] = widen_lo<DT>(apk[i]);
+        af[2 * i + 1] = widen_hi<DT>(apk[i]);
+    }
+}
+
 // m = rint(a * r), one byte per element, element 4g+k in byte k of m[g].  The rounding is done by
 // v_cvt_pk_u8_f32 itself, which converts with round-to-nearest-even (checked on gfx950 on exact
 // halves 0.5, 1.5, 2.5, ... and pinned by the tie rows of the parity tests) and saturates at 255.
 // A clamp min(., Q) to the code range never binds: a <= amax and r = fl(Q/amax) give
 // a*r <= Q*(1+2^-24)^2 < Q + 1/2, so rint already yields at most Q.
-template <int DT>
-__device__ __forceinline__ void quantize_run(const uint32_t (&apk)[16], float r, uint32_t (&m)[8]) {
+__device__ __forceinline__ void quantize_run(const float (&af)[32], float r, uint32_t (&m)[8]) {
 #pragma unroll
     for (int g = 0; g < 8; ++g) {
         uint32_t acc = 0;
-        acc = __builtin_amdgcn_cvt_pk_u8_f32(widen_lo<DT>(apk[2 * g]) * r, 0, acc);
-        acc = __builtin_amdgcn_cvt_pk_u8_f32(widen_hi<DT>(apk[2 * g]) * r, 1, acc);
-        acc = __builtin_amdgcn_cvt_pk_u8_f32(widen_lo<DT>(apk[2 * g + 1]) * r, 2, acc);
-        acc = __builtin_amdgcn_cvt_pk_u8_f32(widen_hi<DT>(apk[2 * g + 1]) * r, 3, acc);
+        acc = __builtin_amdgcn_cvt_pk_u8_f32(af[4 * g] * r, 0, acc);
+        acc = __builtin_amdgcn_cvt_pk_u8_f32(af[4 * g + 1] * r, 1, acc);
+        acc = __builtin_amdgcn_cvt_pk_u8_f32(af[4 * g + 2] * r, 2, acc);
+        acc = __builtin_amdgcn_cvt_pk_u8_f32(af[4 * g + 3] * r, 3, acc);
         m[g] = acc;
     }
 }

@@ -47,6 +47,7 @@ struct Params {
     uint64_t payload_capacity, outlier_capacity;
     // workspace sections (bytes from d_ws)
     uint64_t ws_cnt;        // u32[T]  outliers per token           (staged)
+    uint64_t ws_amax;       // f32[T]  inlier absmax per token      (staged)
     uint64_t ws_agg;        // u64[2][T] per-token (words, count), two generations   (fused)
     uint64_t ws_pref;       // u64[2][T] per-token exclusive prefix, two generations (fused)
     uint64_t ws_ctrl;       // u32[64]   generation, error flag                      (fused)

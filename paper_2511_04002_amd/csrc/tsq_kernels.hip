@@ -31,6 +31,8 @@ struct Choice {
 template <int DT>
 __device__ __forceinline__ Choice choose_width(const Params &p, const uint32_t (&apk)[16], uint32_t omask,
                                                uint32_t amax_pk, uint32_t *scratch, uint32_t (&m)[8]) {
+    float af[32];
+    widen_run<DT>(apk, af);
     uint32_t *red0 = scratch, *red1 = scratch + 2 * kMaxWaves;
     uint32_t mx = (amax_pk & 0xFFFFu) > (amax_pk >> 16) ? (amax_pk & 0xFFFFu) : (amax_pk >> 16);
     uint32_t cnt = (uint32_t)__builtin_popcount(omask);
@@ -44,7 +46,7 @@ __device__ __forceinline__ Choice choose_width(const Params &p, const uint32_t (
 
     const uint32_t b0 = width_at(p, 0);
     const uint32_t Q0 = (1u << (b0 - 1)) - 1u;
-    quantize_run<DT>(apk, __uint_as_float(__builtin_amdgcn_readlane(__float_as_uint(rq), 0)), m);
+    quantize_run(af, __uint_as_float(__builtin_amdgcn_readlane(__float_as_uint(rq), 0)), m);
     uint32_t sel = b0;
 
     if (p.n_widths > 1) {
@@ -55,11 +57,9 @@ __device__ __forceinline__ Choice choose_width(const Params &p, const uint32_t (
         for (uint32_t i = 1; i < p.n_widths; ++i) {
             const uint32_t bi = width_at(p, i);
             uint32_t mi[8];
-            quantize_run<DT>(apk, __uint_as_float(__builtin_amdgcn_readlane(__float_as_uint(rq), (int)i)), mi);
+            quantize_run(af, __uint_as_float(__builtin_amdgcn_readlane(__float_as_uint(rq), (int)i)), mi);
             uint32_t sad = sad_run(m0, mi, b0 - bi);
-            uint32_t ss = (i == 1) ? ss0 : 0u;
-            block_sum2(sad, ss, (i & 1) ? red1 : red0);
-            if (i == 1) ss0 = ss;
+            if (i == 1) block_sum2(sad, ss0, red1); else block_sum1(sad, (i & 1) ? red1 : red0);
             if (violates(p.mode, p.budget, p.hidden, Q0, (1u << (bi - 1)) - 1u, sad, ss0)) break;
             sel = bi;
 #pragma unroll
@@ -141,11 +141,12 @@ k_row_stats(const Params p, const uint16_t *__restrict__ in, uint8_t *__restrict
     const uint32_t run = threadIdx.x;
 
     stage_row(reinterpret_cast<const uint4 *>(in + (size_t)t * p.hidden), p.pieces, p.runs, lrow);
+    clear_reduce_areas(scratch);
     __syncthreads();
 
     uint32_t apk[16], omask = 0, amax_pk = 0;
     if (run < p.runs) {
-        split_run(lrow + run * kRunLdsDw, p.thr_pk, apk, omask, amax_pk);
+        split_run<true>(lrow + run * kRunLdsDw, p.thr_pk, apk, omask, amax_pk);
     } else {
 #pragma unroll
         for (int i = 0; i < 16; ++i) apk[i] = 0;
@@ -156,6 +157,7 @@ k_row_stats(const Params p, const uint16_t *__restrict__ in, uint8_t *__restrict
         blob[p.off_bits + t] = (uint8_t)c.width;
         reinterpret_cast<float *>(blob + p.off_scale)[t] = scale_of(c.amax, c.width);
         reinterpret_cast<uint32_t *>(ws + p.ws_cnt)[t] = c.cnt;
+        reinterpret_cast<float *>(ws + p.ws_amax)[t] = c.amax;
     }
 }
 
@@ -225,7 +227,7 @@ k_scan(const Params p, uint8_t *__restrict__ blob, const uint8_t *__restrict__ w
 
 template <int DT>
 __global__ void __launch_bounds__(1024)
-k_pack(const Params p, const uint16_t *__restrict__ in, uint8_t *__restrict__ blob) {
+k_pack(const Params p, const uint16_t *__restrict__ in, uint8_t *__restrict__ blob, const uint8_t *__restrict__ ws) {
     extern __shared__ __align__(16) uint32_t lds[];
     uint32_t *lrow = lds;
     uint32_t *scratch = lds + p.runs * kRunLdsDw;
@@ -236,28 +238,24 @@ k_pack(const Params p, const uint16_t *__restrict__ in, uint8_t *__restrict__ bl
     const uint64_t po = reinterpret_cast<const uint64_t *>(blob + p.off_pay_off)[t];
     const uint64_t rp0 = reinterpret_cast<const uint64_t *>(blob + p.off_row_ptr)[t];
     const uint64_t rp1 = reinterpret_cast<const uint64_t *>(blob + p.off_row_ptr)[t + 1];
+    // the token's inlier absmax and outlier count are k_row_stats' results
+    const float amax = reinterpret_cast<const float *>(ws + p.ws_amax)[t];
+    const uint32_t cnt = reinterpret_cast<const uint32_t *>(ws + p.ws_cnt)[t];
 
     stage_row(reinterpret_cast<const uint4 *>(in + (size_t)t * p.hidden), p.pieces, p.runs, lrow);
     __syncthreads();
 
     uint32_t apk[16], omask = 0, amax_pk = 0;
-    if (run < p.runs) {
-        split_run(lrow + run * kRunLdsDw, p.thr_pk, apk, omask, amax_pk);
-    } else {
-#pragma unroll
-        for (int i = 0; i < 16; ++i) apk[i] = 0;
-    }
-    uint32_t mx = (amax_pk & 0xFFFFu) > (amax_pk >> 16) ? (amax_pk & 0xFFFFu) : (amax_pk >> 16);
-    uint32_t cnt = (uint32_t)__builtin_popcount(omask);
-    block_max_sum(mx, cnt, scratch);
-    const float amax = widen16<DT>(mx);
+    if (run < p.runs) split_run<false>(lrow + run * kRunLdsDw, p.thr_pk, apk, omask, amax_pk);
     const float r = amax >= kAmaxFloor ? level_count(width) / amax : 0.0f;
 
     // a width outside the plan's set would overrun the payload section: write nothing for it
     const bool width_ok = width >= 2 && width <= 8 && po + row_bytes(p.hidden, width) <= p.payload_capacity;
     if (run < p.runs && width_ok) {
+        float af[32];
+        widen_run<DT>(apk, af);
         uint32_t m[8];
-        quantize_run<DT>(apk, r, m);
+        quantize_run(af, r, m);
         const uint32_t left = p.pieces - 4 * run;
         store_codes_any(width, m, lrow + run * kRunLdsDw, reinterpret_cast<uint32_t *>(blob + p.off_payload + po),
                         run, left < 4 ? left : 4);
@@ -503,6 +501,8 @@ k_fused(const Params p, const uint16_t *__restrict__ in, uint8_t *__restrict__ b
     const uint32_t run = threadIdx.x;
     const bool owns = run < p.runs;
     const uint32_t left = owns ? p.pieces - 4 * run : 0;
+    clear_reduce_areas(scratch);
+    __syncthreads();
 
     uint32_t apk[16], omask = 0, amax_pk = 0;
     if (owns) {
@@ -515,7 +515,7 @@ k_fused(const Params p, const uint16_t *__restrict__ in, uint8_t *__restrict__ b
             w[4 * k] = q.x; w[4 * k + 1] = q.y; w[4 * k + 2] = q.z; w[4 * k + 3] = q.w;
         }
         slot_write(slot, run, w);
-        split_regs(w, p.thr_pk, apk, omask, amax_pk);
+        split_regs<true>(w, p.thr_pk, apk, omask, amax_pk);
     } else {
 #pragma unroll
         for (int i = 0; i < 16; ++i) apk[i] = 0;
@@ -686,14 +686,15 @@ int launch_scan(const Params &p, void *d_blob, void *d_ws, void *stream) {
 }
 
 int launch_pack(const Params &p, const Geometry &g, const void *d_in, void *d_blob, void *d_ws, void *stream) {
-    (void)d_ws;
     const dim3 grid(p.tokens), block(g.block);
     if (p.dtype == kF16)
         hipLaunchKernelGGL(k_pack<kF16>, grid, block, g.lds_bytes, as_stream(stream), p,
-                           static_cast<const uint16_t *>(d_in), static_cast<uint8_t *>(d_blob));
+                           static_cast<const uint16_t *>(d_in), static_cast<uint8_t *>(d_blob),
+                           static_cast<const uint8_t *>(d_ws));
     else
         hipLaunchKernelGGL(k_pack<kBF16>, grid, block, g.lds_bytes, as_stream(stream), p,
-                           static_cast<const uint16_t *>(d_in), static_cast<uint8_t *>(d_blob));
+                           static_cast<const uint16_t *>(d_in), static_cast<uint8_t *>(d_blob),
+                           static_cast<const uint8_t *>(d_ws));
     return (int)hipGetLastError();
 }
 
