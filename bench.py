@@ -39,6 +39,7 @@ def parse():
     ap.add_argument("--eps", type=float, default=0.05, help="error budget, relative to the row RMS")
     ap.add_argument("--pipeline", default="auto", choices=["auto", "staged", "fused"])
     ap.add_argument("--nbuf", type=int, default=4, help="buffer sets rotated through")
+    ap.add_argument("--bits", default="", help="allowed widths, e.g. 2,4,8 (default: the workload's set)")
     ap.add_argument("--c5-seqs", type=int, default=32)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-sample-rows", type=int, default=0, help="0 = sized for about 10-30 s")
@@ -92,7 +93,8 @@ def main():
     w, x = make_input(args)
     T, H = x.shape
     pipe = "staged" if args.pipeline == "auto" else args.pipeline    # what "auto" resolves to
-    plan = tsq.Plan(T, H, w.dtype, w.tau, w.bit_set, args.eps, mode="rel_rms", pipeline=pipe,
+    bit_set = tuple(int(b) for b in args.bits.split(",")) if args.bits else tuple(w.bit_set)
+    plan = tsq.Plan(T, H, w.dtype, w.tau, bit_set, args.eps, mode="rel_rms", pipeline=pipe,
                     max_outliers=max(1, (T * H) // 8))
     x0 = torch.from_numpy(x.view(np.int16)).cuda()
     nbuf = max(1, args.nbuf)
@@ -172,7 +174,7 @@ def main():
         "dtype": "f32",
         "data": "synthetic",
         "config": {"workload": "%s %dx%d %s" % (w.name, T, H, w.dtype), "tau": w.tau,
-                   "bit_set": list(w.bit_set), "budget": "%.3g x row RMS" % args.eps,
+                   "bit_set": list(bit_set), "budget": "%.3g x row RMS" % args.eps,
                    "pipeline": pipe, "buffer_sets": nbuf, "mean_width": round(bbar, 3),
                    "outlier_fraction": round(rho, 6), "width_hist": list(info.width_hist),
                    "compression_ratio": round(2.0 * n / info.compressed_bytes, 3)},

@@ -21,6 +21,10 @@ struct tsq_plan {
     Geometry g;
     tsq_layout layout;
     int pipeline;  // resolved: TSQ_PIPE_STAGED or TSQ_PIPE_FUSED
+    // persistent grid of the fused kernel, found on the first compress call (needs the device)
+    std::once_flag fused_once;
+    uint32_t fused_grid = 0;
+    int fused_rc = 0;
 };
 
 namespace {
@@ -132,8 +136,7 @@ tsq_status tsq_plan_create(const tsq_config *cfg, tsq_plan **out) {
     uint64_t w = 0;
     p.ws_cnt = w;    w = align_up(w + 4ull * T, 256);
     p.ws_amax = w;   w = align_up(w + 4ull * T, 256);
-    p.ws_agg = w;    w = align_up(w + 16ull * T, 256);
-    p.ws_pref = w;   w = align_up(w + 16ull * T, 256);
+    p.ws_agg = w;    w = align_up(w + 4ull * 2 * 4 * kFusedGridCap, 256);
     p.ws_ctrl = w;   w = align_up(w + 256, 256);
     L.workspace_bytes = w;
 
@@ -144,7 +147,8 @@ tsq_status tsq_plan_create(const tsq_config *cfg, tsq_plan **out) {
 
     pl->g.block = 64u * ((p.runs + 63u) / 64u);
     pl->g.lds_bytes = (p.runs * kRunLdsDw + kScratchDw) * 4u;
-    pl->g.lds_fused_bytes = (p.runs * 16u + kScratchDw) * 4u;
+    pl->g.waves = compress_waves(p.runs);
+    pl->g.lds_fused_bytes = (p.runs * kRunLdsDw + kFusedScratchDw) * 4u;
     pl->pipeline = cfg->pipeline == TSQ_PIPE_FUSED ? TSQ_PIPE_FUSED : TSQ_PIPE_STAGED;
     *out = pl;
     return TSQ_OK;
@@ -162,8 +166,28 @@ size_t tsq_plan_blob_bytes(const tsq_plan *plan) { return plan ? (size_t)plan->l
 size_t tsq_plan_workspace_bytes(const tsq_plan *plan) { return plan ? (size_t)plan->layout.workspace_bytes : 0; }
 
 static tsq_status ensure_prepared() {
-    std::call_once(g_prepare_once, [] { g_prepare_rc = prepare_kernels(); });
+    std::call_once(g_prepare_once, [] {
+        g_prepare_rc = prepare_kernels();
+        if (g_prepare_rc == 0) g_prepare_rc = prepare_fused_kernels();
+    });
     return hip_rc(g_prepare_rc);
+}
+
+// Grid of the fused kernel: every workgroup must be resident (they wait for each other's table
+// words), and the tokens should spread evenly over the iterations.
+static tsq_status fused_grid(const tsq_plan *plan, uint32_t *grid) {
+    tsq_plan *pl = const_cast<tsq_plan *>(plan);
+    std::call_once(pl->fused_once, [pl] {
+        uint32_t resident = 0;
+        pl->fused_rc = fused_resident_workgroups(pl->p, pl->g, &resident);
+        if (pl->fused_rc != 0) return;
+        uint32_t gmax = resident < kFusedGridCap ? resident : kFusedGridCap;
+        if (gmax > pl->p.tokens) gmax = pl->p.tokens;
+        const uint32_t iters = (pl->p.tokens + gmax - 1) / gmax;
+        pl->fused_grid = (pl->p.tokens + iters - 1) / iters;
+    });
+    *grid = pl->fused_grid;
+    return hip_rc(pl->fused_rc);
 }
 
 tsq_status tsq_workspace_reset(const tsq_plan *plan, void *d_ws, void *stream) {
@@ -176,7 +200,12 @@ tsq_status tsq_compress(const tsq_plan *plan, const void *d_in, void *d_blob, vo
     if (((uintptr_t)d_in & 15u) || ((uintptr_t)d_blob & 255u) || ((uintptr_t)d_ws & 255u)) return TSQ_ERR_INVALID_ARG;
     tsq_status st = ensure_prepared();
     if (st != TSQ_OK) return st;
-    if (plan->pipeline == TSQ_PIPE_FUSED) return hip_rc(launch_fused(plan->p, plan->g, d_in, d_blob, d_ws, stream));
+    if (plan->pipeline == TSQ_PIPE_FUSED) {
+        uint32_t grid = 0;
+        st = fused_grid(plan, &grid);
+        if (st != TSQ_OK) return st;
+        return hip_rc(launch_fused(plan->p, plan->g, grid, d_in, d_blob, d_ws, stream));
+    }
     int e = launch_row_stats(plan->p, plan->g, d_in, d_blob, d_ws, stream);
     if (e == 0) e = launch_scan(plan->p, d_blob, d_ws, stream);
     if (e == 0) e = launch_pack(plan->p, plan->g, d_in, d_blob, d_ws, stream);
@@ -196,7 +225,9 @@ tsq_status tsq_compress_timed(const tsq_plan *plan, const void *d_in, void *d_bl
     int rc = 0, n = 0;
     (void)hipEventRecord(ev[0], s);
     if (plan->pipeline == TSQ_PIPE_FUSED) {
-        rc = launch_fused(plan->p, plan->g, d_in, d_blob, d_ws, stream);
+        uint32_t grid = 0;
+        st = fused_grid(plan, &grid);
+        if (st == TSQ_OK) rc = launch_fused(plan->p, plan->g, grid, d_in, d_blob, d_ws, stream); else rc = 1;
         (void)hipEventRecord(ev[1], s);
         n = 1;
     } else {

@@ -48,6 +48,10 @@ __device__ __forceinline__ uint32_t lane_value(uint32_t v, int lane) {
     return (uint32_t)__builtin_amdgcn_readlane((int)v, lane);
 }
 
+// A value that is the same in every lane, moved to a scalar register (frees a vector register and
+// lets the arithmetic that follows run on the scalar unit).
+__device__ __forceinline__ uint32_t uniform(uint32_t v) { return (uint32_t)__builtin_amdgcn_readfirstlane((int)v); }
+
 // Reductions over the 64 lanes of a wave; the result is uniform.  Four DPP steps leave the
 // total of each row of 16 lanes in all of its lanes; the four row totals are combined as scalars.
 __device__ __forceinline__ uint32_t wave_max_u32(uint32_t v) {
@@ -78,72 +82,6 @@ __device__ __forceinline__ uint32_t wave_incl_scan_u32(uint32_t v) {
     return v + (row > 0 ? r0 : 0u) + (row > 1 ? r1 : 0u) + (row > 2 ? r2 : 0u);
 }
 
-// Cross-wave step of the block reductions.  A reduce area is 2*kMaxWaves dwords of LDS: slot w
-// holds wave w's first value, slot kMaxWaves + w its second.  Slots of waves that do not exist
-// must hold 0 (clear_reduce_areas), so that whole quads of slots can be read with one 16-byte
-// load each; 0 is the identity of both max and sum on unsigned values.
-__device__ __forceinline__ void clear_reduce_areas(uint32_t *scratch) {
-    if (threadIdx.x < 4 * kMaxWaves) scratch[threadIdx.x] = 0;
-}
-__device__ __forceinline__ uint32_t max4(const uint4 v, uint32_t m) {
-    const uint32_t a = v.x > v.y ? v.x : v.y, b = v.z > v.w ? v.z : v.w;
-    const uint32_t c = a > b ? a : b;
-    return c > m ? c : m;
-}
-
-// Every thread gets max over the block of mx and sum over the block of sm.
-// red: a reduce area; consecutive calls must alternate between two such areas.
-__device__ __forceinline__ void block_max_sum(uint32_t &mx, uint32_t &sm, uint32_t *red) {
-    mx = wave_max_u32(mx);
-    sm = wave_sum_u32(sm);
-    const uint32_t nw = blockDim.x >> 6;
-    if (nw == 1) return;
-    const uint32_t lane = threadIdx.x & 63, wv = threadIdx.x >> 6;
-    if (lane == 0) { red[wv] = mx; red[kMaxWaves + wv] = sm; }
-    __syncthreads();
-    uint32_t M = 0, S = 0;
-    for (uint32_t q = 0; 4 * q < nw; ++q) {
-        const uint4 a = reinterpret_cast<const uint4 *>(red)[q];
-        const uint4 b = reinterpret_cast<const uint4 *>(red + kMaxWaves)[q];
-        M = max4(a, M);
-        S += (b.x + b.y) + (b.z + b.w);
-    }
-    mx = M;
-    sm = S;
-}
-__device__ __forceinline__ void block_sum2(uint32_t &x, uint32_t &y, uint32_t *red) {
-    x = wave_sum_u32(x);
-    y = wave_sum_u32(y);
-    const uint32_t nw = blockDim.x >> 6;
-    if (nw == 1) return;
-    const uint32_t lane = threadIdx.x & 63, wv = threadIdx.x >> 6;
-    if (lane == 0) { red[wv] = x; red[kMaxWaves + wv] = y; }
-    __syncthreads();
-    uint32_t X = 0, Y = 0;
-    for (uint32_t q = 0; 4 * q < nw; ++q) {
-        const uint4 a = reinterpret_cast<const uint4 *>(red)[q];
-        const uint4 b = reinterpret_cast<const uint4 *>(red + kMaxWaves)[q];
-        X += (a.x + a.y) + (a.z + a.w);
-        Y += (b.x + b.y) + (b.z + b.w);
-    }
-    x = X;
-    y = Y;
-}
-__device__ __forceinline__ void block_sum1(uint32_t &x, uint32_t *red) {
-    x = wave_sum_u32(x);
-    const uint32_t nw = blockDim.x >> 6;
-    if (nw == 1) return;
-    const uint32_t lane = threadIdx.x & 63, wv = threadIdx.x >> 6;
-    if (lane == 0) red[wv] = x;
-    __syncthreads();
-    uint32_t X = 0;
-    for (uint32_t q = 0; 4 * q < nw; ++q) {
-        const uint4 a = reinterpret_cast<const uint4 *>(red)[q];
-        X += (a.x + a.y) + (a.z + a.w);
-    }
-    x = X;
-}
-
 // Exclusive prefix sum of v over the threads of the block, in thread order.
 // scr: kMaxWaves dwords of LDS not in use by anything else until the next barrier.
 __device__ __forceinline__ uint32_t block_excl_scan(uint32_t v, uint32_t *scr) {
@@ -158,51 +96,103 @@ __device__ __forceinline__ uint32_t block_excl_scan(uint32_t v, uint32_t *scr) {
 
 // ---------------------------------------------------------------- row staging
 
-// HBM -> LDS, coalesced: slot p of the LDS row holds 16-byte piece p (zeros past the row's end).
-__device__ __forceinline__ void stage_row(const uint4 *__restrict__ src, uint32_t pieces, uint32_t runs,
-                                          uint32_t *lrow) {
-    uint4 v[4];
+// Row movement HBM -> registers -> LDS, private to each wave: wave w moves the 4 KB of the row
+// that its own lanes own (runs 64w .. 64w+63): four coalesced loads of 16 B per lane, then four
+// 16-byte LDS writes in the run layout.  Since a wave only reads back what it wrote itself and
+// the LDS operations of one wave execute in order, the row needs no workgroup barrier.
+__device__ __forceinline__ void fetch_row_part(const uint4 *__restrict__ src, uint32_t pieces, uint4 (&pre)[4]) {
+    const uint32_t lane = threadIdx.x & 63u, wv = threadIdx.x >> 6;
 #pragma unroll
-    for (int k = 0; k < 4; ++k) {
-        const uint32_t p = threadIdx.x + k * blockDim.x;
-        v[k] = make_uint4(0, 0, 0, 0);
-        if (p < pieces) v[k] = src[p];
+    for (uint32_t k = 0; k < 4; ++k) {
+        const uint32_t q = 256u * wv + 64u * k + lane;
+        pre[k] = make_uint4(0, 0, 0, 0);
+        if (q < pieces) pre[k] = src[q];
     }
+}
+__device__ __forceinline__ void write_row_part(uint32_t *lrow, uint32_t runs, const uint4 (&pre)[4]) {
+    const uint32_t lane = threadIdx.x & 63u, wv = threadIdx.x >> 6;
 #pragma unroll
-    for (int k = 0; k < 4; ++k) {
-        const uint32_t p = threadIdx.x + k * blockDim.x;
-        if (p < 4 * runs) *reinterpret_cast<uint4 *>(lrow + (p >> 2) * kRunLdsDw + (p & 3) * 4) = v[k];
+    for (uint32_t k = 0; k < 4; ++k) {
+        const uint32_t q = 256u * wv + 64u * k + lane;
+        if (q < 4 * runs) *reinterpret_cast<uint4 *>(lrow + (q >> 2) * kRunLdsDw + (q & 3) * 4) = pre[k];
     }
 }
 
 // ---------------------------------------------------------------- Eq. (ts) on one run
 
-// Threshold splitting of the 32 elements a lane owns, on the 16-bit magnitude
-// patterns: for fp16 and bf16 alike the pattern of |x| grows with |x|, and the
-// patterns of Inf and NaN lie above every finite one, so
+// The inlier magnitudes |T_below| of a run in the form the quantizer consumes:
+//   bf16: 32 binary32 values;
+//   fp16: 16 dwords of packed half-precision magnitudes (the multiply reads them directly
+//         through v_fma_mix_f32).
+// Outlier slots hold 0 in both forms.
+template <int DT> struct Mags;
+template <> struct Mags<kBF16> { float v[32]; };
+template <> struct Mags<kF16> { uint32_t v[16]; };
+
+// ((w & inl) & 0xFFFF) << 16 in one SDWA instruction.  A VALU result written with a partial
+// dst_sel must not be read by the very next VALU instruction on gfx950: the s_nop provides the
+// wait state, since the compiler cannot see into the asm statement.
+__device__ __forceinline__ float masked_low_half_as_bf16(uint32_t w, uint32_t inl) {
+    uint32_t d;
+    asm("v_and_b32_sdwa %0, %1, %2 dst_sel:WORD_1 dst_unused:UNUSED_PAD src0_sel:WORD_0 src1_sel:WORD_0\n\ts_nop 0"
+        : "=v"(d)
+        : "v"(w), "v"(inl));
+    return __uint_as_float(d);
+}
+// (keep & sel) | (old & ~sel) with sel in a scalar register: one v_bfi_b32
+__device__ __forceinline__ uint32_t bit_insert(uint32_t sel, uint32_t keep, uint32_t old) {
+    uint32_t d;
+    asm("v_bfi_b32 %0, %1, %2, %3" : "=v"(d) : "s"(sel), "v"(keep), "v"(old));
+    return d;
+}
+
+// Threshold splitting (Eq. (ts)) of the 32 elements a lane owns, on the 16-bit magnitude
+// patterns: for fp16 and bf16 alike the pattern of |x| grows with |x|, and the patterns of Inf
+// and NaN lie above every finite one, so
 //   !(|x| < tau)  <=>  (pattern & 0x7FFF) >= thr,
 // thr being the smallest pattern whose value is >= tau (computed on the host).
-//   apk   : |x| patterns of the inliers, 0 at outlier slots (|T_below|)
-//   omask : outlier flags; bit i = element 2i, bit 16+i = element 2i+1
-//   amax  : running maximum of the inlier patterns, both halves (only if WANT_MAX)
-// Six instructions per pair of elements: and, packed subtract, packed arithmetic shift
-// (the borrow of pattern - thr marks the inliers), and, packed max, bit-field insert.
-template <bool WANT_MAX>
-__device__ __forceinline__ void split_regs(const uint32_t (&w)[16], uint32_t thr_pk, uint32_t (&apk)[16],
-                                           uint32_t &omask, uint32_t &amax_pk) {
-    uint32_t im = 0, mx = amax_pk;
+//   mg        : |T_below| of the run (see Mags)
+//   omask     : outlier flags; bit i = element 2i, bit 16+i = element 2i+1
+//   amax_bits : binary32 bit pattern of the largest inlier magnitude of the run (only if WANT_MAX)
+// Per pair of elements: and, packed subtract, packed arithmetic shift (the borrow of
+// pattern - thr marks the inliers), bit-field insert into omask; then bf16: two masked widenings
+// and one three-way max (7 instructions), fp16: one and and one packed max (6).
+template <int DT, bool WANT_MAX>
+__device__ __forceinline__ void split_regs(const uint32_t (&w)[16], uint32_t thr_pk, Mags<DT> &mg, uint32_t &omask,
+                                           uint32_t &amax_bits) {
+    uint32_t im = 0;
+    if constexpr (DT == kBF16) {
+        uint32_t mx = 0;                   // non-negative binary32 patterns order like unsigned integers
 #pragma unroll
-    for (int i = 0; i < 16; ++i) {
-        const uint32_t absw = w[i] & 0x7FFF7FFFu;
-        const uint32_t inl = pk_ashr15_i16(pk_sub_u16(absw, thr_pk));  // 0xFFFF where |x| < tau
-        const uint32_t a = absw & inl;
-        apk[i] = a;
-        if (WANT_MAX) mx = pk_max_u16(mx, a);
-        const uint32_t sel = 0x00010001u << i;
-        im = (inl & sel) | (im & ~sel);                                // v_bfi_b32
+        for (int i = 0; i < 16; ++i) {
+            const uint32_t absw = w[i] & 0x7FFF7FFFu;
+            const uint32_t inl = pk_ashr15_i16(pk_sub_u16(absw, thr_pk));  // 0xFFFF where |x| < tau
+            const float lo = masked_low_half_as_bf16(absw, inl);
+            const uint32_t hi = absw & inl & 0xFFFF0000u;
+            mg.v[2 * i] = lo;
+            mg.v[2 * i + 1] = __uint_as_float(hi);
+            if (WANT_MAX) {
+                const uint32_t l = __float_as_uint(lo), t = l > hi ? l : hi;
+                mx = t > mx ? t : mx;                                      // v_max3_u32
+            }
+            im = bit_insert(0x00010001u << i, inl, im);
+        }
+        amax_bits = mx;
+    } else {
+        uint32_t mx = 0;
+#pragma unroll
+        for (int i = 0; i < 16; ++i) {
+            const uint32_t absw = w[i] & 0x7FFF7FFFu;
+            const uint32_t inl = pk_ashr15_i16(pk_sub_u16(absw, thr_pk));
+            const uint32_t a = absw & inl;
+            mg.v[i] = a;
+            if (WANT_MAX) mx = pk_max_u16(mx, a);
+            im = bit_insert(0x00010001u << i, inl, im);
+        }
+        const uint32_t m16 = (mx & 0xFFFFu) > (mx >> 16) ? (mx & 0xFFFFu) : (mx >> 16);
+        amax_bits = __float_as_uint((float)__builtin_bit_cast(_Float16, (unsigned short)m16));
     }
     omask = ~im;
-    amax_pk = mx;
 }
 
 // A run in the padded LDS row of the staged kernels.
@@ -213,12 +203,12 @@ __device__ __forceinline__ void load_run_padded(const uint32_t *lrun, uint32_t (
         w[4 * k] = q.x; w[4 * k + 1] = q.y; w[4 * k + 2] = q.z; w[4 * k + 3] = q.w;
     }
 }
-template <bool WANT_MAX>
-__device__ __forceinline__ void split_run(const uint32_t *lrun, uint32_t thr_pk, uint32_t (&apk)[16],
-                                          uint32_t &omask, uint32_t &amax_pk) {
+template <int DT, bool WANT_MAX>
+__device__ __forceinline__ void split_run(const uint32_t *lrun, uint32_t thr_pk, Mags<DT> &mg, uint32_t &omask,
+                                          uint32_t &amax_bits) {
     uint32_t w[16];
     load_run_padded(lrun, w);
-    split_regs<WANT_MAX>(w, thr_pk, apk, omask, amax_pk);
+    split_regs<DT, WANT_MAX>(w, thr_pk, mg, omask, amax_bits);
 }
 
 // Lane-private copy of a run in LDS, 16 dwords per lane, no padding: the four 16-byte chunks
@@ -263,30 +253,40 @@ __device__ __forceinline__ float widen16(uint32_t pattern) {
 
 // ---------------------------------------------------------------- Eq. (Proposed) on one run
 
-// The inlier magnitudes of a run as binary32 (exact for both 16-bit formats); widened once and
-// kept in registers, so that every quantization pass costs one multiply and one convert per element.
-template <int DT>
-__device__ __forceinline__ void widen_run(const uint32_t (&apk)[16], float (&af)[32]) {
-#pragma unroll
-    for (int i = 0; i < 16; ++i) {
-        af[2 * i] = widen_lo<DT>(apk[i]);
-        af[2 * i + 1] = widen_hi<DT>(apk[i]);
-    }
+// fl(a * r) for the low / high half-precision value of a packed pair: v_fma_mix_f32 widens the
+// half exactly and rounds the product once, which is the binary32 product of the widened value.
+__device__ __forceinline__ float mul_f16_lo(uint32_t pk, float r) {
+    float d;
+    asm("v_fma_mix_f32 %0, %1, %2, 0 op_sel_hi:[1,0,0]" : "=v"(d) : "v"(pk), "v"(r));
+    return d;
+}
+__device__ __forceinline__ float mul_f16_hi(uint32_t pk, float r) {
+    float d;
+    asm("v_fma_mix_f32 %0, %1, %2, 0 op_sel:[1,0,0] op_sel_hi:[1,0,0]" : "=v"(d) : "v"(pk), "v"(r));
+    return d;
 }
 
-// m = rint(a * r), one byte per element, element 4g+k in byte k of m[g].  The rounding is done by
-// v_cvt_pk_u8_f32 itself, which converts with round-to-nearest-even (checked on gfx950 on exact
-// halves 0.5, 1.5, 2.5, ... and pinned by the tie rows of the parity tests) and saturates at 255.
-// A clamp min(., Q) to the code range never binds: a <= amax and r = fl(Q/amax) give
-// a*r <= Q*(1+2^-24)^2 < Q + 1/2, so rint already yields at most Q.
-__device__ __forceinline__ void quantize_run(const float (&af)[32], float r, uint32_t (&m)[8]) {
+// m = rint(a * r), one byte per element, element 4g+k in byte k of m[g]: one multiply and one
+// convert per element.  The rounding is done by v_cvt_pk_u8_f32 itself, which converts with
+// round-to-nearest-even (checked on gfx950 on exact halves 0.5, 1.5, 2.5, ... and pinned by the
+// tie rows of the parity tests) and saturates at 255.  A clamp min(., Q) to the code range never
+// binds: a <= amax and r = fl(Q/amax) give a*r <= Q*(1+2^-24)^2 < Q + 1/2, so rint already
+// yields at most Q.
+template <int DT>
+__device__ __forceinline__ void quantize_run(const Mags<DT> &mg, float r, uint32_t (&m)[8]) {
 #pragma unroll
     for (int g = 0; g < 8; ++g) {
         uint32_t acc = 0;
-        acc = __builtin_amdgcn_cvt_pk_u8_f32(af[4 * g] * r, 0, acc);
-        acc = __builtin_amdgcn_cvt_pk_u8_f32(af[4 * g + 1] * r, 1, acc);
-        acc = __builtin_amdgcn_cvt_pk_u8_f32(af[4 * g + 2] * r, 2, acc);
-        acc = __builtin_amdgcn_cvt_pk_u8_f32(af[4 * g + 3] * r, 3, acc);
+        if constexpr (DT == kBF16) {
+#pragma unroll
+            for (int k = 0; k < 4; ++k)
+                acc = __builtin_amdgcn_cvt_pk_u8_f32(mg.v[4 * g + k] * r, k, acc);
+        } else {
+            acc = __builtin_amdgcn_cvt_pk_u8_f32(mul_f16_lo(mg.v[2 * g], r), 0, acc);
+            acc = __builtin_amdgcn_cvt_pk_u8_f32(mul_f16_hi(mg.v[2 * g], r), 1, acc);
+            acc = __builtin_amdgcn_cvt_pk_u8_f32(mul_f16_lo(mg.v[2 * g + 1], r), 2, acc);
+            acc = __builtin_amdgcn_cvt_pk_u8_f32(mul_f16_hi(mg.v[2 * g + 1], r), 3, acc);
+        }
         m[g] = acc;
     }
 }
@@ -397,6 +397,136 @@ template <int DT, int B>
 __device__ __forceinline__ void unpack_run(const uint32_t (&d)[B], float s, uint32_t (&o)[16]) {
 #pragma unroll
     for (int i = 0; i < 16; ++i) o[i] = narrow2<DT>(decode_one<B>(d, 2 * i, s), decode_one<B>(d, 2 * i + 1, s));
+}
+
+// LDS scratch of the staged row kernels (behind the row): four reduce areas | scan area
+constexpr uint32_t kScrScan = 4 * 2 * kMaxWaves;
+
+__device__ __forceinline__ uint32_t row_bytes(uint32_t H, uint32_t b) { return 4u * ((H * b + 31u) >> 5); }
+
+// ---------------------------------------------------------------- Algorithm 1 for the token of this block
+
+struct Choice {
+    uint32_t width;  // b_t
+    float amax;      // inlier absmax
+    uint32_t cnt;    // outliers in the token
+};
+
+// ---- block collectives for NW waves (known at compile time) ----
+// A reduce area is 2*kMaxWaves dwords; slot w = wave w's first value, kMaxWaves + w its second.
+// The caller rotates over four areas, so a wave that is one barrier ahead never overwrites
+// values another wave still has to read.
+
+// max of mx, sum of sm over the block; pre = sum of sm over the waves before this one
+template <int NW>
+__device__ __forceinline__ void block_max_sum_prefix(uint32_t &mx, uint32_t &sm, uint32_t &pre, uint32_t *red) {
+    mx = wave_max_u32(mx);
+    sm = wave_sum_u32(sm);
+    pre = 0;
+    if (NW == 1) return;
+    const uint32_t lane = threadIdx.x & 63, wv = threadIdx.x >> 6;
+    if (lane == 0) { red[wv] = mx; red[kMaxWaves + wv] = sm; }
+    __syncthreads();
+    uint32_t M = 0, S = 0, P = 0;
+#pragma unroll
+    for (int w = 0; w < NW; ++w) {
+        const uint32_t a = red[w], b = red[kMaxWaves + w];
+        M = a > M ? a : M;
+        S += b;
+        P += (uint32_t)w < wv ? b : 0u;
+    }
+    mx = uniform(M); sm = uniform(S); pre = uniform(P);
+}
+template <int NW>
+__device__ __forceinline__ void block_sum2_nw(uint32_t &x, uint32_t &y, uint32_t *red) {
+    x = wave_sum_u32(x);
+    y = wave_sum_u32(y);
+    if (NW == 1) return;
+    const uint32_t lane = threadIdx.x & 63, wv = threadIdx.x >> 6;
+    if (lane == 0) { red[wv] = x; red[kMaxWaves + wv] = y; }
+    __syncthreads();
+    uint32_t X = 0, Y = 0;
+#pragma unroll
+    for (int w = 0; w < NW; ++w) { X += red[w]; Y += red[kMaxWaves + w]; }
+    x = uniform(X); y = uniform(Y);
+}
+template <int NW>
+__device__ __forceinline__ void block_sum1_nw(uint32_t &x, uint32_t *red) {
+    x = wave_sum_u32(x);
+    if (NW == 1) return;
+    const uint32_t lane = threadIdx.x & 63, wv = threadIdx.x >> 6;
+    if (lane == 0) red[wv] = x;
+    __syncthreads();
+    uint32_t X = 0;
+#pragma unroll
+    for (int w = 0; w < NW; ++w) X += red[w];
+    x = uniform(X);
+}
+
+// Algorithm 1 for the token of this block.  ring: four reduce areas; turn: running count of
+// reductions; live: false for lanes that own no run (they compute on a copy of run 0 and are
+// left out of every sum).  On return m holds the magnitude bytes of the run at the chosen width
+// and cnt_before the outliers of the token in the waves before this one.
+template <int DT, int NW>
+__device__ __forceinline__ Choice choose_width(const Params &p, const Mags<DT> &af, uint32_t omask,
+                                                  uint32_t amax_bits, bool live, uint32_t *ring, uint32_t &turn,
+                                                  uint32_t (&m)[8], uint32_t &cnt_before) {
+    uint32_t mx = live ? amax_bits : 0u;  // non-negative binary32 patterns order like unsigned integers
+    uint32_t cnt = live ? (uint32_t)__builtin_popcount(omask) : 0u;
+    block_max_sum_prefix<NW>(mx, cnt, cnt_before, ring + (turn++ & 3u) * 2 * kMaxWaves);
+    const float amax = __uint_as_float(mx);
+
+    const uint32_t lane = threadIdx.x & 63;
+    float rq = 0.0f;
+    if (lane < p.n_widths && amax >= kAmaxFloor) rq = level_count(width_at(p, lane)) / amax;
+
+    const uint32_t b0 = width_at(p, 0);
+    const uint32_t Q0 = (1u << (b0 - 1)) - 1u;
+    quantize_run<DT>(af, __uint_as_float(__builtin_amdgcn_readlane(__float_as_uint(rq), 0)), m);
+    uint32_t sel = b0;
+    if (p.n_widths > 1) {
+        uint32_t m0[8];
+#pragma unroll
+        for (int g = 0; g < 8; ++g) m0[g] = m[g];
+        uint32_t ss0 = live ? sum_squares_run(m0) : 0u;
+        for (uint32_t i = 1; i < p.n_widths; ++i) {
+            const uint32_t bi = width_at(p, i);
+            uint32_t mi[8];
+            quantize_run<DT>(af, __uint_as_float(__builtin_amdgcn_readlane(__float_as_uint(rq), (int)i)), mi);
+            uint32_t sad = live ? sad_run(m0, mi, b0 - bi) : 0u;
+            uint32_t *red = ring + (turn++ & 3u) * 2 * kMaxWaves;
+            if (i == 1) block_sum2_nw<NW>(sad, ss0, red); else block_sum1_nw<NW>(sad, red);
+            if (violates(p.mode, p.budget, p.hidden, Q0, (1u << (bi - 1)) - 1u, sad, ss0)) break;
+            sel = bi;
+#pragma unroll
+            for (int g = 0; g < 8; ++g) m[g] = mi[g];
+        }
+    }
+    Choice c;
+    c.width = sel;
+    c.amax = amax;
+    c.cnt = cnt;
+    return c;
+}
+
+__device__ __forceinline__ float scale_of(float amax, uint32_t width) {
+    return amax >= kAmaxFloor ? amax / level_count(width) : 0.0f;
+}
+
+// The 128-byte header at the start of the blob (written by one thread).
+__device__ __forceinline__ void write_header(const Params &p, uint8_t *blob, uint64_t nnz, uint64_t payload_bytes,
+                                             uint32_t status) {
+    BlobHeader h;
+    h.magic = kMagic; h.version = kVersion; h.dtype = p.dtype; h.tokens = p.tokens; h.hidden = p.hidden;
+    h.tau_bits = __float_as_uint(p.tau); h.bit_mask = p.bit_mask; h.budget_bits = __float_as_uint(p.budget);
+    h.mode = (uint32_t)p.mode;
+    h.status = status;
+    h.nnz = nnz; h.payload_bytes = payload_bytes;
+    h.off_bits = p.off_bits; h.off_scale = p.off_scale; h.off_pay_off = p.off_pay_off;
+    h.off_row_ptr = p.off_row_ptr; h.off_payload = p.off_payload; h.off_out_col = p.off_out_col;
+    h.off_out_val = p.off_out_val; h.payload_capacity = p.payload_capacity;
+    h.outlier_capacity = p.outlier_capacity;
+    *reinterpret_cast<BlobHeader *>(blob) = h;
 }
 
 }  // namespace tsq

@@ -14,10 +14,16 @@ constexpr int kRun      = 32;   // elements owned by one lane (a "run")
 constexpr int kRunLdsDw = 20;   // dwords one run occupies in LDS: 16 of data + 4 of padding,
                                 // so that 8 lanes reading 16 B each hit 32 distinct banks
 constexpr int kMaxWaves = 16;   // 1024 threads per workgroup at most
-// LDS scratch of the row kernels behind the row: two reduce areas (3 dwords per wave), one scan
-// area, one broadcast area
-constexpr uint32_t kScratchDw = 2 * 3 * kMaxWaves + kMaxWaves + 8;
+// LDS scratch of the staged row kernels behind the row: four reduce areas (2 dwords per wave
+// each) and one scan area
+constexpr uint32_t kScratchDw = 4 * 2 * kMaxWaves + kMaxWaves;
 constexpr uint32_t kMaxHidden = 32768;
+// fused kernel: outliers of one token that fit an LDS stash (longer tokens take a slower path),
+// the largest persistent grid (table slots per generation), and its LDS behind the row in dwords
+// (four reduce areas, two areas of generation sums, two stashes)
+constexpr uint32_t kStashCap = 1024;
+constexpr uint32_t kFusedGridCap = 4096;
+constexpr uint32_t kFusedScratchDw = 4 * 2 * kMaxWaves + 2 * 5 * kMaxWaves + 2 * kStashCap;
 
 // 128-byte header at the start of every blob.
 struct BlobHeader {
@@ -48,9 +54,9 @@ struct Params {
     // workspace sections (bytes from d_ws)
     uint64_t ws_cnt;        // u32[T]  outliers per token           (staged)
     uint64_t ws_amax;       // f32[T]  inlier absmax per token      (staged)
-    uint64_t ws_agg;        // u64[2][T] per-token (words, count), two generations   (fused)
-    uint64_t ws_pref;       // u64[2][T] per-token exclusive prefix, two generations (fused)
-    uint64_t ws_ctrl;       // u32[64]   generation, error flag                      (fused)
+    uint64_t ws_agg;        // u32[2][4][kFusedGridCap] published (words, count) pairs: two banks
+                            //   (alternating calls) of four generation slots per workgroup (fused)
+    uint64_t ws_ctrl;       // u32[64]   bank of the next call, error flag           (fused)
 };
 
 inline __host__ __device__ uint32_t width_at(const Params &p, uint32_t i) {
@@ -59,9 +65,10 @@ inline __host__ __device__ uint32_t width_at(const Params &p, uint32_t i) {
 
 // Launch geometry fixed by the plan.
 struct Geometry {
-    uint32_t block;         // threads per workgroup = 64 * ceil(runs / 64)
+    uint32_t block;         // threads per workgroup of unpack = 64 * ceil(runs / 64)
     uint32_t lds_bytes;     // dynamic LDS of the staged row kernels and of unpack
-    uint32_t lds_fused_bytes;  // dynamic LDS of the fused kernel (one lane-private row copy)
+    uint32_t waves;         // waves per workgroup of the compress kernels (an instantiated size >= block / 64)
+    uint32_t lds_fused_bytes;  // dynamic LDS of the fused kernel: row, scratch, outlier stash
 };
 
 // launchers implemented in tsq_kernels.hip; each returns a hipError_t as int
@@ -70,8 +77,11 @@ int launch_row_stats(const Params &p, const Geometry &g, const void *d_in, void 
 int launch_scan(const Params &p, void *d_blob, void *d_ws, void *stream);
 int launch_pack(const Params &p, const Geometry &g, const void *d_in, void *d_blob, void *d_ws,
                 void *stream);
-int launch_fused(const Params &p, const Geometry &g, const void *d_in, void *d_blob, void *d_ws,
-                 void *stream);
+int launch_fused(const Params &p, const Geometry &g, uint32_t grid, const void *d_in, void *d_blob,
+                 void *d_ws, void *stream);
+uint32_t compress_waves(uint32_t runs);
+int fused_resident_workgroups(const Params &p, const Geometry &g, uint32_t *out);
+int prepare_fused_kernels();
 int launch_ws_reset(const Params &p, void *d_ws, void *stream);
 int launch_unpack(const Params &p, const Geometry &g, const void *d_blob, void *d_out, void *stream);
 int prepare_kernels();  // raises the dynamic-LDS limit of the row kernels once per process
