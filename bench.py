@@ -92,7 +92,7 @@ def main():
     torch.cuda.set_device(0)
     w, x = make_input(args)
     T, H = x.shape
-    pipe = "staged" if args.pipeline == "auto" else args.pipeline    # what "auto" resolves to
+    pipe = "fused" if args.pipeline == "auto" else args.pipeline     # what "auto" resolves to
     bit_set = tuple(int(b) for b in args.bits.split(",")) if args.bits else tuple(w.bit_set)
     plan = tsq.Plan(T, H, w.dtype, w.tau, bit_set, args.eps, mode="rel_rms", pipeline=pipe,
                     max_outliers=max(1, (T * H) // 8))

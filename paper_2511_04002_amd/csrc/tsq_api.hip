@@ -136,7 +136,8 @@ tsq_status tsq_plan_create(const tsq_config *cfg, tsq_plan **out) {
     uint64_t w = 0;
     p.ws_cnt = w;    w = align_up(w + 4ull * T, 256);
     p.ws_amax = w;   w = align_up(w + 4ull * T, 256);
-    p.ws_agg = w;    w = align_up(w + 4ull * 2 * 4 * kFusedGridCap, 256);
+    p.ws_sizes = w;  w = align_up(w + 4ull * T, 256);
+    p.ws_tickets = w; w = align_up(w + 4ull * 2 * kTicketClasses * kTicketStride, 256);
     p.ws_ctrl = w;   w = align_up(w + 256, 256);
     L.workspace_bytes = w;
 
@@ -148,8 +149,8 @@ tsq_status tsq_plan_create(const tsq_config *cfg, tsq_plan **out) {
     pl->g.block = 64u * ((p.runs + 63u) / 64u);
     pl->g.lds_bytes = (p.runs * kRunLdsDw + kScratchDw) * 4u;
     pl->g.waves = compress_waves(p.runs);
-    pl->g.lds_fused_bytes = (p.runs * kRunLdsDw + kFusedScratchDw) * 4u;
-    pl->pipeline = cfg->pipeline == TSQ_PIPE_FUSED ? TSQ_PIPE_FUSED : TSQ_PIPE_STAGED;
+    pl->g.lds_fused_bytes = (p.runs * 32u + kFusedScratchDw) * 4u;   // row 16 + two images 8 dwords per run
+    pl->pipeline = cfg->pipeline == TSQ_PIPE_STAGED ? TSQ_PIPE_STAGED : TSQ_PIPE_FUSED;
     *out = pl;
     return TSQ_OK;
 }
@@ -183,8 +184,8 @@ static tsq_status fused_grid(const tsq_plan *plan, uint32_t *grid) {
         if (pl->fused_rc != 0) return;
         uint32_t gmax = resident < kFusedGridCap ? resident : kFusedGridCap;
         if (gmax > pl->p.tokens) gmax = pl->p.tokens;
-        const uint32_t iters = (pl->p.tokens + gmax - 1) / gmax;
-        pl->fused_grid = (pl->p.tokens + iters - 1) / iters;
+        pl->fused_grid = gmax;
+        pl->p.fused_classes = gmax < kTicketClasses ? gmax : kTicketClasses;
     });
     *grid = pl->fused_grid;
     return hip_rc(pl->fused_rc);

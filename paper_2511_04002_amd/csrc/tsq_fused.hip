@@ -1,29 +1,35 @@
 // Single-pass compress kernel (gfx950): Eq. (ts), Algorithm 1, Eq. (Proposed), bit packing and
 // CSR emission with ONE read of the input.
 //
-// A persistent grid of G workgroups, all resident at once; workgroup g compresses tokens
-// g, g + G, g + 2G, ...  The tokens [k*G, (k+1)*G) form "generation" k: every workgroup is
-// working on the same generation at roughly the same time.
+// A persistent grid of G workgroups.  Workgroup g starts with token g; every further token comes
+// from a ticket counter.  The workgroups are spread over C classes (g % C), class c owns the
+// tokens t with t % C == c and hands them out in ascending order from its own counter, so that
+// no counter sees more than one atomic per C tokens (atomics on one address are slow across the
+// chip's eight dies) and a workgroup that is slowed down simply takes fewer tokens.
 //
 // Placement of the variable-length outputs (payload words, CSR entries) needs the exclusive
-// prefix over all earlier tokens.  Each workgroup publishes its token's (words, outliers) pair
-// in a table slot; a workgroup finds the prefix of its token by reading the G pairs of the
-// token's generation (earlier workgroup ids give the prefix inside the generation, all of them
-// the generation's total, which is carried forward as a running base).  Nobody scans on behalf
-// of the others, so there is no serial chain across workgroups: one hop from publish to use.
+// prefix over all earlier tokens.  A workgroup publishes, per token, one 32-bit word (words,
+// outliers) in a per-token table.  A workgroup's tokens ascend, so it keeps the sum over the
+// tokens it has already seen and, for each new token of its own, one of its waves reads the
+// table words of the tokens in between (about G of them).  Nobody scans on behalf of the others,
+// nothing forms a serial chain, and apart from the tickets there are no atomic read-modify-write
+// operations (on this chip they cost microseconds when several dies touch one address).
 //
-// To keep that hop off the critical path, a token is stored one iteration late: iteration i
-// computes token i (codes stay in registers, outliers in an LDS stash), publishes it, and then
-// stores token i-1, whose generation was published by everybody about one iteration ago.  The
-// input row of iteration i+1 is fetched into registers at the top of iteration i.
+// To keep the wait for slower neighbours off the critical path a token is stored one iteration
+// late: iteration i computes token i (codes stay in registers, outliers in an LDS stash),
+// publishes it, and then stores token i-1.  All earlier tokens were handed out before token i-1
+// was, so by then they have normally been published.  The row of iteration i+1 is fetched into
+// registers in the middle of iteration i; its ticket was requested an iteration earlier.
 //
-// Table words are 32 bit (2-bit generation tag, payload words, outlier count).  There are four
-// slots per workgroup (generation & 3): a workgroup can be at most two generations ahead of the
-// slowest reader of a slot.  Two banks of the table alternate between calls; a call
-// clears the bank of the next call, so no separate clearing pass is needed.  Words are written
-// and read with relaxed device-scope atomics; they carry their own validity, nothing else is
-// ordered through them.  Every wait is bounded by p.spin_limit; an expired wait marks the blob
-// as failed (TSQ_ERR_INTERNAL) instead of hanging.
+// Progress: the smallest token that is not stored yet has all its predecessors published, and if
+// nobody has taken it yet, no workgroup of its class is waiting (their pending tokens would be
+// smaller); so some workgroup can always move.  Every wait is bounded by p.spin_limit anyway; an
+// expired wait marks the blob as failed (TSQ_ERR_INTERNAL) instead of hanging.
+//
+// Per-call state: table words carry a 2-bit tag of the call (epoch % 3 + 1), so a word of an
+// earlier call is never taken for a current one; the ticket counters exist in two banks
+// (epoch & 1).  The workgroup that stores the last token waits until every workgroup has
+// drawn its final (failing) ticket, clears the other bank for the next call and advances the epoch.
 #include <hip/hip_runtime.h>
 
 #include "tsq_device.hpp"
@@ -31,125 +37,166 @@
 
 namespace tsq {
 
-enum { kCtlBank = 0, kCtlError = 1 };
+enum { kCtlEpoch = 0, kCtlError = 1 };
+constexpr uint32_t kNoToken = 0xFFFFFFFFu;
 
-// Table words (32 bit): bits 31..30 = tag of the generation (generation % 3 + 1; 0 = empty),
-// bits 29..16 = payload words of the token (<= 8192), bits 15..0 = its outliers (<= 32768).
-// A slot (generation & 3) is reused every fourth generation; three successive users of a slot
-// have three different tags, and no reader is ever more than two generations behind a writer.
+// Table word: bits 31..30 = tag of the call (0 = never written), bits 29..16 = payload words of
+// the token (<= 8192), bits 15..0 = its outliers (<= 32768).
 __device__ __forceinline__ uint32_t word_load(const uint32_t *p) {
     return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
 __device__ __forceinline__ void word_store(uint32_t *p, uint32_t v) {
     __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
-__device__ __forceinline__ uint32_t gen_tag(uint32_t gen) { return gen % 3u + 1u; }
 
-template <int B>
-__device__ __forceinline__ void pack_into(const uint32_t (&m)[8], const uint32_t (&w)[16], uint32_t (&out)[8]) {
-    uint32_t o[B];
-    pack_regs<B>(m, w, o);
+// One more round of a bounded wait: false when the limit is reached or another workgroup has
+// already given up (checked now and then, so that a broken run ends quickly everywhere).
+__device__ __forceinline__ bool keep_waiting(uint32_t &spins, uint32_t limit, const uint32_t *error_flag) {
+    if (++spins >= limit) return false;
+    if ((spins & 255u) == 0 && __hip_atomic_load(error_flag, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT)) return false;
+    __builtin_amdgcn_s_sleep(2);
+    return true;
+}
+
+struct __attribute__((packed, aligned(4))) Dw4 { uint32_t a, b, c, d; };   // 16 bytes at a 4-byte aligned address
+
+// ---- the row in LDS, fused kernel: 16 dwords per run, no padding.  The four 16-byte chunks of
+// run r are stored in the order k ^ ((r >> 1) & 3), which spreads eight neighbouring runs over
+// all 32 banks for 16-byte accesses. ----
+__device__ __forceinline__ void write_row_part_sw(uint32_t *lrow, uint32_t runs, const uint4 (&pre)[4]) {
+    const uint32_t lane = threadIdx.x & 63u, wv = threadIdx.x >> 6;
 #pragma unroll
-    for (int k = 0; k < B; ++k) out[k] = o[k];
+    for (uint32_t k = 0; k < 4; ++k) {
+        const uint32_t q = 256u * wv + 64u * k + lane;     // 16-byte piece of the row
+        const uint32_t r = q >> 2, c = (q & 3u) ^ ((r >> 1) & 3u);
+        if (r < runs) *reinterpret_cast<uint4 *>(lrow + r * 16u + c * 4u) = pre[k];
+    }
+}
+__device__ __forceinline__ void load_run_sw(const uint32_t *lrow, uint32_t r, uint32_t (&w)[16]) {
+    const uint32_t sw = (r >> 1) & 3u;
+#pragma unroll
+    for (uint32_t k = 0; k < 4; ++k) {
+        const uint4 q = *reinterpret_cast<const uint4 *>(lrow + r * 16u + ((k ^ sw) << 2));
+        w[4 * k] = q.x; w[4 * k + 1] = q.y; w[4 * k + 2] = q.z; w[4 * k + 3] = q.w;
+    }
+}
+__device__ __forceinline__ uint32_t raw_element_sw(const uint32_t *lrow, uint32_t r, uint32_t j) {
+    const uint32_t d = j >> 1;                               // dword of the run
+    const uint32_t pos = r * 16u + ((((d >> 2) ^ ((r >> 1) & 3u)) << 2) | (d & 3u));
+    return reinterpret_cast<const uint16_t *>(lrow)[2u * pos + (j & 1u)];
 }
 
-// B consecutive dwords to a 4-byte aligned address, in as few store instructions as possible.
-struct __attribute__((packed, aligned(4))) Dw4 { uint32_t a, b, c, d; };
-struct __attribute__((packed, aligned(4))) Dw2 { uint32_t a, b; };
+// nd dwords of packed codes of a run into the token's payload image in LDS
 template <int B>
-__device__ __forceinline__ void store_dwords(uint32_t *dst, const uint32_t (&o)[8]) {
-    int k = 0;
-    if (B - k >= 4) { *reinterpret_cast<Dw4 *>(dst + k) = Dw4{o[k], o[k + 1], o[k + 2], o[k + 3]}; k += 4; }
-    if (B - k >= 4) { *reinterpret_cast<Dw4 *>(dst + k) = Dw4{o[k], o[k + 1], o[k + 2], o[k + 3]}; k += 4; }
-    if (B - k >= 2) { *reinterpret_cast<Dw2 *>(dst + k) = Dw2{o[k], o[k + 1]}; k += 2; }
-    if (B - k >= 1) { dst[k] = o[k]; }
+__device__ __forceinline__ void put_codes(uint32_t *dst, const uint32_t (&o)[8], uint32_t nd) {
+    if (nd >= (uint32_t)B) {
+        int k = 0;
+        // the image is 16-byte aligned and run*B dwords in: use the widest stores the alignment allows
+        if (B % 4 == 0) {
+#pragma unroll
+            for (; k + 4 <= B; k += 4) *reinterpret_cast<uint4 *>(dst + k) = make_uint4(o[k], o[k + 1], o[k + 2], o[k + 3]);
+        } else if (B % 2 == 0) {
+#pragma unroll
+            for (; k + 2 <= B; k += 2) *reinterpret_cast<uint2 *>(dst + k) = make_uint2(o[k], o[k + 1]);
+        } else {
+#pragma unroll
+            for (; k < B; ++k) dst[k] = o[k];
+        }
+    } else {
+#pragma unroll
+        for (int k = 0; k < B; ++k)
+            if ((uint32_t)k < nd) dst[k] = o[k];
+    }
+}
+template <int B>
+__device__ __forceinline__ void pack_to_image(const uint32_t (&m)[8], const uint32_t (&w)[16], uint32_t *dst,
+                                              uint32_t nd) {
+    uint32_t o[8];
+    {
+        uint32_t t[B];
+        pack_regs<B>(m, w, t);
+#pragma unroll
+        for (int k = 0; k < B; ++k) o[k] = t[k];
+    }
+    put_codes<B>(dst, o, nd);
 }
 
-// ---- placement: prefix of this workgroup inside a generation, and the generation's totals ----
-struct GenSums {
-    uint32_t pre_w, pre_c;   // payload words / outliers of the generation's tokens before ours
-    uint32_t tot_w, tot_c;   // of all tokens of the generation
+// ---- placement ----
+// What a workgroup knows about the tokens before one of its own.
+struct Place {
+    uint32_t done;           // tokens 0 .. done-1 are contained in base_*
+    uint32_t base_w, base_c; // their payload words / outliers
+};
+struct Prefix {
+    uint32_t ew, ec;         // payload words / outliers of all tokens before the token
     uint32_t bad;            // a wait expired
 };
-constexpr int kEarly = 4;    // table words per thread that are requested an iteration's work early
 
+// Exclusive prefix of token t (t >= pl.done), in two steps so that the memory latency of the
+// table reads overlaps with other work: place_request asks for the table words of the tokens
+// pl.done .. t-1 (kEarly per thread; all waves take part), place_finish waits for those that
+// were not published yet, reads what lies beyond kEarly words per thread, and adds up.
+// area: 3*kMaxWaves dwords.  All threads of the block call both (one barrier, NW > 1).
+constexpr int kEarly = 4;
 template <int NW>
-__device__ __forceinline__ void request_generation(const uint32_t *slots, uint32_t n, uint32_t (&e)[kEarly]) {
+__device__ __forceinline__ void place_request(const uint32_t *sizes, uint32_t tag, uint32_t t, const Place &pl,
+                                              uint32_t (&v)[kEarly]) {
 #pragma unroll
     for (int k = 0; k < kEarly; ++k) {
-        const uint32_t j = threadIdx.x + (uint32_t)k * 64u * NW;
-        e[k] = 0;
-        if (j < n) e[k] = word_load(slots + j);
+        const uint32_t j = pl.done + (uint32_t)k * 64u * NW + threadIdx.x;
+        v[k] = tag << 30;                 // "published, empty" for positions past the range
+        if (j < t) v[k] = word_load(sizes + j);
     }
 }
-
-// e: the words request_generation asked for (re-read here while they are not valid yet);
-// words beyond kEarly per thread are read here.  area: 5*kMaxWaves dwords of LDS.
-// All threads of the block call this (one barrier).
 template <int NW>
-__device__ __forceinline__ GenSums resolve_generation(const uint32_t *slots, uint32_t n, uint32_t wg, uint32_t tag,
-                                                      uint32_t spin_limit, const uint32_t (&e)[kEarly],
-                                                      uint32_t *area) {
-    constexpr uint32_t kThreads = 64 * NW;
-#ifdef X_NORESOLVE
-    { GenSums z; z.pre_w = z.pre_c = z.tot_w = z.tot_c = z.bad = 0; return z; }
-#endif
-    uint32_t pw = 0, pc = 0, tw = 0, tc = 0, bad = 0;
-    auto take = [&](uint32_t j, uint32_t v) {
+__device__ __forceinline__ Prefix place_finish(const Params &p, const uint32_t *sizes, uint32_t tag, uint32_t t,
+                                               Place &pl, const uint32_t (&v)[kEarly], uint32_t *area,
+                                               uint32_t *error_flag) {
+    constexpr uint32_t kThreads = 64u * NW;
+    const uint32_t lane = threadIdx.x & 63u, wv = threadIdx.x >> 6;
+    uint32_t sw = 0, sc = 0, bad = 0;
+    auto take = [&](uint32_t j, uint32_t w) {
         uint32_t spins = 0;
-        while ((v >> 30) != tag && spins < spin_limit) {
-            __builtin_amdgcn_s_sleep(2);
-            v = word_load(slots + j);
-            ++spins;
-        }
-        if ((v >> 30) != tag) { bad = 1; v = 0; }
-        const uint32_t w = (v >> 16) & 0x3FFFu, c = v & 0xFFFFu;
-        tw += w;
-        tc += c;
-        if (j < wg) { pw += w; pc += c; }
+        while ((w >> 30) != tag && keep_waiting(spins, p.spin_limit, error_flag)) w = word_load(sizes + j);
+        if ((w >> 30) != tag) { bad = 1; w = 0; }
+        sw += (w >> 16) & 0x3FFFu;
+        sc += w & 0xFFFFu;
     };
 #pragma unroll
-    for (int k = 0; k < kEarly; ++k) {
-        const uint32_t j = threadIdx.x + (uint32_t)k * kThreads;
-        if (j < n) take(j, e[k]);
-    }
-    for (uint32_t j = threadIdx.x + kEarly * kThreads; j < n; j += kThreads) take(j, word_load(slots + j));
+    for (int k = 0; k < kEarly; ++k) take(pl.done + (uint32_t)k * kThreads + threadIdx.x, v[k]);
+    for (uint32_t j = pl.done + kEarly * kThreads + threadIdx.x; j < t; j += kThreads) take(j, word_load(sizes + j));
 
-    pw = wave_sum_u32(pw); pc = wave_sum_u32(pc); tw = wave_sum_u32(tw); tc = wave_sum_u32(tc);
-    bad = __builtin_amdgcn_ballot_w64(bad != 0) != 0 ? 1u : 0u;
-    GenSums g;
-    if (NW == 1) {
-        g.pre_w = pw; g.pre_c = pc; g.tot_w = tw; g.tot_c = tc; g.bad = bad;
-        return g;
-    }
-    const uint32_t lane = threadIdx.x & 63, wv = threadIdx.x >> 6;
-    if (lane == 0) {
-        area[0 * kMaxWaves + wv] = pw; area[1 * kMaxWaves + wv] = pc; area[2 * kMaxWaves + wv] = tw;
-        area[3 * kMaxWaves + wv] = tc; area[4 * kMaxWaves + wv] = bad;
-    }
-    __syncthreads();
-    uint32_t s[5];
+    uint32_t r0 = wave_sum_u32(sw), r1 = wave_sum_u32(sc);
+    uint32_t r2 = __builtin_amdgcn_ballot_w64(bad != 0) != 0 ? 1u : 0u;
+    if (r2 && lane == 0) __hip_atomic_fetch_or(error_flag, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    if (NW > 1) {
+        if (lane == 0) { area[wv] = r0; area[kMaxWaves + wv] = r1; area[2 * kMaxWaves + wv] = r2; }
+        __syncthreads();
+        uint32_t a0 = 0, a1 = 0, a2 = 0;
 #pragma unroll
-    for (int k = 0; k < 5; ++k) {
-        uint32_t a = 0;
-#pragma unroll
-        for (int w = 0; w < NW; ++w) a += area[k * kMaxWaves + w];
-        s[k] = a;
+        for (int w = 0; w < NW; ++w) { a0 += area[w]; a1 += area[kMaxWaves + w]; a2 |= area[2 * kMaxWaves + w]; }
+        r0 = uniform(a0); r1 = uniform(a1); r2 = uniform(a2);
     }
-    g.pre_w = uniform(s[0]); g.pre_c = uniform(s[1]); g.tot_w = uniform(s[2]); g.tot_c = uniform(s[3]);
-    g.bad = uniform(s[4]);
-    return g;
+    pl.done = t;
+    pl.base_w += r0;
+    pl.base_c += r1;
+    Prefix x;
+    x.ew = pl.base_w;
+    x.ec = pl.base_c;
+    x.bad = r2;
+    return x;
 }
 
 // What a workgroup keeps of a token between computing it and storing it.
 struct Pending {
-    uint32_t out[8];   // packed codes of the lane's run (first `width` dwords)
-    uint32_t width, cnt, token, gen;
+    uint32_t width, cnt, words, token;
+    uint32_t parity;   // which payload image and which stash hold it
 };
 
-// LDS map (dynamic): row: runs*kRunLdsDw | ring: 4 reduce areas | two resolve areas | two stashes
-constexpr uint32_t kLdsRing = 4 * 2 * kMaxWaves, kLdsResolve = 5 * kMaxWaves;
-static_assert(kFusedScratchDw == kLdsRing + 2 * kLdsResolve + 2 * kStashCap, "LDS map of the fused kernel");
+// LDS map (dynamic): row: runs*16 | two payload images: runs*8 each | ring: 4 reduce areas |
+// 2 placement areas | 2 ticket slots (8 dwords) | two stashes
+constexpr uint32_t kLdsRing = 4 * 2 * kMaxWaves, kLdsPlace = 3 * kMaxWaves;
+static_assert(kFusedScratchDw == kLdsRing + 2 * kLdsPlace + 8 + 2 * kStashCap, "LDS map of the fused kernel");
 
 template <int DT, int NW>
 __global__ void __launch_bounds__(64 * NW, 4)
@@ -157,19 +204,28 @@ k_fused(const Params p, const uint16_t *__restrict__ in, uint8_t *__restrict__ b
     extern __shared__ __align__(16) uint32_t lds[];
     constexpr uint32_t kThreads = 64 * NW;
     uint32_t *lrow = lds;
-    uint32_t *ring = lds + p.runs * kRunLdsDw;
+    uint32_t *images = lds + p.runs * 16u;                  // packed codes of the current and the pending token
+    uint32_t *ring = images + 2u * p.runs * 8u;
     uint32_t *areas = ring + kLdsRing;
-    uint32_t *stashes = areas + 2 * kLdsResolve;            // 2 x kStashCap dwords: col << 16 | raw value
+    uint32_t *tslot = areas + 2 * kLdsPlace;                // next token, one slot per iteration parity
+    uint32_t *stashes = tslot + 8;                          // 2 x kStashCap dwords: col << 16 | raw value
     const uint32_t tid = threadIdx.x, run = tid;
     const uint32_t wg = blockIdx.x, G = gridDim.x;
     const bool owns = run < p.runs;
     const uint32_t left = owns ? p.pieces - 4 * run : 0;    // 16-byte pieces of the lane's run inside the row
 
     uint32_t *ctrl = reinterpret_cast<uint32_t *>(ws + p.ws_ctrl);
-    const uint32_t bank = ctrl[kCtlBank] & 1u;
-    uint32_t *table = reinterpret_cast<uint32_t *>(ws + p.ws_agg) + (size_t)bank * 4 * kFusedGridCap;
-    uint32_t *table_next = reinterpret_cast<uint32_t *>(ws + p.ws_agg) + (size_t)(1u - bank) * 4 * kFusedGridCap;
-    if (tid < 4) table_next[tid * kFusedGridCap + wg] = 0;
+    const uint32_t epoch = uniform(ctrl[kCtlEpoch]);
+    const uint32_t bank = epoch & 1u, tag = epoch % 3u + 1u;
+    uint32_t *sizes = reinterpret_cast<uint32_t *>(ws + p.ws_sizes);
+    uint32_t *tickets = reinterpret_cast<uint32_t *>(ws + p.ws_tickets) + (size_t)bank * kTicketClasses * kTicketStride;
+
+    // ticket class of this workgroup: class c owns the tokens t % C == c; its first Wc tokens go to
+    // its Wc workgroups without a ticket (workgroup g starts with token g)
+    const uint32_t C = p.fused_classes, cls = wg % C;
+    const uint32_t n_cls = (p.tokens - cls + C - 1u) / C;   // tokens of the class
+    const uint32_t w_cls = (G - cls + C - 1u) / C;          // workgroups of the class
+    uint32_t *counter = tickets + cls * kTicketStride;
 
     uint8_t *bits = blob + p.off_bits;
     float *scale = reinterpret_cast<float *>(blob + p.off_scale);
@@ -184,144 +240,143 @@ k_fused(const Params p, const uint16_t *__restrict__ in, uint8_t *__restrict__ b
     auto fetch_row = [&](uint32_t t) {
         fetch_row_part(reinterpret_cast<const uint4 *>(in + (size_t)t * p.hidden), p.pieces, pre);
     };
-    auto write_row = [&]() { write_row_part(lrow, p.runs, pre); };
+    auto write_row = [&]() { write_row_part_sw(lrow, p.runs, pre); };
 
-    uint32_t base_w = 0, base_c = 0;     // totals of all generations already resolved
+    Place pl;
+    pl.done = 0; pl.base_w = 0; pl.base_c = 0;
     uint32_t failed = 0, turn = 0;
     Pending pd;
     bool have_pending = false;
-    pd.width = 8; pd.cnt = 0; pd.token = 0; pd.gen = 0;
-#pragma unroll
-    for (int k = 0; k < 8; ++k) pd.out[k] = 0;
+    pd.width = 8; pd.cnt = 0; pd.words = 0; pd.token = 0; pd.parity = 0;
+    uint32_t last_stored = kNoToken, last_ew = 0, last_ec = 0, last_words = 0, last_cnt = 0;
 
-    auto gen_size = [&](uint32_t gen) { return p.tokens - gen * G < G ? p.tokens - gen * G : G; };
-
-    // stores a token whose generation sums are known: payload from registers, outliers from its stash
-    auto store_token = [&](const Pending &q, const GenSums &g, bool from_stash) {
-        const uint32_t ew = base_w + g.pre_w, ec = base_c + g.pre_c;
+    // stores a token whose prefix is known: payload from registers, outliers from its stash
+    auto store_token = [&](const Pending &q, const Prefix &x, bool from_stash) {
+        // never store outside the payload section, whatever the table said
+        if ((uint64_t)x.ew + q.words > (p.payload_capacity >> 2)) { failed = 1; return; }
         if (tid == 0) {
-            pay_off[q.token] = (uint64_t)ew << 2;
-            row_ptr[q.token] = ec;
+            pay_off[q.token] = (uint64_t)x.ew << 2;
+            row_ptr[q.token] = x.ec;
         }
-        if (owns) {
-            uint32_t *dst = payload + ew + run * q.width;
-            if (left >= 4) {
-                switch (q.width) {
-                    case 2: store_dwords<2>(dst, q.out); break;
-                    case 3: store_dwords<3>(dst, q.out); break;
-                    case 4: store_dwords<4>(dst, q.out); break;
-                    case 5: store_dwords<5>(dst, q.out); break;
-                    case 6: store_dwords<6>(dst, q.out); break;
-                    case 7: store_dwords<7>(dst, q.out); break;
-                    default: store_dwords<8>(dst, q.out); break;
-                }
-            } else {
-                const uint32_t nd = (left * q.width + 3u) >> 2;
-#pragma unroll
-                for (uint32_t k = 0; k < 8; ++k)
-                    if (k < nd) dst[k] = q.out[k];
+        {
+            // the token's payload image, LDS -> HBM, 16 bytes per thread and step
+            const uint32_t *img = images + q.parity * p.runs * 8u;
+            uint32_t *dst = payload + x.ew;
+            const uint32_t quads = q.words >> 2;
+            for (uint32_t i = tid; i < quads; i += kThreads) {
+                const uint4 v = *reinterpret_cast<const uint4 *>(img + 4u * i);
+                *reinterpret_cast<Dw4 *>(dst + 4u * i) = Dw4{v.x, v.y, v.z, v.w};
             }
+            const uint32_t rest = q.words & 3u;
+            if (tid < rest) dst[4u * quads + tid] = img[4u * quads + tid];
         }
-        if (from_stash && q.cnt > 0 && (uint64_t)ec + q.cnt <= p.outlier_capacity) {
-            const uint32_t *stash = stashes + (q.gen & 1u) * kStashCap;
+        if (from_stash && q.cnt > 0 && (uint64_t)x.ec + q.cnt <= p.outlier_capacity) {
+            const uint32_t *stash = stashes + q.parity * kStashCap;
             for (uint32_t k = tid; k < q.cnt; k += kThreads) {
                 const uint32_t e = stash[k];
-                out_col[(size_t)ec + k] = (uint16_t)(e >> 16);
-                out_val[(size_t)ec + k] = (uint16_t)e;
+                out_col[(size_t)x.ec + k] = (uint16_t)(e >> 16);
+                out_val[(size_t)x.ec + k] = (uint16_t)e;
             }
         }
+        last_stored = q.token; last_ew = x.ew; last_ec = x.ec; last_words = q.words; last_cnt = q.cnt;
     };
 
-    uint32_t t = wg;
+    // ---- first token: the workgroup's own id; its row; the ticket of the second token
+    uint32_t t = wg;                       // the grid never exceeds the token count
     fetch_row(t);
+    uint32_t req = 0;                      // thread 0: the ticket in flight
+    bool requesting = true;                // uniform: a ticket is in flight
+    if (tid == 0) req = __hip_atomic_fetch_add(counter, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     write_row();
 
     uint32_t it = 0;
-    for (; t < p.tokens; ++it, t += G) {
-        const uint32_t tn = t + G;
-        // the table words of the pending token's generation: asked for now, used after the width search
+    for (; t != kNoToken; ++it) {
+        // ---- the ticket requested an iteration ago: the token after this one; ask for the one after that
+        if (tid == 0) {
+            uint32_t tn = kNoToken;
+            if (requesting) {
+                const uint32_t k = w_cls + req;
+                if (k < n_cls) {
+                    tn = k * C + cls;
+                    req = __hip_atomic_fetch_add(counter, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                }
+            }
+            tslot[it & 1u] = tn;
+        }
+
+        // the table words before the pending token: asked for now, used after the width search
         uint32_t early[kEarly];
-#ifndef X_NORESOLVE
-        if (have_pending)
-            request_generation<NW>(table + (pd.gen & 3u) * kFusedGridCap, gen_size(pd.gen), early);
-#endif
+        if (have_pending) place_request<NW>(sizes, tag, pd.token, pl, early);
 
         // ---- Eq. (ts) and Algorithm 1 for token t
         Mags<DT> mg;
         uint32_t omask = 0, amax_bits = 0;
-        split_run<DT, true>(lrow + (owns ? run : 0u) * kRunLdsDw, p.thr_pk, mg, omask, amax_bits);
+        {
+            uint32_t w[16];
+            load_run_sw(lrow, owns ? run : 0u, w);
+            split_regs<DT, true>(w, p.thr_pk, mg, omask, amax_bits);
+        }
         if (!owns) omask = 0;
         uint32_t m[8], cnt_before;
         const Choice c = choose_width<DT, NW>(p, mg, omask, amax_bits, owns, ring, turn, m, cnt_before);
+        const uint32_t tn = uniform(tslot[it & 1u]);     // written before the barrier inside choose_width
+        requesting = tn != kNoToken;
         const uint32_t words = row_bytes(p.hidden, c.width) >> 2;
         if (tid == 0) {
-            word_store(table + (it & 3u) * kFusedGridCap + wg, (gen_tag(it) << 30) | (words << 16) | c.cnt);
+            word_store(sizes + t, (tag << 30) | (words << 16) | c.cnt);
             bits[t] = (uint8_t)c.width;
             scale[t] = scale_of(c.amax, c.width);
         }
         // the next row starts its way from HBM now that the registers of the width search are free
-        if (tn < p.tokens) fetch_row(tn);
+        if (tn != kNoToken) fetch_row(tn);
 
-        // ---- codes of the lane's run at the chosen width
+        // ---- codes of the lane's run at the chosen width, into this iteration's payload image
         Pending cur;
-        cur.width = c.width; cur.cnt = c.cnt; cur.token = t; cur.gen = it;
-#pragma unroll
-        for (int k = 0; k < 8; ++k) cur.out[k] = 0;
+        cur.width = c.width; cur.cnt = c.cnt; cur.words = words; cur.token = t; cur.parity = it & 1u;
         if (owns) {
             uint32_t wr[16];
-            load_run_padded(lrow + run * kRunLdsDw, wr);
+            load_run_sw(lrow, run, wr);
+            uint32_t *dst = images + cur.parity * p.runs * 8u + run * c.width;
+            const uint32_t nd = left >= 4 ? c.width : ((left * c.width + 3u) >> 2);
             switch (c.width) {
-                case 2: pack_into<2>(m, wr, cur.out); break;
-                case 3: pack_into<3>(m, wr, cur.out); break;
-                case 4: pack_into<4>(m, wr, cur.out); break;
-                case 5: pack_into<5>(m, wr, cur.out); break;
-                case 6: pack_into<6>(m, wr, cur.out); break;
-                case 7: pack_into<7>(m, wr, cur.out); break;
-                default: pack_into<8>(m, wr, cur.out); break;
+                case 2: pack_to_image<2>(m, wr, dst, nd); break;
+                case 3: pack_to_image<3>(m, wr, dst, nd); break;
+                case 4: pack_to_image<4>(m, wr, dst, nd); break;
+                case 5: pack_to_image<5>(m, wr, dst, nd); break;
+                case 6: pack_to_image<6>(m, wr, dst, nd); break;
+                case 7: pack_to_image<7>(m, wr, dst, nd); break;
+                default: pack_to_image<8>(m, wr, dst, nd); break;
             }
         }
 
         // ---- store the token of the previous iteration
         if (have_pending) {
-#ifdef X_NORESOLVE
-            GenSums g; g.pre_w = g.pre_c = g.tot_w = g.tot_c = g.bad = 0;
-#else
-            const GenSums g = resolve_generation<NW>(table + (pd.gen & 3u) * kFusedGridCap, gen_size(pd.gen), wg,
-                                                     gen_tag(pd.gen), p.spin_limit, early,
-                                                     areas + (pd.gen & 1u) * kLdsResolve);
-#endif
-            failed |= g.bad;
-#ifndef X_NOSTORE
-            if (!g.bad) store_token(pd, g, true);
-#endif
-            base_w += g.tot_w;
-            base_c += g.tot_c;
+            const Prefix x = place_finish<NW>(p, sizes, tag, pd.token, pl, early, areas + (it & 1u) * kLdsPlace,
+                                              ctrl + kCtlError);
+            failed |= x.bad;
+            if (!x.bad) store_token(pd, x, true);
             have_pending = false;
         }
 
-        // ---- T_above of token t: into this generation's stash in column order, or straight out if
+        // ---- T_above of token t: into this iteration's stash in column order, or straight out if
         //      it is too long for the stash
         bool placed = false;
         if (c.cnt > 0) {
             const uint32_t nl = (uint32_t)__builtin_popcount(omask);
             const uint32_t loff = cnt_before + wave_incl_scan_u32(nl) - nl;
             const bool stashed = c.cnt <= kStashCap;
-            GenSums g;
-            g.pre_w = g.pre_c = g.tot_w = g.tot_c = g.bad = 0;
-            uint32_t ec = 0;
+            Prefix x;
+            x.ew = x.ec = x.bad = 0;
             bool direct_ok = false;
             if (!stashed) {
                 // rare: more outliers than the stash holds.  Place the token now.
                 uint32_t now[kEarly];
-                request_generation<NW>(table + (it & 3u) * kFusedGridCap, gen_size(it), now);
-                g = resolve_generation<NW>(table + (it & 3u) * kFusedGridCap, gen_size(it), wg, gen_tag(it),
-                                           p.spin_limit, now, areas + (it & 1u) * kLdsResolve);
-                failed |= g.bad;
-                ec = base_c + g.pre_c;
-                direct_ok = !g.bad && (uint64_t)ec + c.cnt <= p.outlier_capacity;
+                place_request<NW>(sizes, tag, t, pl, now);
+                x = place_finish<NW>(p, sizes, tag, t, pl, now, areas + ((it + 1u) & 1u) * kLdsPlace, ctrl + kCtlError);
+                failed |= x.bad;
+                direct_ok = !x.bad && (uint64_t)x.ec + c.cnt <= p.outlier_capacity;
             }
             if (omask && (stashed || direct_ok)) {
-                const uint16_t *raw = reinterpret_cast<const uint16_t *>(lrow + run * kRunLdsDw);
                 uint32_t *stash = stashes + (it & 1u) * kStashCap;
                 uint32_t pos = loff;
                 uint32_t ev = omask & 0xFFFFu, od = omask >> 16;
@@ -332,57 +387,62 @@ k_fused(const Params p, const uint16_t *__restrict__ in, uint8_t *__restrict__ b
                     if (je < jo) { j = je; ev &= ev - 1u; } else { j = jo; od &= od - 1u; }
                     const uint32_t col = run * kRun + j;
                     if (stashed) {
-                        stash[pos] = (col << 16) | raw[j];
+                        stash[pos] = (col << 16) | raw_element_sw(lrow, run, j);
                     } else {
-                        out_col[(size_t)ec + pos] = (uint16_t)col;
-                        out_val[(size_t)ec + pos] = raw[j];
+                        out_col[(size_t)x.ec + pos] = (uint16_t)col;
+                        out_val[(size_t)x.ec + pos] = (uint16_t)raw_element_sw(lrow, run, j);
                     }
                     ++pos;
                 }
             }
             if (!stashed) {
-                if (!g.bad) store_token(cur, g, false);
-                base_w += g.tot_w;
-                base_c += g.tot_c;
+                if (!x.bad) store_token(cur, x, false);
                 placed = true;
             }
         }
         have_pending = !placed;
         pd = cur;
 
-        if (tn < p.tokens) write_row();   // this wave is done with its part of the row
+        if (tn != kNoToken) write_row();  // this wave is done with its part of the row
+        t = tn;
     }
 
     // ---- the last token of this workgroup
-    GenSums g;
-    g.pre_w = g.pre_c = g.tot_w = g.tot_c = g.bad = 0;
     if (have_pending) {
         uint32_t now[kEarly];
-        if (NW > 1) __syncthreads();      // the stash of the last token is complete
-#ifndef X_NORESOLVE
-        request_generation<NW>(table + (pd.gen & 3u) * kFusedGridCap, gen_size(pd.gen), now);
-        g = resolve_generation<NW>(table + (pd.gen & 3u) * kFusedGridCap, gen_size(pd.gen), wg, gen_tag(pd.gen),
-                                   p.spin_limit, now, areas + (pd.gen & 1u) * kLdsResolve);
-#endif
-        failed |= g.bad;
-        if (!g.bad) store_token(pd, g, true);
+        place_request<NW>(sizes, tag, pd.token, pl, now);
+        const Prefix x = place_finish<NW>(p, sizes, tag, pd.token, pl, now, areas + (it & 1u) * kLdsPlace,
+                                          ctrl + kCtlError);
+        failed |= x.bad;
+        if (!x.bad) store_token(pd, x, true);
     }
-    if (failed && tid == 0) {
-        __hip_atomic_fetch_or(ctrl + kCtlError, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        write_header(p, blob, 0, 0, 6u);    // the header may already be final: overwrite it
-    }
-    // the workgroup that owns the last token closes the blob
-    if (pd.token == p.tokens - 1u && tid == 0) {
-        // totals: everything before the last generation plus the last generation itself; if the
-        // last token was placed directly, base already contains its generation
-        const uint64_t nnz = have_pending ? (uint64_t)base_c + g.tot_c : base_c;
-        const uint64_t wordsum = have_pending ? (uint64_t)base_w + g.tot_w : base_w;
-        row_ptr[p.tokens] = nnz;
-        pay_off[p.tokens] = wordsum << 2;
-        const uint32_t err = failed | __hip_atomic_load(ctrl + kCtlError, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        write_header(p, blob, nnz, wordsum << 2, err ? 6u : (nnz > p.outlier_capacity ? 3u : 0u));
-        __hip_atomic_store(ctrl + kCtlError, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        __hip_atomic_store(ctrl + kCtlBank, bank ^ 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    if (failed && tid == 0) write_header(p, blob, 0, 0, 6u);   // the header may already be final: overwrite it
+
+    // ---- the workgroup that stored the last token closes the blob and prepares the next call
+    if (last_stored == p.tokens - 1u) {
+        const uint64_t nnz = (uint64_t)last_ec + last_cnt, wordsum = (uint64_t)last_ew + last_words;
+        // every workgroup draws exactly one failing ticket, after which all counters add up to the
+        // token count; until then somebody may not even have read the epoch yet
+        uint32_t spins = 0, drawn = 0;
+        for (;;) {
+            uint32_t v = 0;
+            if ((tid & 63u) < C) v = word_load(tickets + (tid & 63u) * kTicketStride);
+            drawn = wave_sum_u32(v);                          // C <= 64 classes: one lane each
+            if (drawn == p.tokens || !keep_waiting(spins, p.spin_limit, ctrl + kCtlError)) break;
+        }
+        const bool late = drawn != p.tokens;
+        uint32_t *tickets_next =
+            reinterpret_cast<uint32_t *>(ws + p.ws_tickets) + (size_t)(1u - bank) * kTicketClasses * kTicketStride;
+        for (uint32_t i = tid; i < kTicketClasses; i += kThreads) tickets_next[i * kTicketStride] = 0;
+        if (tid == 0) {
+            row_ptr[p.tokens] = nnz;
+            pay_off[p.tokens] = wordsum << 2;
+            const uint32_t err = failed | (late ? 1u : 0u) |
+                                 __hip_atomic_load(ctrl + kCtlError, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            write_header(p, blob, nnz, wordsum << 2, err ? 6u : (nnz > p.outlier_capacity ? 3u : 0u));
+            __hip_atomic_store(ctrl + kCtlError, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            __hip_atomic_store(ctrl + kCtlEpoch, epoch + 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        }
     }
 }
 
@@ -416,7 +476,7 @@ uint32_t compress_waves(uint32_t runs) {
 }
 
 int prepare_fused_kernels() {
-    const int big = (int)(((kMaxHidden / kRun) * kRunLdsDw + kFusedScratchDw) * 4);
+    const int big = (int)(((kMaxHidden / kRun) * 32u + kFusedScratchDw) * 4);
     static const uint32_t sizes[] = {1, 2, 3, 4, 8, 16};
     for (uint32_t dt = 0; dt < 2; ++dt)
         for (uint32_t nw : sizes) {
@@ -452,17 +512,21 @@ int launch_fused(const Params &p, const Geometry &g, uint32_t grid, const void *
 // ---------------------------------------------------------------- workspace reset
 
 __global__ void k_ws_reset(const Params p, uint8_t *__restrict__ ws) {
-    uint32_t *table = reinterpret_cast<uint32_t *>(ws + p.ws_agg);
+    uint32_t *sizes = reinterpret_cast<uint32_t *>(ws + p.ws_sizes);
+    uint32_t *tickets = reinterpret_cast<uint32_t *>(ws + p.ws_tickets);
     uint32_t *ctrl = reinterpret_cast<uint32_t *>(ws + p.ws_ctrl);
-    const uint32_t i = blockIdx.x * blockDim.x + threadIdx.x;
-    if (i < 2u * 4u * kFusedGridCap) table[i] = 0;
-    if (i < 64) ctrl[i] = 0;
+    const uint32_t stride = gridDim.x * blockDim.x;
+    for (uint32_t i = blockIdx.x * blockDim.x + threadIdx.x; i < p.tokens; i += stride) sizes[i] = 0;
+    for (uint32_t i = blockIdx.x * blockDim.x + threadIdx.x; i < 2u * kTicketClasses * kTicketStride; i += stride)
+        tickets[i] = 0;
+    if (blockIdx.x == 0 && threadIdx.x < 64) ctrl[threadIdx.x] = 0;
 }
 
 int launch_ws_reset(const Params &p, void *d_ws, void *stream) {
-    const uint32_t n = 2u * 4u * kFusedGridCap;
-    hipLaunchKernelGGL(k_ws_reset, dim3((n + 255) / 256), dim3(256), 0, as_stream(stream), p,
-                       static_cast<uint8_t *>(d_ws));
+    uint32_t blocks = (p.tokens + 255u) / 256u;
+    if (blocks < 32) blocks = 32;
+    if (blocks > 1024) blocks = 1024;
+    hipLaunchKernelGGL(k_ws_reset, dim3(blocks), dim3(256), 0, as_stream(stream), p, static_cast<uint8_t *>(d_ws));
     return (int)hipGetLastError();
 }
 

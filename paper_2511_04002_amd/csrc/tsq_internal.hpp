@@ -19,11 +19,13 @@ constexpr int kMaxWaves = 16;   // 1024 threads per workgroup at most
 constexpr uint32_t kScratchDw = 4 * 2 * kMaxWaves + kMaxWaves;
 constexpr uint32_t kMaxHidden = 32768;
 // fused kernel: outliers of one token that fit an LDS stash (longer tokens take a slower path),
-// the largest persistent grid (table slots per generation), and its LDS behind the row in dwords
-// (four reduce areas, two areas of generation sums, two stashes)
-constexpr uint32_t kStashCap = 1024;
+// the largest persistent grid, the ticket classes (one counter each, kTicketStride dwords apart
+// so that no two share a 256-byte line), and its LDS behind the row in dwords (four reduce
+// areas, two placement areas, ticket slots, two stashes)
+constexpr uint32_t kStashCap = 512;
 constexpr uint32_t kFusedGridCap = 4096;
-constexpr uint32_t kFusedScratchDw = 4 * 2 * kMaxWaves + 2 * 5 * kMaxWaves + 2 * kStashCap;
+constexpr uint32_t kTicketClasses = 64, kTicketStride = 64;
+constexpr uint32_t kFusedScratchDw = 4 * 2 * kMaxWaves + 2 * 3 * kMaxWaves + 8 + 2 * kStashCap;
 
 // 128-byte header at the start of every blob.
 struct BlobHeader {
@@ -54,9 +56,11 @@ struct Params {
     // workspace sections (bytes from d_ws)
     uint64_t ws_cnt;        // u32[T]  outliers per token           (staged)
     uint64_t ws_amax;       // f32[T]  inlier absmax per token      (staged)
-    uint64_t ws_agg;        // u32[2][4][kFusedGridCap] published (words, count) pairs: two banks
-                            //   (alternating calls) of four generation slots per workgroup (fused)
-    uint64_t ws_ctrl;       // u32[64]   bank of the next call, error flag           (fused)
+    uint64_t ws_sizes;      // u32[T]   published (tag, words, count) of every token   (fused)
+    uint64_t ws_tickets;    // u32[2][kTicketClasses][kTicketStride] ticket counters, two banks (fused)
+    uint64_t ws_ctrl;       // u32[64]  epoch (calls completed), error flag            (fused)
+    uint32_t fused_classes; // ticket classes in use: min(kTicketClasses, grid)        (fused)
+    uint32_t pad1;
 };
 
 inline __host__ __device__ uint32_t width_at(const Params &p, uint32_t i) {
