@@ -41,6 +41,8 @@ def parse():
     ap.add_argument("--nbuf", type=int, default=4, help="buffer sets rotated through")
     ap.add_argument("--bits", default="", help="allowed widths, e.g. 2,4,8 (default: the workload's set)")
     ap.add_argument("--c5-seqs", type=int, default=32)
+    ap.add_argument("--c5-workers", type=int, default=8,
+                    help="processes that generate C5 (use 1 under a profiler: its preloaded tool does not survive a fork)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-sample-rows", type=int, default=0, help="0 = sized for about 10-30 s")
     return ap.parse_args()
@@ -50,7 +52,7 @@ def make_input(args):
     from paper_2511_04002_amd import synth
     w = synth.WORKLOADS[args.workload]
     if args.workload == "C5":
-        x = synth.make_c5(seqs=args.c5_seqs, workers=8)
+        x = synth.make_c5(seqs=args.c5_seqs, workers=args.c5_workers)
     elif args.workload == "C3":
         x = synth.make_c3(0)
     else:
@@ -84,13 +86,13 @@ def main():
               "run with --gpus 1", file=sys.stderr)
         sys.exit(2)
     import numpy as np
+    w, x = make_input(args)               # host only, before anything touches the GPU (it may fork)
     import torch
     from paper_2511_04002_amd import tsq
 
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     tsq.lib()
     torch.cuda.set_device(0)
-    w, x = make_input(args)
     T, H = x.shape
     pipe = "fused" if args.pipeline == "auto" else args.pipeline     # what "auto" resolves to
     bit_set = tuple(int(b) for b in args.bits.split(",")) if args.bits else tuple(w.bit_set)

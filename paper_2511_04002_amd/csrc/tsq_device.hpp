@@ -139,11 +139,10 @@ __device__ __forceinline__ float masked_low_half_as_bf16(uint32_t w, uint32_t in
         : "v"(w), "v"(inl));
     return __uint_as_float(d);
 }
-// (keep & sel) | (old & ~sel) with sel in a scalar register: one v_bfi_b32
+// bits `sel` of keep into old: an and with a literal, merged by the compiler into three-way ors
+// (a bit-field insert would need the 16 masks in scalar registers, which the kernels cannot spare)
 __device__ __forceinline__ uint32_t bit_insert(uint32_t sel, uint32_t keep, uint32_t old) {
-    uint32_t d;
-    asm("v_bfi_b32 %0, %1, %2, %3" : "=v"(d) : "s"(sel), "v"(keep), "v"(old));
-    return d;
+    return old | (keep & sel);
 }
 
 // Threshold splitting (Eq. (ts)) of the 32 elements a lane owns, on the 16-bit magnitude
@@ -160,7 +159,7 @@ __device__ __forceinline__ uint32_t bit_insert(uint32_t sel, uint32_t keep, uint
 template <int DT, bool WANT_MAX>
 __device__ __forceinline__ void split_regs(const uint32_t (&w)[16], uint32_t thr_pk, Mags<DT> &mg, uint32_t &omask,
                                            uint32_t &amax_bits) {
-    uint32_t im = 0;
+    uint32_t im = 0;                       // inlier flags, collected bit by bit
     if constexpr (DT == kBF16) {
         uint32_t mx = 0;                   // non-negative binary32 patterns order like unsigned integers
 #pragma unroll

@@ -226,3 +226,113 @@ def test_decompress_refuses_a_foreign_blob(tsq):
     assert bool((out == 0x0BAD).all())
     info = plan.info(blob, check=False)
     assert info.return_status == tsq.TSQ_ERR_FORMAT
+
+
+@pytest.mark.parametrize("pipeline", PIPELINES)
+def test_workspace_and_plan_serve_many_calls(tsq, oracle, pipeline):
+    # one plan, one workspace, eleven calls on changing inputs: whatever a call leaves in the
+    # workspace (tags, ticket counters, epoch) must not leak into the next one
+    import torch
+    T, H = 700, 2048
+    g = np.random.Generator(np.random.PCG64(11))
+    xs = []
+    for k in range(3):
+        v = g.standard_normal((T, H)) * g.lognormal(0.0, 0.6, (T, 1))
+        v[:, g.choice(H, 5, replace=False)] *= 40.0
+        xs.append(synth.to_bf16_bits(v))
+    refs = [oracle.compress(x, BF16, 8.0, (2, 4, 5, 8), 0.1, 1, nthreads=8) for x in xs]
+    plan = tsq.Plan(T, H, "bf16", 8.0, (2, 4, 5, 8), 0.1, pipeline=pipeline)
+    ws = plan.new_workspace()
+    blob = plan.new_blob()
+    out = plan.new_output()
+    for call in range(11):
+        k = (call * 2) % 3
+        print("call", call, "input", k, flush=True)
+        plan.compress(torch.from_numpy(xs[k].view(np.int16)).cuda(), blob, ws)
+        info = plan.info(blob)
+        sec = plan.sections(blob)
+        ref = refs[k]
+        assert info.status == 0 and info.nnz == ref.nnz and info.payload_bytes == ref.payload_bytes
+        for name, want in (("bits", ref.bits), ("row_ptr", ref.row_ptr), ("pay_off", ref.pay_off),
+                           ("out_col", ref.out_col), ("out_val", ref.out_val), ("payload", ref.payload)):
+            assert np.array_equal(sec[name], want), (call, name)
+        plan.decompress(blob, out)
+        assert np.array_equal(out.cpu().numpy().view(np.uint16), oracle.decompress(ref, nthreads=8)), call
+
+
+@pytest.mark.parametrize("pipeline", PIPELINES)
+@pytest.mark.parametrize("T,H", [(1, 64), (2, 64), (63, 64), (64, 64), (65, 64), (130, 256), (1025, 256),
+                                 (4097, 64), (9000, 64), (5000, 2048 + 64)])
+def test_token_counts_around_the_grid_size(tsq, oracle, pipeline, T, H):
+    # fewer tokens than workgroups, exactly as many, and several per workgroup (short rows keep
+    # many workgroups resident, so the larger counts need more than one round of tickets)
+    g = np.random.Generator(np.random.PCG64(T * 131 + H))
+    v = g.standard_normal((T, H)) * g.lognormal(0.0, 0.8, (T, 1))
+    v[g.random((T, H)) < 0.004] *= 30.0
+    x = synth.to_f16_bits(v)
+    check_parity(tsq, oracle, x, "f16", 6.0, (2, 3, 4, 6, 8), 0.15, "rel_rms", pipeline, label="T=%d H=%d" % (T, H))
+
+
+@pytest.mark.parametrize("pipeline", PIPELINES)
+def test_tokens_with_more_outliers_than_the_stash_holds(tsq, oracle, pipeline):
+    # rows whose outlier count exceeds what the single-pass kernel keeps in LDS (512) are placed
+    # by its direct path; mix them with ordinary rows and with rows that are all outliers
+    g = np.random.Generator(np.random.PCG64(5))
+    T, H = 300, 4096
+    v = g.standard_normal((T, H))
+    heavy = g.choice(T, 40, replace=False)
+    for i, t in enumerate(heavy):
+        n = (513, 600, 1024, 2048, 4096)[i % 5]
+        v[t, g.choice(H, n, replace=False)] = 50.0 * g.choice([-1.0, 1.0], n)
+    x = synth.to_bf16_bits(v)
+    ref, _ = check_parity(tsq, oracle, x, "bf16", 6.0, (2, 4, 8), 0.05, "rel_rms", pipeline, label="heavy rows")
+    cnt = np.diff(ref.row_ptr.astype(np.int64))
+    assert (cnt > 512).sum() >= 40 and cnt.max() == H
+
+
+def test_c5_stress_full_size_sampled_rows(tsq, oracle):
+    # the whole heavy-outlier workload (131072 x 8192 bf16, 2 GiB) in the configuration bench.py
+    # times; the oracle recomputes a sample of rows one by one, the rest is checked through
+    # properties that hold for every row
+    import torch
+    tau, bit_set, eps = 8.0, (2, 4, 8), 0.05
+    print("generating C5", flush=True)
+    x = synth.make_c5(workers=8)
+    T, H = x.shape
+    plan = tsq.Plan(T, H, "bf16", tau, bit_set, eps, max_outliers=(T * H) // 16)
+    xd = torch.from_numpy(x.view(np.int16)).cuda()
+    print("compress", flush=True)
+    blob = plan.compress(xd)
+    info = plan.info(blob)
+    assert info.status == 0
+    out = plan.decompress(blob)
+    sec = plan.sections(blob)
+    bits, pay_off, row_ptr = sec["bits"], sec["pay_off"].astype(np.int64), sec["row_ptr"].astype(np.int64)
+    # properties: widths from the allowed set, offsets are the exclusive sums of the closed-form sizes
+    assert set(np.unique(bits).tolist()) <= set(bit_set)
+    sizes = 4 * ((H * bits.astype(np.int64) + 31) // 32)
+    assert np.array_equal(pay_off, np.concatenate([[0], np.cumsum(sizes)]))
+    assert info.payload_bytes == int(sizes.sum())
+    # outlier counts of every row against an independent numpy count, in slabs
+    cnt = np.empty(T, np.int64)
+    for a in range(0, T, 8192):
+        mag = (x[a:a + 8192].astype(np.uint32) & 0x7FFF) << 16
+        cnt[a:a + 8192] = (~(mag.view(np.float32) < np.float32(tau))).sum(axis=1)
+    assert np.array_equal(row_ptr, np.concatenate([[0], np.cumsum(cnt)]))
+    assert info.nnz == int(cnt.sum())
+    assert info.compressed_bytes == 128 + 5 * T + 16 * (T + 1) + int(sizes.sum()) + 4 * int(cnt.sum())
+    # sampled rows, element by element
+    g = np.random.Generator(np.random.PCG64(99))
+    rows = np.unique(np.concatenate([[0, 1, T - 2, T - 1, 4095, 4096], g.choice(T, 250, replace=False),
+                                     np.argsort(cnt)[-3:]]))
+    ref = oracle.compress(np.ascontiguousarray(x[rows]), BF16, tau, bit_set, eps, 1, nthreads=8)
+    ref_out = oracle.decompress(ref, nthreads=8)
+    got_out = out[torch.from_numpy(rows).cuda()].cpu().numpy().view(np.uint16)
+    assert np.array_equal(got_out, ref_out), "decoded rows"
+    assert np.array_equal(bits[rows], ref.bits)
+    assert np.array_equal(sec["scale"][rows].view(np.uint32), ref.scale.view(np.uint32))
+    rp, po = ref.row_ptr.astype(np.int64), ref.pay_off.astype(np.int64)
+    for i, t in enumerate(rows):
+        assert np.array_equal(sec["payload"][pay_off[t]:pay_off[t + 1]], ref.payload[po[i]:po[i + 1]]), t
+        assert np.array_equal(sec["out_col"][row_ptr[t]:row_ptr[t + 1]], ref.out_col[rp[i]:rp[i + 1]]), t
+        assert np.array_equal(sec["out_val"][row_ptr[t]:row_ptr[t + 1]], ref.out_val[rp[i]:rp[i + 1]]), t
