@@ -22,11 +22,12 @@ if ROOT not in sys.path:
 HBM_PEAK_GBS = 8000.0     # MI355X HBM3E, published peak
 
 # HBM bytes per launch from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of this command, scaled by
-# what the same counters read for a plain 128 MiB copy (profiles/C4_staged_hbm_traffic.txt);
+# what the same counters read for a plain 128 MiB copy (profiles/C4_*_hbm_traffic.txt);
 # keyed by (workload, pipeline, eps) -> kernel -> bytes.  None where no such run was made.
 TRAFFIC = {
     ("C4", "staged", 0.05): {"k_row_stats": 134.3e6 + 0.6e6, "k_pack": 136.6e6 + 62.7e6,
                              "k_unpack": 67.1e6 + 134.2e6, "k_scan": 0.2e6},
+    ("C4", "fused", 0.05): {"k_fused": 141.4e6 + 81.0e6, "k_unpack": 67.1e6 + 134.2e6},
 }
 
 
@@ -60,7 +61,7 @@ def make_input(args):
     return w, x
 
 
-def cpu_baseline(x, w, eps, rows):
+def cpu_baseline(x, w, bit_set, eps, rows):
     """The oracle as it stands, on a bounded sample of the same workload."""
     from oracle import tsq_oracle as O
     O.build()
@@ -68,15 +69,23 @@ def cpu_baseline(x, w, eps, rows):
     threads = min(O.max_threads(), os.cpu_count() or 1, 16)
     rows = min(rows, x.shape[0])
     xs = x[:rows]
-    t0 = time.perf_counter()
-    c = O.compress(xs, dt, w.tau, w.bit_set, eps, O.BUDGET_REL_RMS, nthreads=threads)
-    t1 = time.perf_counter()
-    O.decompress(c, nthreads=threads)
-    t2 = time.perf_counter()
     gb = xs.size * 2 / 1e9
-    return {"value": gb / (t2 - t0), "unit": "GB/s", "cores": threads, "kind": "oracle",
-            "sample": "first %d of %d rows of %s, compress %.3f s + decompress %.3f s, %d threads"
-                      % (rows, x.shape[0], w.name, t1 - t0, t2 - t1, threads)}
+    # repeat the sample until about 15 core-seconds of work have been done; report the best pass
+    best, passes, spent = None, 0, 0.0
+    while passes < 1 or (spent * threads < 15.0 and passes < 50):
+        t0 = time.perf_counter()
+        c = O.compress(xs, dt, w.tau, bit_set, eps, O.BUDGET_REL_RMS, nthreads=threads)
+        t1 = time.perf_counter()
+        O.decompress(c, nthreads=threads)
+        t2 = time.perf_counter()
+        passes += 1
+        spent += t2 - t0
+        if best is None or t2 - t0 < best[0]:
+            best = (t2 - t0, t1 - t0, t2 - t1)
+    return {"value": gb / best[0], "unit": "GB/s", "cores": threads, "kind": "oracle",
+            "sample": "first %d of %d rows of %s, best of %d passes (%.1f s in all): compress %.3f s + "
+                      "decompress %.3f s, %d threads" % (rows, x.shape[0], w.name, passes, spent, best[1], best[2],
+                                                          threads)}
 
 
 def main():
@@ -189,7 +198,7 @@ def main():
     }
     if not args.no_cpu_baseline:
         rows = args.cpu_sample_rows or max(64, min(T, int(2.5e8 // H)))
-        res["cpu_baseline"] = cpu_baseline(x, w, args.eps, rows)
+        res["cpu_baseline"] = cpu_baseline(x, w, bit_set, args.eps, rows)
     print(json.dumps(res))
 
 

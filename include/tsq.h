@@ -48,11 +48,12 @@ typedef enum {
 } tsq_budget_mode;
 
 typedef enum {
-    TSQ_PIPE_AUTO   = 0,      /* the library picks                                              */
+    TSQ_PIPE_AUTO   = 0,      /* the library picks (at present: TSQ_PIPE_FUSED)                 */
     TSQ_PIPE_STAGED = 1,      /* row statistics -> device-wide scan -> pack: three launches,
                                  the input is read twice                                        */
-    TSQ_PIPE_FUSED  = 2       /* one launch, the input is read once; output placement by a
-                                 chained scan between workgroups                                */
+    TSQ_PIPE_FUSED  = 2       /* one launch of a persistent grid, the input is read once;
+                                 tokens are handed out by ticket counters in the workspace and
+                                 outputs are placed through a per-token size table there        */
 } tsq_pipeline;
 
 /* Problem statement (Algorithm 1 "Require": T, Q-bar, Delta; Eq. (ts): tau). */
@@ -115,9 +116,10 @@ size_t     tsq_plan_workspace_bytes(const tsq_plan *plan);
 /*
  * Puts d_ws into its initial state (enqueues one small kernel on `stream`).
  * Required once after d_ws is allocated, and again after any compress call on
- * it that was aborted or returned TSQ_ERR_INTERNAL through tsq_blob_info; the
- * fused pipeline leaves the workspace ready for the next call by itself.  A
- * workspace serves one compress call at a time.
+ * it that was aborted or returned TSQ_ERR_INTERNAL through tsq_blob_info; every
+ * completed compress call leaves the workspace ready for the next call by
+ * itself.  A workspace serves one compress call at a time (calls that overlap
+ * on one workspace race), and only plans of one shape (tokens, hidden).
  */
 tsq_status tsq_workspace_reset(const tsq_plan *plan, void *d_ws, void *stream);
 
