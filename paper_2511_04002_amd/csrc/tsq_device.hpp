@@ -100,21 +100,30 @@ __device__ __forceinline__ uint32_t block_excl_scan(uint32_t v, uint32_t *scr) {
 // that its own lanes own (runs 64w .. 64w+63): four coalesced loads of 16 B per lane, then four
 // 16-byte LDS writes in the run layout.  Since a wave only reads back what it wrote itself and
 // the LDS operations of one wave execute in order, the row needs no workgroup barrier.
-__device__ __forceinline__ void fetch_row_part(const uint4 *__restrict__ src, uint32_t pieces, uint4 (&pre)[4]) {
+struct RowPart { uint32_t w[16]; };   // the four 16-byte pieces a lane moves, as scalars
+
+template <bool FULL = false>
+__device__ __forceinline__ void fetch_row_part(const uint4 *__restrict__ src, uint32_t pieces, RowPart &pre) {
     const uint32_t lane = threadIdx.x & 63u, wv = threadIdx.x >> 6;
 #pragma unroll
-    for (uint32_t k = 0; k < 4; ++k) {
+    for (int k = 0; k < 4; ++k) {
         const uint32_t q = 256u * wv + 64u * k + lane;
-        pre[k] = make_uint4(0, 0, 0, 0);
-        if (q < pieces) pre[k] = src[q];
+        uint32_t x = 0, y = 0, z = 0, w = 0;
+        if (FULL || q < pieces) {
+            const uint4 v = src[q];
+            x = v.x; y = v.y; z = v.z; w = v.w;
+        }
+        pre.w[4 * k] = x; pre.w[4 * k + 1] = y; pre.w[4 * k + 2] = z; pre.w[4 * k + 3] = w;
     }
 }
-__device__ __forceinline__ void write_row_part(uint32_t *lrow, uint32_t runs, const uint4 (&pre)[4]) {
+__device__ __forceinline__ void write_row_part(uint32_t *lrow, uint32_t runs, const RowPart &pre) {
     const uint32_t lane = threadIdx.x & 63u, wv = threadIdx.x >> 6;
 #pragma unroll
-    for (uint32_t k = 0; k < 4; ++k) {
+    for (int k = 0; k < 4; ++k) {
         const uint32_t q = 256u * wv + 64u * k + lane;
-        if (q < 4 * runs) *reinterpret_cast<uint4 *>(lrow + (q >> 2) * kRunLdsDw + (q & 3) * 4) = pre[k];
+        if (q < 4 * runs)
+            *reinterpret_cast<uint4 *>(lrow + (q >> 2) * kRunLdsDw + (q & 3) * 4) =
+                make_uint4(pre.w[4 * k], pre.w[4 * k + 1], pre.w[4 * k + 2], pre.w[4 * k + 3]);
     }
 }
 

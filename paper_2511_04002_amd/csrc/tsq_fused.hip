@@ -63,13 +63,16 @@ struct __attribute__((packed, aligned(4))) Dw4 { uint32_t a, b, c, d; };   // 16
 // ---- the row in LDS, fused kernel: 16 dwords per run, no padding.  The four 16-byte chunks of
 // run r are stored in the order k ^ ((r >> 1) & 3), which spreads eight neighbouring runs over
 // all 32 banks for 16-byte accesses. ----
-__device__ __forceinline__ void write_row_part_sw(uint32_t *lrow, uint32_t runs, const uint4 (&pre)[4]) {
+template <bool FULL>
+__device__ __forceinline__ void write_row_part_sw(uint32_t *lrow, uint32_t runs, const RowPart &pre) {
     const uint32_t lane = threadIdx.x & 63u, wv = threadIdx.x >> 6;
+    const uint32_t q0 = 256u * wv + lane;                  // first 16-byte piece of the row this lane moves
 #pragma unroll
-    for (uint32_t k = 0; k < 4; ++k) {
-        const uint32_t q = 256u * wv + 64u * k + lane;     // 16-byte piece of the row
-        const uint32_t r = q >> 2, c = (q & 3u) ^ ((r >> 1) & 3u);
-        if (r < runs) *reinterpret_cast<uint4 *>(lrow + r * 16u + c * 4u) = pre[k];
+    for (int k = 0; k < 4; ++k) {
+        const uint32_t q = q0 + 64u * k, r = q >> 2, c = (q & 3u) ^ ((r >> 1) & 3u);
+        if (FULL || r < runs)
+            *reinterpret_cast<uint4 *>(lrow + r * 16u + c * 4u) =
+                make_uint4(pre.w[4 * k], pre.w[4 * k + 1], pre.w[4 * k + 2], pre.w[4 * k + 3]);
     }
 }
 __device__ __forceinline__ void load_run_sw(const uint32_t *lrow, uint32_t r, uint32_t (&w)[16]) {
@@ -87,9 +90,9 @@ __device__ __forceinline__ uint32_t raw_element_sw(const uint32_t *lrow, uint32_
 }
 
 // nd dwords of packed codes of a run into the token's payload image in LDS
-template <int B>
+template <int B, bool FULL>
 __device__ __forceinline__ void put_codes(uint32_t *dst, const uint32_t (&o)[8], uint32_t nd) {
-    if (nd >= (uint32_t)B) {
+    if (FULL || nd >= (uint32_t)B) {
         int k = 0;
         // the image is 16-byte aligned and run*B dwords in: use the widest stores the alignment allows
         if (B % 4 == 0) {
@@ -108,7 +111,7 @@ __device__ __forceinline__ void put_codes(uint32_t *dst, const uint32_t (&o)[8],
             if ((uint32_t)k < nd) dst[k] = o[k];
     }
 }
-template <int B>
+template <int B, bool FULL>
 __device__ __forceinline__ void pack_to_image(const uint32_t (&m)[8], const uint32_t (&w)[16], uint32_t *dst,
                                               uint32_t nd) {
     uint32_t o[8];
@@ -118,7 +121,7 @@ __device__ __forceinline__ void pack_to_image(const uint32_t (&m)[8], const uint
 #pragma unroll
         for (int k = 0; k < B; ++k) o[k] = t[k];
     }
-    put_codes<B>(dst, o, nd);
+    put_codes<B, FULL>(dst, o, nd);
 }
 
 // ---- placement ----
@@ -193,26 +196,77 @@ struct Pending {
     uint32_t parity;   // which payload image and which stash hold it
 };
 
+// Where a token's outputs go, and the LDS areas they come from.
+struct StoreTargets {
+    uint64_t *pay_off, *row_ptr;
+    uint32_t *payload;
+    uint16_t *out_col, *out_val;
+    const uint32_t *images, *stashes;
+    uint32_t runs;
+    uint64_t payload_words, outlier_capacity;
+};
+// What the workgroup that stores the very last token needs to close the blob.
+struct Tail {
+    uint32_t token, ew, ec, words, cnt;
+};
+
+// Stores a token whose prefix is known: the payload image LDS -> HBM (16 bytes per thread and
+// step), its offsets, and (from_stash) its outliers.  Returns false without storing anything if
+// the payload would leave its section, whatever the table said.
+template <int NW>
+__device__ __forceinline__ bool store_token(const StoreTargets &o, const Pending &q, const Prefix &x, bool from_stash,
+                                            Tail &tail) {
+    constexpr uint32_t kThreads = 64u * NW;
+    const uint32_t tid = threadIdx.x;
+    if ((uint64_t)x.ew + q.words > o.payload_words) return false;
+    if (tid == 0) {
+        o.pay_off[q.token] = (uint64_t)x.ew << 2;
+        o.row_ptr[q.token] = x.ec;
+    }
+    const uint32_t *img = o.images + q.parity * o.runs * 8u;
+    uint32_t *dst = o.payload + x.ew;
+    const uint32_t quads = q.words >> 2;
+    for (uint32_t i = tid; i < quads; i += kThreads) {
+        const uint4 v = *reinterpret_cast<const uint4 *>(img + 4u * i);
+        *reinterpret_cast<Dw4 *>(dst + 4u * i) = Dw4{v.x, v.y, v.z, v.w};
+    }
+    const uint32_t rest = q.words & 3u;
+    if (tid < rest) dst[4u * quads + tid] = img[4u * quads + tid];
+    if (from_stash && q.cnt > 0 && (uint64_t)x.ec + q.cnt <= o.outlier_capacity) {
+        const uint32_t *stash = o.stashes + q.parity * kStashCap;
+        for (uint32_t k = tid; k < q.cnt; k += kThreads) {
+            const uint32_t e = stash[k];
+            o.out_col[(size_t)x.ec + k] = (uint16_t)(e >> 16);
+            o.out_val[(size_t)x.ec + k] = (uint16_t)e;
+        }
+    }
+    tail.token = q.token; tail.ew = x.ew; tail.ec = x.ec; tail.words = q.words; tail.cnt = q.cnt;
+    return true;
+}
+
 // LDS map (dynamic): row: runs*16 | two payload images: runs*8 each | ring: 4 reduce areas |
 // 2 placement areas | 2 ticket slots (8 dwords) | two stashes
 constexpr uint32_t kLdsRing = 4 * 2 * kMaxWaves, kLdsPlace = 3 * kMaxWaves;
 static_assert(kFusedScratchDw == kLdsRing + 2 * kLdsPlace + 8 + 2 * kStashCap, "LDS map of the fused kernel");
 
-template <int DT, int NW>
+// FULL: the row fills the workgroup exactly (hidden == 2048 * NW), so every lane owns a whole run
+// and none of the range checks of the general case is needed.
+template <int DT, int NW, bool FULL>
 __global__ void __launch_bounds__(64 * NW, 4)
 k_fused(const Params p, const uint16_t *__restrict__ in, uint8_t *__restrict__ blob, uint8_t *__restrict__ ws) {
     extern __shared__ __align__(16) uint32_t lds[];
     constexpr uint32_t kThreads = 64 * NW;
     uint32_t *lrow = lds;
-    uint32_t *images = lds + p.runs * 16u;                  // packed codes of the current and the pending token
-    uint32_t *ring = images + 2u * p.runs * 8u;
+    const uint32_t runs = FULL ? 64u * NW : p.runs, pieces = FULL ? 256u * NW : p.pieces;
+    uint32_t *images = lds + runs * 16u;                    // packed codes of the current and the pending token
+    uint32_t *ring = images + 2u * runs * 8u;
     uint32_t *areas = ring + kLdsRing;
     uint32_t *tslot = areas + 2 * kLdsPlace;                // next token, one slot per iteration parity
     uint32_t *stashes = tslot + 8;                          // 2 x kStashCap dwords: col << 16 | raw value
     const uint32_t tid = threadIdx.x, run = tid;
     const uint32_t wg = blockIdx.x, G = gridDim.x;
-    const bool owns = run < p.runs;
-    const uint32_t left = owns ? p.pieces - 4 * run : 0;    // 16-byte pieces of the lane's run inside the row
+    const bool owns = FULL || run < runs;
+    const uint32_t left = FULL ? 4u : (owns ? pieces - 4 * run : 0);   // 16-byte pieces of the lane's run inside the row
 
     uint32_t *ctrl = reinterpret_cast<uint32_t *>(ws + p.ws_ctrl);
     const uint32_t epoch = uniform(ctrl[kCtlEpoch]);
@@ -236,11 +290,8 @@ k_fused(const Params p, const uint16_t *__restrict__ in, uint8_t *__restrict__ b
     uint16_t *out_val = reinterpret_cast<uint16_t *>(blob + p.off_out_val);
 
     // the row of the next iteration on its way HBM -> registers -> LDS (each wave its own part)
-    uint4 pre[4];
-    auto fetch_row = [&](uint32_t t) {
-        fetch_row_part(reinterpret_cast<const uint4 *>(in + (size_t)t * p.hidden), p.pieces, pre);
-    };
-    auto write_row = [&]() { write_row_part_sw(lrow, p.runs, pre); };
+    RowPart pre;
+    const uint32_t hidden = FULL ? 2048u * NW : p.hidden;
 
     Place pl;
     pl.done = 0; pl.base_w = 0; pl.base_c = 0;
@@ -248,46 +299,19 @@ k_fused(const Params p, const uint16_t *__restrict__ in, uint8_t *__restrict__ b
     Pending pd;
     bool have_pending = false;
     pd.width = 8; pd.cnt = 0; pd.words = 0; pd.token = 0; pd.parity = 0;
-    uint32_t last_stored = kNoToken, last_ew = 0, last_ec = 0, last_words = 0, last_cnt = 0;
+    Tail tail;
+    tail.token = kNoToken; tail.ew = tail.ec = tail.words = tail.cnt = 0;
 
-    // stores a token whose prefix is known: payload from registers, outliers from its stash
-    auto store_token = [&](const Pending &q, const Prefix &x, bool from_stash) {
-        // never store outside the payload section, whatever the table said
-        if ((uint64_t)x.ew + q.words > (p.payload_capacity >> 2)) { failed = 1; return; }
-        if (tid == 0) {
-            pay_off[q.token] = (uint64_t)x.ew << 2;
-            row_ptr[q.token] = x.ec;
-        }
-        {
-            // the token's payload image, LDS -> HBM, 16 bytes per thread and step
-            const uint32_t *img = images + q.parity * p.runs * 8u;
-            uint32_t *dst = payload + x.ew;
-            const uint32_t quads = q.words >> 2;
-            for (uint32_t i = tid; i < quads; i += kThreads) {
-                const uint4 v = *reinterpret_cast<const uint4 *>(img + 4u * i);
-                *reinterpret_cast<Dw4 *>(dst + 4u * i) = Dw4{v.x, v.y, v.z, v.w};
-            }
-            const uint32_t rest = q.words & 3u;
-            if (tid < rest) dst[4u * quads + tid] = img[4u * quads + tid];
-        }
-        if (from_stash && q.cnt > 0 && (uint64_t)x.ec + q.cnt <= p.outlier_capacity) {
-            const uint32_t *stash = stashes + q.parity * kStashCap;
-            for (uint32_t k = tid; k < q.cnt; k += kThreads) {
-                const uint32_t e = stash[k];
-                out_col[(size_t)x.ec + k] = (uint16_t)(e >> 16);
-                out_val[(size_t)x.ec + k] = (uint16_t)e;
-            }
-        }
-        last_stored = q.token; last_ew = x.ew; last_ec = x.ec; last_words = q.words; last_cnt = q.cnt;
-    };
+    const StoreTargets out{pay_off, row_ptr, payload, out_col, out_val, images, stashes, runs,
+                           p.payload_capacity >> 2, p.outlier_capacity};
 
     // ---- first token: the workgroup's own id; its row; the ticket of the second token
     uint32_t t = wg;                       // the grid never exceeds the token count
-    fetch_row(t);
+    fetch_row_part<FULL>(reinterpret_cast<const uint4 *>(in + (size_t)t * hidden), pieces, pre);
     uint32_t req = 0;                      // thread 0: the ticket in flight
     bool requesting = true;                // uniform: a ticket is in flight
     if (tid == 0) req = __hip_atomic_fetch_add(counter, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-    write_row();
+    write_row_part_sw<FULL>(lrow, runs, pre);
 
     uint32_t it = 0;
     for (; t != kNoToken; ++it) {
@@ -328,7 +352,7 @@ k_fused(const Params p, const uint16_t *__restrict__ in, uint8_t *__restrict__ b
             scale[t] = scale_of(c.amax, c.width);
         }
         // the next row starts its way from HBM now that the registers of the width search are free
-        if (tn != kNoToken) fetch_row(tn);
+        if (tn != kNoToken) fetch_row_part<FULL>(reinterpret_cast<const uint4 *>(in + (size_t)tn * hidden), pieces, pre);
 
         // ---- codes of the lane's run at the chosen width, into this iteration's payload image
         Pending cur;
@@ -336,16 +360,16 @@ k_fused(const Params p, const uint16_t *__restrict__ in, uint8_t *__restrict__ b
         if (owns) {
             uint32_t wr[16];
             load_run_sw(lrow, run, wr);
-            uint32_t *dst = images + cur.parity * p.runs * 8u + run * c.width;
-            const uint32_t nd = left >= 4 ? c.width : ((left * c.width + 3u) >> 2);
+            uint32_t *dst = images + cur.parity * runs * 8u + run * c.width;
+            const uint32_t nd = (FULL || left >= 4) ? c.width : ((left * c.width + 3u) >> 2);
             switch (c.width) {
-                case 2: pack_to_image<2>(m, wr, dst, nd); break;
-                case 3: pack_to_image<3>(m, wr, dst, nd); break;
-                case 4: pack_to_image<4>(m, wr, dst, nd); break;
-                case 5: pack_to_image<5>(m, wr, dst, nd); break;
-                case 6: pack_to_image<6>(m, wr, dst, nd); break;
-                case 7: pack_to_image<7>(m, wr, dst, nd); break;
-                default: pack_to_image<8>(m, wr, dst, nd); break;
+                case 2: pack_to_image<2, FULL>(m, wr, dst, nd); break;
+                case 3: pack_to_image<3, FULL>(m, wr, dst, nd); break;
+                case 4: pack_to_image<4, FULL>(m, wr, dst, nd); break;
+                case 5: pack_to_image<5, FULL>(m, wr, dst, nd); break;
+                case 6: pack_to_image<6, FULL>(m, wr, dst, nd); break;
+                case 7: pack_to_image<7, FULL>(m, wr, dst, nd); break;
+                default: pack_to_image<8, FULL>(m, wr, dst, nd); break;
             }
         }
 
@@ -354,7 +378,7 @@ k_fused(const Params p, const uint16_t *__restrict__ in, uint8_t *__restrict__ b
             const Prefix x = place_finish<NW>(p, sizes, tag, pd.token, pl, early, areas + (it & 1u) * kLdsPlace,
                                               ctrl + kCtlError);
             failed |= x.bad;
-            if (!x.bad) store_token(pd, x, true);
+            if (!x.bad && !store_token<NW>(out, pd, x, true, tail)) failed = 1;
             have_pending = false;
         }
 
@@ -396,14 +420,14 @@ k_fused(const Params p, const uint16_t *__restrict__ in, uint8_t *__restrict__ b
                 }
             }
             if (!stashed) {
-                if (!x.bad) store_token(cur, x, false);
+                if (!x.bad && !store_token<NW>(out, cur, x, false, tail)) failed = 1;
                 placed = true;
             }
         }
         have_pending = !placed;
         pd = cur;
 
-        if (tn != kNoToken) write_row();  // this wave is done with its part of the row
+        if (tn != kNoToken) write_row_part_sw<FULL>(lrow, runs, pre);   // this wave is done with its part of the row
         t = tn;
     }
 
@@ -414,13 +438,13 @@ k_fused(const Params p, const uint16_t *__restrict__ in, uint8_t *__restrict__ b
         const Prefix x = place_finish<NW>(p, sizes, tag, pd.token, pl, now, areas + (it & 1u) * kLdsPlace,
                                           ctrl + kCtlError);
         failed |= x.bad;
-        if (!x.bad) store_token(pd, x, true);
+        if (!x.bad && !store_token<NW>(out, pd, x, true, tail)) failed = 1;
     }
     if (failed && tid == 0) write_header(p, blob, 0, 0, 6u);   // the header may already be final: overwrite it
 
     // ---- the workgroup that stored the last token closes the blob and prepares the next call
-    if (last_stored == p.tokens - 1u) {
-        const uint64_t nnz = (uint64_t)last_ec + last_cnt, wordsum = (uint64_t)last_ew + last_words;
+    if (tail.token == p.tokens - 1u) {
+        const uint64_t nnz = (uint64_t)tail.ec + tail.cnt, wordsum = (uint64_t)tail.ew + tail.words;
         // every workgroup draws exactly one failing ticket, after which all counters add up to the
         // token count; until then somebody may not even have read the epoch yet
         uint32_t spins = 0, drawn = 0;
@@ -452,21 +476,23 @@ static hipStream_t as_stream(void *s) { return reinterpret_cast<hipStream_t>(s);
 
 typedef void (*FusedKernel)(const Params, const uint16_t *, uint8_t *, uint8_t *);
 
-template <int DT>
+template <int DT, bool FULL>
 static FusedKernel fused_kernel_for(uint32_t nw) {
     switch (nw) {
-        case 1: return k_fused<DT, 1>;
-        case 2: return k_fused<DT, 2>;
-        case 3: return k_fused<DT, 3>;
-        case 4: return k_fused<DT, 4>;
-        case 8: return k_fused<DT, 8>;
-        default: return k_fused<DT, 16>;
+        case 1: return k_fused<DT, 1, FULL>;
+        case 2: return k_fused<DT, 2, FULL>;
+        case 3: return k_fused<DT, 3, FULL>;
+        case 4: return k_fused<DT, 4, FULL>;
+        case 8: return k_fused<DT, 8, FULL>;
+        default: return k_fused<DT, 16, FULL>;
     }
 }
 
-static FusedKernel fused_kernel(uint32_t dtype, uint32_t nw) {
-    return dtype == (uint32_t)kF16 ? fused_kernel_for<kF16>(nw) : fused_kernel_for<kBF16>(nw);
+static FusedKernel fused_kernel(uint32_t dtype, uint32_t nw, bool full) {
+    if (full) return dtype == (uint32_t)kF16 ? fused_kernel_for<kF16, true>(nw) : fused_kernel_for<kBF16, true>(nw);
+    return dtype == (uint32_t)kF16 ? fused_kernel_for<kF16, false>(nw) : fused_kernel_for<kBF16, false>(nw);
 }
+static bool fills_workgroup(const Params &p, const Geometry &g) { return p.hidden == 2048u * g.waves; }
 
 // waves per workgroup of the fused kernel for a row of `runs` runs: the smallest instantiated size
 uint32_t compress_waves(uint32_t runs) {
@@ -479,11 +505,12 @@ int prepare_fused_kernels() {
     const int big = (int)(((kMaxHidden / kRun) * 32u + kFusedScratchDw) * 4);
     static const uint32_t sizes[] = {1, 2, 3, 4, 8, 16};
     for (uint32_t dt = 0; dt < 2; ++dt)
-        for (uint32_t nw : sizes) {
-            hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(fused_kernel(dt, nw)),
-                                               hipFuncAttributeMaxDynamicSharedMemorySize, big);
-            if (e != hipSuccess) return (int)e;
-        }
+        for (uint32_t nw : sizes)
+            for (int full = 0; full < 2; ++full) {
+                hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(fused_kernel(dt, nw, full != 0)),
+                                                   hipFuncAttributeMaxDynamicSharedMemorySize, big);
+                if (e != hipSuccess) return (int)e;
+            }
     return 0;
 }
 
@@ -493,7 +520,7 @@ int fused_resident_workgroups(const Params &p, const Geometry &g, uint32_t *out)
     hipError_t e = hipGetDevice(&dev);
     if (e == hipSuccess) e = hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev);
     if (e == hipSuccess)
-        e = hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, reinterpret_cast<const void *>(fused_kernel(p.dtype, g.waves)),
+        e = hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, reinterpret_cast<const void *>(fused_kernel(p.dtype, g.waves, fills_workgroup(p, g))),
                                                          (int)(64u * g.waves), g.lds_fused_bytes);
     if (e != hipSuccess) return (int)e;
     if (per_cu < 1 || cus < 1) return (int)hipErrorInvalidConfiguration;
@@ -503,7 +530,7 @@ int fused_resident_workgroups(const Params &p, const Geometry &g, uint32_t *out)
 
 int launch_fused(const Params &p, const Geometry &g, uint32_t grid, const void *d_in, void *d_blob, void *d_ws,
                  void *stream) {
-    hipLaunchKernelGGL(fused_kernel(p.dtype, g.waves), dim3(grid), dim3(64u * g.waves), g.lds_fused_bytes,
+    hipLaunchKernelGGL(fused_kernel(p.dtype, g.waves, fills_workgroup(p, g)), dim3(grid), dim3(64u * g.waves), g.lds_fused_bytes,
                        as_stream(stream), p, static_cast<const uint16_t *>(d_in), static_cast<uint8_t *>(d_blob),
                        static_cast<uint8_t *>(d_ws));
     return (int)hipGetLastError();

@@ -78,7 +78,7 @@ k_row_stats(const Params p, const uint16_t *__restrict__ in, uint8_t *__restrict
     const uint32_t run = threadIdx.x;
     const bool owns = run < p.runs;
 
-    uint4 pre[4];
+    RowPart pre;
     fetch_row_part(reinterpret_cast<const uint4 *>(in + (size_t)t * p.hidden), p.pieces, pre);
     write_row_part(lrow, p.runs, pre);
 
@@ -158,7 +158,7 @@ k_pack(const Params p, const uint16_t *__restrict__ in, uint8_t *__restrict__ bl
     const uint32_t t = blockIdx.x;
     const uint32_t run = threadIdx.x;
 
-    uint4 pre[4];
+    RowPart pre;
     fetch_row_part(reinterpret_cast<const uint4 *>(in + (size_t)t * p.hidden), p.pieces, pre);
 
     const uint32_t width = blob[p.off_bits + t];
