@@ -15,10 +15,11 @@
 // nothing forms a serial chain, and apart from the tickets there are no atomic read-modify-write
 // operations (on this chip they cost microseconds when several dies touch one address).
 //
-// To keep the wait for slower neighbours off the critical path a token is stored one iteration
-// late: iteration i computes token i (codes stay in registers, outliers in an LDS stash),
-// publishes it, and then stores token i-1.  All earlier tokens were handed out before token i-1
-// was, so by then they have normally been published.  The row of iteration i+1 is fetched into
+// To keep the wait for slower neighbours off the critical path a token is stored almost two
+// iterations late: iteration i computes token i, publishes it, stores token i-2, and only then
+// packs token i's codes into the payload
+// image in LDS that token i-2 occupied (two images and two outlier stashes alternate).  All
+// earlier tokens were handed out before token i-2 was, so by then they have been published.  The row of iteration i+1 is fetched into
 // registers in the middle of iteration i; its ticket was requested an iteration earlier.
 //
 // Progress: the smallest token that is not stored yet has all its predecessors published, and if
@@ -211,8 +212,10 @@ struct Tail {
 };
 
 // Stores a token whose prefix is known: the payload image LDS -> HBM (16 bytes per thread and
-// step), its offsets, and (from_stash) its outliers.  Returns false without storing anything if
-// the payload would leave its section, whatever the table said.
+// step, contiguous over the workgroup), its offsets, and (from_stash) its outliers.  The image
+// and the stash were written by all waves: a barrier lies between their writes and this call.
+// Returns false without storing anything if the payload would leave its section, whatever the
+// table said.
 template <int NW>
 __device__ __forceinline__ bool store_token(const StoreTargets &o, const Pending &q, const Prefix &x, bool from_stash,
                                             Tail &tail) {
@@ -245,9 +248,9 @@ __device__ __forceinline__ bool store_token(const StoreTargets &o, const Pending
 }
 
 // LDS map (dynamic): row: runs*16 | two payload images: runs*8 each | ring: 4 reduce areas |
-// 2 placement areas | 2 ticket slots (8 dwords) | two stashes
+// 4 placement areas (used in rotation, like the reduce areas) | 2 ticket slots (8 dwords) | two stashes
 constexpr uint32_t kLdsRing = 4 * 2 * kMaxWaves, kLdsPlace = 3 * kMaxWaves;
-static_assert(kFusedScratchDw == kLdsRing + 2 * kLdsPlace + 8 + 2 * kStashCap, "LDS map of the fused kernel");
+static_assert(kFusedScratchDw == kLdsRing + 4 * kLdsPlace + 8 + 2 * kStashCap, "LDS map of the fused kernel");
 
 // FULL: the row fills the workgroup exactly (hidden == 2048 * NW), so every lane owns a whole run
 // and none of the range checks of the general case is needed.
@@ -261,7 +264,7 @@ k_fused(const Params p, const uint16_t *__restrict__ in, uint8_t *__restrict__ b
     uint32_t *images = lds + runs * 16u;                    // packed codes of the current and the pending token
     uint32_t *ring = images + 2u * runs * 8u;
     uint32_t *areas = ring + kLdsRing;
-    uint32_t *tslot = areas + 2 * kLdsPlace;                // next token, one slot per iteration parity
+    uint32_t *tslot = areas + 4 * kLdsPlace;                // next token, one slot per iteration parity
     uint32_t *stashes = tslot + 8;                          // 2 x kStashCap dwords: col << 16 | raw value
     const uint32_t tid = threadIdx.x, run = tid;
     const uint32_t wg = blockIdx.x, G = gridDim.x;
@@ -295,10 +298,14 @@ k_fused(const Params p, const uint16_t *__restrict__ in, uint8_t *__restrict__ b
 
     Place pl;
     pl.done = 0; pl.base_w = 0; pl.base_c = 0;
-    uint32_t failed = 0, turn = 0;
-    Pending pd;
-    bool have_pending = false;
-    pd.width = 8; pd.cnt = 0; pd.words = 0; pd.token = 0; pd.parity = 0;
+    uint32_t failed = 0, turn = 0, pturn = 0;   // turn / pturn: rotation through the reduce / placement areas
+    // tokens computed but not stored yet: `young` is from the previous iteration, `old` from the one
+    // before.  A token's payload image and stash are those of its iteration's parity, so `old` has
+    // to leave before the current token's codes are packed into the same image.
+    Pending young, old;
+    bool have_young = false, have_old = false;
+    young.width = 8; young.cnt = 0; young.words = 0; young.token = 0; young.parity = 0;
+    old = young;
     Tail tail;
     tail.token = kNoToken; tail.ew = tail.ec = tail.words = tail.cnt = 0;
 
@@ -328,9 +335,9 @@ k_fused(const Params p, const uint16_t *__restrict__ in, uint8_t *__restrict__ b
             tslot[it & 1u] = tn;
         }
 
-        // the table words before the pending token: asked for now, used after the width search
+        // the table words before the older pending token: asked for now, used after the width search
         uint32_t early[kEarly];
-        if (have_pending) place_request<NW>(sizes, tag, pd.token, pl, early);
+        if (have_old) place_request<NW>(sizes, tag, old.token, pl, early);
 
         // ---- Eq. (ts) and Algorithm 1 for token t
         Mags<DT> mg;
@@ -354,6 +361,16 @@ k_fused(const Params p, const uint16_t *__restrict__ in, uint8_t *__restrict__ b
         // the next row starts its way from HBM now that the registers of the width search are free
         if (tn != kNoToken) fetch_row_part<FULL>(reinterpret_cast<const uint4 *>(in + (size_t)tn * hidden), pieces, pre);
 
+        // ---- store the token of two iterations ago: its image and stash are needed now
+        if (have_old) {
+            const Prefix x = place_finish<NW>(p, sizes, tag, old.token, pl, early, areas + (pturn++ & 3u) * kLdsPlace,
+                                              ctrl + kCtlError);
+            failed |= x.bad;
+            if (!x.bad && !store_token<NW>(out, old, x, true, tail)) failed = 1;
+            have_old = false;
+            if (NW > 1) __syncthreads();      // the image and the stash of this parity are free again
+        }
+
         // ---- codes of the lane's run at the chosen width, into this iteration's payload image
         Pending cur;
         cur.width = c.width; cur.cnt = c.cnt; cur.words = words; cur.token = t; cur.parity = it & 1u;
@@ -373,15 +390,6 @@ k_fused(const Params p, const uint16_t *__restrict__ in, uint8_t *__restrict__ b
             }
         }
 
-        // ---- store the token of the previous iteration
-        if (have_pending) {
-            const Prefix x = place_finish<NW>(p, sizes, tag, pd.token, pl, early, areas + (it & 1u) * kLdsPlace,
-                                              ctrl + kCtlError);
-            failed |= x.bad;
-            if (!x.bad && !store_token<NW>(out, pd, x, true, tail)) failed = 1;
-            have_pending = false;
-        }
-
         // ---- T_above of token t: into this iteration's stash in column order, or straight out if
         //      it is too long for the stash
         bool placed = false;
@@ -393,10 +401,19 @@ k_fused(const Params p, const uint16_t *__restrict__ in, uint8_t *__restrict__ b
             x.ew = x.ec = x.bad = 0;
             bool direct_ok = false;
             if (!stashed) {
-                // rare: more outliers than the stash holds.  Place the token now.
+                // rare: more outliers than the stash holds.  Place everything that is pending, then
+                // this token, now.
                 uint32_t now[kEarly];
+                if (have_young) {
+                    place_request<NW>(sizes, tag, young.token, pl, now);
+                    const Prefix y = place_finish<NW>(p, sizes, tag, young.token, pl, now,
+                                                      areas + (pturn++ & 3u) * kLdsPlace, ctrl + kCtlError);
+                    failed |= y.bad;
+                    if (!y.bad && !store_token<NW>(out, young, y, true, tail)) failed = 1;
+                    have_young = false;
+                }
                 place_request<NW>(sizes, tag, t, pl, now);
-                x = place_finish<NW>(p, sizes, tag, t, pl, now, areas + ((it + 1u) & 1u) * kLdsPlace, ctrl + kCtlError);
+                x = place_finish<NW>(p, sizes, tag, t, pl, now, areas + (pturn++ & 3u) * kLdsPlace, ctrl + kCtlError);
                 failed |= x.bad;
                 direct_ok = !x.bad && (uint64_t)x.ec + c.cnt <= p.outlier_capacity;
             }
@@ -424,21 +441,29 @@ k_fused(const Params p, const uint16_t *__restrict__ in, uint8_t *__restrict__ b
                 placed = true;
             }
         }
-        have_pending = !placed;
-        pd = cur;
+        old = young; have_old = have_young;
+        young = cur; have_young = !placed;
 
         if (tn != kNoToken) write_row_part_sw<FULL>(lrow, runs, pre);   // this wave is done with its part of the row
         t = tn;
     }
 
-    // ---- the last token of this workgroup
-    if (have_pending) {
+    // ---- the tokens still pending, oldest first
+    if (have_old) {
         uint32_t now[kEarly];
-        place_request<NW>(sizes, tag, pd.token, pl, now);
-        const Prefix x = place_finish<NW>(p, sizes, tag, pd.token, pl, now, areas + (it & 1u) * kLdsPlace,
+        place_request<NW>(sizes, tag, old.token, pl, now);
+        const Prefix x = place_finish<NW>(p, sizes, tag, old.token, pl, now, areas + (pturn++ & 3u) * kLdsPlace,
                                           ctrl + kCtlError);
         failed |= x.bad;
-        if (!x.bad && !store_token<NW>(out, pd, x, true, tail)) failed = 1;
+        if (!x.bad && !store_token<NW>(out, old, x, true, tail)) failed = 1;
+    }
+    if (have_young) {
+        uint32_t now[kEarly];
+        place_request<NW>(sizes, tag, young.token, pl, now);
+        const Prefix x = place_finish<NW>(p, sizes, tag, young.token, pl, now, areas + (pturn++ & 3u) * kLdsPlace,
+                                          ctrl + kCtlError);
+        failed |= x.bad;
+        if (!x.bad && !store_token<NW>(out, young, x, true, tail)) failed = 1;
     }
     if (failed && tid == 0) write_header(p, blob, 0, 0, 6u);   // the header may already be final: overwrite it
 

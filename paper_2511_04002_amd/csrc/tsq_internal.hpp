@@ -21,11 +21,11 @@ constexpr uint32_t kMaxHidden = 32768;
 // fused kernel: outliers of one token that fit an LDS stash (longer tokens take a slower path),
 // the largest persistent grid, the ticket classes (one counter each, kTicketStride dwords apart
 // so that no two share a 256-byte line), and its LDS behind the row in dwords (four reduce
-// areas, two placement areas, ticket slots, two stashes)
+// areas, four placement areas, ticket slots, two stashes)
 constexpr uint32_t kStashCap = 512;
 constexpr uint32_t kFusedGridCap = 4096;
 constexpr uint32_t kTicketClasses = 64, kTicketStride = 64;
-constexpr uint32_t kFusedScratchDw = 4 * 2 * kMaxWaves + 2 * 3 * kMaxWaves + 8 + 2 * kStashCap;
+constexpr uint32_t kFusedScratchDw = 4 * 2 * kMaxWaves + 4 * 3 * kMaxWaves + 8 + 2 * kStashCap;
 
 // 128-byte header at the start of every blob.
 struct BlobHeader {
