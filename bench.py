@@ -27,7 +27,7 @@ HBM_PEAK_GBS = 8000.0     # MI355X HBM3E, published peak
 TRAFFIC = {
     ("C4", "staged", 0.05): {"k_row_stats": 134.3e6 + 0.6e6, "k_pack": 136.6e6 + 62.7e6,
                              "k_unpack": 67.1e6 + 134.2e6, "k_scan": 0.2e6},
-    ("C4", "fused", 0.05): {"k_fused": 141.4e6 + 81.0e6, "k_unpack": 67.1e6 + 134.2e6},
+    ("C4", "fused", 0.05): {"k_fused": 135.2e6 + 64.1e6, "k_unpack": 67.1e6 + 134.2e6},
 }
 
 

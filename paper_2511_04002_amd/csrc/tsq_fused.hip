@@ -142,6 +142,10 @@ struct Prefix {
 // were not published yet, reads what lies beyond kEarly words per thread, and adds up.
 // area: 3*kMaxWaves dwords.  All threads of the block call both (one barrier, NW > 1).
 constexpr int kEarly = 4;
+__device__ __forceinline__ uint32_t dot_halves(uint32_t v, uint32_t sel, uint32_t acc) {
+    // v.lo * sel.lo + v.hi * sel.hi + acc in one instruction
+    return __builtin_amdgcn_udot2(__builtin_bit_cast(u16x2, v), __builtin_bit_cast(u16x2, sel), acc, false);
+}
 template <int NW>
 __device__ __forceinline__ void place_request(const uint32_t *sizes, uint32_t tag, uint32_t t, const Place &pl,
                                               uint32_t (&v)[kEarly]) {
@@ -158,17 +162,37 @@ __device__ __forceinline__ Prefix place_finish(const Params &p, const uint32_t *
                                                uint32_t *error_flag) {
     constexpr uint32_t kThreads = 64u * NW;
     const uint32_t lane = threadIdx.x & 63u, wv = threadIdx.x >> 6;
-    uint32_t sw = 0, sc = 0, bad = 0;
-    auto take = [&](uint32_t j, uint32_t w) {
-        uint32_t spins = 0;
-        while ((w >> 30) != tag && keep_waiting(spins, p.spin_limit, error_flag)) w = word_load(sizes + j);
-        if ((w >> 30) != tag) { bad = 1; w = 0; }
-        sw += (w >> 16) & 0x3FFFu;
-        sc += w & 0xFFFFu;
-    };
+    const uint32_t tag3 = tag << 30;
+    uint32_t w[kEarly];
+    uint32_t differ = 0, bad = 0;
 #pragma unroll
-    for (int k = 0; k < kEarly; ++k) take(pl.done + (uint32_t)k * kThreads + threadIdx.x, v[k]);
-    for (uint32_t j = pl.done + kEarly * kThreads + threadIdx.x; j < t; j += kThreads) take(j, word_load(sizes + j));
+    for (int k = 0; k < kEarly; ++k) { w[k] = v[k]; differ |= w[k] ^ tag3; }
+    if (differ >> 30) {
+        // some word does not carry this call's tag yet: wait for it
+#pragma unroll
+        for (int k = 0; k < kEarly; ++k) {
+            const uint32_t j = pl.done + (uint32_t)k * kThreads + threadIdx.x;
+            uint32_t spins = 0;
+            while ((w[k] >> 30) != tag && keep_waiting(spins, p.spin_limit, error_flag)) w[k] = word_load(sizes + j);
+            if ((w[k] >> 30) != tag) { bad = 1; w[k] = tag3; }
+        }
+    }
+    // sums of the low halves (outliers) and of the high halves (tag | words): one dot product each
+    uint32_t sc = 0, sh = 0;
+#pragma unroll
+    for (int k = 0; k < kEarly; ++k) {
+        sc = dot_halves(w[k], 0x00000001u, sc);
+        sh = dot_halves(w[k], 0x00010000u, sh);
+    }
+    uint32_t sw = sh - (uint32_t)kEarly * (tag << 14);       // the tags that rode along in the high halves
+    for (uint32_t j = pl.done + kEarly * kThreads + threadIdx.x; j < t; j += kThreads) {
+        uint32_t x = word_load(sizes + j);
+        uint32_t spins = 0;
+        while ((x >> 30) != tag && keep_waiting(spins, p.spin_limit, error_flag)) x = word_load(sizes + j);
+        if ((x >> 30) != tag) { bad = 1; x = 0; }
+        sw += (x >> 16) & 0x3FFFu;
+        sc += x & 0xFFFFu;
+    }
 
     uint32_t r0 = wave_sum_u32(sw), r1 = wave_sum_u32(sc);
     uint32_t r2 = __builtin_amdgcn_ballot_w64(bad != 0) != 0 ? 1u : 0u;
