@@ -21,6 +21,8 @@ constexpr int kModeLsb = 0;
 
 typedef unsigned short u16x2 __attribute__((ext_vector_type(2)));
 typedef short i16x2 __attribute__((ext_vector_type(2)));
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x4_a4 __attribute__((ext_vector_type(4), aligned(4)));   // 16 bytes at a 4-byte aligned address
 
 __device__ __forceinline__ uint32_t pk_sub_u16(uint32_t a, uint32_t b) {
     return __builtin_bit_cast(uint32_t, (u16x2)(__builtin_bit_cast(u16x2, a) - __builtin_bit_cast(u16x2, b)));
@@ -110,7 +112,8 @@ __device__ __forceinline__ void fetch_row_part(const uint4 *__restrict__ src, ui
         const uint32_t q = 256u * wv + 64u * k + lane;
         uint32_t x = 0, y = 0, z = 0, w = 0;
         if (FULL || q < pieces) {
-            const uint4 v = src[q];
+            // the input is read once: streaming load
+            const u32x4 v = __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(src + q));
             x = v.x; y = v.y; z = v.z; w = v.w;
         }
         pre.w[4 * k] = x; pre.w[4 * k + 1] = y; pre.w[4 * k + 2] = z; pre.w[4 * k + 3] = w;

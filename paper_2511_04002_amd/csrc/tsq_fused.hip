@@ -254,8 +254,9 @@ __device__ __forceinline__ bool store_token(const StoreTargets &o, const Pending
     uint32_t *dst = o.payload + x.ew;
     const uint32_t quads = q.words >> 2;
     for (uint32_t i = tid; i < quads; i += kThreads) {
-        const uint4 v = *reinterpret_cast<const uint4 *>(img + 4u * i);
-        *reinterpret_cast<Dw4 *>(dst + 4u * i) = Dw4{v.x, v.y, v.z, v.w};
+        // plain stores: the payload is what decompress reads next, it should stay in the caches
+        const u32x4 v = *reinterpret_cast<const u32x4 *>(img + 4u * i);
+        *reinterpret_cast<u32x4_a4 *>(dst + 4u * i) = v;
     }
     const uint32_t rest = q.words & 3u;
     if (tid < rest) dst[4u * quads + tid] = img[4u * quads + tid];

@@ -272,7 +272,11 @@ k_unpack(const Params p, const uint8_t *__restrict__ blob, uint16_t *__restrict_
 #pragma unroll
     for (int k = 0; k < 4; ++k) {
         const uint32_t q = threadIdx.x + k * blockDim.x;
-        if (q < p.pieces) dst[q] = *reinterpret_cast<const uint4 *>(lrow + (q >> 2) * kRunLdsDw + (q & 3) * 4);
+        if (q < p.pieces) {
+            // the restored tensor is not read again by this kernel: streaming stores
+            const u32x4 v = *reinterpret_cast<const u32x4 *>(lrow + (q >> 2) * kRunLdsDw + (q & 3) * 4);
+            __builtin_nontemporal_store(v, reinterpret_cast<u32x4 *>(dst + q));
+        }
     }
 }
 
