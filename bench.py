@@ -42,6 +42,7 @@ def parse():
     ap.add_argument("--nbuf", type=int, default=4, help="buffer sets rotated through")
     ap.add_argument("--graph", action="store_true", help="replay the timed steps as one HIP graph")
     ap.add_argument("--bits", default="", help="allowed widths, e.g. 2,4,8 (default: the workload's set)")
+    ap.add_argument("--tau", type=float, default=0.0, help="outlier threshold (default: the workload's)")
     ap.add_argument("--c5-seqs", type=int, default=32)
     ap.add_argument("--c5-workers", type=int, default=8,
                     help="processes that generate C5 (use 1 under a profiler: its preloaded tool does not survive a fork)")
@@ -62,7 +63,7 @@ def make_input(args):
     return w, x
 
 
-def cpu_baseline(x, w, bit_set, eps, rows):
+def cpu_baseline(x, w, tau, bit_set, eps, rows):
     """The oracle as it stands, on a bounded sample of the same workload."""
     from oracle import tsq_oracle as O
     O.build()
@@ -75,7 +76,7 @@ def cpu_baseline(x, w, bit_set, eps, rows):
     best, passes, spent = None, 0, 0.0
     while passes < 1 or (spent * threads < 15.0 and passes < 50):
         t0 = time.perf_counter()
-        c = O.compress(xs, dt, w.tau, bit_set, eps, O.BUDGET_REL_RMS, nthreads=threads)
+        c = O.compress(xs, dt, tau, bit_set, eps, O.BUDGET_REL_RMS, nthreads=threads)
         t1 = time.perf_counter()
         O.decompress(c, nthreads=threads)
         t2 = time.perf_counter()
@@ -106,7 +107,8 @@ def main():
     T, H = x.shape
     pipe = "fused" if args.pipeline == "auto" else args.pipeline     # what "auto" resolves to
     bit_set = tuple(int(b) for b in args.bits.split(",")) if args.bits else tuple(w.bit_set)
-    plan = tsq.Plan(T, H, w.dtype, w.tau, bit_set, args.eps, mode="rel_rms", pipeline=pipe,
+    tau = args.tau if args.tau > 0 else w.tau
+    plan = tsq.Plan(T, H, w.dtype, tau, bit_set, args.eps, mode="rel_rms", pipeline=pipe,
                     max_outliers=max(1, (T * H) // 8))
     x0 = torch.from_numpy(x.view(np.int16)).cuda()
     nbuf = max(1, args.nbuf)
@@ -208,7 +210,7 @@ def main():
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "f32",
         "data": "synthetic",
-        "config": {"workload": "%s %dx%d %s" % (w.name, T, H, w.dtype), "tau": w.tau,
+        "config": {"workload": "%s %dx%d %s" % (w.name, T, H, w.dtype), "tau": tau,
                    "bit_set": list(bit_set), "budget": "%.3g x row RMS" % args.eps,
                    "pipeline": pipe, "launch": "hip graph" if args.graph else "stream", "buffer_sets": nbuf, "mean_width": round(bbar, 3),
                    "outlier_fraction": round(rho, 6), "width_hist": list(info.width_hist),
@@ -222,7 +224,7 @@ def main():
     }
     if not args.no_cpu_baseline:
         rows = args.cpu_sample_rows or max(64, min(T, int(2.5e8 // H)))
-        res["cpu_baseline"] = cpu_baseline(x, w, bit_set, args.eps, rows)
+        res["cpu_baseline"] = cpu_baseline(x, w, tau, bit_set, args.eps, rows)
     print(json.dumps(res))
 
 
