@@ -163,15 +163,18 @@ __device__ __forceinline__ uint32_t bit_insert(uint32_t sel, uint32_t keep, uint
 //   !(|x| < tau)  <=>  (pattern & 0x7FFF) >= thr,
 // thr being the smallest pattern whose value is >= tau (computed on the host).
 //   mg        : |T_below| of the run (see Mags)
-//   omask     : outlier flags; bit i = element 2i, bit 16+i = element 2i+1
+//   omask     : outlier flags in column order, bit j = element j
 //   amax_bits : binary32 bit pattern of the largest inlier magnitude of the run (only if WANT_MAX)
 // Per pair of elements: and, packed subtract, packed arithmetic shift (the borrow of
-// pattern - thr marks the inliers), bit-field insert into omask; then bf16: two masked widenings
+// pattern - thr marks the inliers), bit-field insert into the flags; then bf16: two masked widenings
 // and one three-way max (7 instructions), fp16: one and and one packed max (6).
+// The flags of a pair are 16 bits apart in `inl`, so the pairs 0-7 and 8-15 are collected in two
+// words (low element at bit 2i', high element at bit 17+2i', i' = i mod 8) that are folded into
+// column order at the end.
 template <int DT, bool WANT_MAX>
 __device__ __forceinline__ void split_regs(const uint32_t (&w)[16], uint32_t thr_pk, Mags<DT> &mg, uint32_t &omask,
                                            uint32_t &amax_bits) {
-    uint32_t im = 0;                       // inlier flags, collected bit by bit
+    uint32_t im_a = 0, im_b = 0;           // inlier flags of the pairs 0-7 / 8-15, collected bit by bit
     if constexpr (DT == kBF16) {
         uint32_t mx = 0;                   // non-negative binary32 patterns order like unsigned integers
 #pragma unroll
@@ -186,7 +189,8 @@ __device__ __forceinline__ void split_regs(const uint32_t (&w)[16], uint32_t thr
                 const uint32_t l = __float_as_uint(lo), t = l > hi ? l : hi;
                 mx = t > mx ? t : mx;                                      // v_max3_u32
             }
-            im = bit_insert(0x00010001u << i, inl, im);
+            if (i < 8) im_a = bit_insert(0x00020001u << (2 * i), inl, im_a);
+            else im_b = bit_insert(0x00020001u << (2 * (i - 8)), inl, im_b);
         }
         amax_bits = mx;
     } else {
@@ -198,11 +202,15 @@ __device__ __forceinline__ void split_regs(const uint32_t (&w)[16], uint32_t thr
             const uint32_t a = absw & inl;
             mg.v[i] = a;
             if (WANT_MAX) mx = pk_max_u16(mx, a);
-            im = bit_insert(0x00010001u << i, inl, im);
+            if (i < 8) im_a = bit_insert(0x00020001u << (2 * i), inl, im_a);
+            else im_b = bit_insert(0x00020001u << (2 * (i - 8)), inl, im_b);
         }
         const uint32_t m16 = (mx & 0xFFFFu) > (mx >> 16) ? (mx & 0xFFFFu) : (mx >> 16);
         amax_bits = __float_as_uint((float)__builtin_bit_cast(_Float16, (unsigned short)m16));
     }
+    // pairs 0-7: even columns sit in the low half already, the odd ones come down from the high half;
+    // pairs 8-15: the odd columns sit in the high half already, the even ones go up
+    const uint32_t im = ((im_a | (im_a >> 16)) & 0x0000FFFFu) | ((im_b | (im_b << 16)) & 0xFFFF0000u);
     omask = ~im;
 }
 

@@ -85,9 +85,10 @@ __device__ __forceinline__ void load_run_sw(const uint32_t *lrow, uint32_t r, ui
     }
 }
 __device__ __forceinline__ uint32_t raw_element_sw(const uint32_t *lrow, uint32_t r, uint32_t j) {
-    const uint32_t d = j >> 1;                               // dword of the run
-    const uint32_t pos = r * 16u + ((((d >> 2) ^ ((r >> 1) & 3u)) << 2) | (d & 3u));
-    return reinterpret_cast<const uint16_t *>(lrow)[2u * pos + (j & 1u)];
+    // byte 2j of the run, its 16-byte chunk index xor-ed with the run's swizzle: the run's part of
+    // the address does not depend on j
+    const uint32_t at = ((r * 64u) | (((r >> 1) & 3u) << 4)) ^ (j << 1);
+    return *reinterpret_cast<const uint16_t *>(reinterpret_cast<const uint8_t *>(lrow) + at);
 }
 
 // nd dwords of packed codes of a run into the token's payload image in LDS
@@ -445,12 +446,8 @@ k_fused(const Params p, const uint16_t *__restrict__ in, uint8_t *__restrict__ b
             if (omask && (stashed || direct_ok)) {
                 uint32_t *stash = stashes + (it & 1u) * kStashCap;
                 uint32_t pos = loff;
-                uint32_t ev = omask & 0xFFFFu, od = omask >> 16;
-                while (ev | od) {
-                    const uint32_t je = ev ? 2u * (uint32_t)__builtin_ctz(ev) : 64u;
-                    const uint32_t jo = od ? 2u * (uint32_t)__builtin_ctz(od) + 1u : 64u;
-                    uint32_t j;
-                    if (je < jo) { j = je; ev &= ev - 1u; } else { j = jo; od &= od - 1u; }
+                for (uint32_t rest = omask; rest; rest &= rest - 1u) {
+                    const uint32_t j = (uint32_t)__builtin_ctz(rest);
                     const uint32_t col = run * kRun + j;
                     if (stashed) {
                         stash[pos] = (col << 16) | raw_element_sw(lrow, run, j);

@@ -53,13 +53,9 @@ __device__ __forceinline__ void emit_outliers(uint32_t omask, const uint32_t *lr
                                               uint16_t *val, uint64_t row_start, uint32_t *scan_scr) {
     const uint32_t n = (uint32_t)__builtin_popcount(omask);
     uint64_t pos = row_start + block_excl_scan(n, scan_scr);
-    uint32_t ev = omask & 0xFFFFu, od = omask >> 16;
     const uint16_t *raw = reinterpret_cast<const uint16_t *>(lrow + run * kRunLdsDw);
-    while (ev | od) {
-        const uint32_t je = ev ? 2u * (uint32_t)__builtin_ctz(ev) : 64u;
-        const uint32_t jo = od ? 2u * (uint32_t)__builtin_ctz(od) + 1u : 64u;
-        uint32_t j;
-        if (je < jo) { j = je; ev &= ev - 1u; } else { j = jo; od &= od - 1u; }
+    for (uint32_t rest = omask; rest; rest &= rest - 1u) {
+        const uint32_t j = (uint32_t)__builtin_ctz(rest);
         col[pos] = (uint16_t)(run * kRun + j);
         val[pos] = raw[j];
         ++pos;
