@@ -36,10 +36,12 @@ def parse():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=50)
     ap.add_argument("--warmup", type=int, default=5)
-    ap.add_argument("--workload", default="C4", choices=["C1", "C2", "C3", "C4", "C5"])
+    ap.add_argument("--workload", default="C4", choices=["C1", "C2", "C3", "C4", "C5", "KV7", "KV13"])
     ap.add_argument("--eps", type=float, default=0.05, help="error budget, relative to the row RMS")
     ap.add_argument("--pipeline", default="auto", choices=["auto", "staged", "fused"])
-    ap.add_argument("--nbuf", type=int, default=4, help="buffer sets rotated through")
+    ap.add_argument("--nbuf", type=int, default=0,
+                    help="buffer sets rotated through (default 4; 1 for C5 and the KV workloads, whose "
+                         "single set is beyond the last-level cache already)")
     ap.add_argument("--graph", action="store_true", help="replay the timed steps as one HIP graph")
     ap.add_argument("--bits", default="", help="allowed widths, e.g. 2,4,8 (default: the workload's set)")
     ap.add_argument("--tau", type=float, default=0.0, help="outlier threshold (default: the workload's)")
@@ -54,7 +56,9 @@ def parse():
 def make_input(args):
     from paper_2511_04002_amd import synth
     w = synth.WORKLOADS[args.workload]
-    if args.workload == "C5":
+    if args.workload in synth.KV_WORKLOADS:
+        x = synth.make_kv(args.workload)          # a list of tensors: the batch form of the calls
+    elif args.workload == "C5":
         x = synth.make_c5(seqs=args.c5_seqs, workers=args.c5_workers)
     elif args.workload == "C3":
         x = synth.make_c3(0)
@@ -85,7 +89,7 @@ def cpu_baseline(x, w, tau, bit_set, eps, rows):
         if best is None or t2 - t0 < best[0]:
             best = (t2 - t0, t1 - t0, t2 - t1)
     return {"value": gb / best[0], "unit": "GB/s", "cores": threads, "kind": "oracle",
-            "sample": "first %d of %d rows of %s, best of %d passes (%.1f s in all): compress %.3f s + "
+            "sample": "first %d of the first %d rows of %s, best of %d passes (%.1f s in all): compress %.3f s + "
                       "decompress %.3f s, %d threads" % (rows, x.shape[0], w.name, passes, spent, best[1], best[2],
                                                           threads)}
 
@@ -98,33 +102,49 @@ def main():
         sys.exit(2)
     import numpy as np
     w, x = make_input(args)               # host only, before anything touches the GPU (it may fork)
+    parts = x if isinstance(x, list) else None       # KV workloads: separate tensors, batch calls
+    if parts is not None:
+        x = np.concatenate(parts[:2])                 # what the CPU baseline samples from
     import torch
     from paper_2511_04002_amd import tsq
 
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     tsq.lib()
     torch.cuda.set_device(0)
-    T, H = x.shape
+    T, H = (len(parts) * parts[0].shape[0], parts[0].shape[1]) if parts else x.shape
     pipe = "fused" if args.pipeline == "auto" else args.pipeline     # what "auto" resolves to
     bit_set = tuple(int(b) for b in args.bits.split(",")) if args.bits else tuple(w.bit_set)
     tau = args.tau if args.tau > 0 else w.tau
     plan = tsq.Plan(T, H, w.dtype, tau, bit_set, args.eps, mode="rel_rms", pipeline=pipe,
                     max_outliers=max(1, (T * H) // 8))
-    x0 = torch.from_numpy(x.view(np.int16)).cuda()
-    nbuf = max(1, args.nbuf)
-    xs = [x0] + [x0.clone() for _ in range(nbuf - 1)]
+    nbuf = max(1, args.nbuf or (1 if parts or w.name == "C5" else 4))
+    if parts:
+        x0 = [torch.from_numpy(p.view(np.int16)).cuda() for p in parts]
+        xs = [x0] + [[t.clone() for t in x0] for _ in range(nbuf - 1)]
+        outs = [[torch.empty_like(t) for t in x0] for _ in range(nbuf)]
+        tin = [plan.pointer_table(v) for v in xs]
+        tout = [plan.pointer_table(v) for v in outs]
+    else:
+        x0 = torch.from_numpy(x.view(np.int16)).cuda()
+        xs = [x0] + [x0.clone() for _ in range(nbuf - 1)]
+        outs = [plan.new_output() for _ in range(nbuf)]
     blobs = [plan.new_blob() for _ in range(nbuf)]
-    outs = [plan.new_output() for _ in range(nbuf)]
     ws = plan.new_workspace()
 
     def step(i, ev=None):
         k = i % nbuf
         if ev:
             ev[0].record()
-        plan.compress(xs[k], blobs[k], ws)
+        if parts:
+            plan.compress_batch(xs[k], blobs[k], ws, table=tin[k])
+        else:
+            plan.compress(xs[k], blobs[k], ws)
         if ev:
             ev[1].record()
-        plan.decompress(blobs[k], outs[k])
+        if parts:
+            plan.decompress_batch(blobs[k], outs[k], table=tout[k])
+        else:
+            plan.decompress(blobs[k], outs[k])
         if ev:
             ev[2].record()
 
@@ -181,7 +201,10 @@ def main():
     # (tsq_compress_timed) and around the one decompress kernel
     names = ["k_fused"] if pipe == "fused" else ["k_row_stats", "k_scan", "k_pack"]
     acc = [0.0] * len(names)
-    for i in range(args.steps):
+    if parts:
+        assert pipe == "fused", "the batch form is timed per call: with one kernel per call that is per kernel"
+        acc = [ms_c * args.steps]
+    for i in range(0 if parts else args.steps):
         k = (args.warmup + i) % nbuf
         ms = tsq.tsq_compress_timed(plan.handle, xs[k].data_ptr(), blobs[k].data_ptr(), ws.data_ptr(),
                                     plan._stream())
@@ -210,7 +233,9 @@ def main():
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "f32",
         "data": "synthetic",
-        "config": {"workload": "%s %dx%d %s" % (w.name, T, H, w.dtype), "tau": tau,
+        "config": {"workload": ("%s %dx%d %s" % (w.name, T, H, w.dtype)) +
+                               (" as %d tensors of %d rows" % (len(parts), parts[0].shape[0]) if parts else ""),
+                   "tau": tau,
                    "bit_set": list(bit_set), "budget": "%.3g x row RMS" % args.eps,
                    "pipeline": pipe, "launch": "hip graph" if args.graph else "stream", "buffer_sets": nbuf, "mean_width": round(bbar, 3),
                    "outlier_fraction": round(rho, 6), "width_hist": list(info.width_hist),

@@ -155,6 +155,26 @@ tsq_status tsq_compress_timed(const tsq_plan *plan, const void *d_in, void *d_bl
 tsq_status tsq_decompress(const tsq_plan *plan, const void *d_blob, void *d_out, void *stream);
 
 /*
+ * The KV-cache form of the two calls above (Sec. II-B: Eq. (bkv_lth_stage) counts the key and
+ * value tensors of every layer, Eq. (if_total) with I_kv = 1 sends them; footnote of Sec. II-C.1:
+ * the cache goes through the same TS + TAB-Q as the layer output): the plan's `tokens` rows are
+ * the rows of tokens / rows_per_tensor separate tensors [rows_per_tensor x hidden], taken in
+ * table order, all compressed by ONE launch into ONE blob that is byte for byte what
+ * tsq_compress produces for the concatenation of the tensors.
+ *   d_in_ptrs / d_out_ptrs : DEVICE array (8-byte aligned) of tokens / rows_per_tensor device
+ *                            pointers, each to a row-major, 16-byte aligned tensor; the table
+ *                            and the tensors belong to the caller and must stay valid until the
+ *                            call has run on `stream`
+ *   rows_per_tensor        : >= 1 and a divisor of the plan's tokens, else TSQ_ERR_INVALID_ARG
+ * Everything else (workspace, errors, asynchrony) as for tsq_compress / tsq_decompress; a blob
+ * written by either form is read by either form.
+ */
+tsq_status tsq_compress_batch(const tsq_plan *plan, const void *const *d_in_ptrs,
+                              uint32_t rows_per_tensor, void *d_blob, void *d_ws, void *stream);
+tsq_status tsq_decompress_batch(const tsq_plan *plan, const void *d_blob, void *const *d_out_ptrs,
+                                uint32_t rows_per_tensor, void *stream);
+
+/*
  * Reads the blob's header and widths back to the host.  SYNCHRONIZES `stream`.
  * Returns the status stored in the blob (CAPACITY / INTERNAL), FORMAT when the
  * header is not this plan's, or OK.

@@ -196,21 +196,40 @@ tsq_status tsq_workspace_reset(const tsq_plan *plan, void *d_ws, void *stream) {
     return hip_rc(launch_ws_reset(plan->p, d_ws, stream));
 }
 
-tsq_status tsq_compress(const tsq_plan *plan, const void *d_in, void *d_blob, void *d_ws, void *stream) {
-    if (!plan || !d_in || !d_blob || !d_ws) return TSQ_ERR_INVALID_ARG;
-    if (((uintptr_t)d_in & 15u) || ((uintptr_t)d_blob & 255u) || ((uintptr_t)d_ws & 255u)) return TSQ_ERR_INVALID_ARG;
+// One compress call.  rows_per_tensor == 0: d_in is the tensor; otherwise d_in is a device table of
+// tensor pointers (the kernels pick the row's tensor from it).
+static tsq_status compress_call(const tsq_plan *plan, const void *d_in, uint32_t rows_per_tensor, void *d_blob,
+                                void *d_ws, void *stream) {
     tsq_status st = ensure_prepared();
     if (st != TSQ_OK) return st;
+    Params p = plan->p;
     if (plan->pipeline == TSQ_PIPE_FUSED) {
         uint32_t grid = 0;
         st = fused_grid(plan, &grid);
         if (st != TSQ_OK) return st;
-        return hip_rc(launch_fused(plan->p, plan->g, grid, d_in, d_blob, d_ws, stream));
+        p = plan->p;                       // fused_grid fills in the ticket classes on its first call
+        p.rows_per_tensor = rows_per_tensor;
+        return hip_rc(launch_fused(p, plan->g, grid, d_in, d_blob, d_ws, stream));
     }
-    int e = launch_row_stats(plan->p, plan->g, d_in, d_blob, d_ws, stream);
-    if (e == 0) e = launch_scan(plan->p, d_blob, d_ws, stream);
-    if (e == 0) e = launch_pack(plan->p, plan->g, d_in, d_blob, d_ws, stream);
+    p.rows_per_tensor = rows_per_tensor;
+    int e = launch_row_stats(p, plan->g, d_in, d_blob, d_ws, stream);
+    if (e == 0) e = launch_scan(p, d_blob, d_ws, stream);
+    if (e == 0) e = launch_pack(p, plan->g, d_in, d_blob, d_ws, stream);
     return hip_rc(e);
+}
+
+tsq_status tsq_compress(const tsq_plan *plan, const void *d_in, void *d_blob, void *d_ws, void *stream) {
+    if (!plan || !d_in || !d_blob || !d_ws) return TSQ_ERR_INVALID_ARG;
+    if (((uintptr_t)d_in & 15u) || ((uintptr_t)d_blob & 255u) || ((uintptr_t)d_ws & 255u)) return TSQ_ERR_INVALID_ARG;
+    return compress_call(plan, d_in, 0, d_blob, d_ws, stream);
+}
+
+tsq_status tsq_compress_batch(const tsq_plan *plan, const void *const *d_in_ptrs, uint32_t rows_per_tensor,
+                              void *d_blob, void *d_ws, void *stream) {
+    if (!plan || !d_in_ptrs || !d_blob || !d_ws) return TSQ_ERR_INVALID_ARG;
+    if (rows_per_tensor == 0 || plan->p.tokens % rows_per_tensor != 0) return TSQ_ERR_INVALID_ARG;
+    if (((uintptr_t)d_in_ptrs & 7u) || ((uintptr_t)d_blob & 255u) || ((uintptr_t)d_ws & 255u)) return TSQ_ERR_INVALID_ARG;
+    return compress_call(plan, d_in_ptrs, rows_per_tensor, d_blob, d_ws, stream);
 }
 
 tsq_status tsq_compress_timed(const tsq_plan *plan, const void *d_in, void *d_blob, void *d_ws, void *stream,
@@ -254,6 +273,18 @@ tsq_status tsq_decompress(const tsq_plan *plan, const void *d_blob, void *d_out,
     tsq_status st = ensure_prepared();
     if (st != TSQ_OK) return st;
     return hip_rc(launch_unpack(plan->p, plan->g, d_blob, d_out, stream));
+}
+
+tsq_status tsq_decompress_batch(const tsq_plan *plan, const void *d_blob, void *const *d_out_ptrs,
+                                uint32_t rows_per_tensor, void *stream) {
+    if (!plan || !d_blob || !d_out_ptrs) return TSQ_ERR_INVALID_ARG;
+    if (rows_per_tensor == 0 || plan->p.tokens % rows_per_tensor != 0) return TSQ_ERR_INVALID_ARG;
+    if (((uintptr_t)d_out_ptrs & 7u) || ((uintptr_t)d_blob & 255u)) return TSQ_ERR_INVALID_ARG;
+    tsq_status st = ensure_prepared();
+    if (st != TSQ_OK) return st;
+    Params p = plan->p;
+    p.rows_per_tensor = rows_per_tensor;
+    return hip_rc(launch_unpack(p, plan->g, d_blob, const_cast<void **>(d_out_ptrs), stream));
 }
 
 tsq_status tsq_blob_info(const tsq_plan *plan, const void *d_blob, tsq_info *host_out, void *stream) {

@@ -186,13 +186,24 @@ __device__ __forceinline__ Prefix place_finish(const Params &p, const uint32_t *
         sh = dot_halves(w[k], 0x00010000u, sh);
     }
     uint32_t sw = sh - (uint32_t)kEarly * (tag << 14);       // the tags that rode along in the high halves
-    for (uint32_t j = pl.done + kEarly * kThreads + threadIdx.x; j < t; j += kThreads) {
-        uint32_t x = word_load(sizes + j);
-        uint32_t spins = 0;
-        while ((x >> 30) != tag && keep_waiting(spins, p.spin_limit, error_flag)) x = word_load(sizes + j);
-        if ((x >> 30) != tag) { bad = 1; x = 0; }
-        sw += (x >> 16) & 0x3FFFu;
-        sc += x & 0xFFFFu;
+    // what lies beyond the early words (narrow workgroups, whose grid is large): four loads in flight
+    for (uint32_t j0 = pl.done + kEarly * kThreads + threadIdx.x; j0 < t; j0 += 4u * kThreads) {
+        uint32_t x[4];
+#pragma unroll
+        for (int k = 0; k < 4; ++k) {
+            const uint32_t j = j0 + (uint32_t)k * kThreads;
+            x[k] = tag3;
+            if (j < t) x[k] = word_load(sizes + j);
+        }
+#pragma unroll
+        for (int k = 0; k < 4; ++k) {
+            const uint32_t j = j0 + (uint32_t)k * kThreads;
+            uint32_t spins = 0;
+            while ((x[k] >> 30) != tag && keep_waiting(spins, p.spin_limit, error_flag)) x[k] = word_load(sizes + j);
+            if ((x[k] >> 30) != tag) { bad = 1; x[k] = 0; }
+            sw += (x[k] >> 16) & 0x3FFFu;
+            sc += x[k] & 0xFFFFu;
+        }
     }
 
     uint32_t r0 = wave_sum_u32(sw), r1 = wave_sum_u32(sc);
@@ -340,7 +351,7 @@ k_fused(const Params p, const uint16_t *__restrict__ in, uint8_t *__restrict__ b
 
     // ---- first token: the workgroup's own id; its row; the ticket of the second token
     uint32_t t = wg;                       // the grid never exceeds the token count
-    fetch_row_part<FULL>(reinterpret_cast<const uint4 *>(in + (size_t)t * hidden), pieces, pre);
+    fetch_row_part<FULL>(reinterpret_cast<const uint4 *>(row_address(p, in, t, hidden)), pieces, pre);
     uint32_t req = 0;                      // thread 0: the ticket in flight
     bool requesting = true;                // uniform: a ticket is in flight
     if (tid == 0) req = __hip_atomic_fetch_add(counter, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
@@ -385,7 +396,8 @@ k_fused(const Params p, const uint16_t *__restrict__ in, uint8_t *__restrict__ b
             scale[t] = scale_of(c.amax, c.width);
         }
         // the next row starts its way from HBM now that the registers of the width search are free
-        if (tn != kNoToken) fetch_row_part<FULL>(reinterpret_cast<const uint4 *>(in + (size_t)tn * hidden), pieces, pre);
+        if (tn != kNoToken)
+            fetch_row_part<FULL>(reinterpret_cast<const uint4 *>(row_address(p, in, tn, hidden)), pieces, pre);
 
         // ---- store the token of two iterations ago: its image and stash are needed now
         if (have_old) {

@@ -60,8 +60,19 @@ struct Params {
     uint64_t ws_tickets;    // u32[2][kTicketClasses][kTicketStride] ticket counters, two banks (fused)
     uint64_t ws_ctrl;       // u32[64]  epoch (calls completed), error flag            (fused)
     uint32_t fused_classes; // ticket classes in use: min(kTicketClasses, grid)        (fused)
-    uint32_t pad1;
+    uint32_t rows_per_tensor;  // 0: the rows form one contiguous tensor.  Otherwise the data pointer of a
+                               // call is a device table of tensor pointers, rows_per_tensor rows each
+                               // (set per call from a copy of the plan's block)
 };
+
+// Row t of the input / output of a call (see Params::rows_per_tensor).  t must be uniform.
+template <typename T16>
+__device__ __forceinline__ T16 *row_address(const Params &p, T16 *base, uint32_t t, uint32_t hidden) {
+    if (p.rows_per_tensor == 0) return base + (size_t)t * hidden;
+    T16 *const *table = reinterpret_cast<T16 *const *>(base);
+    const uint32_t k = t / p.rows_per_tensor;
+    return table[k] + (size_t)(t - k * p.rows_per_tensor) * hidden;
+}
 
 inline __host__ __device__ uint32_t width_at(const Params &p, uint32_t i) {
     return (uint32_t)(p.widths_pk >> (8u * i)) & 0xFFu;

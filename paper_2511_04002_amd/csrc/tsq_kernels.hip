@@ -75,7 +75,7 @@ k_row_stats(const Params p, const uint16_t *__restrict__ in, uint8_t *__restrict
     const bool owns = run < p.runs;
 
     RowPart pre;
-    fetch_row_part(reinterpret_cast<const uint4 *>(in + (size_t)t * p.hidden), p.pieces, pre);
+    fetch_row_part(reinterpret_cast<const uint4 *>(row_address(p, in, t, p.hidden)), p.pieces, pre);
     write_row_part(lrow, p.runs, pre);
 
     Mags<DT> mg;
@@ -155,7 +155,7 @@ k_pack(const Params p, const uint16_t *__restrict__ in, uint8_t *__restrict__ bl
     const uint32_t run = threadIdx.x;
 
     RowPart pre;
-    fetch_row_part(reinterpret_cast<const uint4 *>(in + (size_t)t * p.hidden), p.pieces, pre);
+    fetch_row_part(reinterpret_cast<const uint4 *>(row_address(p, in, t, p.hidden)), p.pieces, pre);
 
     const uint32_t width = blob[p.off_bits + t];
     const uint64_t po = reinterpret_cast<const uint64_t *>(blob + p.off_pay_off)[t];
@@ -264,7 +264,7 @@ k_unpack(const Params p, const uint8_t *__restrict__ blob, uint16_t *__restrict_
         }
     }
     __syncthreads();
-    uint4 *dst = reinterpret_cast<uint4 *>(out + (size_t)t * p.hidden);
+    uint4 *dst = reinterpret_cast<uint4 *>(row_address(p, out, t, p.hidden));
 #pragma unroll
     for (int k = 0; k < 4; ++k) {
         const uint32_t q = threadIdx.x + k * blockDim.x;

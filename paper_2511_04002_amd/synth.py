@@ -46,6 +46,15 @@ WORKLOADS: Dict[str, Workload] = {
                    note="stress: 32 sequences x 4096 tokens, Student-t(3), 16 channels, 1% unstructured outliers"),
 }
 
+# KV-cache workloads (Sec. II-B, Eq. (bkv_lth_stage)): the key and value tensors of every layer for
+# w cached tokens, each [w x HD]; `tokens` counts the rows of all of them.  Shapes of the two models
+# the paper evaluates (Llama-2 7B: 32 layers, HD 4096; 13B: 40 layers, HD 5120), w = 1024.
+KV_WORKLOADS: Dict[str, Tuple[int, int]] = {"KV7": (32, 1024), "KV13": (40, 1024)}   # layers, w
+WORKLOADS["KV7"] = Workload("KV7", 2 * 32 * 1024, 4096, "f16", 8.0, (2, 3, 4, 6, 8),
+                            note="KV cache, 7B-shaped: 64 tensors [1024 x 4096]")
+WORKLOADS["KV13"] = Workload("KV13", 2 * 40 * 1024, 5120, "f16", 8.0, (2, 3, 4, 6, 8),
+                             note="KV cache, 13B-shaped: 80 tensors [1024 x 5120]")
+
 # C5 is swept over these thresholds and bit sets
 C5_TAUS = (4.0, 8.0, 16.0)
 C5_BIT_SETS = ((2, 4, 8), (2, 3, 4, 5, 6, 7, 8))
@@ -177,6 +186,34 @@ def make_c5(seqs: int = C5_SEQS, workers: int = 8) -> np.ndarray:
         for s, blk in enumerate(pool.imap(make_c5_seq, range(seqs))):
             out[s * C5_SEQ_TOKENS:(s + 1) * C5_SEQ_TOKENS] = blk
     return out
+
+
+def make_kv_tensor(name: str, layer: int, which: int, rows: Optional[int] = None) -> np.ndarray:
+    """One tensor of a KV-cache workload: which = 0 the keys, 1 the values of `layer`.
+    Keys: N(0,1) x per-token LogNormal(0, 0.3), four channels (drawn per layer) x U(6, 14), as
+    keys carry a few strong channels; values: N(0, 0.6^2) x per-token LogNormal(0, 0.3), and
+    0.005 % of the elements set to +-U(8, 30)."""
+    w = WORKLOADS[name]
+    n = rows or KV_WORKLOADS[name][1]
+    g = _rng(5, KV_WORKLOADS[name][0], layer, which)
+    if which == 0:
+        x = g.standard_normal((n, w.hidden))
+        x *= g.lognormal(0.0, 0.3, size=(n, 1))
+        ch = g.choice(w.hidden, 4, replace=False)
+        x[:, ch] *= g.uniform(6.0, 14.0, size=4)
+    else:
+        x = 0.6 * g.standard_normal((n, w.hidden))
+        x *= g.lognormal(0.0, 0.3, size=(n, 1))
+        k = max(1, int(round(5e-5 * x.size)))
+        idx = g.choice(x.size, k, replace=False)
+        x.reshape(-1)[idx] = g.uniform(8.0, 30.0, size=k) * g.choice([-1.0, 1.0], size=k)
+    return _cast(x, w.dtype)
+
+
+def make_kv(name: str, layers: Optional[int] = None, rows: Optional[int] = None):
+    """The tensors of a KV-cache workload in table order: K_1, V_1, K_2, V_2, ..."""
+    L = layers or KV_WORKLOADS[name][0]
+    return [make_kv_tensor(name, l, kv, rows) for l in range(L) for kv in (0, 1)]
 
 
 def make(name: str, **kw) -> np.ndarray:

@@ -22,7 +22,7 @@ TSQ_PIPE_AUTO, TSQ_PIPE_STAGED, TSQ_PIPE_FUSED = 0, 1, 2
 
 EXPORTS = ("tsq_plan_create", "tsq_plan_destroy", "tsq_plan_layout", "tsq_plan_blob_bytes",
            "tsq_plan_workspace_bytes", "tsq_workspace_reset", "tsq_compress", "tsq_compress_timed",
-           "tsq_decompress",
+           "tsq_decompress", "tsq_compress_batch", "tsq_decompress_batch",
            "tsq_blob_info", "tsq_status_string")
 
 
@@ -81,6 +81,10 @@ def lib():
         L.tsq_compress_timed.argtypes = [vp, vp, vp, vp, vp, C.POINTER(C.c_float)]
         L.tsq_decompress.restype = u
         L.tsq_decompress.argtypes = [vp, vp, vp, vp]
+        L.tsq_compress_batch.restype = u
+        L.tsq_compress_batch.argtypes = [vp, vp, C.c_uint32, vp, vp, vp]
+        L.tsq_decompress_batch.restype = u
+        L.tsq_decompress_batch.argtypes = [vp, vp, vp, C.c_uint32, vp]
         L.tsq_blob_info.restype = u
         L.tsq_blob_info.argtypes = [vp, vp, C.POINTER(tsq_info), vp]
         L.tsq_status_string.restype = C.c_char_p
@@ -149,6 +153,19 @@ def tsq_decompress(plan: int, d_blob: int, d_out: int, stream: int = 0) -> None:
     st = lib().tsq_decompress(plan, d_blob, d_out, stream)
     if st != TSQ_OK:
         raise TsqError(st, "tsq_decompress")
+
+
+def tsq_compress_batch(plan: int, d_in_ptrs: int, rows_per_tensor: int, d_blob: int, d_ws: int,
+                       stream: int = 0) -> None:
+    st = lib().tsq_compress_batch(plan, d_in_ptrs, rows_per_tensor, d_blob, d_ws, stream)
+    if st != TSQ_OK:
+        raise TsqError(st, "tsq_compress_batch")
+
+
+def tsq_decompress_batch(plan: int, d_blob: int, d_out_ptrs: int, rows_per_tensor: int, stream: int = 0) -> None:
+    st = lib().tsq_decompress_batch(plan, d_blob, d_out_ptrs, rows_per_tensor, stream)
+    if st != TSQ_OK:
+        raise TsqError(st, "tsq_decompress_batch")
 
 
 def tsq_blob_info(plan: int, d_blob: int, stream: int = 0, check: bool = True) -> tsq_info:
@@ -224,6 +241,33 @@ class Plan:
         assert out.is_cuda and out.is_contiguous() and out.element_size() == 2
         tsq_decompress(self.handle, blob.data_ptr(), out.data_ptr(), self._stream())
         return out
+
+    @staticmethod
+    def pointer_table(tensors):
+        """Device array of the tensors' data pointers (what the *_batch calls take)."""
+        import torch
+        for x in tensors:
+            assert x.is_cuda and x.is_contiguous() and x.element_size() == 2
+        return torch.tensor([x.data_ptr() for x in tensors], dtype=torch.int64, device="cuda")
+
+    def compress_batch(self, tensors, blob=None, ws=None, table=None):
+        """tensors: equally shaped contiguous CUDA tensors [rows, hidden] whose rows add up to the
+        plan's tokens.  `table` (from pointer_table) may be passed to reuse it across calls; it must
+        stay alive until the call has run."""
+        rows = tensors[0].numel() // self.hidden
+        assert all(x.numel() == rows * self.hidden for x in tensors) and rows * len(tensors) == self.tokens
+        table = self.pointer_table(tensors) if table is None else table
+        blob = self.new_blob() if blob is None else blob
+        ws = self.new_workspace() if ws is None else ws
+        tsq_compress_batch(self.handle, table.data_ptr(), rows, blob.data_ptr(), ws.data_ptr(), self._stream())
+        return blob, table
+
+    def decompress_batch(self, blob, outs, table=None):
+        rows = outs[0].numel() // self.hidden
+        assert all(x.numel() == rows * self.hidden for x in outs) and rows * len(outs) == self.tokens
+        table = self.pointer_table(outs) if table is None else table
+        tsq_decompress_batch(self.handle, blob.data_ptr(), table.data_ptr(), rows, self._stream())
+        return table
 
     def info(self, blob, check: bool = True) -> tsq_info:
         return tsq_blob_info(self.handle, blob.data_ptr(), self._stream(), check)

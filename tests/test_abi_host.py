@@ -75,6 +75,16 @@ def test_null_arguments(L):
         assert L.tsq_decompress(plan, None, None, None) == tsq.TSQ_ERR_INVALID_ARG
         assert L.tsq_blob_info(plan, None, None, None) == tsq.TSQ_ERR_INVALID_ARG
         assert L.tsq_workspace_reset(plan, None, None) == tsq.TSQ_ERR_INVALID_ARG
+        assert L.tsq_compress_batch(plan, None, 1, None, None, None) == tsq.TSQ_ERR_INVALID_ARG
+        assert L.tsq_decompress_batch(plan, None, None, 1, None) == tsq.TSQ_ERR_INVALID_ARG
+        # rows per tensor must be at least 1 and divide the plan's tokens; the table is 8-byte aligned
+        T = c.tokens
+        assert L.tsq_compress_batch(plan, 0x1000, 0, 0x2000, 0x3000, None) == tsq.TSQ_ERR_INVALID_ARG
+        assert L.tsq_compress_batch(plan, 0x1000, T + 1, 0x2000, 0x3000, None) == tsq.TSQ_ERR_INVALID_ARG
+        assert L.tsq_compress_batch(plan, 0x1004, T, 0x2000, 0x3000, None) == tsq.TSQ_ERR_INVALID_ARG
+        assert L.tsq_decompress_batch(plan, 0x2000, 0x1000, 0, None) == tsq.TSQ_ERR_INVALID_ARG
+        assert L.tsq_decompress_batch(plan, 0x2000, 0x1000, T + 1, None) == tsq.TSQ_ERR_INVALID_ARG
+        assert L.tsq_decompress_batch(plan, 0x2000, 0x1004, T, None) == tsq.TSQ_ERR_INVALID_ARG
         # misaligned device pointers are refused before any launch
         assert L.tsq_compress(plan, 0x1008, 0x2000, 0x3000, None) == tsq.TSQ_ERR_INVALID_ARG
         assert L.tsq_compress(plan, 0x1000, 0x2010, 0x3000, None) == tsq.TSQ_ERR_INVALID_ARG
