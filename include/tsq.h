@@ -175,6 +175,18 @@ tsq_status tsq_decompress_batch(const tsq_plan *plan, const void *d_blob, void *
                                 uint32_t rows_per_tensor, void *stream);
 
 /*
+ * Symbol statistics for the entropy coder that follows TAB-Q (Sec. II-C.2, last paragraph: the
+ * quantized symbols are coded with rANS).  d_hist receives tokens*256 32-bit counts, row-major:
+ * entry [t][c] = number of elements of token t whose b_t-bit code (sign in bit b_t-1, magnitude
+ * below it, exactly the field stored in the payload) equals c.  A row sums to `hidden`;
+ * entries c >= 2^b_t are written as 0; outlier slots carry code 0 and count as such.
+ *   d_hist : tokens*256*4 bytes, 4-byte aligned
+ * If the blob's header does not match the plan or carries a non-zero status, nothing is written.
+ * Enqueues only.
+ */
+tsq_status tsq_code_histogram(const tsq_plan *plan, const void *d_blob, void *d_hist, void *stream);
+
+/*
  * Reads the blob's header and widths back to the host.  SYNCHRONIZES `stream`.
  * Returns the status stored in the blob (CAPACITY / INTERNAL), FORMAT when the
  * header is not this plan's, or OK.

@@ -287,6 +287,12 @@ tsq_status tsq_decompress_batch(const tsq_plan *plan, const void *d_blob, void *
     return hip_rc(launch_unpack(p, plan->g, d_blob, const_cast<void **>(d_out_ptrs), stream));
 }
 
+tsq_status tsq_code_histogram(const tsq_plan *plan, const void *d_blob, void *d_hist, void *stream) {
+    if (!plan || !d_blob || !d_hist) return TSQ_ERR_INVALID_ARG;
+    if (((uintptr_t)d_hist & 3u) || ((uintptr_t)d_blob & 255u)) return TSQ_ERR_INVALID_ARG;
+    return hip_rc(launch_code_hist(plan->p, plan->g, d_blob, d_hist, stream));
+}
+
 tsq_status tsq_blob_info(const tsq_plan *plan, const void *d_blob, tsq_info *host_out, void *stream) {
     if (!plan || !d_blob || !host_out) return TSQ_ERR_INVALID_ARG;
     hipStream_t s = reinterpret_cast<hipStream_t>(stream);

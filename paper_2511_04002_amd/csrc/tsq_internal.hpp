@@ -99,6 +99,7 @@ int fused_resident_workgroups(const Params &p, const Geometry &g, uint32_t *out)
 int prepare_fused_kernels();
 int launch_ws_reset(const Params &p, void *d_ws, void *stream);
 int launch_unpack(const Params &p, const Geometry &g, const void *d_blob, void *d_out, void *stream);
+int launch_code_hist(const Params &p, const Geometry &g, const void *d_blob, void *d_hist, void *stream);
 int prepare_kernels();  // raises the dynamic-LDS limit of the row kernels once per process
 
 }  // namespace tsq

@@ -23,7 +23,7 @@ TSQ_PIPE_AUTO, TSQ_PIPE_STAGED, TSQ_PIPE_FUSED = 0, 1, 2
 EXPORTS = ("tsq_plan_create", "tsq_plan_destroy", "tsq_plan_layout", "tsq_plan_blob_bytes",
            "tsq_plan_workspace_bytes", "tsq_workspace_reset", "tsq_compress", "tsq_compress_timed",
            "tsq_decompress", "tsq_compress_batch", "tsq_decompress_batch",
-           "tsq_blob_info", "tsq_status_string")
+           "tsq_code_histogram", "tsq_blob_info", "tsq_status_string")
 
 
 class tsq_config(C.Structure):
@@ -85,6 +85,8 @@ def lib():
         L.tsq_compress_batch.argtypes = [vp, vp, C.c_uint32, vp, vp, vp]
         L.tsq_decompress_batch.restype = u
         L.tsq_decompress_batch.argtypes = [vp, vp, vp, C.c_uint32, vp]
+        L.tsq_code_histogram.restype = u
+        L.tsq_code_histogram.argtypes = [vp, vp, vp, vp]
         L.tsq_blob_info.restype = u
         L.tsq_blob_info.argtypes = [vp, vp, C.POINTER(tsq_info), vp]
         L.tsq_status_string.restype = C.c_char_p
@@ -166,6 +168,12 @@ def tsq_decompress_batch(plan: int, d_blob: int, d_out_ptrs: int, rows_per_tenso
     st = lib().tsq_decompress_batch(plan, d_blob, d_out_ptrs, rows_per_tensor, stream)
     if st != TSQ_OK:
         raise TsqError(st, "tsq_decompress_batch")
+
+
+def tsq_code_histogram(plan: int, d_blob: int, d_hist: int, stream: int = 0) -> None:
+    st = lib().tsq_code_histogram(plan, d_blob, d_hist, stream)
+    if st != TSQ_OK:
+        raise TsqError(st, "tsq_code_histogram")
 
 
 def tsq_blob_info(plan: int, d_blob: int, stream: int = 0, check: bool = True) -> tsq_info:
@@ -268,6 +276,15 @@ class Plan:
         table = self.pointer_table(outs) if table is None else table
         tsq_decompress_batch(self.handle, blob.data_ptr(), table.data_ptr(), rows, self._stream())
         return table
+
+    def code_histogram(self, blob, hist=None):
+        """-> CUDA int32 tensor [tokens, 256]: how often each code occurs in each token."""
+        import torch
+        if hist is None:
+            hist = torch.empty((self.tokens, 256), dtype=torch.int32, device="cuda")
+        assert hist.is_cuda and hist.is_contiguous() and hist.numel() == self.tokens * 256
+        tsq_code_histogram(self.handle, blob.data_ptr(), hist.data_ptr(), self._stream())
+        return hist
 
     def info(self, blob, check: bool = True) -> tsq_info:
         return tsq_blob_info(self.handle, blob.data_ptr(), self._stream(), check)
