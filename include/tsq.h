@@ -194,6 +194,72 @@ tsq_status tsq_code_histogram(const tsq_plan *plan, const void *d_blob, void *d_
 tsq_status tsq_blob_info(const tsq_plan *plan, const void *d_blob, tsq_info *host_out,
                          void *stream);
 
+/*
+ * Link model and early exit (Sec. II-D.2).  HOST-only scalar code, no GPU work; every pointer
+ * is a host pointer.  Sizes are in bits, rates in bits per second, times in seconds.
+ *
+ * tsq_link: bandwidth W in Hz, received SNR gamma, target outage probability epsilon.
+ *   outage probability     P_o(R) = 1 - exp(-(2^(R/W) - 1) / gamma)
+ *   worst-case latency     L_eps(D_tx; R) = D_tx / R * ceil(ln eps / ln P_o(R))   Eq. (comm_latency)
+ *                          (+inf where P_o(R) = 1; at least one transmission; 0 for D_tx = 0)
+ *   best rate              Eq. (epsilon_rstar): the rate in [rate_lo, rate_hi] with the smallest
+ *                          worst-case delay, i.e. the one that maximises R * ln(1 / P_o(R))
+ *                          (Eq. (comm_latency) without its ceiling is proportional to the
+ *                          reciprocal of that product; the function g as printed next to
+ *                          Eq. (epsilon_rstar) has the rate in the denominator and falls to 0 as the
+ *                          link saturates, so it cannot be what is minimised), by search on a
+ *                          uniform grid of steps + 1 rates (the first best wins)
+ * Invalid arguments (NULL, W <= 0, gamma <= 0, epsilon outside (0,1), rate <= 0, ...) give NaN.
+ */
+typedef struct {
+    double bandwidth_hz;
+    double snr;
+    double outage;
+} tsq_link;
+double tsq_link_outage_probability(const tsq_link *link, double rate);
+double tsq_link_latency(const tsq_link *link, double bits, double rate);
+double tsq_link_best_rate(const tsq_link *link, double rate_lo, double rate_hi, uint32_t steps);
+
+/*
+ * One decision of Algorithm 2 (early exit under a delay constraint) for the token count and the
+ * layer at hand: keep going if the intermediate output fits the deadline as it is; else send it
+ * compressed; else compressed without the KV cache (I_kv = 0); else cut tokens from the end
+ * until the deadline holds.  Total latency is L_c(w) + L_eps(size; rate), Eq. (total).
+ *   tokens                   : w, tokens of the hidden state so far
+ *   compute_latency          : w + 1 entries, L_c(k) for k = 0 .. w tokens (profiled by the caller)
+ *   raw_bits                 : B_io of Eq. (if_total) with the cache, uncompressed
+ *   compressed_bits_with_kv  : 8 * compressed_bytes of the hidden state's blob plus the cache's
+ *   hidden_prefix_bits       : w + 1 entries, compressed size of the first k tokens of the hidden
+ *                              state (k = 0 .. w; from the blob's pay_off / row_ptr and the
+ *                              21 bytes of metadata per token)
+ * Returns INVALID_ARG on NULL pointers or a link / rate / deadline out of domain.
+ */
+typedef enum {
+    TSQ_EXIT_CONTINUE = 0,      /* the uncompressed output meets the deadline: no exit            */
+    TSQ_EXIT_COMPRESSED = 1,    /* exit, sending hidden state and cache through TS + TAB-Q        */
+    TSQ_EXIT_WITHOUT_KV = 2,    /* exit, sending the compressed hidden state only                 */
+    TSQ_EXIT_FEWER_TOKENS = 3   /* exit, sending the first `tokens` tokens of it only             */
+} tsq_exit_action;
+typedef struct {
+    tsq_link link;
+    double rate;                /* R*, e.g. from tsq_link_best_rate                               */
+    double deadline;            /* D                                                              */
+    uint32_t tokens;
+    const double *compute_latency;
+    double raw_bits;
+    double compressed_bits_with_kv;
+    const uint64_t *hidden_prefix_bits;
+} tsq_exit_input;
+typedef struct {
+    int32_t action;             /* tsq_exit_action                                                */
+    int32_t with_kv;            /* I_kv of what is sent                                           */
+    uint32_t tokens;            /* tokens of the hidden state that are sent                       */
+    uint32_t reserved;
+    double latency;             /* L_t of the decision (above the deadline only if even zero
+                                   tokens do not meet it)                                         */
+} tsq_exit_decision;
+tsq_status tsq_early_exit_decide(const tsq_exit_input *in, tsq_exit_decision *out);
+
 const char *tsq_status_string(tsq_status s);
 
 #ifdef __cplusplus

@@ -23,7 +23,9 @@ TSQ_PIPE_AUTO, TSQ_PIPE_STAGED, TSQ_PIPE_FUSED = 0, 1, 2
 EXPORTS = ("tsq_plan_create", "tsq_plan_destroy", "tsq_plan_layout", "tsq_plan_blob_bytes",
            "tsq_plan_workspace_bytes", "tsq_workspace_reset", "tsq_compress", "tsq_compress_timed",
            "tsq_decompress", "tsq_compress_batch", "tsq_decompress_batch",
-           "tsq_code_histogram", "tsq_blob_info", "tsq_status_string")
+           "tsq_code_histogram", "tsq_blob_info", "tsq_status_string",
+           "tsq_link_outage_probability", "tsq_link_latency", "tsq_link_best_rate", "tsq_early_exit_decide")
+TSQ_EXIT_CONTINUE, TSQ_EXIT_COMPRESSED, TSQ_EXIT_WITHOUT_KV, TSQ_EXIT_FEWER_TOKENS = 0, 1, 2, 3
 
 
 class tsq_config(C.Structure):
@@ -43,6 +45,21 @@ class tsq_info(C.Structure):
     _fields_ = [("nnz", C.c_uint64), ("payload_bytes", C.c_uint64),
                 ("compressed_bytes", C.c_uint64), ("width_hist", C.c_uint64 * 9),
                 ("status", C.c_uint32), ("reserved", C.c_uint32)]
+
+
+class tsq_link(C.Structure):
+    _fields_ = [("bandwidth_hz", C.c_double), ("snr", C.c_double), ("outage", C.c_double)]
+
+
+class tsq_exit_input(C.Structure):
+    _fields_ = [("link", tsq_link), ("rate", C.c_double), ("deadline", C.c_double), ("tokens", C.c_uint32),
+                ("compute_latency", C.POINTER(C.c_double)), ("raw_bits", C.c_double),
+                ("compressed_bits_with_kv", C.c_double), ("hidden_prefix_bits", C.POINTER(C.c_uint64))]
+
+
+class tsq_exit_decision(C.Structure):
+    _fields_ = [("action", C.c_int32), ("with_kv", C.c_int32), ("tokens", C.c_uint32), ("reserved", C.c_uint32),
+                ("latency", C.c_double)]
 
 
 class TsqError(RuntimeError):
@@ -89,6 +106,14 @@ def lib():
         L.tsq_code_histogram.argtypes = [vp, vp, vp, vp]
         L.tsq_blob_info.restype = u
         L.tsq_blob_info.argtypes = [vp, vp, C.POINTER(tsq_info), vp]
+        L.tsq_link_outage_probability.restype = C.c_double
+        L.tsq_link_outage_probability.argtypes = [C.POINTER(tsq_link), C.c_double]
+        L.tsq_link_latency.restype = C.c_double
+        L.tsq_link_latency.argtypes = [C.POINTER(tsq_link), C.c_double, C.c_double]
+        L.tsq_link_best_rate.restype = C.c_double
+        L.tsq_link_best_rate.argtypes = [C.POINTER(tsq_link), C.c_double, C.c_double, C.c_uint32]
+        L.tsq_early_exit_decide.restype = u
+        L.tsq_early_exit_decide.argtypes = [C.POINTER(tsq_exit_input), C.POINTER(tsq_exit_decision)]
         L.tsq_status_string.restype = C.c_char_p
         L.tsq_status_string.argtypes = [u]
         _lib = L
@@ -182,6 +207,33 @@ def tsq_blob_info(plan: int, d_blob: int, stream: int = 0, check: bool = True) -
     if st != TSQ_OK and check:
         raise TsqError(st, "tsq_blob_info")
     out.return_status = st
+    return out
+
+
+def tsq_link_outage_probability(link: tsq_link, rate: float) -> float:
+    return float(lib().tsq_link_outage_probability(C.byref(link), rate))
+
+
+def tsq_link_latency(link: tsq_link, bits: float, rate: float) -> float:
+    return float(lib().tsq_link_latency(C.byref(link), bits, rate))
+
+
+def tsq_link_best_rate(link: tsq_link, rate_lo: float, rate_hi: float, steps: int) -> float:
+    return float(lib().tsq_link_best_rate(C.byref(link), rate_lo, rate_hi, steps))
+
+
+def tsq_early_exit_decide(link: tsq_link, rate: float, deadline: float, compute_latency, raw_bits: float,
+                          compressed_bits_with_kv: float, hidden_prefix_bits) -> tsq_exit_decision:
+    """compute_latency, hidden_prefix_bits: sequences of w + 1 entries (k = 0 .. w tokens)."""
+    w = len(compute_latency) - 1
+    assert w >= 0 and len(hidden_prefix_bits) == w + 1
+    lc = (C.c_double * (w + 1))(*[float(v) for v in compute_latency])
+    hp = (C.c_uint64 * (w + 1))(*[int(v) for v in hidden_prefix_bits])
+    inp = tsq_exit_input(link, rate, deadline, w, lc, raw_bits, compressed_bits_with_kv, hp)
+    out = tsq_exit_decision()
+    st = lib().tsq_early_exit_decide(C.byref(inp), C.byref(out))
+    if st != TSQ_OK:
+        raise TsqError(st, "tsq_early_exit_decide")
     return out
 
 
