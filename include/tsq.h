@@ -187,6 +187,42 @@ tsq_status tsq_decompress_batch(const tsq_plan *plan, const void *d_blob, void *
 tsq_status tsq_code_histogram(const tsq_plan *plan, const void *d_blob, void *d_hist, void *stream);
 
 /*
+ * Entropy coding of the payload (Sec. II-C.2, last paragraph: the symbols TAB-Q produces are coded
+ * with rANS).  The paper leaves the coder to a third-party package; the format is this library's:
+ * one 12-bit frequency table per width class, built from the pooled code counts (scaled to a sum
+ * of 4096, every occurring code at least 1); per token 64 interleaved rANS coders (state in
+ * [2^16, 2^32), 16-bit renormalisation), coder l owning the runs of 32 codes l, l + 64, ...; a
+ * token's stream is its 64 final states followed by the 16-bit words in the order the decoder
+ * reads them, padded to 4 bytes.
+ *
+ * Entropy-coded payload ("eblob", device memory, little-endian, offsets from its start in
+ * tsq_entropy_layout): 256-byte header | tables u16[7][256] (row b - 2: width b) |
+ * stream offsets u64[tokens + 1] (bytes from the start of the streams) | streams.
+ *
+ * tsq_entropy_encode reads a completed blob and writes d_eblob; only the payload section of the
+ * blob is recoded, its other sections (widths, scales, offsets, outliers) travel as they are.
+ * tsq_entropy_decode writes the payload section of d_blob back from d_eblob; d_blob must hold the
+ * blob's other sections (header, widths, offsets) already.  The restored payload is byte for byte
+ * the one that was encoded.
+ *   d_eblob : tsq_entropy_blob_bytes() bytes (capacity for the longest possible streams), 256-byte aligned
+ *   d_ews   : tsq_entropy_workspace_bytes() bytes, 256-byte aligned, encoder only, needs no reset
+ * Both calls only enqueue.  If the blob (or, for decode, the eblob) is not this plan's or carries
+ * a non-zero status, nothing is written and the eblob's header stays invalid.
+ * tsq_entropy_info SYNCHRONIZES `stream`; it returns FORMAT for an eblob that is not this plan's.
+ */
+typedef struct {
+    uint64_t off_tables, off_stream_off, off_streams;
+    uint64_t stream_capacity;   /* bytes                                                          */
+    uint64_t stream_bytes;      /* bytes of all streams                                           */
+    uint64_t coded_bytes;       /* header + tables + offsets + streams: what replaces the payload */
+} tsq_entropy_layout;
+size_t     tsq_entropy_blob_bytes(const tsq_plan *plan);
+size_t     tsq_entropy_workspace_bytes(const tsq_plan *plan);
+tsq_status tsq_entropy_encode(const tsq_plan *plan, const void *d_blob, void *d_eblob, void *d_ews, void *stream);
+tsq_status tsq_entropy_decode(const tsq_plan *plan, const void *d_eblob, void *d_blob, void *stream);
+tsq_status tsq_entropy_info(const tsq_plan *plan, const void *d_eblob, tsq_entropy_layout *host_out, void *stream);
+
+/*
  * Reads the blob's header and widths back to the host.  SYNCHRONIZES `stream`.
  * Returns the status stored in the blob (CAPACITY / INTERNAL), FORMAT when the
  * header is not this plan's, or OK.

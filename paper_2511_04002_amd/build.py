@@ -12,7 +12,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libtsq.so")
-SOURCES = ["tsq_api.hip", "tsq_kernels.hip", "tsq_fused.hip", "tsq_entropy.hip", "tsq_link.cpp"]
+SOURCES = ["tsq_api.hip", "tsq_kernels.hip", "tsq_fused.hip", "tsq_entropy.hip", "tsq_rans.hip", "tsq_link.cpp"]
 HEADERS = ["tsq_internal.hpp", "tsq_device.hpp", os.path.join(ROOT, "include", "tsq.h")]
 
 # -ffp-contract=off: the quantizer's multiply and every fp64 product of the budget test must

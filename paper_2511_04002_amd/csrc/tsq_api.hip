@@ -19,6 +19,7 @@ struct tsq_plan {
     tsq_config cfg;
     Params p;
     Geometry g;
+    EntropyLayout e;
     tsq_layout layout;
     int pipeline;  // resolved: TSQ_PIPE_STAGED or TSQ_PIPE_FUSED
     // persistent grid of the fused kernel, found on the first compress call (needs the device)
@@ -146,6 +147,22 @@ tsq_status tsq_plan_create(const tsq_config *cfg, tsq_plan **out) {
     p.off_out_val = L.off_out_val; p.payload_capacity = L.payload_capacity;
     p.outlier_capacity = L.outlier_capacity;
 
+    EntropyLayout &E = pl->e;
+    std::memset(&E, 0, sizeof E);
+    E.slot_bytes = 256u + ((p.runs + 63u) / 64u) * 4096u;
+    uint64_t eo = sizeof(EntropyHeader);
+    E.off_tables = eo;      eo = align_up(eo + 7ull * 256 * 2, 256);
+    E.off_stream_off = eo;  eo = align_up(eo + 8ull * (T + 1ull), 256);
+    E.stream_capacity = (uint64_t)T * E.slot_bytes;
+    E.off_streams = eo;     eo = align_up(eo + E.stream_capacity, 256);
+    E.eblob_bytes = eo;
+    uint64_t ew = 0;
+    E.ws_hist = ew;    ew = align_up(ew + 1024ull * T, 256);
+    E.ws_pooled = ew;  ew = align_up(ew + 7ull * 256 * 4, 256);
+    E.ws_len = ew;     ew = align_up(ew + 4ull * T, 256);
+    E.ws_slots = ew;   ew = align_up(ew + (uint64_t)T * E.slot_bytes, 256);
+    E.ws_bytes = ew;
+
     pl->g.block = 64u * ((p.runs + 63u) / 64u);
     pl->g.lds_bytes = (p.runs * kRunLdsDw + kScratchDw) * 4u;
     pl->g.waves = compress_waves(p.runs);
@@ -170,6 +187,7 @@ static tsq_status ensure_prepared() {
     std::call_once(g_prepare_once, [] {
         g_prepare_rc = prepare_kernels();
         if (g_prepare_rc == 0) g_prepare_rc = prepare_fused_kernels();
+        if (g_prepare_rc == 0) g_prepare_rc = prepare_rans_kernels();
     });
     return hip_rc(g_prepare_rc);
 }
@@ -291,6 +309,43 @@ tsq_status tsq_code_histogram(const tsq_plan *plan, const void *d_blob, void *d_
     if (!plan || !d_blob || !d_hist) return TSQ_ERR_INVALID_ARG;
     if (((uintptr_t)d_hist & 3u) || ((uintptr_t)d_blob & 255u)) return TSQ_ERR_INVALID_ARG;
     return hip_rc(launch_code_hist(plan->p, plan->g, d_blob, d_hist, stream));
+}
+
+size_t tsq_entropy_blob_bytes(const tsq_plan *plan) { return plan ? (size_t)plan->e.eblob_bytes : 0; }
+size_t tsq_entropy_workspace_bytes(const tsq_plan *plan) { return plan ? (size_t)plan->e.ws_bytes : 0; }
+
+tsq_status tsq_entropy_encode(const tsq_plan *plan, const void *d_blob, void *d_eblob, void *d_ews, void *stream) {
+    if (!plan || !d_blob || !d_eblob || !d_ews) return TSQ_ERR_INVALID_ARG;
+    if (((uintptr_t)d_blob & 255u) || ((uintptr_t)d_eblob & 255u) || ((uintptr_t)d_ews & 255u)) return TSQ_ERR_INVALID_ARG;
+    tsq_status st = ensure_prepared();
+    if (st != TSQ_OK) return st;
+    return hip_rc(launch_rans_encode(plan->p, plan->g, plan->e, d_blob, d_eblob, d_ews, stream));
+}
+
+tsq_status tsq_entropy_decode(const tsq_plan *plan, const void *d_eblob, void *d_blob, void *stream) {
+    if (!plan || !d_blob || !d_eblob) return TSQ_ERR_INVALID_ARG;
+    if (((uintptr_t)d_blob & 255u) || ((uintptr_t)d_eblob & 255u)) return TSQ_ERR_INVALID_ARG;
+    tsq_status st = ensure_prepared();
+    if (st != TSQ_OK) return st;
+    return hip_rc(launch_rans_decode(plan->p, plan->e, d_eblob, d_blob, stream));
+}
+
+tsq_status tsq_entropy_info(const tsq_plan *plan, const void *d_eblob, tsq_entropy_layout *host_out, void *stream) {
+    if (!plan || !d_eblob || !host_out) return TSQ_ERR_INVALID_ARG;
+    hipStream_t s = reinterpret_cast<hipStream_t>(stream);
+    EntropyHeader h;
+    if (hipMemcpyAsync(&h, d_eblob, sizeof h, hipMemcpyDeviceToHost, s) != hipSuccess) return TSQ_ERR_HIP;
+    if (hipStreamSynchronize(s) != hipSuccess) return TSQ_ERR_HIP;
+    std::memset(host_out, 0, sizeof *host_out);
+    const EntropyLayout &E = plan->e;
+    host_out->off_tables = E.off_tables; host_out->off_stream_off = E.off_stream_off;
+    host_out->off_streams = E.off_streams; host_out->stream_capacity = E.stream_capacity;
+    if (h.magic != kEntropyMagic || h.version != kVersion || h.tokens != plan->p.tokens || h.hidden != plan->p.hidden ||
+        h.off_streams != E.off_streams || h.stream_bytes > E.stream_capacity)
+        return TSQ_ERR_FORMAT;
+    host_out->stream_bytes = h.stream_bytes;
+    host_out->coded_bytes = 256ull + 7ull * 256 * 2 + 8ull * (plan->p.tokens + 1ull) + h.stream_bytes;
+    return TSQ_OK;
 }
 
 tsq_status tsq_blob_info(const tsq_plan *plan, const void *d_blob, tsq_info *host_out, void *stream) {

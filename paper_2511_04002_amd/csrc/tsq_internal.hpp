@@ -36,6 +36,28 @@ struct BlobHeader {
 };
 static_assert(sizeof(BlobHeader) == 128, "blob header must be 128 bytes");
 
+// Entropy-coded payload ("eblob"): 256-byte header | frequency tables u16[7][256] (row b-2: width b) |
+// stream offsets u64[T+1] (bytes from the start of the streams) | the tokens' streams.
+constexpr uint32_t kEntropyMagic = 0x45515354u;   // "TSQE"
+struct EntropyHeader {
+    uint32_t magic, version, tokens, hidden;
+    uint64_t stream_bytes;                          // sum of the tokens' streams
+    uint64_t off_tables, off_stream_off, off_streams, stream_capacity;
+    uint64_t reserved[25];
+};
+static_assert(sizeof(EntropyHeader) == 256, "entropy header must be 256 bytes");
+// Sections of the eblob and of the encoder's workspace (bytes), fixed by the plan.
+struct EntropyLayout {
+    uint64_t off_tables, off_stream_off, off_streams, stream_capacity, eblob_bytes;
+    uint64_t ws_hist;       // u32[T][256] code counts per token
+    uint64_t ws_pooled;     // u32[7][256] code counts per width class
+    uint64_t ws_len;        // u32[T] stream bytes per token
+    uint64_t ws_slots;      // T slots of slot_bytes: the streams before they are moved together
+    uint64_t ws_bytes;
+    uint32_t slot_bytes;    // 256 (states) + 2 bytes per element of the padded row: the longest possible stream
+    uint32_t pad;
+};
+
 // Kernel argument block (passed by value).
 struct Params {
     uint32_t tokens, hidden;
@@ -100,6 +122,10 @@ int prepare_fused_kernels();
 int launch_ws_reset(const Params &p, void *d_ws, void *stream);
 int launch_unpack(const Params &p, const Geometry &g, const void *d_blob, void *d_out, void *stream);
 int launch_code_hist(const Params &p, const Geometry &g, const void *d_blob, void *d_hist, void *stream);
+int prepare_rans_kernels();
+int launch_rans_encode(const Params &p, const Geometry &g, const EntropyLayout &e, const void *d_blob, void *d_eblob,
+                       void *d_ews, void *stream);
+int launch_rans_decode(const Params &p, const EntropyLayout &e, const void *d_eblob, void *d_blob, void *stream);
 int prepare_kernels();  // raises the dynamic-LDS limit of the row kernels once per process
 
 }  // namespace tsq

@@ -1,0 +1,458 @@
+// Entropy coding of the packed codes (gfx950): the rANS stage that the paper places after TAB-Q
+// (Sec. II-C.2, last paragraph).  The paper leaves the coder to a third-party package; format and
+// kernels here are this library's own.
+//
+// Format.  One frequency table per width class (all tokens of one width share it): pooled code
+// counts scaled to 12 bits.  Every token is coded on its own by 64 interleaved rANS coders, one
+// per lane of a wave (state in [2^16, 2^32), 16-bit renormalisation).  The token's codes are cut
+// into runs of 32, as everywhere in this library; coder l owns the runs l, l + 64, ...; step i
+// handles element i % 32 of run number i / 32 of every coder.  The encoder walks the steps
+// backwards, the decoder forwards; the 16-bit words that the coders shed in one step are stored
+// in lane order (a ballot and a population count give every lane its place).  A token's stream
+// is its 64 final states followed by the words in the order the decoder reads them, padded to
+// 4 bytes.
+//
+// Encode: code counts per token (k_code_hist) -> pooled per width (k_rans_pool) -> tables
+// (k_rans_tables) -> one wave per token codes its stream into a slot of the workspace
+// (k_rans_encode) -> offsets (k_rans_scan) -> streams moved to their places (k_rans_gather).
+// Decode: one wave per token (k_rans_decode) rebuilds the packed payload; the words it reads
+// pass through registers (four windows of 64 words), so a token needs 5 KB of LDS for its tables
+// and nothing else, and a compute unit holds its full 32 waves.
+#include <hip/hip_runtime.h>
+
+#include "tsq_device.hpp"
+#include "tsq_internal.hpp"
+
+namespace tsq {
+
+constexpr uint32_t kProbBits = 12, kProbScale = 1u << kProbBits, kRansLow = 1u << 16;
+
+__device__ __forceinline__ bool blob_is_valid(const Params &p, const uint8_t *blob) {
+    const BlobHeader *h = reinterpret_cast<const BlobHeader *>(blob);
+    return h->magic == kMagic && h->version == kVersion && h->status == 0 && h->tokens == p.tokens &&
+           h->hidden == p.hidden && h->dtype == p.dtype && h->off_payload == p.off_payload;
+}
+__device__ __forceinline__ bool eblob_is_valid(const Params &p, const EntropyLayout &e, const uint8_t *eblob) {
+    const EntropyHeader *h = reinterpret_cast<const EntropyHeader *>(eblob);
+    return h->magic == kEntropyMagic && h->version == kVersion && h->tokens == p.tokens && h->hidden == p.hidden &&
+           h->off_streams == e.off_streams && h->stream_bytes <= e.stream_capacity;
+}
+
+// ---------------------------------------------------------------- pooled counts and tables
+
+__global__ void k_rans_begin(const EntropyLayout e, uint8_t *__restrict__ eblob, uint8_t *__restrict__ ews) {
+    uint32_t *pooled = reinterpret_cast<uint32_t *>(ews + e.ws_pooled);
+    for (uint32_t i = threadIdx.x; i < 7u * 256u; i += blockDim.x) pooled[i] = 0;
+    // the header becomes valid only when the last kernel of the call has run
+    if (threadIdx.x < sizeof(EntropyHeader) / 4) reinterpret_cast<uint32_t *>(eblob)[threadIdx.x] = 0;
+}
+
+__global__ void __launch_bounds__(256)
+k_rans_pool(const Params p, const EntropyLayout e, const uint8_t *__restrict__ blob, uint8_t *__restrict__ ews) {
+    __shared__ uint32_t acc[7 * 256];
+    if (!blob_is_valid(p, blob)) return;
+    const uint32_t *hist = reinterpret_cast<const uint32_t *>(ews + e.ws_hist);
+    uint32_t *pooled = reinterpret_cast<uint32_t *>(ews + e.ws_pooled);
+    for (uint32_t i = threadIdx.x; i < 7u * 256u; i += 256u) acc[i] = 0;
+    __syncthreads();
+    for (uint32_t t = blockIdx.x; t < p.tokens; t += gridDim.x) {
+        const uint32_t b = blob[p.off_bits + t];
+        if (b >= 2 && b <= 8) acc[(b - 2u) * 256u + threadIdx.x] += hist[(size_t)t * 256u + threadIdx.x];
+    }
+    __syncthreads();
+    for (uint32_t i = threadIdx.x; i < 7u * 256u; i += 256u)
+        if (acc[i]) atomicAdd(pooled + i, acc[i]);
+}
+
+// One workgroup per width class: counts -> 12-bit frequencies.  f_c = max(1, floor(n_c * 4096 / N))
+// for n_c > 0; while the sum exceeds 4096, one is taken from the largest f (lowest code on ties);
+// a remaining deficit goes to the code with the largest count (lowest code on ties).
+// Taking E times one from the current largest entry is a cut at a level: with
+// g(v) = sum_c max(f_c - v, 0), the level is the v with g(v + 1) < E <= g(v); every entry above
+// v + 1 comes down to v + 1, and the first E - g(v + 1) entries (in code order) that then stand at
+// v + 1 go down to v.  The level is found by bisection, each probe a workgroup-wide sum.
+__global__ void __launch_bounds__(256)
+k_rans_tables(const Params p, const EntropyLayout e, const uint8_t *__restrict__ blob, uint8_t *__restrict__ eblob,
+              const uint8_t *__restrict__ ews) {
+    __shared__ uint32_t n[256], f[256], sum[3];
+    if (!blob_is_valid(p, blob)) return;
+    const uint32_t k = blockIdx.x, c = threadIdx.x;
+    const uint32_t *pooled = reinterpret_cast<const uint32_t *>(ews + e.ws_pooled) + k * 256u;
+    uint16_t *table = reinterpret_cast<uint16_t *>(eblob + e.off_tables) + k * 256u;
+    // workgroup-wide sum of one value per thread: three accumulators in rotation and one barrier per
+    // sum (the accumulator of the sum after the next is cleared behind this sum's barrier)
+    uint32_t turn = 0;
+    auto block_sum = [&](uint32_t v) {
+        uint32_t *acc = &sum[turn % 3u];
+        if (v) atomicAdd(acc, v);
+        __syncthreads();
+        const uint32_t r = *acc;
+        if (c == 0) sum[(turn + 2u) % 3u] = 0;
+        ++turn;
+        return r;
+    };
+    if (c == 0) { sum[0] = 0; sum[1] = 0; sum[2] = 0; }
+    n[c] = pooled[c];
+    __syncthreads();
+    const uint32_t N = block_sum(n[c]);
+    uint32_t fc = 0;
+    if (N && n[c]) {
+        fc = (uint32_t)(((uint64_t)n[c] << kProbBits) / N);
+        if (fc == 0) fc = 1;
+    }
+    const uint32_t S = block_sum(fc);
+    f[c] = fc;
+    __syncthreads();
+    if (S > kProbScale) {
+        const uint32_t E = S - kProbScale;
+        uint32_t lo = 0, hi = kProbScale;        // g(lo) >= E always (g(0) = S > E); g(hi) = 0 < E
+        while (hi - lo > 1u) {                   // invariant: g(lo) >= E > g(hi)
+            const uint32_t mid = (lo + hi) >> 1;
+            const uint32_t g = block_sum(fc > mid ? fc - mid : 0u);
+            if (g >= E) lo = mid; else hi = mid;
+        }
+        // level lo: g(lo + 1) < E <= g(lo)
+        const uint32_t above = block_sum(fc > lo + 1u ? fc - (lo + 1u) : 0u);
+        const uint32_t rest = E - above;         // entries at lo + 1 (after the cut) that go one further down
+        uint32_t rank = 0;
+        for (uint32_t i = 0; i < c; ++i) rank += f[i] > lo ? 1u : 0u;
+        if (fc > lo) fc = rank < rest ? lo : lo + 1u;
+    } else if (N && S < kProbScale) {
+        bool first_largest = n[c] > 0;
+        for (uint32_t i = 0; i < 256u && first_largest; ++i)
+            if (i < c ? n[i] >= n[c] : n[i] > n[c]) first_largest = false;
+        if (first_largest) fc += kProbScale - S;
+    }
+    table[c] = (uint16_t)fc;
+}
+
+// The table of a token's class into LDS as f | cum << 16 (cum = exclusive running sum, < 4096),
+// by one wave: lane l owns the codes 4l .. 4l+3.
+__device__ __forceinline__ void load_table(const uint16_t *table, uint32_t *ftab) {
+    const uint32_t lane = threadIdx.x & 63u;
+    uint32_t f[4], s = 0;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) { f[i] = table[4u * lane + i]; s += f[i]; }
+    uint32_t cum = wave_incl_scan_u32(s) - s;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        ftab[4u * lane + i] = f[i] | (cum << 16);
+        cum += f[i];
+    }
+}
+
+// ---------------------------------------------------------------- encode
+
+// The steps of one round (run number `round` of every lane), last element first.  The words go
+// straight to the token's slot in the workspace, which fills from its end downwards.
+template <int B>
+__device__ __forceinline__ void encode_round(const uint32_t *src_row, uint32_t run, int valid, const uint32_t *ftab,
+                                             uint16_t *out, uint32_t &ptr, uint32_t &x) {
+    uint32_t d[B];
+    const uint32_t nd = valid >= 32 ? (uint32_t)B : (valid > 0 ? ((uint32_t)valid * B + 31u) >> 5 : 0u);
+#pragma unroll
+    for (int k = 0; k < B; ++k) d[k] = (uint32_t)k < nd ? src_row[run * B + k] : 0u;
+    const uint64_t below = (1ull << (threadIdx.x & 63u)) - 1ull;
+#pragma unroll
+    for (int j = 31; j >= 0; --j) {
+        const int off = j * B, k = off >> 5, sh = off & 31;
+        uint32_t code = d[k] >> sh;
+        if (sh + B > 32) code |= d[k + 1 < B ? k + 1 : k] << (32 - sh);
+        code &= (1u << B) - 1u;
+        const bool active = j < valid;
+        const uint32_t fc = ftab[code];
+        uint32_t f = fc & 0xFFFFu;
+        const uint32_t c = fc >> 16;
+        if (f == 0) f = 1;                                     // a code the table does not know: cannot happen for a
+                                                               // table built from this blob; keeps the division defined
+        const bool shed = active && (x >> 20) >= f;            // x >= f << 20, without overflow for f = 4096
+        const uint64_t who = __builtin_amdgcn_ballot_w64(shed);
+        ptr -= (uint32_t)__builtin_popcountll(who);
+        if (shed) {
+            out[ptr + (uint32_t)__builtin_popcountll(who & below)] = (uint16_t)x;
+            x >>= 16;
+        }
+        if (active) x = ((x / f) << kProbBits) + (x % f) + c;
+    }
+}
+
+// Slot of a token in the workspace: 64 states (256 bytes), then room for one word per element of
+// the padded row; the words stand at the END of that room (the encoder fills it backwards).
+__global__ void __launch_bounds__(64)
+k_rans_encode(const Params p, const EntropyLayout e, const uint8_t *__restrict__ blob, const uint8_t *__restrict__ eblob,
+              uint8_t *__restrict__ ews) {
+    __shared__ uint32_t ftab[256];
+    const uint32_t t = blockIdx.x, lane = threadIdx.x;
+    uint32_t *len = reinterpret_cast<uint32_t *>(ews + e.ws_len);
+    if (!blob_is_valid(p, blob)) return;
+    const uint32_t width = blob[p.off_bits + t];
+    const uint64_t po = reinterpret_cast<const uint64_t *>(blob + p.off_pay_off)[t];
+    if (width < 2 || width > 8 || (po & 3u) || po + row_bytes(p.hidden, width) > p.payload_capacity) {
+        if (lane == 0) len[t] = 0;
+        return;
+    }
+    load_table(reinterpret_cast<const uint16_t *>(eblob + e.off_tables) + (width - 2u) * 256u, ftab);
+    __syncthreads();
+    const uint32_t *src_row = reinterpret_cast<const uint32_t *>(blob + p.off_payload + po);
+    uint8_t *slot = ews + e.ws_slots + (size_t)t * e.slot_bytes;
+    uint16_t *out = reinterpret_cast<uint16_t *>(slot + 256);
+    const uint32_t rounds = (p.runs + 63u) / 64u, cap = rounds * 2048u;
+    uint32_t x = kRansLow, ptr = cap;
+    for (uint32_t r = rounds; r-- > 0;) {
+        const uint32_t run = lane + 64u * r;
+        const int valid = (int)p.hidden - (int)(run * kRun);          // may be <= 0: nothing of this run exists
+        switch (width) {
+            case 2: encode_round<2>(src_row, run, valid, ftab, out, ptr, x); break;
+            case 3: encode_round<3>(src_row, run, valid, ftab, out, ptr, x); break;
+            case 4: encode_round<4>(src_row, run, valid, ftab, out, ptr, x); break;
+            case 5: encode_round<5>(src_row, run, valid, ftab, out, ptr, x); break;
+            case 6: encode_round<6>(src_row, run, valid, ftab, out, ptr, x); break;
+            case 7: encode_round<7>(src_row, run, valid, ftab, out, ptr, x); break;
+            default: encode_round<8>(src_row, run, valid, ftab, out, ptr, x); break;
+        }
+    }
+    reinterpret_cast<uint32_t *>(slot)[lane] = x;
+    if (lane == 0) {
+        len[t] = 256u + 2u * (cap - ptr);                  // unpadded; the stream is padded to 4 bytes when it is placed
+    }
+}
+
+// Exclusive running sum of the (padded) stream lengths, and the header: one workgroup.  A thread
+// adds up its share of the tokens (that fits 32 bits: at most 128 tokens of at most 64 KB), a wave
+// scans its 64 shares, and the 16 wave totals are chained in 64 bits.
+__global__ void __launch_bounds__(1024)
+k_rans_scan(const Params p, const EntropyLayout e, const uint8_t *__restrict__ blob, uint8_t *__restrict__ eblob,
+            const uint8_t *__restrict__ ews) {
+    __shared__ uint64_t wave_base[17];
+    if (!blob_is_valid(p, blob)) return;
+    const uint32_t *len = reinterpret_cast<const uint32_t *>(ews + e.ws_len);
+    uint64_t *off = reinterpret_cast<uint64_t *>(eblob + e.off_stream_off);
+    const uint32_t per = (p.tokens + 1023u) / 1024u;
+    const uint32_t lo = threadIdx.x * per, hi = lo + per < p.tokens ? lo + per : p.tokens;
+    uint32_t s = 0;
+    for (uint32_t t = lo; t < hi; ++t) s += (len[t] + 3u) & ~3u;
+    const uint32_t incl = wave_incl_scan_u32(s);
+    if ((threadIdx.x & 63u) == 63u) wave_base[1u + (threadIdx.x >> 6)] = incl;
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        uint64_t run = 0;
+        wave_base[0] = 0;
+        for (uint32_t i = 1; i <= 16u; ++i) { run += wave_base[i]; wave_base[i] = run; }
+        EntropyHeader h = {};
+        h.magic = kEntropyMagic; h.version = kVersion; h.tokens = p.tokens; h.hidden = p.hidden;
+        h.stream_bytes = run;
+        h.off_tables = e.off_tables; h.off_stream_off = e.off_stream_off; h.off_streams = e.off_streams;
+        h.stream_capacity = e.stream_capacity;
+        *reinterpret_cast<EntropyHeader *>(eblob) = h;
+        off[p.tokens] = run;
+    }
+    __syncthreads();
+    uint64_t at = wave_base[threadIdx.x >> 6] + (incl - s);
+    for (uint32_t t = lo; t < hi; ++t) { off[t] = at; at += (len[t] + 3u) & ~3u; }
+}
+
+__global__ void __launch_bounds__(256)
+k_rans_gather(const Params p, const EntropyLayout e, const uint8_t *__restrict__ blob, uint8_t *__restrict__ eblob,
+              const uint8_t *__restrict__ ews) {
+    if (!blob_is_valid(p, blob)) return;
+    const uint32_t t = blockIdx.x;
+    const uint32_t bytes = reinterpret_cast<const uint32_t *>(ews + e.ws_len)[t];      // states + words, unpadded
+    const uint64_t at = reinterpret_cast<const uint64_t *>(eblob + e.off_stream_off)[t];
+    if (bytes < 256u || bytes > e.slot_bytes || at + ((bytes + 3u) & ~3u) > e.stream_capacity) return;
+    const uint8_t *slot = ews + e.ws_slots + (size_t)t * e.slot_bytes;
+    uint8_t *dst = eblob + e.off_streams + at;
+    if (threadIdx.x < 64u) reinterpret_cast<uint32_t *>(dst)[threadIdx.x] = reinterpret_cast<const uint32_t *>(slot)[threadIdx.x];
+    // the words stand at the end of the slot
+    const uint32_t nwords = (bytes - 256u) >> 1, room = (e.slot_bytes - 256u) >> 1;
+    const uint16_t *src = reinterpret_cast<const uint16_t *>(slot + 256) + (room - nwords);
+    uint16_t *words = reinterpret_cast<uint16_t *>(dst + 256);
+    for (uint32_t i = threadIdx.x; i < nwords; i += 256u) words[i] = src[i];
+    if ((nwords & 1u) && threadIdx.x == 0) words[nwords] = 0;                          // padding to 4 bytes
+}
+
+// ---------------------------------------------------------------- decode
+
+// Inclusive running maximum over the lanes of a wave, in lane order.
+__device__ __forceinline__ uint32_t wave_incl_scan_max(uint32_t v) {
+    uint32_t n;
+    n = dpp<kDppRowShr + 1>(v); v = n > v ? n : v;     // lanes without a source inside their row see 0
+    n = dpp<kDppRowShr + 2>(v); v = n > v ? n : v;
+    n = dpp<kDppRowShr + 4>(v); v = n > v ? n : v;
+    n = dpp<kDppRowShr + 8>(v); v = n > v ? n : v;
+    const uint32_t r0 = lane_value(v, 15), r1 = lane_value(v, 31), r2 = lane_value(v, 47);
+    const uint32_t row = (threadIdx.x & 63) >> 4;
+    uint32_t before = 0;
+    if (row > 0) before = r0;
+    if (row > 1) before = r1 > before ? r1 : before;
+    if (row > 2) before = r2 > before ? r2 : before;
+    return v > before ? v : before;
+}
+
+// slot -> code for all 4096 slots: a code's index is written at the slot where its range starts,
+// and a running maximum carries it over the range (later codes start at later slots).
+__device__ __forceinline__ void build_slot_table(const uint32_t *ftab, uint32_t *sym32) {
+    const uint32_t lane = threadIdx.x & 63u;
+    uint8_t *sym = reinterpret_cast<uint8_t *>(sym32);
+#pragma unroll
+    for (int i = 0; i < 16; ++i) sym32[16u * lane + i] = 0;
+    __syncthreads();
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        const uint32_t c = 4u * lane + i, fc = ftab[c];
+        if (fc & 0xFFFFu) sym[fc >> 16] = (uint8_t)c;
+    }
+    __syncthreads();
+    // lane l owns the slots 64l .. 64l+63
+    uint32_t w[16], mx = 0;
+#pragma unroll
+    for (int i = 0; i < 16; ++i) {
+        w[i] = sym32[16u * lane + i];
+#pragma unroll
+        for (int k = 0; k < 4; ++k) {
+            const uint32_t v = (w[i] >> (8 * k)) & 0xFFu;
+            mx = v > mx ? v : mx;
+        }
+    }
+    const uint32_t incl = wave_incl_scan_max(mx);
+    // the maximum over the lanes before this one: shift the inclusive result down by one lane
+    uint32_t run = (uint32_t)__builtin_amdgcn_ds_bpermute((int)(((lane + 63u) & 63u) << 2), (int)incl);
+    if (lane == 0) run = 0;
+#pragma unroll
+    for (int i = 0; i < 16; ++i) {
+        uint32_t o = 0;
+#pragma unroll
+        for (int k = 0; k < 4; ++k) {
+            const uint32_t v = (w[i] >> (8 * k)) & 0xFFu;
+            run = v > run ? v : run;
+            o |= run << (8 * k);
+        }
+        sym32[16u * lane + i] = o;
+    }
+    __syncthreads();
+}
+
+// The token's words as the decoder consumes them: four windows of 64 words in registers (lane l
+// of window k holds word base + 64k + l); a step reads at most 64 words from the first two, and
+// when the first is used up the windows move on and the fourth is fetched from memory again.
+struct Words {
+    const uint16_t *src;
+    uint32_t count, base;
+    uint32_t w0, w1, w2, w3;
+};
+__device__ __forceinline__ uint32_t word_at(const Words &q, uint32_t k) {
+    const uint32_t i = k + (threadIdx.x & 63u);
+    return i < q.count ? (uint32_t)q.src[i] : 0u;               // past the end: a damaged stream is read as zeros
+}
+__device__ __forceinline__ void words_open(Words &q, const uint16_t *src, uint32_t count) {
+    q.src = src; q.count = count; q.base = 0;
+    q.w0 = word_at(q, 0); q.w1 = word_at(q, 64); q.w2 = word_at(q, 128); q.w3 = word_at(q, 192);
+}
+
+template <int B>
+__device__ __forceinline__ void decode_round(uint32_t *dst_row, uint32_t run, int valid, const uint32_t *ftab,
+                                             const uint8_t *sym, Words &q, uint32_t &pos, uint32_t &x) {
+    uint32_t d[B];
+#pragma unroll
+    for (int k = 0; k < B; ++k) d[k] = 0;
+    const uint64_t below = (1ull << (threadIdx.x & 63u)) - 1ull;
+#pragma unroll
+    for (int j = 0; j < 32; ++j) {
+        const bool active = j < valid;
+        const uint32_t slot = x & (kProbScale - 1u);
+        const uint32_t s = sym[slot];
+        const uint32_t fc = ftab[s];
+        if (active) {
+            x = (fc & 0xFFFFu) * (x >> kProbBits) + slot - (fc >> 16);
+            const int off = j * B, k = off >> 5, sh = off & 31;
+            d[k] |= s << sh;
+            if (sh + B > 32) d[k + 1 < B ? k + 1 : k] |= s >> (32 - sh);
+        }
+        const bool need = active && x < kRansLow;
+        const uint64_t who = __builtin_amdgcn_ballot_w64(need);
+        if (who) {
+            const uint32_t at = pos - q.base + (uint32_t)__builtin_popcountll(who & below);   // < 128
+            const uint32_t a = (uint32_t)__builtin_amdgcn_ds_bpermute((int)((at & 63u) << 2), (int)q.w0);
+            const uint32_t b = (uint32_t)__builtin_amdgcn_ds_bpermute((int)((at & 63u) << 2), (int)q.w1);
+            if (need) x = (x << 16) | (at < 64u ? a : b);
+            pos += (uint32_t)__builtin_popcountll(who);
+            if (pos - q.base >= 64u) {
+                q.base += 64u;
+                q.w0 = q.w1; q.w1 = q.w2; q.w2 = q.w3;
+                q.w3 = word_at(q, q.base + 192u);
+            }
+        }
+    }
+    const uint32_t nd = valid >= 32 ? (uint32_t)B : (valid > 0 ? ((uint32_t)valid * B + 31u) >> 5 : 0u);
+#pragma unroll
+    for (int k = 0; k < B; ++k)
+        if ((uint32_t)k < nd) dst_row[run * B + k] = d[k];
+}
+
+__global__ void __launch_bounds__(64)
+k_rans_decode(const Params p, const EntropyLayout e, const uint8_t *__restrict__ eblob, uint8_t *__restrict__ blob) {
+    __shared__ uint32_t ftab[256];
+    __shared__ uint32_t sym32[1024];                                   // slot -> code, one byte per slot
+    const uint32_t t = blockIdx.x, lane = threadIdx.x;
+    if (!blob_is_valid(p, blob) || !eblob_is_valid(p, e, eblob)) return;
+    const uint32_t width = blob[p.off_bits + t];
+    const uint64_t po = reinterpret_cast<const uint64_t *>(blob + p.off_pay_off)[t];
+    if (width < 2 || width > 8 || (po & 3u) || po + row_bytes(p.hidden, width) > p.payload_capacity) return;
+    const uint64_t *off = reinterpret_cast<const uint64_t *>(eblob + e.off_stream_off);
+    const uint64_t a = off[t], b = off[t + 1];
+    if (b < a + 256u || b > e.stream_capacity || b - a > e.slot_bytes || (a & 3u)) return;
+    load_table(reinterpret_cast<const uint16_t *>(eblob + e.off_tables) + (width - 2u) * 256u, ftab);
+    __syncthreads();
+    build_slot_table(ftab, sym32);
+    const uint8_t *sym = reinterpret_cast<const uint8_t *>(sym32);
+    const uint8_t *stream = eblob + e.off_streams + a;
+    Words q;
+    words_open(q, reinterpret_cast<const uint16_t *>(stream + 256), (uint32_t)(b - a - 256u) >> 1);
+    uint32_t x = reinterpret_cast<const uint32_t *>(stream)[lane], pos = 0;
+    uint32_t *dst_row = reinterpret_cast<uint32_t *>(blob + p.off_payload + po);
+    const uint32_t rounds = (p.runs + 63u) / 64u;
+    for (uint32_t r = 0; r < rounds; ++r) {
+        const uint32_t run = lane + 64u * r;
+        const int valid = (int)p.hidden - (int)(run * kRun);
+        switch (width) {
+            case 2: decode_round<2>(dst_row, run, valid, ftab, sym, q, pos, x); break;
+            case 3: decode_round<3>(dst_row, run, valid, ftab, sym, q, pos, x); break;
+            case 4: decode_round<4>(dst_row, run, valid, ftab, sym, q, pos, x); break;
+            case 5: decode_round<5>(dst_row, run, valid, ftab, sym, q, pos, x); break;
+            case 6: decode_round<6>(dst_row, run, valid, ftab, sym, q, pos, x); break;
+            case 7: decode_round<7>(dst_row, run, valid, ftab, sym, q, pos, x); break;
+            default: decode_round<8>(dst_row, run, valid, ftab, sym, q, pos, x); break;
+        }
+    }
+}
+
+// ---------------------------------------------------------------- launchers
+
+static hipStream_t as_stream(void *s) { return reinterpret_cast<hipStream_t>(s); }
+
+int prepare_rans_kernels() { return 0; }
+
+int launch_rans_encode(const Params &p, const Geometry &g, const EntropyLayout &e, const void *d_blob, void *d_eblob,
+                       void *d_ews, void *stream) {
+    const uint8_t *blob = static_cast<const uint8_t *>(d_blob);
+    uint8_t *eblob = static_cast<uint8_t *>(d_eblob), *ews = static_cast<uint8_t *>(d_ews);
+    hipStream_t s = as_stream(stream);
+    hipLaunchKernelGGL(k_rans_begin, dim3(1), dim3(256), 0, s, e, eblob, ews);
+    int rc = launch_code_hist(p, g, d_blob, ews + e.ws_hist, stream);
+    if (rc != 0) return rc;
+    uint32_t blocks = (p.tokens + 7u) / 8u;
+    if (blocks > 1024u) blocks = 1024u;
+    hipLaunchKernelGGL(k_rans_pool, dim3(blocks), dim3(256), 0, s, p, e, blob, ews);
+    hipLaunchKernelGGL(k_rans_tables, dim3(7), dim3(256), 0, s, p, e, blob, eblob, ews);
+    hipLaunchKernelGGL(k_rans_encode, dim3(p.tokens), dim3(64), 0, s, p, e, blob, eblob, ews);
+    hipLaunchKernelGGL(k_rans_scan, dim3(1), dim3(1024), 0, s, p, e, blob, eblob, ews);
+    hipLaunchKernelGGL(k_rans_gather, dim3(p.tokens), dim3(256), 0, s, p, e, blob, eblob, ews);
+    return (int)hipGetLastError();
+}
+
+int launch_rans_decode(const Params &p, const EntropyLayout &e, const void *d_eblob, void *d_blob, void *stream) {
+    hipLaunchKernelGGL(k_rans_decode, dim3(p.tokens), dim3(64), 0, as_stream(stream), p, e,
+                       static_cast<const uint8_t *>(d_eblob), static_cast<uint8_t *>(d_blob));
+    return (int)hipGetLastError();
+}
+
+}  // namespace tsq

@@ -57,6 +57,22 @@ def main():
     table_per_token = float(sum(16.0 * (1 << int(b)) for b in bits))        # 2-byte entries
     table_per_width = float(sum(16.0 * (1 << int(b)) for b in widths))
     moved = info.payload_bytes + 1024.0 * T
+    # the coder itself: encode (counts, tables, streams) and decode, timed the same way
+    eblob, ews = plan.new_entropy_blob(), plan.new_entropy_workspace()
+    plan.entropy_encode(blob, eblob, ews)
+    einfo = tsq.tsq_entropy_info(plan.handle, eblob.data_ptr(), plan._stream())
+    back = blob.clone()
+    ev = [torch.cuda.Event(enable_timing=True) for _ in range(3)]
+    ev[0].record()
+    for _ in range(args.steps):
+        plan.entropy_encode(blob, eblob, ews)
+    ev[1].record()
+    for _ in range(args.steps):
+        plan.entropy_decode(eblob, back)
+    ev[2].record()
+    torch.cuda.synchronize()
+    assert torch.equal(back, blob)
+    ms_enc, ms_dec = ev[0].elapsed_time(ev[1]) / args.steps, ev[1].elapsed_time(ev[2]) / args.steps
     print(json.dumps({
         "workload": "%s %dx%d %s" % (w.name, T, H, w.dtype), "budget": "%.3g x row RMS" % args.eps,
         "bits_per_element": {
@@ -67,6 +83,10 @@ def main():
             "ideal_one_table_per_width_with_tables": (pooled + table_per_width) / n},
         "width_hist": list(info.width_hist),
         "k_code_hist": {"ms": ms, "bytes": moved, "GBps": moved / ms / 1e6, "frac_of_8TBps": moved / ms / 1e6 / 8000.0},
+        "rans": {"stream_bytes": einfo.stream_bytes, "coded_bytes": einfo.coded_bytes, "payload_bytes": info.payload_bytes,
+                 "bits_per_element": 8.0 * einfo.coded_bytes / n, "encode_ms": ms_enc, "decode_ms": ms_dec,
+                 "encode_GBps_of_payload": info.payload_bytes / ms_enc / 1e6,
+                 "decode_GBps_of_payload": info.payload_bytes / ms_dec / 1e6},
     }))
 
 

@@ -24,7 +24,8 @@ EXPORTS = ("tsq_plan_create", "tsq_plan_destroy", "tsq_plan_layout", "tsq_plan_b
            "tsq_plan_workspace_bytes", "tsq_workspace_reset", "tsq_compress", "tsq_compress_timed",
            "tsq_decompress", "tsq_compress_batch", "tsq_decompress_batch",
            "tsq_code_histogram", "tsq_blob_info", "tsq_status_string",
-           "tsq_link_outage_probability", "tsq_link_latency", "tsq_link_best_rate", "tsq_early_exit_decide")
+           "tsq_entropy_blob_bytes", "tsq_entropy_workspace_bytes", "tsq_entropy_encode", "tsq_entropy_decode",
+           "tsq_entropy_info", "tsq_link_outage_probability", "tsq_link_latency", "tsq_link_best_rate", "tsq_early_exit_decide")
 TSQ_EXIT_CONTINUE, TSQ_EXIT_COMPRESSED, TSQ_EXIT_WITHOUT_KV, TSQ_EXIT_FEWER_TOKENS = 0, 1, 2, 3
 
 
@@ -45,6 +46,11 @@ class tsq_info(C.Structure):
     _fields_ = [("nnz", C.c_uint64), ("payload_bytes", C.c_uint64),
                 ("compressed_bytes", C.c_uint64), ("width_hist", C.c_uint64 * 9),
                 ("status", C.c_uint32), ("reserved", C.c_uint32)]
+
+
+class tsq_entropy_layout(C.Structure):
+    _fields_ = [(n, C.c_uint64) for n in ("off_tables", "off_stream_off", "off_streams", "stream_capacity",
+                                          "stream_bytes", "coded_bytes")]
 
 
 class tsq_link(C.Structure):
@@ -106,6 +112,16 @@ def lib():
         L.tsq_code_histogram.argtypes = [vp, vp, vp, vp]
         L.tsq_blob_info.restype = u
         L.tsq_blob_info.argtypes = [vp, vp, C.POINTER(tsq_info), vp]
+        L.tsq_entropy_blob_bytes.restype = C.c_size_t
+        L.tsq_entropy_blob_bytes.argtypes = [vp]
+        L.tsq_entropy_workspace_bytes.restype = C.c_size_t
+        L.tsq_entropy_workspace_bytes.argtypes = [vp]
+        L.tsq_entropy_encode.restype = u
+        L.tsq_entropy_encode.argtypes = [vp, vp, vp, vp, vp]
+        L.tsq_entropy_decode.restype = u
+        L.tsq_entropy_decode.argtypes = [vp, vp, vp, vp]
+        L.tsq_entropy_info.restype = u
+        L.tsq_entropy_info.argtypes = [vp, vp, C.POINTER(tsq_entropy_layout), vp]
         L.tsq_link_outage_probability.restype = C.c_double
         L.tsq_link_outage_probability.argtypes = [C.POINTER(tsq_link), C.c_double]
         L.tsq_link_latency.restype = C.c_double
@@ -206,6 +222,35 @@ def tsq_blob_info(plan: int, d_blob: int, stream: int = 0, check: bool = True) -
     st = lib().tsq_blob_info(plan, d_blob, C.byref(out), stream)
     if st != TSQ_OK and check:
         raise TsqError(st, "tsq_blob_info")
+    out.return_status = st
+    return out
+
+
+def tsq_entropy_blob_bytes(plan: int) -> int:
+    return int(lib().tsq_entropy_blob_bytes(plan))
+
+
+def tsq_entropy_workspace_bytes(plan: int) -> int:
+    return int(lib().tsq_entropy_workspace_bytes(plan))
+
+
+def tsq_entropy_encode(plan: int, d_blob: int, d_eblob: int, d_ews: int, stream: int = 0) -> None:
+    st = lib().tsq_entropy_encode(plan, d_blob, d_eblob, d_ews, stream)
+    if st != TSQ_OK:
+        raise TsqError(st, "tsq_entropy_encode")
+
+
+def tsq_entropy_decode(plan: int, d_eblob: int, d_blob: int, stream: int = 0) -> None:
+    st = lib().tsq_entropy_decode(plan, d_eblob, d_blob, stream)
+    if st != TSQ_OK:
+        raise TsqError(st, "tsq_entropy_decode")
+
+
+def tsq_entropy_info(plan: int, d_eblob: int, stream: int = 0, check: bool = True) -> tsq_entropy_layout:
+    out = tsq_entropy_layout()
+    st = lib().tsq_entropy_info(plan, d_eblob, C.byref(out), stream)
+    if st != TSQ_OK and check:
+        raise TsqError(st, "tsq_entropy_info")
     out.return_status = st
     return out
 
@@ -337,6 +382,37 @@ class Plan:
         assert hist.is_cuda and hist.is_contiguous() and hist.numel() == self.tokens * 256
         tsq_code_histogram(self.handle, blob.data_ptr(), hist.data_ptr(), self._stream())
         return hist
+
+    def new_entropy_blob(self):
+        import torch
+        return torch.empty(tsq_entropy_blob_bytes(self.handle), dtype=torch.uint8, device="cuda")
+
+    def new_entropy_workspace(self):
+        import torch
+        return torch.empty(tsq_entropy_workspace_bytes(self.handle), dtype=torch.uint8, device="cuda")
+
+    def entropy_encode(self, blob, eblob=None, ews=None):
+        eblob = self.new_entropy_blob() if eblob is None else eblob
+        ews = self.new_entropy_workspace() if ews is None else ews
+        tsq_entropy_encode(self.handle, blob.data_ptr(), eblob.data_ptr(), ews.data_ptr(), self._stream())
+        return eblob
+
+    def entropy_decode(self, eblob, blob):
+        tsq_entropy_decode(self.handle, eblob.data_ptr(), blob.data_ptr(), self._stream())
+        return blob
+
+    def entropy_sections(self, eblob):
+        """Host copies of the eblob's sections, the streams cut to their actual length."""
+        import numpy as np
+        import torch
+        info = tsq_entropy_info(self.handle, eblob.data_ptr(), self._stream())
+        torch.cuda.synchronize()
+        raw = eblob.cpu().numpy()
+        T = self.tokens
+        return {"tables": raw[info.off_tables: info.off_tables + 7 * 512].view(np.uint16).reshape(7, 256).copy(),
+                "stream_off": raw[info.off_stream_off: info.off_stream_off + 8 * (T + 1)].view(np.uint64).copy(),
+                "streams": raw[info.off_streams: info.off_streams + info.stream_bytes].copy(),
+                "info": info}
 
     def info(self, blob, check: bool = True) -> tsq_info:
         return tsq_blob_info(self.handle, blob.data_ptr(), self._stream(), check)

@@ -1,0 +1,135 @@
+"""Parity of the rANS stage (tsq_entropy_encode / tsq_entropy_decode) with its oracle: tables,
+stream offsets and stream bytes bit-exact; decode restores the payload byte for byte."""
+import numpy as np
+import pytest
+
+from paper_2511_04002_amd import synth
+
+pytestmark = pytest.mark.gpu
+
+DT = {"f16": 0, "bf16": 1}
+
+
+@pytest.fixture(scope="module")
+def tsq():
+    import torch
+    assert torch.cuda.is_available(), "these tests need the GPU"
+    from paper_2511_04002_amd import tsq as m
+    m.lib()
+    return m
+
+
+@pytest.fixture(scope="module")
+def RE(oracle):
+    from oracle import entropy_oracle, rans_oracle
+    return rans_oracle, entropy_oracle
+
+
+def check(tsq, oracle, RE, x, dtype, tau, bit_set, budget, mode=1, label=""):
+    import torch
+    R, E = RE
+    print("case", label, x.shape, dtype, tau, bit_set, budget, flush=True)
+    T, H = x.shape
+    ref = oracle.compress(x, DT[dtype], tau, bit_set, budget, mode, nthreads=8)
+    tables, off, streams = R.encode(ref, E.code_histogram(ref))
+
+    plan = tsq.Plan(T, H, dtype, tau, bit_set, budget, mode="rel_rms" if mode == 1 else "lsb",
+                    max_outliers=max(ref.nnz, 1))
+    blob = plan.compress(torch.from_numpy(x.view(np.int16)).cuda())
+    assert plan.info(blob).status == 0
+    eblob = plan.new_entropy_blob()
+    eblob.fill_(0xA5)
+    plan.entropy_encode(blob, eblob)
+    sec = plan.entropy_sections(eblob)
+    assert np.array_equal(sec["tables"], tables), "tables"
+    assert np.array_equal(sec["stream_off"], off), "stream offsets"
+    assert sec["info"].stream_bytes == len(streams)
+    assert sec["streams"].tobytes() == streams, "streams"
+    assert sec["info"].coded_bytes == 256 + 7 * 512 + 8 * (T + 1) + len(streams)
+
+    # decode into a blob whose payload section has been wiped
+    L = plan.layout
+    blob2 = blob.clone()
+    blob2[int(L.off_payload): int(L.off_payload) + int(L.payload_capacity)] = 0xEE
+    plan.entropy_decode(eblob, blob2)
+    a, b = plan.sections(blob), plan.sections(blob2)
+    assert np.array_equal(a["payload"], b["payload"]) and np.array_equal(a["payload"], ref.payload)
+    out = plan.decompress(blob2)
+    assert np.array_equal(out.cpu().numpy().view(np.uint16), oracle.decompress(ref, nthreads=8))
+    return ref, len(streams)
+
+
+def test_c1_and_mixed_widths(tsq, oracle, RE):
+    for eps in (0.05, 0.1, 0.3):
+        check(tsq, oracle, RE, synth.make_c1(), "f16", 6.0, (2, 4, 8), eps, label="C1")
+    ref, n = check(tsq, oracle, RE, synth.make_c2(tokens=128), "f16", 8.0, (2, 3, 4, 6, 8), 0.2, label="C2 rows")
+    assert len(set(ref.bits.tolist())) >= 2
+    assert n < ref.payload_bytes                    # the coder pays: fewer bytes than the packed payload
+
+
+def test_c4_rows_every_width(tsq, oracle, RE):
+    x = synth.make_c4(tokens=96)
+    seen = set()
+    for bs, eps in (((2, 3, 4, 5, 6, 8), 0.05), ((2, 3, 4, 5, 6, 8), 0.2), ((7,), 0.0), ((2, 3), 0.0)):
+        ref, _ = check(tsq, oracle, RE, x, "bf16", 10.0, bs, eps, label="C4 rows")
+        seen |= set(ref.bits.tolist())
+    assert seen >= {2, 3, 4, 5, 6, 7, 8}
+
+
+@pytest.mark.parametrize("dtype", ["f16", "bf16"])
+@pytest.mark.parametrize("H", [8, 24, 40, 264, 1000, 2056, 4096 + 8])
+def test_edge_rows_and_ragged_hidden(tsq, oracle, RE, dtype, H):
+    x = synth.edge_rows(H, dtype, 6.0) if H >= 264 else None
+    if x is None:
+        g = np.random.Generator(np.random.PCG64(H))
+        v = g.standard_normal((37, H)) * 3.0
+        x = synth.to_f16_bits(v) if dtype == "f16" else synth.to_bf16_bits(v)
+    for bs, bud, mode in (((2, 4, 5, 8), 0.05, 1), ((2, 3, 4, 5, 6, 7, 8), 0.3, 0)):
+        check(tsq, oracle, RE, x, dtype, 6.0, bs, bud, mode, label="edge H=%d" % H)
+
+
+def test_a_foreign_blob_gives_no_valid_eblob(tsq):
+    import torch
+    plan = tsq.Plan(16, 64, "f16", 6.0, (4, 8), 0.05)
+    blob = plan.new_blob()
+    blob.zero_()
+    eblob = plan.entropy_encode(blob)
+    info = tsq.tsq_entropy_info(plan.handle, eblob.data_ptr(), 0, check=False)
+    assert info.return_status == tsq.TSQ_ERR_FORMAT
+    # and decode of a foreign eblob leaves the blob alone
+    x = torch.from_numpy(synth.to_f16_bits(np.ones((16, 64))).view(np.int16)).cuda()
+    good = plan.compress(x)
+    before = good.clone()
+    plan.entropy_decode(eblob, good)
+    torch.cuda.synchronize()
+    assert torch.equal(before, good)
+
+
+def test_c4_full_size_sampled_tokens_and_round_trip(tsq, oracle, RE):
+    """The full target tensor in the launch configuration that is timed: tables and offsets complete,
+    streams of sampled tokens against the oracle, and the round trip of the whole payload."""
+    import torch
+    R, E = RE
+    w = synth.WORKLOADS["C4"]
+    x = synth.make_c4()
+    T, H = x.shape
+    ref = oracle.compress(x, oracle.BF16, w.tau, w.bit_set, 0.05, 1, nthreads=8)
+    hist = E.code_histogram(ref)
+    tables = R.class_tables(hist, ref.bits)
+    plan = tsq.Plan(T, H, w.dtype, w.tau, w.bit_set, 0.05, max_outliers=max(ref.nnz, 1))
+    blob = plan.compress(torch.from_numpy(x.view(np.int16)).cuda())
+    eblob = plan.entropy_encode(blob)
+    sec = plan.entropy_sections(eblob)
+    assert np.array_equal(sec["tables"], tables)
+    off = sec["stream_off"]
+    assert off[0] == 0 and np.all(np.diff(off.astype(np.int64)) >= 256) and int(off[-1]) == sec["info"].stream_bytes
+    g = np.random.Generator(np.random.PCG64(2))
+    for t in sorted(set(g.integers(0, T, 12).tolist()) | {0, T - 1}):
+        want = R.encode_token(E.token_codes(ref, t), tables[int(ref.bits[t]) - 2])
+        assert sec["streams"][int(off[t]): int(off[t + 1])].tobytes() == want, "token %d" % t
+    L = plan.layout
+    blob2 = blob.clone()
+    blob2[int(L.off_payload): int(L.off_payload) + int(L.payload_capacity)] = 0
+    plan.entropy_decode(eblob, blob2)
+    assert np.array_equal(plan.sections(blob2)["payload"], ref.payload)
+    assert sec["info"].stream_bytes < 0.85 * ref.payload_bytes
