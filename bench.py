@@ -7,7 +7,8 @@ followed by decompress (unpack, dequantize, outlier scatter).  Inputs are reside
 in HBM before the timed region; the step rotates over several buffer sets so that
 the 256 MB last-level cache does not serve the input.
 
-Prints ONE JSON line (see README for the fields).
+Prints ONE JSON line: metric, value, unit, ms_per_step, config, plus the objects `roofline` (the dominant
+kernel against the HBM peak, per-kernel times) and `cpu_baseline` (the CPU checker timed on a sample).
 """
 import argparse
 import json

@@ -84,9 +84,59 @@ k_code_hist(const Params p, const uint8_t *__restrict__ blob, uint32_t *__restri
     }
 }
 
+// The same counts pooled per width class (what the frequency tables of the entropy coder are built
+// from): a workgroup counts kPoolTokens tokens one after the other, keeps the class sums in LDS and
+// adds them to pooled[7][256] (row b - 2: width b; zeroed by the caller) at the end.
+constexpr uint32_t kPoolTokens = 8;
+__global__ void __launch_bounds__(1024)
+k_code_pool(const Params p, const uint8_t *__restrict__ blob, uint32_t *__restrict__ pooled) {
+    __shared__ uint32_t bins[kCopies * kCopyStride];
+    __shared__ uint32_t acc[7 * 256];
+    const BlobHeader *h = reinterpret_cast<const BlobHeader *>(blob);
+    if (h->magic != kMagic || h->version != kVersion || h->status != 0 || h->tokens != p.tokens ||
+        h->hidden != p.hidden || h->dtype != p.dtype || h->off_payload != p.off_payload)
+        return;
+    const uint32_t run = threadIdx.x;
+    for (uint32_t i = threadIdx.x; i < 7u * 256u; i += blockDim.x) acc[i] = 0;
+    for (uint32_t k = 0; k < kPoolTokens; ++k) {
+        const uint32_t t = blockIdx.x * kPoolTokens + k;
+        if (t >= p.tokens) break;
+        const uint32_t width = blob[p.off_bits + t];
+        const uint64_t po = reinterpret_cast<const uint64_t *>(blob + p.off_pay_off)[t];
+        if (width < 2 || width > 8 || (po & 3u) || po + row_bytes(p.hidden, width) > p.payload_capacity) continue;
+        for (uint32_t i = threadIdx.x; i < kCopies * kCopyStride; i += blockDim.x) bins[i] = 0;
+        __syncthreads();
+        if (run < p.runs) {
+            const uint32_t left = p.hidden - run * kRun;
+            const uint32_t *src_row = reinterpret_cast<const uint32_t *>(blob + p.off_payload + po);
+            uint32_t *mine = bins + (threadIdx.x & (kCopies - 1u)) * kCopyStride;
+            if (__builtin_amdgcn_ballot_w64(left < 32u) == 0) count_run_any<false>(width, src_row, run, left, mine);
+            else count_run_any<true>(width, src_row, run, left, mine);
+        }
+        __syncthreads();
+        for (uint32_t c = threadIdx.x; c < 256u; c += blockDim.x) {
+            uint32_t n = 0;
+#pragma unroll
+            for (uint32_t j = 0; j < kCopies; ++j) n += bins[j * kCopyStride + c];
+            acc[(width - 2u) * 256u + c] += n;
+        }
+        __syncthreads();
+    }
+    __syncthreads();
+    for (uint32_t i = threadIdx.x; i < 7u * 256u; i += blockDim.x)
+        if (acc[i]) atomicAdd(pooled + i, acc[i]);
+}
+
 int launch_code_hist(const Params &p, const Geometry &g, const void *d_blob, void *d_hist, void *stream) {
     hipLaunchKernelGGL(k_code_hist, dim3(p.tokens), dim3(g.block), 0, reinterpret_cast<hipStream_t>(stream), p,
                        static_cast<const uint8_t *>(d_blob), static_cast<uint32_t *>(d_hist));
+    return (int)hipGetLastError();
+}
+
+int launch_code_pool(const Params &p, const Geometry &g, const void *d_blob, void *d_pooled, void *stream) {
+    hipLaunchKernelGGL(k_code_pool, dim3((p.tokens + kPoolTokens - 1u) / kPoolTokens), dim3(g.block), 0,
+                       reinterpret_cast<hipStream_t>(stream), p, static_cast<const uint8_t *>(d_blob),
+                       static_cast<uint32_t *>(d_pooled));
     return (int)hipGetLastError();
 }
 

@@ -49,7 +49,6 @@ static_assert(sizeof(EntropyHeader) == 256, "entropy header must be 256 bytes");
 // Sections of the eblob and of the encoder's workspace (bytes), fixed by the plan.
 struct EntropyLayout {
     uint64_t off_tables, off_stream_off, off_streams, stream_capacity, eblob_bytes;
-    uint64_t ws_hist;       // u32[T][256] code counts per token
     uint64_t ws_pooled;     // u32[7][256] code counts per width class
     uint64_t ws_len;        // u32[T] stream bytes per token
     uint64_t ws_slots;      // T slots of slot_bytes: the streams before they are moved together
@@ -122,6 +121,7 @@ int prepare_fused_kernels();
 int launch_ws_reset(const Params &p, void *d_ws, void *stream);
 int launch_unpack(const Params &p, const Geometry &g, const void *d_blob, void *d_out, void *stream);
 int launch_code_hist(const Params &p, const Geometry &g, const void *d_blob, void *d_hist, void *stream);
+int launch_code_pool(const Params &p, const Geometry &g, const void *d_blob, void *d_pooled, void *stream);
 int prepare_rans_kernels();
 int launch_rans_encode(const Params &p, const Geometry &g, const EntropyLayout &e, const void *d_blob, void *d_eblob,
                        void *d_ews, void *stream);

@@ -12,7 +12,7 @@
 // is its 64 final states followed by the words in the order the decoder reads them, padded to
 // 4 bytes.
 //
-// Encode: code counts per token (k_code_hist) -> pooled per width (k_rans_pool) -> tables
+// Encode: code counts pooled per width (k_code_pool) -> tables
 // (k_rans_tables) -> one wave per token codes its stream into a slot of the workspace
 // (k_rans_encode) -> offsets (k_rans_scan) -> streams moved to their places (k_rans_gather).
 // Decode: one wave per token (k_rans_decode) rebuilds the packed payload; the words it reads
@@ -47,23 +47,6 @@ __global__ void k_rans_begin(const EntropyLayout e, uint8_t *__restrict__ eblob,
     if (threadIdx.x < sizeof(EntropyHeader) / 4) reinterpret_cast<uint32_t *>(eblob)[threadIdx.x] = 0;
 }
 
-__global__ void __launch_bounds__(256)
-k_rans_pool(const Params p, const EntropyLayout e, const uint8_t *__restrict__ blob, uint8_t *__restrict__ ews) {
-    __shared__ uint32_t acc[7 * 256];
-    if (!blob_is_valid(p, blob)) return;
-    const uint32_t *hist = reinterpret_cast<const uint32_t *>(ews + e.ws_hist);
-    uint32_t *pooled = reinterpret_cast<uint32_t *>(ews + e.ws_pooled);
-    for (uint32_t i = threadIdx.x; i < 7u * 256u; i += 256u) acc[i] = 0;
-    __syncthreads();
-    for (uint32_t t = blockIdx.x; t < p.tokens; t += gridDim.x) {
-        const uint32_t b = blob[p.off_bits + t];
-        if (b >= 2 && b <= 8) acc[(b - 2u) * 256u + threadIdx.x] += hist[(size_t)t * 256u + threadIdx.x];
-    }
-    __syncthreads();
-    for (uint32_t i = threadIdx.x; i < 7u * 256u; i += 256u)
-        if (acc[i]) atomicAdd(pooled + i, acc[i]);
-}
-
 // One workgroup per width class: counts -> 12-bit frequencies.  f_c = max(1, floor(n_c * 4096 / N))
 // for n_c > 0; while the sum exceeds 4096, one is taken from the largest f (lowest code on ties);
 // a remaining deficit goes to the code with the largest count (lowest code on ties).
@@ -74,35 +57,39 @@ k_rans_pool(const Params p, const EntropyLayout e, const uint8_t *__restrict__ b
 __global__ void __launch_bounds__(256)
 k_rans_tables(const Params p, const EntropyLayout e, const uint8_t *__restrict__ blob, uint8_t *__restrict__ eblob,
               const uint8_t *__restrict__ ews) {
-    __shared__ uint32_t n[256], f[256], sum[3];
+    __shared__ uint32_t part[3][4];
     if (!blob_is_valid(p, blob)) return;
     const uint32_t k = blockIdx.x, c = threadIdx.x;
     const uint32_t *pooled = reinterpret_cast<const uint32_t *>(ews + e.ws_pooled) + k * 256u;
     uint16_t *table = reinterpret_cast<uint16_t *>(eblob + e.off_tables) + k * 256u;
-    // workgroup-wide sum of one value per thread: three accumulators in rotation and one barrier per
-    // sum (the accumulator of the sum after the next is cleared behind this sum's barrier)
+    // workgroup-wide sum of one value per thread: wave sums, exchanged through one of three areas in
+    // rotation (an area is written again two barriers after it was read), one barrier per sum
     uint32_t turn = 0;
     auto block_sum = [&](uint32_t v) {
-        uint32_t *acc = &sum[turn % 3u];
-        if (v) atomicAdd(acc, v);
-        __syncthreads();
-        const uint32_t r = *acc;
-        if (c == 0) sum[(turn + 2u) % 3u] = 0;
+        uint32_t *area = part[turn % 3u];
         ++turn;
-        return r;
+        const uint32_t w = wave_sum_u32(v);
+        if ((c & 63u) == 0) area[c >> 6] = w;
+        __syncthreads();
+        return area[0] + area[1] + area[2] + area[3];
     };
-    if (c == 0) { sum[0] = 0; sum[1] = 0; sum[2] = 0; }
-    n[c] = pooled[c];
-    __syncthreads();
-    const uint32_t N = block_sum(n[c]);
+    auto block_max = [&](uint32_t v) {
+        uint32_t *area = part[turn % 3u];
+        ++turn;
+        const uint32_t w = wave_max_u32(v);
+        if ((c & 63u) == 0) area[c >> 6] = w;
+        __syncthreads();
+        const uint32_t a = area[0] > area[1] ? area[0] : area[1], b = area[2] > area[3] ? area[2] : area[3];
+        return a > b ? a : b;
+    };
+    const uint32_t nc = pooled[c];
+    const uint32_t N = block_sum(nc);
     uint32_t fc = 0;
-    if (N && n[c]) {
-        fc = (uint32_t)(((uint64_t)n[c] << kProbBits) / N);
+    if (N && nc) {
+        fc = (uint32_t)(((uint64_t)nc << kProbBits) / N);
         if (fc == 0) fc = 1;
     }
     const uint32_t S = block_sum(fc);
-    f[c] = fc;
-    __syncthreads();
     if (S > kProbScale) {
         const uint32_t E = S - kProbScale;
         uint32_t lo = 0, hi = kProbScale;        // g(lo) >= E always (g(0) = S > E); g(hi) = 0 < E
@@ -114,21 +101,27 @@ k_rans_tables(const Params p, const EntropyLayout e, const uint8_t *__restrict__
         // level lo: g(lo + 1) < E <= g(lo)
         const uint32_t above = block_sum(fc > lo + 1u ? fc - (lo + 1u) : 0u);
         const uint32_t rest = E - above;         // entries at lo + 1 (after the cut) that go one further down
-        uint32_t rank = 0;
-        for (uint32_t i = 0; i < c; ++i) rank += f[i] > lo ? 1u : 0u;
+        // rank of this code among those above the level, in code order: lanes below in the wave, waves before
+        const uint64_t mine = __builtin_amdgcn_ballot_w64(fc > lo);
+        uint32_t *area = part[turn % 3u];
+        ++turn;
+        if ((c & 63u) == 0) area[c >> 6] = (uint32_t)__builtin_popcountll(mine);
+        __syncthreads();
+        uint32_t rank = (uint32_t)__builtin_popcountll(mine & ((1ull << (c & 63u)) - 1ull));
+        for (uint32_t w = 0; w < (c >> 6); ++w) rank += area[w];
         if (fc > lo) fc = rank < rest ? lo : lo + 1u;
     } else if (N && S < kProbScale) {
-        bool first_largest = n[c] > 0;
-        for (uint32_t i = 0; i < 256u && first_largest; ++i)
-            if (i < c ? n[i] >= n[c] : n[i] > n[c]) first_largest = false;
-        if (first_largest) fc += kProbScale - S;
+        // the lowest code among those with the largest count: the largest of 256 - c over them
+        const uint32_t most = block_max(nc);
+        const uint32_t pick = block_max(nc == most ? 256u - c : 0u);
+        if (256u - c == pick) fc += kProbScale - S;
     }
     table[c] = (uint16_t)fc;
 }
 
-// The table of a token's class into LDS as f | cum << 16 (cum = exclusive running sum, < 4096),
-// by one wave: lane l owns the codes 4l .. 4l+3.
-__device__ __forceinline__ void load_table(const uint16_t *table, uint32_t *ftab) {
+// The table of a token's class into LDS, by one wave (lane l owns the codes 4l .. 4l+3): per code
+// x = f | cum << 16 (cum = exclusive running sum, < 4096) and y = the binary32 pattern of 1 / f.
+__device__ __forceinline__ void load_table(const uint16_t *table, uint2 *ftab) {
     const uint32_t lane = threadIdx.x & 63u;
     uint32_t f[4], s = 0;
 #pragma unroll
@@ -136,9 +129,22 @@ __device__ __forceinline__ void load_table(const uint16_t *table, uint32_t *ftab
     uint32_t cum = wave_incl_scan_u32(s) - s;
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
-        ftab[4u * lane + i] = f[i] | (cum << 16);
+        ftab[4u * lane + i] = make_uint2(f[i] | (cum << 16), __float_as_uint(1.0f / (float)(f[i] ? f[i] : 1u)));
         cum += f[i];
     }
+}
+
+// x / f and x % f for x < f << 20 (so the quotient is below 2^20) and f <= 4096: the binary32
+// product of x and 1/f is within 0.2 of the true quotient (three roundings of relative size
+// 2^-24 on a value below 2^20), so its integer part is off by at most one, which the sign and
+// size of the remainder tell.  All multiplications fit 24 bits.
+__device__ __forceinline__ void divide_small(uint32_t x, uint32_t f, float rcp, uint32_t &q, uint32_t &r) {
+    uint32_t qq = (uint32_t)((float)x * rcp);
+    int32_t rr = (int32_t)(x - __umul24(qq, f));
+    if (rr < 0) { --qq; rr += (int32_t)f; }
+    else if ((uint32_t)rr >= f) { ++qq; rr -= (int32_t)f; }
+    q = qq;
+    r = (uint32_t)rr;
 }
 
 // ---------------------------------------------------------------- encode
@@ -146,7 +152,7 @@ __device__ __forceinline__ void load_table(const uint16_t *table, uint32_t *ftab
 // The steps of one round (run number `round` of every lane), last element first.  The words go
 // straight to the token's slot in the workspace, which fills from its end downwards.
 template <int B>
-__device__ __forceinline__ void encode_round(const uint32_t *src_row, uint32_t run, int valid, const uint32_t *ftab,
+__device__ __forceinline__ void encode_round(const uint32_t *src_row, uint32_t run, int valid, const uint2 *ftab,
                                              uint16_t *out, uint32_t &ptr, uint32_t &x) {
     uint32_t d[B];
     const uint32_t nd = valid >= 32 ? (uint32_t)B : (valid > 0 ? ((uint32_t)valid * B + 31u) >> 5 : 0u);
@@ -160,9 +166,9 @@ __device__ __forceinline__ void encode_round(const uint32_t *src_row, uint32_t r
         if (sh + B > 32) code |= d[k + 1 < B ? k + 1 : k] << (32 - sh);
         code &= (1u << B) - 1u;
         const bool active = j < valid;
-        const uint32_t fc = ftab[code];
-        uint32_t f = fc & 0xFFFFu;
-        const uint32_t c = fc >> 16;
+        const uint2 entry = ftab[code];
+        uint32_t f = entry.x & 0xFFFFu;
+        const uint32_t c = entry.x >> 16;
         if (f == 0) f = 1;                                     // a code the table does not know: cannot happen for a
                                                                // table built from this blob; keeps the division defined
         const bool shed = active && (x >> 20) >= f;            // x >= f << 20, without overflow for f = 4096
@@ -172,7 +178,11 @@ __device__ __forceinline__ void encode_round(const uint32_t *src_row, uint32_t r
             out[ptr + (uint32_t)__builtin_popcountll(who & below)] = (uint16_t)x;
             x >>= 16;
         }
-        if (active) x = ((x / f) << kProbBits) + (x % f) + c;
+        if (active) {
+            uint32_t q, r;
+            divide_small(x, f, __uint_as_float(entry.y), q, r);
+            x = (q << kProbBits) + r + c;
+        }
     }
 }
 
@@ -181,7 +191,7 @@ __device__ __forceinline__ void encode_round(const uint32_t *src_row, uint32_t r
 __global__ void __launch_bounds__(64)
 k_rans_encode(const Params p, const EntropyLayout e, const uint8_t *__restrict__ blob, const uint8_t *__restrict__ eblob,
               uint8_t *__restrict__ ews) {
-    __shared__ uint32_t ftab[256];
+    __shared__ uint2 ftab[256];
     const uint32_t t = blockIdx.x, lane = threadIdx.x;
     uint32_t *len = reinterpret_cast<uint32_t *>(ews + e.ws_len);
     if (!blob_is_valid(p, blob)) return;
@@ -290,7 +300,7 @@ __device__ __forceinline__ uint32_t wave_incl_scan_max(uint32_t v) {
 
 // slot -> code for all 4096 slots: a code's index is written at the slot where its range starts,
 // and a running maximum carries it over the range (later codes start at later slots).
-__device__ __forceinline__ void build_slot_table(const uint32_t *ftab, uint32_t *sym32) {
+__device__ __forceinline__ void build_slot_table(const uint2 *ftab, uint32_t *sym32) {
     const uint32_t lane = threadIdx.x & 63u;
     uint8_t *sym = reinterpret_cast<uint8_t *>(sym32);
 #pragma unroll
@@ -298,7 +308,7 @@ __device__ __forceinline__ void build_slot_table(const uint32_t *ftab, uint32_t 
     __syncthreads();
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
-        const uint32_t c = 4u * lane + i, fc = ftab[c];
+        const uint32_t c = 4u * lane + i, fc = ftab[c].x;
         if (fc & 0xFFFFu) sym[fc >> 16] = (uint8_t)c;
     }
     __syncthreads();
@@ -349,7 +359,7 @@ __device__ __forceinline__ void words_open(Words &q, const uint16_t *src, uint32
 }
 
 template <int B>
-__device__ __forceinline__ void decode_round(uint32_t *dst_row, uint32_t run, int valid, const uint32_t *ftab,
+__device__ __forceinline__ void decode_round(uint32_t *dst_row, uint32_t run, int valid, const uint2 *ftab,
                                              const uint8_t *sym, Words &q, uint32_t &pos, uint32_t &x) {
     uint32_t d[B];
 #pragma unroll
@@ -360,9 +370,9 @@ __device__ __forceinline__ void decode_round(uint32_t *dst_row, uint32_t run, in
         const bool active = j < valid;
         const uint32_t slot = x & (kProbScale - 1u);
         const uint32_t s = sym[slot];
-        const uint32_t fc = ftab[s];
+        const uint32_t fc = ftab[s].x;
         if (active) {
-            x = (fc & 0xFFFFu) * (x >> kProbBits) + slot - (fc >> 16);
+            x = __umul24(fc & 0xFFFFu, x >> kProbBits) + slot - (fc >> 16);    // f <= 2^12, x >> 12 < 2^20
             const int off = j * B, k = off >> 5, sh = off & 31;
             d[k] |= s << sh;
             if (sh + B > 32) d[k + 1 < B ? k + 1 : k] |= s >> (32 - sh);
@@ -390,7 +400,7 @@ __device__ __forceinline__ void decode_round(uint32_t *dst_row, uint32_t run, in
 
 __global__ void __launch_bounds__(64)
 k_rans_decode(const Params p, const EntropyLayout e, const uint8_t *__restrict__ eblob, uint8_t *__restrict__ blob) {
-    __shared__ uint32_t ftab[256];
+    __shared__ uint2 ftab[256];
     __shared__ uint32_t sym32[1024];                                   // slot -> code, one byte per slot
     const uint32_t t = blockIdx.x, lane = threadIdx.x;
     if (!blob_is_valid(p, blob) || !eblob_is_valid(p, e, eblob)) return;
@@ -437,11 +447,8 @@ int launch_rans_encode(const Params &p, const Geometry &g, const EntropyLayout &
     uint8_t *eblob = static_cast<uint8_t *>(d_eblob), *ews = static_cast<uint8_t *>(d_ews);
     hipStream_t s = as_stream(stream);
     hipLaunchKernelGGL(k_rans_begin, dim3(1), dim3(256), 0, s, e, eblob, ews);
-    int rc = launch_code_hist(p, g, d_blob, ews + e.ws_hist, stream);
+    int rc = launch_code_pool(p, g, d_blob, ews + e.ws_pooled, stream);
     if (rc != 0) return rc;
-    uint32_t blocks = (p.tokens + 7u) / 8u;
-    if (blocks > 1024u) blocks = 1024u;
-    hipLaunchKernelGGL(k_rans_pool, dim3(blocks), dim3(256), 0, s, p, e, blob, ews);
     hipLaunchKernelGGL(k_rans_tables, dim3(7), dim3(256), 0, s, p, e, blob, eblob, ews);
     hipLaunchKernelGGL(k_rans_encode, dim3(p.tokens), dim3(64), 0, s, p, e, blob, eblob, ews);
     hipLaunchKernelGGL(k_rans_scan, dim3(1), dim3(1024), 0, s, p, e, blob, eblob, ews);
