@@ -53,7 +53,11 @@ typedef enum {
                                  the input is read twice                                        */
     TSQ_PIPE_FUSED  = 2       /* one launch of a persistent grid, the input is read once;
                                  tokens are handed out by ticket counters in the workspace and
-                                 outputs are placed through a per-token size table there        */
+                                 outputs are placed through a per-token size table there.  The
+                                 grid is as large as the device can hold at once; on a device that
+                                 other kernels occupy at the same time its workgroups may not all
+                                 start, and the call then ends with TSQ_ERR_INTERNAL in the blob's
+                                 status (every device-side wait is bounded)                      */
 } tsq_pipeline;
 
 /* Problem statement (Algorithm 1 "Require": T, Q-bar, Delta; Eq. (ts): tau). */
