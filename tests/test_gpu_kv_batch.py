@@ -126,3 +126,27 @@ def test_rows_per_tensor_must_divide_the_tokens(tsq):
         with pytest.raises(tsq.TsqError) as e:
             tsq.tsq_decompress_batch(plan.handle, blob.data_ptr(), table.data_ptr(), rows, 0)
         assert e.value.status == tsq.TSQ_ERR_INVALID_ARG
+
+
+def test_kv7_full_size(tsq, oracle):
+    """The KV-cache workload at the size that is timed (64 tensors of 1024 x 4096), whole blob against the oracle."""
+    import torch
+    w = synth.WORKLOADS["KV7"]
+    parts = synth.make_kv("KV7")
+    x = np.concatenate(parts)
+    ref = oracle.compress(x, DT[w.dtype], w.tau, w.bit_set, 0.05, 1, nthreads=8)
+    plan = tsq.Plan(x.shape[0], w.hidden, w.dtype, w.tau, w.bit_set, 0.05, max_outliers=max(ref.nnz, 1))
+    xs = [torch.from_numpy(p.view(np.int16)).cuda() for p in parts]
+    blob, _ = plan.compress_batch(xs)
+    assert plan.info(blob).status == 0
+    sec = plan.sections(blob)
+    for k, want in (("bits", ref.bits), ("row_ptr", ref.row_ptr), ("pay_off", ref.pay_off), ("out_col", ref.out_col),
+                    ("out_val", ref.out_val), ("payload", ref.payload)):
+        assert np.array_equal(sec[k], want), k
+    assert np.array_equal(sec["scale"].view(np.uint32), ref.scale.view(np.uint32))
+    outs = [torch.empty_like(t) for t in xs]
+    plan.decompress_batch(blob, outs)
+    ref_out = oracle.decompress(ref, nthreads=8)
+    rows = parts[0].shape[0]
+    for i in (0, 1, 31, 63):
+        assert np.array_equal(outs[i].cpu().numpy().view(np.uint16), ref_out[i * rows:(i + 1) * rows])
