@@ -196,8 +196,8 @@ tsq_status tsq_code_histogram(const tsq_plan *plan, const void *d_blob, void *d_
  * one 12-bit frequency table per width class, built from the pooled code counts (scaled to a sum
  * of 4096, every occurring code at least 1); per token 64 interleaved rANS coders (state in
  * [2^16, 2^32), 16-bit renormalisation), coder l owning the runs of 32 codes l, l + 64, ...; a
- * token's stream is its 64 final states followed by the 16-bit words in the order the decoder
- * reads them, padded to 4 bytes.
+ * token's stream is the final states of the coders that own a run (min(64, runs) of them)
+ * followed by the 16-bit words in the order the decoder reads them, padded to 4 bytes.
  *
  * Entropy-coded payload ("eblob", device memory, little-endian, offsets from its start in
  * tsq_entropy_layout): 256-byte header | tables u16[7][256] (row b - 2: width b) |

@@ -22,8 +22,9 @@ format below is this build's own, stated in full so that the GPU coder can be ch
                 ceil(runs / 64) - 1) handles, for every coder, element (i mod 32) of its run
                 number (i div 32), if that element exists.  The encoder walks the steps
                 backwards, the decoder forwards; the words of one step are stored in coder order
-  token stream  the 64 final states (u32, little-endian, coder order), then the words (u16) in
-                the order the decoder reads them, zero padded to a multiple of 4 bytes
+  token stream  the final states of the coders that own a run (min(64, runs) of them; u32,
+                little-endian, coder order), then the words (u16) in the order the decoder reads
+                them, zero padded to a multiple of 4 bytes
 """
 from __future__ import annotations
 
@@ -69,6 +70,10 @@ def _element(i: int, l: int) -> int:
     return (l + CODERS * (i // RUN)) * RUN + (i % RUN)
 
 
+def coders_in_use(H: int) -> int:
+    return min(CODERS, (H + RUN - 1) // RUN)
+
+
 def _steps(H: int) -> int:
     runs = (H + RUN - 1) // RUN
     return RUN * ((runs + CODERS - 1) // CODERS)
@@ -95,7 +100,8 @@ def encode_token(codes, freq) -> bytes:
             x[l] = ((x[l] // f) << PROB_BITS) + (x[l] % f) + c
         chunks.append(words)
     words = [w for ch in reversed(chunks) for w in ch]
-    out = np.array(x, "<u4").tobytes() + np.array(words, "<u2").tobytes()
+    assert all(v == LOW for v in x[coders_in_use(H):])
+    out = np.array(x[:coders_in_use(H)], "<u4").tobytes() + np.array(words, "<u2").tobytes()
     return out + b"\0" * (-len(out) % 4)
 
 
@@ -104,8 +110,9 @@ def decode_token(stream: bytes, H: int, freq) -> np.ndarray:
     sym = np.zeros(M, np.int64)
     for s, (c, f) in enumerate(zip(cum, freq)):
         sym[c:c + int(f)] = s
-    x = [int(v) for v in np.frombuffer(stream[:4 * CODERS], "<u4")]
-    words = np.frombuffer(stream[4 * CODERS:len(stream) - (len(stream) - 4 * CODERS) % 2], "<u2")
+    k = coders_in_use(H)
+    x = [int(v) for v in np.frombuffer(stream[:4 * k], "<u4")] + [LOW] * (CODERS - k)
+    words = np.frombuffer(stream[4 * k:len(stream) - (len(stream) - 4 * k) % 2], "<u2")
     pos = 0
     codes = np.zeros(H, np.uint32)
     for i in range(_steps(H)):

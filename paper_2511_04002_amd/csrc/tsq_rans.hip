@@ -9,8 +9,8 @@
 // handles element i % 32 of run number i / 32 of every coder.  The encoder walks the steps
 // backwards, the decoder forwards; the 16-bit words that the coders shed in one step are stored
 // in lane order (a ballot and a population count give every lane its place).  A token's stream
-// is its 64 final states followed by the words in the order the decoder reads them, padded to
-// 4 bytes.
+// is the final states of the coders that own a run (min(64, runs) of them) followed by the words
+// in the order the decoder reads them, padded to 4 bytes.
 //
 // Encode: code counts pooled per width (k_code_pool) -> tables
 // (k_rans_tables) -> one wave per token codes its stream into a slot of the workspace
@@ -186,7 +186,7 @@ __device__ __forceinline__ void encode_round(const uint32_t *src_row, uint32_t r
     }
 }
 
-// Slot of a token in the workspace: 64 states (256 bytes), then room for one word per element of
+// Slot of a token in the workspace: room for 64 states (256 bytes), then room for one word per element of
 // the padded row; the words stand at the END of that room (the encoder fills it backwards).
 __global__ void __launch_bounds__(64)
 k_rans_encode(const Params p, const EntropyLayout e, const uint8_t *__restrict__ blob, const uint8_t *__restrict__ eblob,
@@ -221,9 +221,10 @@ k_rans_encode(const Params p, const EntropyLayout e, const uint8_t *__restrict__
             default: encode_round<8>(src_row, run, valid, ftab, out, ptr, x); break;
         }
     }
-    reinterpret_cast<uint32_t *>(slot)[lane] = x;
+    const uint32_t coders = p.runs < 64u ? p.runs : 64u;  // coders that own a run; the others still hold 2^16
+    if (lane < coders) reinterpret_cast<uint32_t *>(slot)[lane] = x;
     if (lane == 0) {
-        len[t] = 256u + 2u * (cap - ptr);                  // unpadded; the stream is padded to 4 bytes when it is placed
+        len[t] = 4u * coders + 2u * (cap - ptr);           // unpadded; the stream is padded to 4 bytes when it is placed
     }
 }
 
@@ -268,14 +269,15 @@ k_rans_gather(const Params p, const EntropyLayout e, const uint8_t *__restrict__
     const uint32_t t = blockIdx.x;
     const uint32_t bytes = reinterpret_cast<const uint32_t *>(ews + e.ws_len)[t];      // states + words, unpadded
     const uint64_t at = reinterpret_cast<const uint64_t *>(eblob + e.off_stream_off)[t];
-    if (bytes < 256u || bytes > e.slot_bytes || at + ((bytes + 3u) & ~3u) > e.stream_capacity) return;
+    const uint32_t coders = p.runs < 64u ? p.runs : 64u;
+    if (bytes < 4u * coders || bytes > e.slot_bytes || at + ((bytes + 3u) & ~3u) > e.stream_capacity) return;
     const uint8_t *slot = ews + e.ws_slots + (size_t)t * e.slot_bytes;
     uint8_t *dst = eblob + e.off_streams + at;
-    if (threadIdx.x < 64u) reinterpret_cast<uint32_t *>(dst)[threadIdx.x] = reinterpret_cast<const uint32_t *>(slot)[threadIdx.x];
+    if (threadIdx.x < coders) reinterpret_cast<uint32_t *>(dst)[threadIdx.x] = reinterpret_cast<const uint32_t *>(slot)[threadIdx.x];
     // the words stand at the end of the slot
-    const uint32_t nwords = (bytes - 256u) >> 1, room = (e.slot_bytes - 256u) >> 1;
+    const uint32_t nwords = (bytes - 4u * coders) >> 1, room = (e.slot_bytes - 256u) >> 1;
     const uint16_t *src = reinterpret_cast<const uint16_t *>(slot + 256) + (room - nwords);
-    uint16_t *words = reinterpret_cast<uint16_t *>(dst + 256);
+    uint16_t *words = reinterpret_cast<uint16_t *>(dst + 4u * coders);
     for (uint32_t i = threadIdx.x; i < nwords; i += 256u) words[i] = src[i];
     if ((nwords & 1u) && threadIdx.x == 0) words[nwords] = 0;                          // padding to 4 bytes
 }
@@ -409,15 +411,16 @@ k_rans_decode(const Params p, const EntropyLayout e, const uint8_t *__restrict__
     if (width < 2 || width > 8 || (po & 3u) || po + row_bytes(p.hidden, width) > p.payload_capacity) return;
     const uint64_t *off = reinterpret_cast<const uint64_t *>(eblob + e.off_stream_off);
     const uint64_t a = off[t], b = off[t + 1];
-    if (b < a + 256u || b > e.stream_capacity || b - a > e.slot_bytes || (a & 3u)) return;
+    const uint32_t coders = p.runs < 64u ? p.runs : 64u;  // states in the stream; the other coders start (and stay) at 2^16
+    if (b < a + 4u * coders || b > e.stream_capacity || b - a > e.slot_bytes || (a & 3u)) return;
     load_table(reinterpret_cast<const uint16_t *>(eblob + e.off_tables) + (width - 2u) * 256u, ftab);
     __syncthreads();
     build_slot_table(ftab, sym32);
     const uint8_t *sym = reinterpret_cast<const uint8_t *>(sym32);
     const uint8_t *stream = eblob + e.off_streams + a;
     Words q;
-    words_open(q, reinterpret_cast<const uint16_t *>(stream + 256), (uint32_t)(b - a - 256u) >> 1);
-    uint32_t x = reinterpret_cast<const uint32_t *>(stream)[lane], pos = 0;
+    words_open(q, reinterpret_cast<const uint16_t *>(stream + 4u * coders), (uint32_t)(b - a - 4u * coders) >> 1);
+    uint32_t x = lane < coders ? reinterpret_cast<const uint32_t *>(stream)[lane] : kRansLow, pos = 0;
     uint32_t *dst_row = reinterpret_cast<uint32_t *>(blob + p.off_payload + po);
     const uint32_t rounds = (p.runs + 63u) / 64u;
     for (uint32_t r = 0; r < rounds; ++r) {
