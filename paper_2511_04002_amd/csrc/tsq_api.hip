@@ -149,7 +149,7 @@ tsq_status tsq_plan_create(const tsq_config *cfg, tsq_plan **out) {
 
     EntropyLayout &E = pl->e;
     std::memset(&E, 0, sizeof E);
-    E.slot_bytes = 256u + ((p.runs + 63u) / 64u) * 4096u;
+    E.slot_bytes = 256u + 2u * ((H + 1u) & ~1u);     // 64 states, and at most one 16-bit word per element
     uint64_t eo = sizeof(EntropyHeader);
     E.off_tables = eo;      eo = align_up(eo + 7ull * 256 * 2, 256);
     E.off_stream_off = eo;  eo = align_up(eo + 8ull * (T + 1ull), 256);

@@ -53,7 +53,7 @@ struct EntropyLayout {
     uint64_t ws_len;        // u32[T] stream bytes per token
     uint64_t ws_slots;      // T slots of slot_bytes: the streams before they are moved together
     uint64_t ws_bytes;
-    uint32_t slot_bytes;    // 256 (states) + 2 bytes per element of the padded row: the longest possible stream
+    uint32_t slot_bytes;    // 256 (states) + 2 bytes per element (rounded up to 4): the longest possible stream
     uint32_t pad;
 };
 

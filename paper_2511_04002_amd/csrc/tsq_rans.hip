@@ -206,7 +206,7 @@ k_rans_encode(const Params p, const EntropyLayout e, const uint8_t *__restrict__
     const uint32_t *src_row = reinterpret_cast<const uint32_t *>(blob + p.off_payload + po);
     uint8_t *slot = ews + e.ws_slots + (size_t)t * e.slot_bytes;
     uint16_t *out = reinterpret_cast<uint16_t *>(slot + 256);
-    const uint32_t rounds = (p.runs + 63u) / 64u, cap = rounds * 2048u;
+    const uint32_t rounds = (p.runs + 63u) / 64u, cap = (e.slot_bytes - 256u) >> 1;   // one word per element at most
     uint32_t x = kRansLow, ptr = cap;
     for (uint32_t r = rounds; r-- > 0;) {
         const uint32_t run = lane + 64u * r;
@@ -228,22 +228,29 @@ k_rans_encode(const Params p, const EntropyLayout e, const uint8_t *__restrict__
     }
 }
 
-// Exclusive running sum of the (padded) stream lengths, and the header: one workgroup.  A thread
-// adds up its share of the tokens (that fits 32 bits: at most 128 tokens of at most 64 KB), a wave
-// scans its 64 shares, and the 16 wave totals are chained in 64 bits.
+// Exclusive running sum of the (padded) stream lengths, and the header: one workgroup, 64-bit sums
+// throughout (tokens * slot size may exceed 32 bits).  A thread adds up its share of the tokens;
+// the first thread of every wave chains the 64 shares of its wave, then thread 0 the 16 waves.
 __global__ void __launch_bounds__(1024)
 k_rans_scan(const Params p, const EntropyLayout e, const uint8_t *__restrict__ blob, uint8_t *__restrict__ eblob,
             const uint8_t *__restrict__ ews) {
-    __shared__ uint64_t wave_base[17];
+    __shared__ uint64_t share[1024], wave_base[17];
     if (!blob_is_valid(p, blob)) return;
     const uint32_t *len = reinterpret_cast<const uint32_t *>(ews + e.ws_len);
     uint64_t *off = reinterpret_cast<uint64_t *>(eblob + e.off_stream_off);
     const uint32_t per = (p.tokens + 1023u) / 1024u;
-    const uint32_t lo = threadIdx.x * per, hi = lo + per < p.tokens ? lo + per : p.tokens;
-    uint32_t s = 0;
+    const uint64_t lo64 = (uint64_t)threadIdx.x * per;
+    const uint32_t lo = lo64 < p.tokens ? (uint32_t)lo64 : p.tokens;
+    const uint32_t hi = lo64 + per < p.tokens ? (uint32_t)(lo64 + per) : p.tokens;
+    uint64_t s = 0;
     for (uint32_t t = lo; t < hi; ++t) s += (len[t] + 3u) & ~3u;
-    const uint32_t incl = wave_incl_scan_u32(s);
-    if ((threadIdx.x & 63u) == 63u) wave_base[1u + (threadIdx.x >> 6)] = incl;
+    share[threadIdx.x] = s;
+    __syncthreads();
+    if ((threadIdx.x & 63u) == 0) {
+        uint64_t run = 0;
+        for (uint32_t i = 0; i < 64u; ++i) { const uint64_t v = share[threadIdx.x + i]; share[threadIdx.x + i] = run; run += v; }
+        wave_base[1u + (threadIdx.x >> 6)] = run;
+    }
     __syncthreads();
     if (threadIdx.x == 0) {
         uint64_t run = 0;
@@ -258,7 +265,7 @@ k_rans_scan(const Params p, const EntropyLayout e, const uint8_t *__restrict__ b
         off[p.tokens] = run;
     }
     __syncthreads();
-    uint64_t at = wave_base[threadIdx.x >> 6] + (incl - s);
+    uint64_t at = wave_base[threadIdx.x >> 6] + share[threadIdx.x];
     for (uint32_t t = lo; t < hi; ++t) { off[t] = at; at += (len[t] + 3u) & ~3u; }
 }
 
