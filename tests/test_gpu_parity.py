@@ -262,7 +262,7 @@ def test_workspace_and_plan_serve_many_calls(tsq, oracle, pipeline):
 
 @pytest.mark.parametrize("pipeline", PIPELINES)
 @pytest.mark.parametrize("T,H", [(1, 64), (2, 64), (63, 64), (64, 64), (65, 64), (130, 256), (1025, 256),
-                                 (4097, 64), (9000, 64), (5000, 2048 + 64)])
+                                 (4097, 64), (9000, 64), (40000, 96), (5000, 2048 + 64)])
 def test_token_counts_around_the_grid_size(tsq, oracle, pipeline, T, H):
     # fewer tokens than workgroups, exactly as many, and several per workgroup (short rows keep
     # many workgroups resident, so the larger counts need more than one round of tickets)
