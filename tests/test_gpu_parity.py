@@ -290,6 +290,31 @@ def test_tokens_with_more_outliers_than_the_stash_holds(tsq, oracle, pipeline):
     assert (cnt > 512).sum() >= 40 and cnt.max() == H
 
 
+@pytest.mark.parametrize("seed", range(6))
+def test_random_configurations(tsq, oracle, seed):
+    # shapes, thresholds, width sets, budgets and data scales drawn at random (seeded): ten cases per seed
+    g = np.random.Generator(np.random.PCG64(1000 + seed))
+    for k in range(10):
+        H = 8 * int(g.integers(1, 600))
+        T = int(g.integers(1, 400))
+        dtype = ("f16", "bf16")[int(g.integers(0, 2))]
+        tau = float(g.choice([0.5, 2.0, 4.0, 6.0, 10.0, 16.0, 100.0]))
+        widths = sorted(set(int(b) for b in g.choice(np.arange(2, 9), size=int(g.integers(1, 8)))))
+        mode = ("lsb", "rel_rms")[int(g.integers(0, 2))]
+        budget = float(g.choice([0.0, 0.02, 0.05, 0.1, 0.2, 0.3, 0.5, 1.0])) if mode == "rel_rms" else \
+            float(g.choice([0.0, 0.05, 0.2, 0.3, 0.5, 2.0]))
+        scale = 10.0 ** g.uniform(-3, 1.3)
+        v = g.standard_t(4, size=(T, H)) * scale * g.lognormal(0.0, 0.6, (T, 1))
+        if g.random() < 0.5:
+            v[:, g.choice(H, max(1, H // 200), replace=False)] *= 25.0
+        if g.random() < 0.3:
+            v[g.random((T, H)) < 0.3] = 0.0
+        with np.errstate(over="ignore"):
+            x = synth.to_f16_bits(v) if dtype == "f16" else synth.to_bf16_bits(np.clip(v, -3e38, 3e38))
+        pipeline = PIPELINES[int(g.integers(0, 2))]
+        check_parity(tsq, oracle, x, dtype, tau, widths, budget, mode, pipeline, label="random %d.%d" % (seed, k))
+
+
 def test_c5_stress_full_size_sampled_rows(tsq, oracle):
     # the whole heavy-outlier workload (131072 x 8192 bf16, 2 GiB) in the configuration bench.py
     # times; the oracle recomputes a sample of rows one by one, the rest is checked through

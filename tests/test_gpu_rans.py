@@ -88,6 +88,22 @@ def test_edge_rows_and_ragged_hidden(tsq, oracle, RE, dtype, H):
         check(tsq, oracle, RE, x, dtype, 6.0, bs, bud, mode, label="edge H=%d" % H)
 
 
+@pytest.mark.parametrize("seed", range(3))
+def test_random_configurations(tsq, oracle, RE, seed):
+    g = np.random.Generator(np.random.PCG64(2000 + seed))
+    for k in range(6):
+        H = 8 * int(g.integers(1, 300))
+        T = int(g.integers(1, 60))
+        dtype = ("f16", "bf16")[int(g.integers(0, 2))]
+        widths = sorted(set(int(b) for b in g.choice(np.arange(2, 9), size=int(g.integers(1, 8)))))
+        budget = float(g.choice([0.0, 0.05, 0.1, 0.2, 0.5]))
+        v = g.standard_t(4, size=(T, H)) * 10.0 ** g.uniform(-2, 1) * g.lognormal(0.0, 0.6, (T, 1))
+        if g.random() < 0.3:
+            v[g.random((T, H)) < 0.4] = 0.0
+        x = synth.to_f16_bits(v) if dtype == "f16" else synth.to_bf16_bits(v)
+        check(tsq, oracle, RE, x, dtype, float(g.choice([2.0, 6.0, 50.0])), widths, budget, label="random %d.%d" % (seed, k))
+
+
 def test_a_foreign_blob_gives_no_valid_eblob(tsq):
     import torch
     plan = tsq.Plan(16, 64, "f16", 6.0, (4, 8), 0.05)
