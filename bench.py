@@ -32,6 +32,14 @@ TRAFFIC = {
 }
 
 
+# VALU instructions per launch (wave level) from a rocprofv3 --pmc SQ_INSTS_VALU run of this command
+# (profiles/C4_fused_valu_counts.txt), and the issue peak they are priced against: 256 CUs x 4 SIMDs x 16 lanes
+# x 2.4 GHz = 39.3e12 lane-operations per second (packed fp32 is not used, so every VALU instruction occupies
+# its SIMD for four cycles per wave of 64).
+VALU_INSTS = {("C4", "fused", 0.05): {"k_fused": 24.2e6, "k_unpack": 7.67e6}}
+VALU_PEAK_LANE_OPS = 256 * 4 * 16 * 2.4e9
+
+
 def parse():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -224,6 +232,12 @@ def main():
     achieved = kern[dom]["GBps"]
     pair_gbps = (alg_c + alg_d) / (ms_c + ms_d) / 1e6
     traffic = TRAFFIC.get((w.name, pipe, args.eps), {}).get(dom)
+    insts = VALU_INSTS.get((w.name, pipe, args.eps), {}).get(dom)
+    valu = None
+    if insts:
+        ops = insts * 64.0 / (kern[dom]["ms"] * 1e-3)
+        valu = {"wave_instructions": insts, "achieved_lane_ops_per_s": ops, "peak_lane_ops_per_s": VALU_PEAK_LANE_OPS,
+                "frac": ops / VALU_PEAK_LANE_OPS}
 
     res = {
         "metric": "compress+decompress GB/s of split-point activations",
@@ -245,7 +259,7 @@ def main():
                      "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS, "traffic": traffic,
                      "compress_ms": ms_c, "decompress_ms": ms_d,
                      "pair_achieved": pair_gbps, "pair_frac": pair_gbps / HBM_PEAK_GBS,
-                     "kernels": kern},
+                     "valu_issue": valu, "kernels": kern},
         "host_wall_ms_per_step": wall * 1e3 / args.steps,
     }
     if not args.no_cpu_baseline:
