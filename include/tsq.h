@@ -209,7 +209,8 @@ tsq_status tsq_code_histogram(const tsq_plan *plan, const void *d_blob, void *d_
  * blob's other sections (header, widths, offsets) already.  The restored payload is byte for byte
  * the one that was encoded.
  *   d_eblob : tsq_entropy_blob_bytes() bytes (capacity for the longest possible streams), 256-byte aligned
- *   d_ews   : tsq_entropy_workspace_bytes() bytes, 256-byte aligned, encoder only, needs no reset
+ *   d_ews   : tsq_entropy_workspace_bytes() bytes, 256-byte aligned, encoder only, needs no reset;
+ *             it serves one encode call at a time (calls that overlap on one workspace race)
  * Both calls only enqueue.  If the blob (or, for decode, the eblob) is not this plan's or carries
  * a non-zero status, nothing is written and the eblob's header stays invalid.
  * tsq_entropy_info SYNCHRONIZES `stream`; it returns FORMAT for an eblob that is not this plan's.
