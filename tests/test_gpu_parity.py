@@ -290,6 +290,46 @@ def test_tokens_with_more_outliers_than_the_stash_holds(tsq, oracle, pipeline):
     assert (cnt > 512).sum() >= 40 and cnt.max() == H
 
 
+@pytest.mark.parametrize("pipeline", PIPELINES)
+def test_calls_captured_in_a_hip_graph_replay_correctly(tsq, oracle, pipeline):
+    # compress + decompress captured once, replayed on changing input with eager work and synchronisation in
+    # between; every replay must give what the eager calls give (the workspace state moves on from call to call)
+    import torch
+    T, H = 700, 4096
+    g = np.random.Generator(np.random.PCG64(21))
+    plan = tsq.Plan(T, H, "f16", 6.0, (2, 3, 4, 6, 8), 0.1, pipeline=pipeline)
+    x_static = torch.zeros((T, H), dtype=torch.int16, device="cuda")
+    blob, out, ws = plan.new_blob(), plan.new_output(), plan.new_workspace()
+    plan.compress(x_static, blob, ws)                         # warm-up outside the capture (first-call set-up)
+    plan.decompress(blob, out)
+    torch.cuda.synchronize()
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.stream(side):
+        with torch.cuda.graph(graph, stream=side):
+            plan.compress(x_static, blob, ws)
+            plan.decompress(blob, out)
+    torch.cuda.current_stream().wait_stream(side)
+    for rep in range(4):
+        v = g.standard_normal((T, H)) * g.lognormal(0.0, 0.7, (T, 1)) * (1.0 + rep)
+        v[g.random((T, H)) < 0.003] *= 20.0
+        x = synth.to_f16_bits(v)
+        x_static.copy_(torch.from_numpy(x.view(np.int16)))
+        graph.replay()
+        torch.cuda.synchronize()
+        ref = oracle.compress(x, F16, 6.0, (2, 3, 4, 6, 8), 0.1, 1, nthreads=8)
+        sec = plan.sections(blob)
+        assert plan.info(blob).status == 0
+        for k, want in (("bits", ref.bits), ("row_ptr", ref.row_ptr), ("pay_off", ref.pay_off),
+                        ("out_col", ref.out_col), ("out_val", ref.out_val), ("payload", ref.payload)):
+            assert np.array_equal(sec[k], want), "replay %d: %s" % (rep, k)
+        assert np.array_equal(out.cpu().numpy().view(np.uint16), oracle.decompress(ref, nthreads=8)), "replay %d" % rep
+        # eager work between the replays: another call on the same workspace
+        plan.compress(x_static, plan.new_blob(), ws)
+        torch.cuda.synchronize()
+
+
 @pytest.mark.parametrize("seed", range(6))
 def test_random_configurations(tsq, oracle, seed):
     # shapes, thresholds, width sets, budgets and data scales drawn at random (seeded): ten cases per seed
