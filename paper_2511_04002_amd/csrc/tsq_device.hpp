@@ -104,16 +104,21 @@ __device__ __forceinline__ uint32_t block_excl_scan(uint32_t v, uint32_t *scr) {
 // the LDS operations of one wave execute in order, the row needs no workgroup barrier.
 struct RowPart { uint32_t w[16]; };   // the four 16-byte pieces a lane moves, as scalars
 
+// src is uniform and points into device memory (it may come out of a table of pointers, which hides
+// that from the compiler): the loads name the global address space, so that they are ordinary
+// vector memory loads and not loads that might also hit LDS or scratch.
+typedef const __attribute__((address_space(1))) uint8_t *GlobalBytes;
 template <bool FULL = false>
 __device__ __forceinline__ void fetch_row_part(const uint4 *__restrict__ src, uint32_t pieces, RowPart &pre) {
     const uint32_t lane = threadIdx.x & 63u, wv = threadIdx.x >> 6;
+    const GlobalBytes base = (GlobalBytes)src;
 #pragma unroll
     for (int k = 0; k < 4; ++k) {
         const uint32_t q = 256u * wv + 64u * k + lane;
         uint32_t x = 0, y = 0, z = 0, w = 0;
         if (FULL || q < pieces) {
             // the input is read once: streaming load
-            const u32x4 v = __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(src + q));
+            const u32x4 v = __builtin_nontemporal_load((const __attribute__((address_space(1))) u32x4 *)(base + 16u * q));
             x = v.x; y = v.y; z = v.z; w = v.w;
         }
         pre.w[4 * k] = x; pre.w[4 * k + 1] = y; pre.w[4 * k + 2] = z; pre.w[4 * k + 3] = w;

@@ -227,6 +227,16 @@ __device__ __forceinline__ Prefix place_finish(const Params &p, const uint32_t *
     return x;
 }
 
+// One ticket of a class counter; the caller needs the result an iteration later.  The address goes
+// through a register the compiler knows nothing about (the offset is zero): an address that is
+// the same in every lane would have the atomic rewritten into a wave-wide reduction whose result
+// is read, and so waited for, on the spot.
+__device__ __forceinline__ uint32_t draw_ticket(uint32_t *counter) {
+    uint32_t zero = 0;
+    asm volatile("" : "+v"(zero));
+    return __hip_atomic_fetch_add(counter + zero, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+
 // What a workgroup keeps of a token between computing it and storing it.
 struct Pending {
     uint32_t width, cnt, words, token;
@@ -256,28 +266,38 @@ template <int NW>
 __device__ __forceinline__ bool store_token(const StoreTargets &o, const Pending &q, const Prefix &x, bool from_stash,
                                             Tail &tail) {
     constexpr uint32_t kThreads = 64u * NW;
-    const uint32_t tid = threadIdx.x;
+    // the thread index through a register the compiler knows nothing about: the addresses derived
+    // from it are computed here, not once before the token loop and then kept (or spilled) across it
+    uint32_t tid = threadIdx.x;
+    asm volatile("" : "+v"(tid));
     if ((uint64_t)x.ew + q.words > o.payload_words) return false;
     if (tid == 0) {
         o.pay_off[q.token] = (uint64_t)x.ew << 2;
         o.row_ptr[q.token] = x.ec;
     }
+    // Every address below is a uniform base (x is uniform) plus a byte offset of 32 bits: the base
+    // stays in scalar registers and no thread holds a 64-bit pointer of its own.
     const uint32_t *img = o.images + q.parity * o.runs * 8u;
-    uint32_t *dst = o.payload + x.ew;
-    const uint32_t quads = q.words >> 2;
-    for (uint32_t i = tid; i < quads; i += kThreads) {
-        // plain stores: the payload is what decompress reads next, it should stay in the caches
-        const u32x4 v = *reinterpret_cast<const u32x4 *>(img + 4u * i);
-        *reinterpret_cast<u32x4_a4 *>(dst + 4u * i) = v;
+    uint8_t *dst = reinterpret_cast<uint8_t *>(o.payload + x.ew);
+    const uint32_t quads = q.words >> 2;      // at most 2 * kThreads: 8 bits x 32 elements per thread = 32 bytes
+#pragma unroll
+    for (uint32_t r = 0; r < 2; ++r) {
+        const uint32_t i = tid + r * kThreads;
+        if (i < quads) {
+            // plain stores: the payload is what decompress reads next, it should stay in the caches
+            const u32x4 v = *reinterpret_cast<const u32x4 *>(img + 4u * i);
+            *reinterpret_cast<u32x4_a4 *>(dst + 16u * i) = v;
+        }
     }
     const uint32_t rest = q.words & 3u;
-    if (tid < rest) dst[4u * quads + tid] = img[4u * quads + tid];
+    if (tid < rest) *reinterpret_cast<uint32_t *>(dst + 4u * (4u * quads + tid)) = img[4u * quads + tid];
     if (from_stash && q.cnt > 0 && (uint64_t)x.ec + q.cnt <= o.outlier_capacity) {
         const uint32_t *stash = o.stashes + q.parity * kStashCap;
+        uint8_t *col = reinterpret_cast<uint8_t *>(o.out_col + x.ec), *val = reinterpret_cast<uint8_t *>(o.out_val + x.ec);
         for (uint32_t k = tid; k < q.cnt; k += kThreads) {
             const uint32_t e = stash[k];
-            o.out_col[(size_t)x.ec + k] = (uint16_t)(e >> 16);
-            o.out_val[(size_t)x.ec + k] = (uint16_t)e;
+            *reinterpret_cast<uint16_t *>(col + 2u * k) = (uint16_t)(e >> 16);
+            *reinterpret_cast<uint16_t *>(val + 2u * k) = (uint16_t)e;
         }
     }
     tail.token = q.token; tail.ew = x.ew; tail.ec = x.ec; tail.words = q.words; tail.cnt = q.cnt;
@@ -354,7 +374,7 @@ k_fused(const Params p, const uint16_t *__restrict__ in, uint8_t *__restrict__ b
     fetch_row_part<FULL>(reinterpret_cast<const uint4 *>(row_address(p, in, t, hidden)), pieces, pre);
     uint32_t req = 0;                      // thread 0: the ticket in flight
     bool requesting = true;                // uniform: a ticket is in flight
-    if (tid == 0) req = __hip_atomic_fetch_add(counter, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    if (tid == 0) req = draw_ticket(counter);
     write_row_part_sw<FULL>(lrow, runs, pre);
 
     uint32_t it = 0;
@@ -366,7 +386,7 @@ k_fused(const Params p, const uint16_t *__restrict__ in, uint8_t *__restrict__ b
                 const uint32_t k = w_cls + req;
                 if (k < n_cls) {
                     tn = k * C + cls;
-                    req = __hip_atomic_fetch_add(counter, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                    req = draw_ticket(counter);
                 }
             }
             tslot[it & 1u] = tn;
