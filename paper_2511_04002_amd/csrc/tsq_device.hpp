@@ -96,6 +96,18 @@ __device__ __forceinline__ uint32_t block_excl_scan(uint32_t v, uint32_t *scr) {
     return base + inc - v;
 }
 
+// A window of `bytes` bytes of device memory at a uniform address as a raw buffer resource (stride 0,
+// the untyped 32-bit format word of this chip family): stores beyond the window are dropped by
+// the hardware.
+__device__ __forceinline__ __amdgpu_buffer_rsrc_t raw_window(void *base, uint32_t bytes) {
+    return __builtin_amdgcn_make_buffer_rsrc(base, 0, (int)bytes, 0x00027000);
+}
+// 16 bytes to window + offset (4-byte aligned) with device-scope write-through (cache policy sc1):
+// the line does not stay dirty in the L2.
+__device__ __forceinline__ void store_quad_through(__amdgpu_buffer_rsrc_t window, uint32_t offset, u32x4 v) {
+    __builtin_amdgcn_raw_buffer_store_b128(v, window, (int)offset, 0, 16);
+}
+
 // ---------------------------------------------------------------- row staging
 
 // Row movement HBM -> registers -> LDS, private to each wave: wave w moves the 4 KB of the row

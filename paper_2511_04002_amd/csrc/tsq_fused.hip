@@ -280,13 +280,16 @@ __device__ __forceinline__ bool store_token(const StoreTargets &o, const Pending
     const uint32_t *img = o.images + q.parity * o.runs * 8u;
     uint8_t *dst = reinterpret_cast<uint8_t *>(o.payload + x.ew);
     const uint32_t quads = q.words >> 2;      // at most 2 * kThreads: 8 bits x 32 elements per thread = 32 bytes
+    const __amdgpu_buffer_rsrc_t window = raw_window(dst, q.words << 2);
 #pragma unroll
     for (uint32_t r = 0; r < 2; ++r) {
         const uint32_t i = tid + r * kThreads;
         if (i < quads) {
-            // plain stores: the payload is what decompress reads next, it should stay in the caches
+            // written through the L2 as it goes (the payload is what decompress reads next: it should stay
+            // in the memory-side cache, which a streaming store would bypass; a plain store would leave
+            // it dirty in the L2 until the end of the kernel, where writing it back costs about 2 us)
             const u32x4 v = *reinterpret_cast<const u32x4 *>(img + 4u * i);
-            *reinterpret_cast<u32x4_a4 *>(dst + 16u * i) = v;
+            store_quad_through(window, 16u * i, v);
         }
     }
     const uint32_t rest = q.words & 3u;
