@@ -191,9 +191,12 @@ __device__ __forceinline__ uint32_t bit_insert(uint32_t sel, uint32_t keep, uint
 //   mg        : |T_below| of the run (see Mags)
 //   omask     : outlier flags in column order, bit j = element j
 //   amax_bits : binary32 bit pattern of the largest inlier magnitude of the run (only if WANT_MAX)
-// Per pair of elements: and, packed subtract, packed arithmetic shift (the borrow of
-// pattern - thr marks the inliers), bit-field insert into the flags; then bf16: two masked widenings
-// and one three-way max (7 instructions), fp16: one and and one packed max (6).
+// Per pair of elements: and, subtract, packed arithmetic shift, bit-field insert into the flags;
+// then bf16: two masked widenings and one three-way max (7 instructions), fp16: one and and one
+// packed max (6).  The subtract is a plain 32-bit one (it issues at twice the rate of the packed
+// 16-bit form): with g = thr + 0x7FFF = (thr - 1) | 0x8000 in both halves, g - pattern leaves in
+// each half 0x8000 + (thr - 1 - pattern), which is never negative (pattern <= 0x7FFF, thr >= 1),
+// so nothing is borrowed from the upper half, and whose bit 15 is set exactly for the inliers.
 // The flags of a pair are 16 bits apart in `inl`, so the pairs 0-7 and 8-15 are collected in two
 // words (low element at bit 2i', high element at bit 17+2i', i' = i mod 8) that are folded into
 // column order at the end.
@@ -201,12 +204,13 @@ template <int DT, bool WANT_MAX>
 __device__ __forceinline__ void split_regs(const uint32_t (&w)[16], uint32_t thr_pk, Mags<DT> &mg, uint32_t &omask,
                                            uint32_t &amax_bits) {
     uint32_t im_a = 0, im_b = 0;           // inlier flags of the pairs 0-7 / 8-15, collected bit by bit
+    const uint32_t guard_pk = thr_pk + 0x7FFF7FFFu;
     if constexpr (DT == kBF16) {
         uint32_t mx = 0;                   // non-negative binary32 patterns order like unsigned integers
 #pragma unroll
         for (int i = 0; i < 16; ++i) {
             const uint32_t absw = w[i] & 0x7FFF7FFFu;
-            const uint32_t inl = pk_ashr15_i16(pk_sub_u16(absw, thr_pk));  // 0xFFFF where |x| < tau
+            const uint32_t inl = pk_ashr15_i16(guard_pk - absw);  // 0xFFFF where |x| < tau
             const float lo = masked_low_half_as_bf16(absw, inl);
             const uint32_t hi = absw & inl & 0xFFFF0000u;
             mg.v[2 * i] = lo;
@@ -224,7 +228,7 @@ __device__ __forceinline__ void split_regs(const uint32_t (&w)[16], uint32_t thr
 #pragma unroll
         for (int i = 0; i < 16; ++i) {
             const uint32_t absw = w[i] & 0x7FFF7FFFu;
-            const uint32_t inl = pk_ashr15_i16(pk_sub_u16(absw, thr_pk));
+            const uint32_t inl = pk_ashr15_i16(guard_pk - absw);
             const uint32_t a = absw & inl;
             mg.v[i] = a;
             if (WANT_MAX) mx = pk_max_u16(mx, a);
