@@ -85,46 +85,69 @@ k_code_hist(const Params p, const uint8_t *__restrict__ blob, uint32_t *__restri
 }
 
 // The same counts pooled per width class (what the frequency tables of the entropy coder are built
-// from): a workgroup counts kPoolTokens tokens one after the other, keeps the class sums in LDS and
-// adds them to pooled[7][256] (row b - 2: width b; zeroed by the caller) at the end.
-constexpr uint32_t kPoolTokens = 8;
+// from).  A workgroup counts `per` consecutive tokens, class by class: all its tokens of one width
+// go into the bins before the copies are added up, so the adding up happens once per width that
+// occurs, not once per token.  The sums are added to one of kPoolCopies sets counts[set][7][256]
+// (row b - 2: width b; zeroed by the caller), which k_rans_tables adds up: atomic adds on one
+// address from all over the chip take about 30 ns each, one after the other, so both the number
+// of counting workgroups and the number of them that share a set are kept small.
+constexpr uint32_t kPoolMaxTokens = 64;   // widths held in LDS at a time
 __global__ void __launch_bounds__(1024)
-k_code_pool(const Params p, const uint8_t *__restrict__ blob, uint32_t *__restrict__ pooled) {
+k_code_pool(const Params p, const uint8_t *__restrict__ blob, uint32_t *__restrict__ counts, uint32_t per) {
     __shared__ uint32_t bins[kCopies * kCopyStride];
     __shared__ uint32_t acc[7 * 256];
+    __shared__ uint8_t widths[kPoolMaxTokens];
     const BlobHeader *h = reinterpret_cast<const BlobHeader *>(blob);
-    if (h->magic != kMagic || h->version != kVersion || h->status != 0 || h->tokens != p.tokens ||
-        h->hidden != p.hidden || h->dtype != p.dtype || h->off_payload != p.off_payload)
-        return;
+    const bool ok = h->magic == kMagic && h->version == kVersion && h->status == 0 && h->tokens == p.tokens &&
+                    h->hidden == p.hidden && h->dtype == p.dtype && h->off_payload == p.off_payload;
     const uint32_t run = threadIdx.x;
+    uint32_t *mine_out = counts + (blockIdx.x % kPoolCopies) * 7u * 256u;
     for (uint32_t i = threadIdx.x; i < 7u * 256u; i += blockDim.x) acc[i] = 0;
-    for (uint32_t k = 0; k < kPoolTokens; ++k) {
-        const uint32_t t = blockIdx.x * kPoolTokens + k;
-        if (t >= p.tokens) break;
-        const uint32_t width = blob[p.off_bits + t];
-        const uint64_t po = reinterpret_cast<const uint64_t *>(blob + p.off_pay_off)[t];
-        if (width < 2 || width > 8 || (po & 3u) || po + row_bytes(p.hidden, width) > p.payload_capacity) continue;
-        for (uint32_t i = threadIdx.x; i < kCopies * kCopyStride; i += blockDim.x) bins[i] = 0;
-        __syncthreads();
-        if (run < p.runs) {
-            const uint32_t left = p.hidden - run * kRun;
-            const uint32_t *src_row = reinterpret_cast<const uint32_t *>(blob + p.off_payload + po);
-            uint32_t *mine = bins + (threadIdx.x & (kCopies - 1u)) * kCopyStride;
-            if (__builtin_amdgcn_ballot_w64(left < 32u) == 0) count_run_any<false>(width, src_row, run, left, mine);
-            else count_run_any<true>(width, src_row, run, left, mine);
+    for (uint32_t i = threadIdx.x; i < kCopies * kCopyStride; i += blockDim.x) bins[i] = 0;
+    const uint32_t t0 = blockIdx.x * per, t1 = t0 + per < p.tokens ? t0 + per : p.tokens;
+    for (uint32_t base = t0; ok && base < t1; base += kPoolMaxTokens) {
+        const uint32_t n = t1 - base < kPoolMaxTokens ? t1 - base : kPoolMaxTokens;
+        __syncthreads();                                   // bins and acc are zero / complete; widths[] is free
+        if (threadIdx.x < n) {
+            const uint32_t t = base + threadIdx.x;
+            const uint32_t width = blob[p.off_bits + t];
+            const uint64_t po = reinterpret_cast<const uint64_t *>(blob + p.off_pay_off)[t];
+            // a damaged token is skipped rather than read out of bounds
+            const bool good = width >= 2 && width <= 8 && !(po & 3u) && po + row_bytes(p.hidden, width) <= p.payload_capacity;
+            widths[threadIdx.x] = good ? (uint8_t)width : 0;
         }
         __syncthreads();
-        for (uint32_t c = threadIdx.x; c < 256u; c += blockDim.x) {
-            uint32_t n = 0;
+        for (uint32_t b = 2; b <= 8; ++b) {
+            bool any = false;                              // uniform: depends on widths[] only
+            for (uint32_t k = 0; k < n; ++k) {
+                if (widths[k] != b) continue;
+                any = true;
+                if (run < p.runs) {
+                    const uint32_t t = base + k;
+                    const uint64_t po = reinterpret_cast<const uint64_t *>(blob + p.off_pay_off)[t];
+                    const uint32_t left = p.hidden - run * kRun;
+                    const uint32_t *src_row = reinterpret_cast<const uint32_t *>(blob + p.off_payload + po);
+                    uint32_t *mine = bins + (threadIdx.x & (kCopies - 1u)) * kCopyStride;
+                    if (__builtin_amdgcn_ballot_w64(left < 32u) == 0) count_run_any<false>(b, src_row, run, left, mine);
+                    else count_run_any<true>(b, src_row, run, left, mine);
+                }
+            }
+            if (!any) continue;
+            __syncthreads();
+            for (uint32_t c = threadIdx.x; c < 256u; c += blockDim.x) {
+                uint32_t s = 0;
 #pragma unroll
-            for (uint32_t j = 0; j < kCopies; ++j) n += bins[j * kCopyStride + c];
-            acc[(width - 2u) * 256u + c] += n;
+                for (uint32_t j = 0; j < kCopies; ++j) s += bins[j * kCopyStride + c];
+                acc[(b - 2u) * 256u + c] += s;
+            }
+            __syncthreads();
+            for (uint32_t i = threadIdx.x; i < kCopies * kCopyStride; i += blockDim.x) bins[i] = 0;
+            __syncthreads();
         }
-        __syncthreads();
     }
     __syncthreads();
     for (uint32_t i = threadIdx.x; i < 7u * 256u; i += blockDim.x)
-        if (acc[i]) atomicAdd(pooled + i, acc[i]);
+        if (acc[i]) atomicAdd(mine_out + i, acc[i]);
 }
 
 int launch_code_hist(const Params &p, const Geometry &g, const void *d_blob, void *d_hist, void *stream) {
@@ -133,10 +156,10 @@ int launch_code_hist(const Params &p, const Geometry &g, const void *d_blob, voi
     return (int)hipGetLastError();
 }
 
-int launch_code_pool(const Params &p, const Geometry &g, const void *d_blob, void *d_pooled, void *stream) {
-    hipLaunchKernelGGL(k_code_pool, dim3((p.tokens + kPoolTokens - 1u) / kPoolTokens), dim3(g.block), 0,
-                       reinterpret_cast<hipStream_t>(stream), p, static_cast<const uint8_t *>(d_blob),
-                       static_cast<uint32_t *>(d_pooled));
+int launch_code_pool(const Params &p, const Geometry &g, const EntropyLayout &e, const void *d_blob, void *d_counts,
+                     void *stream) {
+    hipLaunchKernelGGL(k_code_pool, dim3(e.pool_groups), dim3(g.block), 0, reinterpret_cast<hipStream_t>(stream), p,
+                       static_cast<const uint8_t *>(d_blob), static_cast<uint32_t *>(d_counts), e.pool_tokens);
     return (int)hipGetLastError();
 }
 

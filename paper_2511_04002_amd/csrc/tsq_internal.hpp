@@ -49,13 +49,19 @@ static_assert(sizeof(EntropyHeader) == 256, "entropy header must be 256 bytes");
 // Sections of the eblob and of the encoder's workspace (bytes), fixed by the plan.
 struct EntropyLayout {
     uint64_t off_tables, off_stream_off, off_streams, stream_capacity, eblob_bytes;
-    uint64_t ws_pooled;     // u32[7][256] code counts per width class
+    uint64_t ws_pooled;     // u32[kPoolCopies][7][256] code counts per width class (a counting workgroup adds to set id % kPoolCopies)
+    uint64_t ws_block;      // u32[ceil(T / kLenBlock)] padded stream bytes of each block of kLenBlock tokens
     uint64_t ws_len;        // u32[T] stream bytes per token
     uint64_t ws_slots;      // T slots of slot_bytes: the streams before they are moved together
     uint64_t ws_bytes;
     uint32_t slot_bytes;    // 256 (states) + 2 bytes per element (rounded up to 4): the longest possible stream
+    uint32_t pool_groups;   // workgroups of k_code_pool
+    uint32_t pool_tokens;   // consecutive tokens each of them counts
     uint32_t pad;
 };
+constexpr uint32_t kLenBlock = 256;     // tokens per partial sum of stream lengths
+constexpr uint32_t kMaxPoolGroups = 2048;
+constexpr uint32_t kPoolCopies = 16;    // sets of pooled counts: 16 times fewer atomic adds per address
 
 // Kernel argument block (passed by value).
 struct Params {
@@ -121,7 +127,8 @@ int prepare_fused_kernels();
 int launch_ws_reset(const Params &p, void *d_ws, void *stream);
 int launch_unpack(const Params &p, const Geometry &g, const void *d_blob, void *d_out, void *stream);
 int launch_code_hist(const Params &p, const Geometry &g, const void *d_blob, void *d_hist, void *stream);
-int launch_code_pool(const Params &p, const Geometry &g, const void *d_blob, void *d_pooled, void *stream);
+int launch_code_pool(const Params &p, const Geometry &g, const EntropyLayout &e, const void *d_blob, void *d_counts,
+                     void *stream);
 int prepare_rans_kernels();
 int launch_rans_encode(const Params &p, const Geometry &g, const EntropyLayout &e, const void *d_blob, void *d_eblob,
                        void *d_ews, void *stream);

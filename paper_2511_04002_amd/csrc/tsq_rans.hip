@@ -12,9 +12,11 @@
 // is the final states of the coders that own a run (min(64, runs) of them) followed by the words
 // in the order the decoder reads them, padded to 4 bytes.
 //
-// Encode: code counts pooled per width (k_code_pool) -> tables
-// (k_rans_tables) -> one wave per token codes its stream into a slot of the workspace
-// (k_rans_encode) -> offsets (k_rans_scan) -> streams moved to their places (k_rans_gather).
+// Encode: code counts per width, added to one of 16 sets (k_code_pool) -> sets added up,
+// tables (k_rans_tables) -> one wave per token codes its stream into a slot of the workspace
+// (k_rans_encode) -> stream bytes per block of 256 tokens (k_rans_blocks) -> every token finds its
+// offset from the block sums before it and the lengths before it inside its block, and its stream
+// moves to its place (k_rans_gather).
 // Decode: one wave per token (k_rans_decode) rebuilds the packed payload; the words it reads
 // pass through registers (four windows of 64 words), so a token needs 5 KB of LDS for its tables
 // and nothing else, and a compute unit holds its full 32 waves.
@@ -40,9 +42,9 @@ __device__ __forceinline__ bool eblob_is_valid(const Params &p, const EntropyLay
 
 // ---------------------------------------------------------------- pooled counts and tables
 
-__global__ void k_rans_begin(const EntropyLayout e, uint8_t *__restrict__ eblob, uint8_t *__restrict__ ews) {
-    uint32_t *pooled = reinterpret_cast<uint32_t *>(ews + e.ws_pooled);
-    for (uint32_t i = threadIdx.x; i < 7u * 256u; i += blockDim.x) pooled[i] = 0;
+__global__ void k_rans_begin(const Params p, const EntropyLayout e, uint8_t *__restrict__ eblob, uint8_t *__restrict__ ews) {
+    uint32_t *counts = reinterpret_cast<uint32_t *>(ews + e.ws_pooled);
+    for (uint32_t i = threadIdx.x; i < kPoolCopies * 7u * 256u; i += blockDim.x) counts[i] = 0;
     // the header becomes valid only when the last kernel of the call has run
     if (threadIdx.x < sizeof(EntropyHeader) / 4) reinterpret_cast<uint32_t *>(eblob)[threadIdx.x] = 0;
 }
@@ -60,7 +62,8 @@ k_rans_tables(const Params p, const EntropyLayout e, const uint8_t *__restrict__
     __shared__ uint32_t part[3][4];
     if (!blob_is_valid(p, blob)) return;
     const uint32_t k = blockIdx.x, c = threadIdx.x;
-    const uint32_t *pooled = reinterpret_cast<const uint32_t *>(ews + e.ws_pooled) + k * 256u;
+    // this class's counts: the sets that the counting workgroups added to, added up
+    const uint32_t *counts = reinterpret_cast<const uint32_t *>(ews + e.ws_pooled) + k * 256u;
     uint16_t *table = reinterpret_cast<uint16_t *>(eblob + e.off_tables) + k * 256u;
     // workgroup-wide sum of one value per thread: wave sums, exchanged through one of three areas in
     // rotation (an area is written again two barriers after it was read), one barrier per sum
@@ -82,7 +85,9 @@ k_rans_tables(const Params p, const EntropyLayout e, const uint8_t *__restrict__
         const uint32_t a = area[0] > area[1] ? area[0] : area[1], b = area[2] > area[3] ? area[2] : area[3];
         return a > b ? a : b;
     };
-    const uint32_t nc = pooled[c];
+    uint32_t nc = 0;
+#pragma unroll
+    for (uint32_t g = 0; g < kPoolCopies; ++g) nc += counts[g * 7u * 256u + c];
     const uint32_t N = block_sum(nc);
     uint32_t fc = 0;
     if (N && nc) {
@@ -121,6 +126,9 @@ k_rans_tables(const Params p, const EntropyLayout e, const uint8_t *__restrict__
 
 // The table of a token's class into LDS, by one wave (lane l owns the codes 4l .. 4l+3): per code
 // x = f | cum << 16 (cum = exclusive running sum, < 4096) and y = the binary32 pattern of 1 / f.
+// GUARD (the encoder's form): a code the table does not know (f = 0; cannot happen for a table built
+// from the blob that is coded) is entered with f = 1, which keeps the division defined.
+template <bool GUARD>
 __device__ __forceinline__ void load_table(const uint16_t *table, uint2 *ftab) {
     const uint32_t lane = threadIdx.x & 63u;
     uint32_t f[4], s = 0;
@@ -129,7 +137,8 @@ __device__ __forceinline__ void load_table(const uint16_t *table, uint2 *ftab) {
     uint32_t cum = wave_incl_scan_u32(s) - s;
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
-        ftab[4u * lane + i] = make_uint2(f[i] | (cum << 16), __float_as_uint(1.0f / (float)(f[i] ? f[i] : 1u)));
+        const uint32_t fi = f[i] ? f[i] : 1u;
+        ftab[4u * lane + i] = make_uint2((GUARD ? fi : f[i]) | (cum << 16), __float_as_uint(1.0f / (float)fi));
         cum += f[i];
     }
 }
@@ -147,35 +156,39 @@ __device__ __forceinline__ void divide_small(uint32_t x, uint32_t f, float rcp, 
     r = (uint32_t)rr;
 }
 
+// How many of the lanes before this one are set in `who`.
+__device__ __forceinline__ uint32_t rank_in(uint64_t who) {
+    return __builtin_amdgcn_mbcnt_hi((uint32_t)(who >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)who, 0u));
+}
+
 // ---------------------------------------------------------------- encode
 
 // The steps of one round (run number `round` of every lane), last element first.  The words go
 // straight to the token's slot in the workspace, which fills from its end downwards.
-template <int B>
+// WHOLE: every lane's run of this round lies inside the row (valid >= 32 everywhere), so no step
+// needs a range check.
+template <int B, bool WHOLE>
 __device__ __forceinline__ void encode_round(const uint32_t *src_row, uint32_t run, int valid, const uint2 *ftab,
                                              uint16_t *out, uint32_t &ptr, uint32_t &x) {
     uint32_t d[B];
-    const uint32_t nd = valid >= 32 ? (uint32_t)B : (valid > 0 ? ((uint32_t)valid * B + 31u) >> 5 : 0u);
+    const uint32_t nd = (WHOLE || valid >= 32) ? (uint32_t)B : (valid > 0 ? ((uint32_t)valid * B + 31u) >> 5 : 0u);
 #pragma unroll
-    for (int k = 0; k < B; ++k) d[k] = (uint32_t)k < nd ? src_row[run * B + k] : 0u;
-    const uint64_t below = (1ull << (threadIdx.x & 63u)) - 1ull;
+    for (int k = 0; k < B; ++k) d[k] = (WHOLE || (uint32_t)k < nd) ? src_row[run * B + k] : 0u;
 #pragma unroll
     for (int j = 31; j >= 0; --j) {
         const int off = j * B, k = off >> 5, sh = off & 31;
         uint32_t code = d[k] >> sh;
         if (sh + B > 32) code |= d[k + 1 < B ? k + 1 : k] << (32 - sh);
         code &= (1u << B) - 1u;
-        const bool active = j < valid;
+        const bool active = WHOLE || j < valid;
         const uint2 entry = ftab[code];
-        uint32_t f = entry.x & 0xFFFFu;
+        const uint32_t f = entry.x & 0xFFFFu;
         const uint32_t c = entry.x >> 16;
-        if (f == 0) f = 1;                                     // a code the table does not know: cannot happen for a
-                                                               // table built from this blob; keeps the division defined
         const bool shed = active && (x >> 20) >= f;            // x >= f << 20, without overflow for f = 4096
         const uint64_t who = __builtin_amdgcn_ballot_w64(shed);
         ptr -= (uint32_t)__builtin_popcountll(who);
         if (shed) {
-            out[ptr + (uint32_t)__builtin_popcountll(who & below)] = (uint16_t)x;
+            out[ptr + rank_in(who)] = (uint16_t)x;
             x >>= 16;
         }
         if (active) {
@@ -201,7 +214,7 @@ k_rans_encode(const Params p, const EntropyLayout e, const uint8_t *__restrict__
         if (lane == 0) len[t] = 0;
         return;
     }
-    load_table(reinterpret_cast<const uint16_t *>(eblob + e.off_tables) + (width - 2u) * 256u, ftab);
+    load_table<true>(reinterpret_cast<const uint16_t *>(eblob + e.off_tables) + (width - 2u) * 256u, ftab);
     __syncthreads();
     const uint32_t *src_row = reinterpret_cast<const uint32_t *>(blob + p.off_payload + po);
     uint8_t *slot = ews + e.ws_slots + (size_t)t * e.slot_bytes;
@@ -211,14 +224,26 @@ k_rans_encode(const Params p, const EntropyLayout e, const uint8_t *__restrict__
     for (uint32_t r = rounds; r-- > 0;) {
         const uint32_t run = lane + 64u * r;
         const int valid = (int)p.hidden - (int)(run * kRun);          // may be <= 0: nothing of this run exists
-        switch (width) {
-            case 2: encode_round<2>(src_row, run, valid, ftab, out, ptr, x); break;
-            case 3: encode_round<3>(src_row, run, valid, ftab, out, ptr, x); break;
-            case 4: encode_round<4>(src_row, run, valid, ftab, out, ptr, x); break;
-            case 5: encode_round<5>(src_row, run, valid, ftab, out, ptr, x); break;
-            case 6: encode_round<6>(src_row, run, valid, ftab, out, ptr, x); break;
-            case 7: encode_round<7>(src_row, run, valid, ftab, out, ptr, x); break;
-            default: encode_round<8>(src_row, run, valid, ftab, out, ptr, x); break;
+        if (__builtin_amdgcn_ballot_w64(valid < 32) == 0) {
+            switch (width) {
+                case 2: encode_round<2, true>(src_row, run, valid, ftab, out, ptr, x); break;
+                case 3: encode_round<3, true>(src_row, run, valid, ftab, out, ptr, x); break;
+                case 4: encode_round<4, true>(src_row, run, valid, ftab, out, ptr, x); break;
+                case 5: encode_round<5, true>(src_row, run, valid, ftab, out, ptr, x); break;
+                case 6: encode_round<6, true>(src_row, run, valid, ftab, out, ptr, x); break;
+                case 7: encode_round<7, true>(src_row, run, valid, ftab, out, ptr, x); break;
+                default: encode_round<8, true>(src_row, run, valid, ftab, out, ptr, x); break;
+            }
+        } else {
+            switch (width) {
+                case 2: encode_round<2, false>(src_row, run, valid, ftab, out, ptr, x); break;
+                case 3: encode_round<3, false>(src_row, run, valid, ftab, out, ptr, x); break;
+                case 4: encode_round<4, false>(src_row, run, valid, ftab, out, ptr, x); break;
+                case 5: encode_round<5, false>(src_row, run, valid, ftab, out, ptr, x); break;
+                case 6: encode_round<6, false>(src_row, run, valid, ftab, out, ptr, x); break;
+                case 7: encode_round<7, false>(src_row, run, valid, ftab, out, ptr, x); break;
+                default: encode_round<8, false>(src_row, run, valid, ftab, out, ptr, x); break;
+            }
         }
     }
     const uint32_t coders = p.runs < 64u ? p.runs : 64u;  // coders that own a run; the others still hold 2^16
@@ -228,56 +253,64 @@ k_rans_encode(const Params p, const EntropyLayout e, const uint8_t *__restrict__
     }
 }
 
-// Exclusive running sum of the (padded) stream lengths, and the header: one workgroup, 64-bit sums
-// throughout (tokens * slot size may exceed 32 bits).  A thread adds up its share of the tokens;
-// the first thread of every wave chains the 64 shares of its wave, then thread 0 the 16 waves.
-__global__ void __launch_bounds__(1024)
-k_rans_scan(const Params p, const EntropyLayout e, const uint8_t *__restrict__ blob, uint8_t *__restrict__ eblob,
-            const uint8_t *__restrict__ ews) {
-    __shared__ uint64_t share[1024], wave_base[17];
+// Padded stream bytes of every block of kLenBlock tokens: one workgroup per block, one thread per
+// token.  kLenBlock slots of at most 64 KiB + 256 bytes: the sum fits 32 bits.
+__global__ void __launch_bounds__(256)
+k_rans_blocks(const Params p, const EntropyLayout e, const uint8_t *__restrict__ blob, uint8_t *__restrict__ ews) {
+    __shared__ uint32_t part[4];
+    static_assert(kLenBlock == 256, "one thread per token of a block");
     if (!blob_is_valid(p, blob)) return;
     const uint32_t *len = reinterpret_cast<const uint32_t *>(ews + e.ws_len);
-    uint64_t *off = reinterpret_cast<uint64_t *>(eblob + e.off_stream_off);
-    const uint32_t per = (p.tokens + 1023u) / 1024u;
-    const uint64_t lo64 = (uint64_t)threadIdx.x * per;
-    const uint32_t lo = lo64 < p.tokens ? (uint32_t)lo64 : p.tokens;
-    const uint32_t hi = lo64 + per < p.tokens ? (uint32_t)(lo64 + per) : p.tokens;
-    uint64_t s = 0;
-    for (uint32_t t = lo; t < hi; ++t) s += (len[t] + 3u) & ~3u;
-    share[threadIdx.x] = s;
+    const uint32_t t = blockIdx.x * kLenBlock + threadIdx.x;
+    const uint32_t w = wave_sum_u32(t < p.tokens ? (len[t] + 3u) & ~3u : 0u);
+    if ((threadIdx.x & 63u) == 0) part[threadIdx.x >> 6] = w;
     __syncthreads();
-    if ((threadIdx.x & 63u) == 0) {
-        uint64_t run = 0;
-        for (uint32_t i = 0; i < 64u; ++i) { const uint64_t v = share[threadIdx.x + i]; share[threadIdx.x + i] = run; run += v; }
-        wave_base[1u + (threadIdx.x >> 6)] = run;
-    }
-    __syncthreads();
-    if (threadIdx.x == 0) {
-        uint64_t run = 0;
-        wave_base[0] = 0;
-        for (uint32_t i = 1; i <= 16u; ++i) { run += wave_base[i]; wave_base[i] = run; }
-        EntropyHeader h = {};
-        h.magic = kEntropyMagic; h.version = kVersion; h.tokens = p.tokens; h.hidden = p.hidden;
-        h.stream_bytes = run;
-        h.off_tables = e.off_tables; h.off_stream_off = e.off_stream_off; h.off_streams = e.off_streams;
-        h.stream_capacity = e.stream_capacity;
-        *reinterpret_cast<EntropyHeader *>(eblob) = h;
-        off[p.tokens] = run;
-    }
-    __syncthreads();
-    uint64_t at = wave_base[threadIdx.x >> 6] + share[threadIdx.x];
-    for (uint32_t t = lo; t < hi; ++t) { off[t] = at; at += (len[t] + 3u) & ~3u; }
+    if (threadIdx.x == 0) reinterpret_cast<uint32_t *>(ews + e.ws_block)[blockIdx.x] = part[0] + part[1] + part[2] + part[3];
 }
 
+// A token's stream moves from its slot to its place: the (padded) lengths of all streams before it
+// are the sums of the blocks before its block plus the lengths before it inside its block, added up
+// by the workgroup (64-bit: tokens * slot size may exceed 32 bits; a thread's share stays below
+// 2^34, so it is split at bit 24 into two parts whose sums over 256 threads fit 32 bits).  The
+// workgroup of the last token also writes the end offset and the header.
 __global__ void __launch_bounds__(256)
 k_rans_gather(const Params p, const EntropyLayout e, const uint8_t *__restrict__ blob, uint8_t *__restrict__ eblob,
               const uint8_t *__restrict__ ews) {
+    __shared__ uint32_t part[2][4];
+    static_assert(kLenBlock == 256, "one thread per token of a block");
     if (!blob_is_valid(p, blob)) return;
     const uint32_t t = blockIdx.x;
-    const uint32_t bytes = reinterpret_cast<const uint32_t *>(ews + e.ws_len)[t];      // states + words, unpadded
-    const uint64_t at = reinterpret_cast<const uint64_t *>(eblob + e.off_stream_off)[t];
+    const uint32_t *len = reinterpret_cast<const uint32_t *>(ews + e.ws_len);
+    const uint32_t *block = reinterpret_cast<const uint32_t *>(ews + e.ws_block);
+    const uint32_t blk = t / kLenBlock;
+    uint64_t s = 0;
+    for (uint32_t b = threadIdx.x; b < blk; b += 256u) s += block[b];
+    const uint32_t u = blk * kLenBlock + threadIdx.x;       // kLenBlock == threads of this workgroup
+    if (u < t) s += (len[u] + 3u) & ~3u;
+    const uint32_t lo = wave_sum_u32((uint32_t)s & 0xFFFFFFu), hi = wave_sum_u32((uint32_t)(s >> 24));
+    if ((threadIdx.x & 63u) == 0) { part[0][threadIdx.x >> 6] = lo; part[1][threadIdx.x >> 6] = hi; }
+    __syncthreads();
+    uint64_t at = 0;
+#pragma unroll
+    for (int w = 0; w < 4; ++w) at += (uint64_t)part[0][w] + ((uint64_t)part[1][w] << 24);
+
+    const uint32_t bytes = len[t];                          // states + words, unpadded
+    const uint32_t padded = (bytes + 3u) & ~3u;
+    uint64_t *off = reinterpret_cast<uint64_t *>(eblob + e.off_stream_off);
+    if (threadIdx.x == 0) {
+        off[t] = at;
+        if (t == p.tokens - 1u) {
+            off[p.tokens] = at + padded;
+            EntropyHeader h = {};
+            h.magic = kEntropyMagic; h.version = kVersion; h.tokens = p.tokens; h.hidden = p.hidden;
+            h.stream_bytes = at + padded;
+            h.off_tables = e.off_tables; h.off_stream_off = e.off_stream_off; h.off_streams = e.off_streams;
+            h.stream_capacity = e.stream_capacity;
+            *reinterpret_cast<EntropyHeader *>(eblob) = h;
+        }
+    }
     const uint32_t coders = p.runs < 64u ? p.runs : 64u;
-    if (bytes < 4u * coders || bytes > e.slot_bytes || at + ((bytes + 3u) & ~3u) > e.stream_capacity) return;
+    if (bytes < 4u * coders || bytes > e.slot_bytes || at + padded > e.stream_capacity) return;
     const uint8_t *slot = ews + e.ws_slots + (size_t)t * e.slot_bytes;
     uint8_t *dst = eblob + e.off_streams + at;
     if (threadIdx.x < coders) reinterpret_cast<uint32_t *>(dst)[threadIdx.x] = reinterpret_cast<const uint32_t *>(slot)[threadIdx.x];
@@ -356,7 +389,7 @@ __device__ __forceinline__ void build_slot_table(const uint2 *ftab, uint32_t *sy
 struct Words {
     const uint16_t *src;
     uint32_t count, base;
-    uint32_t w0, w1, w2, w3;
+    uint32_t w01, w2, w3;      // the first two windows share a register (low / high half): one permute reads both
 };
 __device__ __forceinline__ uint32_t word_at(const Words &q, uint32_t k) {
     const uint32_t i = k + (threadIdx.x & 63u);
@@ -364,19 +397,18 @@ __device__ __forceinline__ uint32_t word_at(const Words &q, uint32_t k) {
 }
 __device__ __forceinline__ void words_open(Words &q, const uint16_t *src, uint32_t count) {
     q.src = src; q.count = count; q.base = 0;
-    q.w0 = word_at(q, 0); q.w1 = word_at(q, 64); q.w2 = word_at(q, 128); q.w3 = word_at(q, 192);
+    q.w01 = word_at(q, 0) | (word_at(q, 64) << 16); q.w2 = word_at(q, 128); q.w3 = word_at(q, 192);
 }
 
-template <int B>
+template <int B, bool WHOLE>
 __device__ __forceinline__ void decode_round(uint32_t *dst_row, uint32_t run, int valid, const uint2 *ftab,
                                              const uint8_t *sym, Words &q, uint32_t &pos, uint32_t &x) {
     uint32_t d[B];
 #pragma unroll
     for (int k = 0; k < B; ++k) d[k] = 0;
-    const uint64_t below = (1ull << (threadIdx.x & 63u)) - 1ull;
 #pragma unroll
     for (int j = 0; j < 32; ++j) {
-        const bool active = j < valid;
+        const bool active = WHOLE || j < valid;
         const uint32_t slot = x & (kProbScale - 1u);
         const uint32_t s = sym[slot];
         const uint32_t fc = ftab[s].x;
@@ -389,22 +421,21 @@ __device__ __forceinline__ void decode_round(uint32_t *dst_row, uint32_t run, in
         const bool need = active && x < kRansLow;
         const uint64_t who = __builtin_amdgcn_ballot_w64(need);
         if (who) {
-            const uint32_t at = pos - q.base + (uint32_t)__builtin_popcountll(who & below);   // < 128
-            const uint32_t a = (uint32_t)__builtin_amdgcn_ds_bpermute((int)((at & 63u) << 2), (int)q.w0);
-            const uint32_t b = (uint32_t)__builtin_amdgcn_ds_bpermute((int)((at & 63u) << 2), (int)q.w1);
-            if (need) x = (x << 16) | (at < 64u ? a : b);
+            const uint32_t at = pos - q.base + rank_in(who);   // < 128
+            const uint32_t both = (uint32_t)__builtin_amdgcn_ds_bpermute((int)((at & 63u) << 2), (int)q.w01);
+            if (need) x = (x << 16) | ((both >> ((at & 64u) >> 2)) & 0xFFFFu);
             pos += (uint32_t)__builtin_popcountll(who);
             if (pos - q.base >= 64u) {
                 q.base += 64u;
-                q.w0 = q.w1; q.w1 = q.w2; q.w2 = q.w3;
+                q.w01 = (q.w01 >> 16) | (q.w2 << 16); q.w2 = q.w3;
                 q.w3 = word_at(q, q.base + 192u);
             }
         }
     }
-    const uint32_t nd = valid >= 32 ? (uint32_t)B : (valid > 0 ? ((uint32_t)valid * B + 31u) >> 5 : 0u);
+    const uint32_t nd = (WHOLE || valid >= 32) ? (uint32_t)B : (valid > 0 ? ((uint32_t)valid * B + 31u) >> 5 : 0u);
 #pragma unroll
     for (int k = 0; k < B; ++k)
-        if ((uint32_t)k < nd) dst_row[run * B + k] = d[k];
+        if (WHOLE || (uint32_t)k < nd) dst_row[run * B + k] = d[k];
 }
 
 __global__ void __launch_bounds__(64)
@@ -420,7 +451,7 @@ k_rans_decode(const Params p, const EntropyLayout e, const uint8_t *__restrict__
     const uint64_t a = off[t], b = off[t + 1];
     const uint32_t coders = p.runs < 64u ? p.runs : 64u;  // states in the stream; the other coders start (and stay) at 2^16
     if (b < a + 4u * coders || b > e.stream_capacity || b - a > e.slot_bytes || (a & 3u)) return;
-    load_table(reinterpret_cast<const uint16_t *>(eblob + e.off_tables) + (width - 2u) * 256u, ftab);
+    load_table<false>(reinterpret_cast<const uint16_t *>(eblob + e.off_tables) + (width - 2u) * 256u, ftab);
     __syncthreads();
     build_slot_table(ftab, sym32);
     const uint8_t *sym = reinterpret_cast<const uint8_t *>(sym32);
@@ -433,14 +464,26 @@ k_rans_decode(const Params p, const EntropyLayout e, const uint8_t *__restrict__
     for (uint32_t r = 0; r < rounds; ++r) {
         const uint32_t run = lane + 64u * r;
         const int valid = (int)p.hidden - (int)(run * kRun);
-        switch (width) {
-            case 2: decode_round<2>(dst_row, run, valid, ftab, sym, q, pos, x); break;
-            case 3: decode_round<3>(dst_row, run, valid, ftab, sym, q, pos, x); break;
-            case 4: decode_round<4>(dst_row, run, valid, ftab, sym, q, pos, x); break;
-            case 5: decode_round<5>(dst_row, run, valid, ftab, sym, q, pos, x); break;
-            case 6: decode_round<6>(dst_row, run, valid, ftab, sym, q, pos, x); break;
-            case 7: decode_round<7>(dst_row, run, valid, ftab, sym, q, pos, x); break;
-            default: decode_round<8>(dst_row, run, valid, ftab, sym, q, pos, x); break;
+        if (__builtin_amdgcn_ballot_w64(valid < 32) == 0) {
+            switch (width) {
+                case 2: decode_round<2, true>(dst_row, run, valid, ftab, sym, q, pos, x); break;
+                case 3: decode_round<3, true>(dst_row, run, valid, ftab, sym, q, pos, x); break;
+                case 4: decode_round<4, true>(dst_row, run, valid, ftab, sym, q, pos, x); break;
+                case 5: decode_round<5, true>(dst_row, run, valid, ftab, sym, q, pos, x); break;
+                case 6: decode_round<6, true>(dst_row, run, valid, ftab, sym, q, pos, x); break;
+                case 7: decode_round<7, true>(dst_row, run, valid, ftab, sym, q, pos, x); break;
+                default: decode_round<8, true>(dst_row, run, valid, ftab, sym, q, pos, x); break;
+            }
+        } else {
+            switch (width) {
+                case 2: decode_round<2, false>(dst_row, run, valid, ftab, sym, q, pos, x); break;
+                case 3: decode_round<3, false>(dst_row, run, valid, ftab, sym, q, pos, x); break;
+                case 4: decode_round<4, false>(dst_row, run, valid, ftab, sym, q, pos, x); break;
+                case 5: decode_round<5, false>(dst_row, run, valid, ftab, sym, q, pos, x); break;
+                case 6: decode_round<6, false>(dst_row, run, valid, ftab, sym, q, pos, x); break;
+                case 7: decode_round<7, false>(dst_row, run, valid, ftab, sym, q, pos, x); break;
+                default: decode_round<8, false>(dst_row, run, valid, ftab, sym, q, pos, x); break;
+            }
         }
     }
 }
@@ -456,12 +499,12 @@ int launch_rans_encode(const Params &p, const Geometry &g, const EntropyLayout &
     const uint8_t *blob = static_cast<const uint8_t *>(d_blob);
     uint8_t *eblob = static_cast<uint8_t *>(d_eblob), *ews = static_cast<uint8_t *>(d_ews);
     hipStream_t s = as_stream(stream);
-    hipLaunchKernelGGL(k_rans_begin, dim3(1), dim3(256), 0, s, e, eblob, ews);
-    int rc = launch_code_pool(p, g, d_blob, ews + e.ws_pooled, stream);
+    hipLaunchKernelGGL(k_rans_begin, dim3(1), dim3(1024), 0, s, p, e, eblob, ews);
+    int rc = launch_code_pool(p, g, e, d_blob, ews + e.ws_pooled, stream);
     if (rc != 0) return rc;
     hipLaunchKernelGGL(k_rans_tables, dim3(7), dim3(256), 0, s, p, e, blob, eblob, ews);
     hipLaunchKernelGGL(k_rans_encode, dim3(p.tokens), dim3(64), 0, s, p, e, blob, eblob, ews);
-    hipLaunchKernelGGL(k_rans_scan, dim3(1), dim3(1024), 0, s, p, e, blob, eblob, ews);
+    hipLaunchKernelGGL(k_rans_blocks, dim3((p.tokens + kLenBlock - 1u) / kLenBlock), dim3(256), 0, s, p, e, blob, ews);
     hipLaunchKernelGGL(k_rans_gather, dim3(p.tokens), dim3(256), 0, s, p, e, blob, eblob, ews);
     return (int)hipGetLastError();
 }
