@@ -60,7 +60,7 @@ struct EntropyLayout {
     uint32_t pad;
 };
 constexpr uint32_t kLenBlock = 256;     // tokens per partial sum of stream lengths
-constexpr uint32_t kMaxPoolGroups = 2048;
+constexpr uint32_t kMaxPoolGroups = 1536;   // counting workgroups: six fit a compute unit (LDS), 256 compute units: one round
 constexpr uint32_t kPoolCopies = 16;    // sets of pooled counts: 16 times fewer atomic adds per address
 
 // Kernel argument block (passed by value).
