@@ -104,6 +104,49 @@ def test_random_configurations(tsq, oracle, RE, seed):
         check(tsq, oracle, RE, x, dtype, float(g.choice([2.0, 6.0, 50.0])), widths, budget, label="random %d.%d" % (seed, k))
 
 
+@pytest.mark.parametrize("T,H", [(1000, 96), (5000, 32)])
+def test_many_tokens_ending_inside_a_block_of_offsets(tsq, oracle, RE, T, H):
+    """Token counts that are not multiples of the 256 tokens whose stream lengths are summed together,
+    and more tokens than counting workgroups."""
+    g = np.random.Generator(np.random.PCG64(77 + T))
+    v = g.standard_t(4, size=(T, H)) * g.lognormal(0.0, 0.8, (T, 1))
+    check(tsq, oracle, RE, synth.to_f16_bits(v), "f16", 6.0, (2, 3, 4, 6, 8), 0.1, label="%d tokens" % T)
+
+
+def test_more_tokens_than_the_counting_kernel_takes_in_one_go(tsq, oracle, RE):
+    """100000 tokens of 8 elements: every counting workgroup goes through its tokens in several
+    portions.  The oracle codes a token in Python, so tables and offsets are compared in full (the
+    offsets against the lengths the oracle's coder gives for sampled tokens and against each other),
+    streams on sampled tokens, and the payload must come back byte for byte."""
+    import torch
+    R, E = RE
+    T, H = 100000, 8
+    g = np.random.Generator(np.random.PCG64(4242))
+    v = g.standard_t(4, size=(T, H)) * g.lognormal(0.0, 0.8, (T, 1))
+    x = synth.to_f16_bits(v)
+    ref = oracle.compress(x, 0, 6.0, (2, 3, 4, 6, 8), 0.1, 1, nthreads=8)
+    tables = R.class_tables(E.code_histogram(ref), ref.bits)
+    plan = tsq.Plan(T, H, "f16", 6.0, (2, 3, 4, 6, 8), 0.1, max_outliers=max(ref.nnz, 1))
+    blob = plan.compress(torch.from_numpy(x.view(np.int16)).cuda())
+    assert plan.info(blob).status == 0
+    eblob = plan.entropy_encode(blob)
+    sec = plan.entropy_sections(eblob)
+    assert np.array_equal(sec["tables"], tables), "tables"
+    off = sec["stream_off"].astype(np.int64)
+    # one coder per token here (one run): a stream is its state and at most 8 words, padded to 4 bytes
+    d = np.diff(off)
+    assert off[0] == 0 and np.all(d >= 4) and np.all(d <= 4 + 16) and np.all(d % 4 == 0)
+    assert int(off[-1]) == sec["info"].stream_bytes
+    for t in sorted(set(g.integers(0, T, 300).tolist()) | {0, 255, 256, 257, T - 1}):
+        want = R.encode_token(E.token_codes(ref, t), tables[int(ref.bits[t]) - 2])
+        assert sec["streams"][int(off[t]): int(off[t + 1])].tobytes() == want, "token %d" % t
+    L = plan.layout
+    blob2 = blob.clone()
+    blob2[int(L.off_payload): int(L.off_payload) + int(L.payload_capacity)] = 0
+    plan.entropy_decode(eblob, blob2)
+    assert np.array_equal(plan.sections(blob2)["payload"], ref.payload)
+
+
 def test_a_foreign_blob_gives_no_valid_eblob(tsq):
     import torch
     plan = tsq.Plan(16, 64, "f16", 6.0, (4, 8), 0.05)
