@@ -1,0 +1,60 @@
+"""Error paths of the single-pass compress that the host can force without breaking a kernel: every
+device-side wait is bounded, so a workspace in an arbitrary state ends in TSQ_ERR_INTERNAL in the
+blob's header, never in a hang, and tsq_workspace_reset brings the workspace back."""
+import numpy as np
+import pytest
+
+from paper_2511_04002_amd import synth
+
+pytestmark = pytest.mark.gpu
+
+SECTIONS = ("bits", "row_ptr", "pay_off", "out_col", "out_val", "payload")
+
+
+@pytest.fixture(scope="module")
+def tsq():
+    import torch
+    assert torch.cuda.is_available(), "these tests need the GPU"
+    from paper_2511_04002_amd import tsq as m
+    m.lib()
+    return m
+
+
+def test_a_workspace_that_was_never_reset_is_reported_and_recovers(tsq, oracle):
+    """A workspace of all-ones bytes: the error word is set, the table words carry no valid tag and
+    the ticket counters wrap around.  Every token index the kernel forms from them is still checked
+    against the token count, and every store against its section, so the call runs to its end and
+    says TSQ_ERR_INTERNAL; after a reset the same buffers give the oracle's blob."""
+    import torch
+    x = synth.make_c2(tokens=3000)                         # more tokens than workgroups: tickets are drawn
+    T, H = x.shape
+    ref = oracle.compress(x, oracle.F16, 8.0, (2, 3, 4, 6, 8), 0.05, 1, nthreads=8)
+    plan = tsq.Plan(T, H, "f16", 8.0, (2, 3, 4, 6, 8), 0.05, pipeline="fused", max_outliers=max(ref.nnz, 1))
+    xd = torch.from_numpy(x.view(np.int16)).cuda()
+    ws = torch.empty(int(plan.layout.workspace_bytes), dtype=torch.uint8, device="cuda")
+    ws.fill_(0xFF)
+    blob = plan.new_blob()
+    blob.zero_()
+    print("compress on a workspace of all-ones bytes", flush=True)
+    plan.compress(xd, blob, ws)
+    info = plan.info(blob, check=False)
+    assert info.return_status == tsq.TSQ_ERR_INTERNAL
+    # decompress refuses such a blob: the output stays as it was
+    out = torch.full((T, H), 0x1234, dtype=torch.int16, device="cuda")
+    plan.decompress(blob, out)
+    torch.cuda.synchronize()
+    assert bool((out == 0x1234).all())
+
+    print("the same call after tsq_workspace_reset", flush=True)
+    tsq.tsq_workspace_reset(plan.handle, ws.data_ptr(), 0)
+    plan.compress(xd, blob, ws)
+    assert plan.info(blob).status == 0
+    sec = plan.sections(blob)
+    for k in SECTIONS:
+        assert np.array_equal(sec[k], getattr(ref, k)), k
+    assert np.array_equal(sec["scale"].view(np.uint32), ref.scale.view(np.uint32))
+    # and once more, without a reset in between: a completed call leaves the workspace ready
+    blob.zero_()
+    plan.compress(xd, blob, ws)
+    assert plan.info(blob).status == 0
+    assert np.array_equal(plan.sections(blob)["payload"], ref.payload)
