@@ -351,7 +351,7 @@ __device__ __forceinline__ void build_slot_table(const uint2 *ftab, uint32_t *sy
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
         const uint32_t c = 4u * lane + i, fc = ftab[c].x;
-        if (fc & 0xFFFFu) sym[fc >> 16] = (uint8_t)c;
+        if (fc & 0xFFFFu) sym[(fc >> 16) & (kProbScale - 1u)] = (uint8_t)c;   // masked: a damaged table stays inside the array
     }
     __syncthreads();
     // lane l owns the slots 64l .. 64l+63

@@ -58,3 +58,45 @@ def test_a_workspace_that_was_never_reset_is_reported_and_recovers(tsq, oracle):
     plan.compress(xd, blob, ws)
     assert plan.info(blob).status == 0
     assert np.array_equal(plan.sections(blob)["payload"], ref.payload)
+
+
+def test_a_damaged_eblob_is_decoded_to_the_end_and_touches_only_the_payload(tsq, oracle):
+    """Tables, stream bytes and stream offsets of a valid eblob overwritten with noise: the decoder
+    checks every offset against the stream capacity, reads past a stream's end as zeros and keeps
+    every table index inside its table, so it writes (wrong) codes into the payload section and
+    nothing else.  What is compared is everything outside the payload section."""
+    import torch
+    x = synth.make_c4(tokens=300)
+    T, H = x.shape
+    w = synth.WORKLOADS["C4"]
+    plan = tsq.Plan(T, H, w.dtype, w.tau, w.bit_set, 0.05)
+    blob = plan.compress(torch.from_numpy(x.view(np.int16)).cuda())
+    assert plan.info(blob).status == 0
+    eblob = plan.entropy_encode(blob)
+    info = plan.entropy_sections(eblob)["info"]
+    L = plan.layout
+    lo, hi = int(L.off_payload), int(L.off_payload) + int(L.payload_capacity)
+    before = blob.cpu().numpy().copy()
+    g = torch.Generator(device="cuda")
+    g.manual_seed(7)
+
+    def noise(n):
+        return torch.randint(0, 256, (n,), dtype=torch.uint8, device="cuda", generator=g)
+
+    cases = {"tables": (int(info.off_tables), 7 * 512),
+             "streams": (int(info.off_streams), int(info.stream_bytes)),
+             "offsets": (int(info.off_stream_off), 8 * (T + 1))}
+    for name, (at, n) in cases.items():
+        print("decode with noise in the", name, flush=True)
+        bad = eblob.clone()
+        bad[at: at + n] = noise(n)
+        work = blob.clone()
+        plan.entropy_decode(bad, work)
+        torch.cuda.synchronize()
+        after = work.cpu().numpy()
+        assert np.array_equal(after[:lo], before[:lo]) and np.array_equal(after[hi:], before[hi:]), name
+    # the undamaged eblob still restores the payload
+    work = blob.clone()
+    work[lo:hi] = 0
+    plan.entropy_decode(eblob, work)
+    assert np.array_equal(plan.sections(work)["payload"], plan.sections(blob)["payload"])
