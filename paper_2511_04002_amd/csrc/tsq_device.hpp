@@ -454,6 +454,12 @@ __device__ __forceinline__ void unpack_run(const uint32_t (&d)[B], float s, uint
 constexpr uint32_t kScrScan = 4 * 2 * kMaxWaves;
 
 __device__ __forceinline__ uint32_t row_bytes(uint32_t H, uint32_t b) { return 4u * ((H * b + 31u) >> 5); }
+// A token of width b whose payload starts at byte po of the payload section: valid width, 4-byte
+// aligned, and inside the section.  Written without a sum of untrusted values, which could wrap.
+__device__ __forceinline__ bool token_in_range(const Params &p, uint32_t b, uint64_t po) {
+    if (b < 2 || b > 8 || (po & 3u) || po > p.payload_capacity) return false;
+    return row_bytes(p.hidden, b) <= p.payload_capacity - po;
+}
 
 // ---------------------------------------------------------------- Algorithm 1 for the token of this block
 

@@ -63,7 +63,7 @@ k_code_hist(const Params p, const uint8_t *__restrict__ blob, uint32_t *__restri
     const uint32_t width = blob[p.off_bits + t];
     const uint64_t po = reinterpret_cast<const uint64_t *>(blob + p.off_pay_off)[t];
     // a damaged token is skipped rather than read out of bounds
-    if (width < 2 || width > 8 || (po & 3u) || po + row_bytes(p.hidden, width) > p.payload_capacity) return;
+    if (!token_in_range(p, width, po)) return;
 
     for (uint32_t i = threadIdx.x; i < kCopies * kCopyStride; i += blockDim.x) bins[i] = 0;
     __syncthreads();
@@ -113,7 +113,7 @@ k_code_pool(const Params p, const uint8_t *__restrict__ blob, uint32_t *__restri
             const uint32_t width = blob[p.off_bits + t];
             const uint64_t po = reinterpret_cast<const uint64_t *>(blob + p.off_pay_off)[t];
             // a damaged token is skipped rather than read out of bounds
-            const bool good = width >= 2 && width <= 8 && !(po & 3u) && po + row_bytes(p.hidden, width) <= p.payload_capacity;
+            const bool good = token_in_range(p, width, po);
             widths[threadIdx.x] = good ? (uint8_t)width : 0;
         }
         __syncthreads();

@@ -172,7 +172,7 @@ k_pack(const Params p, const uint16_t *__restrict__ in, uint8_t *__restrict__ bl
     const float r = amax >= kAmaxFloor ? level_count(width) / amax : 0.0f;
 
     // a width outside the plan's set would overrun the payload section: write nothing for it
-    const bool width_ok = width >= 2 && width <= 8 && po + row_bytes(p.hidden, width) <= p.payload_capacity;
+    const bool width_ok = token_in_range(p, width, po);
     if (run < p.runs) {
         split_run<DT, false>(lrow + run * kRunLdsDw, p.thr_pk, mg, omask, amax_bits);
         if (width_ok) {
@@ -233,8 +233,7 @@ k_unpack(const Params p, const uint8_t *__restrict__ blob, uint16_t *__restrict_
     const uint64_t rp0 = reinterpret_cast<const uint64_t *>(blob + p.off_row_ptr)[t];
     const uint64_t rp1 = reinterpret_cast<const uint64_t *>(blob + p.off_row_ptr)[t + 1];
     // a damaged token is skipped rather than read out of bounds
-    if (width < 2 || width > 8 || (po & 3u) || po + row_bytes(p.hidden, width) > p.payload_capacity ||
-        rp0 > rp1 || rp1 > p.outlier_capacity)
+    if (!token_in_range(p, width, po) || rp0 > rp1 || rp1 > p.outlier_capacity)
         return;
 
     if (run < p.runs) {

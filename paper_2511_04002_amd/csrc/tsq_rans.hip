@@ -210,7 +210,7 @@ k_rans_encode(const Params p, const EntropyLayout e, const uint8_t *__restrict__
     if (!blob_is_valid(p, blob)) return;
     const uint32_t width = blob[p.off_bits + t];
     const uint64_t po = reinterpret_cast<const uint64_t *>(blob + p.off_pay_off)[t];
-    if (width < 2 || width > 8 || (po & 3u) || po + row_bytes(p.hidden, width) > p.payload_capacity) {
+    if (!token_in_range(p, width, po)) {
         if (lane == 0) len[t] = 0;
         return;
     }
@@ -446,11 +446,11 @@ k_rans_decode(const Params p, const EntropyLayout e, const uint8_t *__restrict__
     if (!blob_is_valid(p, blob) || !eblob_is_valid(p, e, eblob)) return;
     const uint32_t width = blob[p.off_bits + t];
     const uint64_t po = reinterpret_cast<const uint64_t *>(blob + p.off_pay_off)[t];
-    if (width < 2 || width > 8 || (po & 3u) || po + row_bytes(p.hidden, width) > p.payload_capacity) return;
+    if (!token_in_range(p, width, po)) return;
     const uint64_t *off = reinterpret_cast<const uint64_t *>(eblob + e.off_stream_off);
     const uint64_t a = off[t], b = off[t + 1];
     const uint32_t coders = p.runs < 64u ? p.runs : 64u;  // states in the stream; the other coders start (and stay) at 2^16
-    if (b < a + 4u * coders || b > e.stream_capacity || b - a > e.slot_bytes || (a & 3u)) return;
+    if (a > b || b > e.stream_capacity || b - a < 4u * coders || b - a > e.slot_bytes || (a & 3u)) return;
     load_table<false>(reinterpret_cast<const uint16_t *>(eblob + e.off_tables) + (width - 2u) * 256u, ftab);
     __syncthreads();
     build_slot_table(ftab, sym32);

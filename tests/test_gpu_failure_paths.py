@@ -100,3 +100,47 @@ def test_a_damaged_eblob_is_decoded_to_the_end_and_touches_only_the_payload(tsq,
     work[lo:hi] = 0
     plan.entropy_decode(eblob, work)
     assert np.array_equal(plan.sections(work)["payload"], plan.sections(blob)["payload"])
+
+
+def test_a_damaged_blob_is_decompressed_without_leaving_its_sections(tsq, oracle):
+    """Widths, payload offsets, CSR row pointers and columns of a valid blob overwritten (with noise,
+    and with offsets just below 2^64, which would wrap if they were added to a length before being
+    compared): every token is either restored from inside the sections or skipped.  The tokens whose
+    metadata stayed intact must still come out as the oracle restores them."""
+    import torch
+    x = synth.make_c4(tokens=300)
+    T, H = x.shape
+    w = synth.WORKLOADS["C4"]
+    ref = oracle.compress(x, oracle.BF16, w.tau, w.bit_set, 0.05, 1, nthreads=8)
+    want = oracle.decompress(ref, nthreads=8)
+    plan = tsq.Plan(T, H, w.dtype, w.tau, w.bit_set, 0.05, max_outliers=max(ref.nnz, 1))
+    blob = plan.compress(torch.from_numpy(x.view(np.int16)).cuda())
+    assert plan.info(blob).status == 0
+    L = plan.layout
+    g = np.random.Generator(np.random.PCG64(99))
+
+    def run(name, at, raw_bytes, intact):
+        print("decompress with a damaged", name, flush=True)
+        bad = blob.clone()
+        bad[at: at + len(raw_bytes)] = torch.from_numpy(raw_bytes).cuda()
+        out = torch.full((T, H), 0x1234, dtype=torch.int16, device="cuda")
+        plan.decompress(bad, out)
+        torch.cuda.synchronize()
+        got = out.cpu().numpy().view(np.uint16)
+        for t in intact:
+            assert np.array_equal(got[t], want[t]), (name, t)
+
+    # token 7's payload offset just below 2^64; all other tokens untouched
+    po = plan.sections(blob)["pay_off"].copy()
+    po[7] = np.uint64(2 ** 64 - 4)
+    run("payload offset (wrapping)", int(L.off_pay_off), po.view(np.uint8), [t for t in range(T) if t != 7])
+    po[7] = np.uint64(2 ** 64 - 8192)
+    run("payload offset (wrapping by a row)", int(L.off_pay_off), po.view(np.uint8), [0, 6, 8, T - 1])
+    run("payload offsets (noise)", int(L.off_pay_off), g.integers(0, 256, 8 * (T + 1), dtype=np.uint8), [])
+    run("widths (noise)", int(L.off_bits), g.integers(0, 256, T, dtype=np.uint8), [])
+    # row pointers: noise in the upper half of the tokens (a pointer pair that is out of order or beyond
+    # the capacity skips the token), columns: noise everywhere (a column beyond the row is ignored)
+    rp = plan.sections(blob)["row_ptr"].copy()
+    rp[T // 2:] = g.integers(0, 2 ** 63, T + 1 - T // 2, dtype=np.uint64)
+    run("row pointers (noise)", int(L.off_row_ptr), rp.view(np.uint8), list(range(0, T // 2 - 1)))
+    run("columns (noise)", int(L.off_out_col), g.integers(0, 256, 2 * max(ref.nnz, 1), dtype=np.uint8), [])
