@@ -122,6 +122,24 @@ def test_layout(L, T, H, bits, cap):
         tsq.tsq_plan_destroy(plan)
 
 
+@pytest.mark.parametrize("T,H", [(128, 768), (2048, 4096), (7, 40), (1, 8), (100000, 8), (300, 32768)])
+def test_entropy_sizes(L, T, H):
+    """The coded blob holds a 256-byte header, seven tables, T + 1 offsets and room for the longest
+    possible streams (per token 64 states and one 16-bit word per element); the encoder's workspace
+    holds a slot of that size per token on top of its counters."""
+    plan = tsq.tsq_plan_create(cfg(tokens=T, hidden=H))
+    try:
+        slot = 256 + 2 * ((H + 1) // 2 * 2)
+        eb, ew = tsq.tsq_entropy_blob_bytes(plan), tsq.tsq_entropy_workspace_bytes(plan)
+        need = 256 + 7 * 512 + 8 * (T + 1) + T * slot
+        assert eb % 256 == 0 and need <= eb <= need + 4 * 256
+        assert ew % 256 == 0 and ew >= T * slot + 4 * T + 16 * 7 * 1024
+        assert ew <= T * slot + 8 * T + (1 << 20)
+    finally:
+        tsq.tsq_plan_destroy(plan)
+    assert tsq.tsq_entropy_blob_bytes(0) == 0 and tsq.tsq_entropy_workspace_bytes(0) == 0
+
+
 def test_status_strings(L):
     seen = {tsq.tsq_status_string(s) for s in range(7)}
     assert len(seen) == 7 and "ok" in seen
