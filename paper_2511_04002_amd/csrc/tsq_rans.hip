@@ -126,9 +126,8 @@ k_rans_tables(const Params p, const EntropyLayout e, const uint8_t *__restrict__
 
 // The table of a token's class into LDS, by one wave (lane l owns the codes 4l .. 4l+3): per code
 // x = f | cum << 16 (cum = exclusive running sum, < 4096) and y = the binary32 pattern of 1 / f.
-// GUARD (the encoder's form): a code the table does not know (f = 0; cannot happen for a table built
-// from the blob that is coded) is entered with f = 1, which keeps the division defined.
-template <bool GUARD>
+// A code the table does not know (f = 0; cannot happen for a table built from the blob that is
+// coded) is entered with f = 1, which keeps the division defined.
 __device__ __forceinline__ void load_table(const uint16_t *table, uint2 *ftab) {
     const uint32_t lane = threadIdx.x & 63u;
     uint32_t f[4], s = 0;
@@ -138,7 +137,22 @@ __device__ __forceinline__ void load_table(const uint16_t *table, uint2 *ftab) {
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
         const uint32_t fi = f[i] ? f[i] : 1u;
-        ftab[4u * lane + i] = make_uint2((GUARD ? fi : f[i]) | (cum << 16), __float_as_uint(1.0f / (float)fi));
+        ftab[4u * lane + i] = make_uint2(fi | (cum << 16), __float_as_uint(1.0f / (float)fi));
+        cum += f[i];
+    }
+}
+
+// The decoder's form of the table: f | cum << 16 only (it never divides), 1 KB, so that a token's
+// tables take 5 KB of LDS and a compute unit holds 32 tokens at once.  Unknown codes keep f = 0.
+__device__ __forceinline__ void load_table_decode(const uint16_t *table, uint32_t *ftab) {
+    const uint32_t lane = threadIdx.x & 63u;
+    uint32_t f[4], s = 0;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) { f[i] = table[4u * lane + i]; s += f[i]; }
+    uint32_t cum = wave_incl_scan_u32(s) - s;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        ftab[4u * lane + i] = f[i] | (cum << 16);
         cum += f[i];
     }
 }
@@ -214,7 +228,7 @@ k_rans_encode(const Params p, const EntropyLayout e, const uint8_t *__restrict__
         if (lane == 0) len[t] = 0;
         return;
     }
-    load_table<true>(reinterpret_cast<const uint16_t *>(eblob + e.off_tables) + (width - 2u) * 256u, ftab);
+    load_table(reinterpret_cast<const uint16_t *>(eblob + e.off_tables) + (width - 2u) * 256u, ftab);
     __syncthreads();
     const uint32_t *src_row = reinterpret_cast<const uint32_t *>(blob + p.off_payload + po);
     uint8_t *slot = ews + e.ws_slots + (size_t)t * e.slot_bytes;
@@ -342,7 +356,7 @@ __device__ __forceinline__ uint32_t wave_incl_scan_max(uint32_t v) {
 
 // slot -> code for all 4096 slots: a code's index is written at the slot where its range starts,
 // and a running maximum carries it over the range (later codes start at later slots).
-__device__ __forceinline__ void build_slot_table(const uint2 *ftab, uint32_t *sym32) {
+__device__ __forceinline__ void build_slot_table(const uint32_t *ftab, uint32_t *sym32) {
     const uint32_t lane = threadIdx.x & 63u;
     uint8_t *sym = reinterpret_cast<uint8_t *>(sym32);
 #pragma unroll
@@ -350,7 +364,7 @@ __device__ __forceinline__ void build_slot_table(const uint2 *ftab, uint32_t *sy
     __syncthreads();
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
-        const uint32_t c = 4u * lane + i, fc = ftab[c].x;
+        const uint32_t c = 4u * lane + i, fc = ftab[c];
         if (fc & 0xFFFFu) sym[(fc >> 16) & (kProbScale - 1u)] = (uint8_t)c;   // masked: a damaged table stays inside the array
     }
     __syncthreads();
@@ -401,7 +415,7 @@ __device__ __forceinline__ void words_open(Words &q, const uint16_t *src, uint32
 }
 
 template <int B, bool WHOLE>
-__device__ __forceinline__ void decode_round(uint32_t *dst_row, uint32_t run, int valid, const uint2 *ftab,
+__device__ __forceinline__ void decode_round(uint32_t *dst_row, uint32_t run, int valid, const uint32_t *ftab,
                                              const uint8_t *sym, Words &q, uint32_t &pos, uint32_t &x) {
     uint32_t d[B];
 #pragma unroll
@@ -411,7 +425,7 @@ __device__ __forceinline__ void decode_round(uint32_t *dst_row, uint32_t run, in
         const bool active = WHOLE || j < valid;
         const uint32_t slot = x & (kProbScale - 1u);
         const uint32_t s = sym[slot];
-        const uint32_t fc = ftab[s].x;
+        const uint32_t fc = ftab[s];
         if (active) {
             x = __umul24(fc & 0xFFFFu, x >> kProbBits) + slot - (fc >> 16);    // f <= 2^12, x >> 12 < 2^20
             const int off = j * B, k = off >> 5, sh = off & 31;
@@ -438,9 +452,9 @@ __device__ __forceinline__ void decode_round(uint32_t *dst_row, uint32_t run, in
         if (WHOLE || (uint32_t)k < nd) dst_row[run * B + k] = d[k];
 }
 
-__global__ void __launch_bounds__(64)
+__global__ void __launch_bounds__(64, 8)    // 8 waves per SIMD: all 32 tokens of a compute unit's share run at once
 k_rans_decode(const Params p, const EntropyLayout e, const uint8_t *__restrict__ eblob, uint8_t *__restrict__ blob) {
-    __shared__ uint2 ftab[256];
+    __shared__ uint32_t ftab[256];
     __shared__ uint32_t sym32[1024];                                   // slot -> code, one byte per slot
     const uint32_t t = blockIdx.x, lane = threadIdx.x;
     if (!blob_is_valid(p, blob) || !eblob_is_valid(p, e, eblob)) return;
@@ -451,7 +465,7 @@ k_rans_decode(const Params p, const EntropyLayout e, const uint8_t *__restrict__
     const uint64_t a = off[t], b = off[t + 1];
     const uint32_t coders = p.runs < 64u ? p.runs : 64u;  // states in the stream; the other coders start (and stay) at 2^16
     if (a > b || b > e.stream_capacity || b - a < 4u * coders || b - a > e.slot_bytes || (a & 3u)) return;
-    load_table<false>(reinterpret_cast<const uint16_t *>(eblob + e.off_tables) + (width - 2u) * 256u, ftab);
+    load_table_decode(reinterpret_cast<const uint16_t *>(eblob + e.off_tables) + (width - 2u) * 256u, ftab);
     __syncthreads();
     build_slot_table(ftab, sym32);
     const uint8_t *sym = reinterpret_cast<const uint8_t *>(sym32);
