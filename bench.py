@@ -36,7 +36,7 @@ TRAFFIC = {
 # (profiles/C4_fused_valu_counts.txt), and the issue peak they are priced against: 256 CUs x 4 SIMDs x 16 lanes
 # x 2.4 GHz = 39.3e12 lane-operations per second (packed fp32 is not used, so every VALU instruction occupies
 # its SIMD for four cycles per wave of 64).
-VALU_INSTS = {("C4", "fused", 0.05): {"k_fused": 23.6e6, "k_unpack": 7.67e6}}
+VALU_INSTS = {("C4", "fused", 0.05): {"k_fused": 23.6e6, "k_unpack": 7.75e6}}
 VALU_PEAK_LANE_OPS = 256 * 4 * 16 * 2.4e9
 
 
