@@ -22,10 +22,6 @@ struct tsq_plan {
     EntropyLayout e;
     tsq_layout layout;
     int pipeline;  // resolved: TSQ_PIPE_STAGED or TSQ_PIPE_FUSED
-    // persistent grid of the fused kernel, found on the first compress call (needs the device)
-    std::once_flag fused_once;
-    uint32_t fused_grid = 0;
-    int fused_rc = 0;
 };
 
 namespace {
@@ -138,7 +134,8 @@ tsq_status tsq_plan_create(const tsq_config *cfg, tsq_plan **out) {
     p.ws_cnt = w;    w = align_up(w + 4ull * T, 256);
     p.ws_amax = w;   w = align_up(w + 4ull * T, 256);
     p.ws_sizes = w;  w = align_up(w + 4ull * T, 256);
-    p.ws_tickets = w; w = align_up(w + 4ull * 2 * kTicketClasses * kTicketStride, 256);
+    p.ws_prefix = w; w = align_up(w + 8ull * (T + 1ull), 256);
+    p.ws_tickets = w; w = align_up(w + 4ull * kTicketClasses * kTicketStride, 256);
     p.ws_ctrl = w;   w = align_up(w + 256, 256);
     L.workspace_bytes = w;
 
@@ -169,7 +166,8 @@ tsq_status tsq_plan_create(const tsq_config *cfg, tsq_plan **out) {
     pl->g.block = 64u * ((p.runs + 63u) / 64u);
     pl->g.lds_bytes = (p.runs * kRunLdsDw + kScratchDw) * 4u;
     pl->g.waves = compress_waves(p.runs);
-    pl->g.lds_fused_bytes = (p.runs * 32u + kFusedScratchDw) * 4u;   // row 16 + two images 8 dwords per run
+    // row 16 + two images 8 dwords per run, reduce areas and ticket slots, two stashes per wave
+    pl->g.lds_fused_bytes = (p.runs * 32u + kFusedScratchDw + 2u * pl->g.waves * kStashWave) * 4u;
     pl->pipeline = cfg->pipeline == TSQ_PIPE_STAGED ? TSQ_PIPE_STAGED : TSQ_PIPE_FUSED;
     *out = pl;
     return TSQ_OK;
@@ -195,21 +193,17 @@ static tsq_status ensure_prepared() {
     return hip_rc(g_prepare_rc);
 }
 
-// Grid of the fused kernel: every workgroup must be resident (they wait for each other's table
-// words), and the tokens should spread evenly over the iterations.
+// Computing workgroups of the fused kernel: as many as the device holds at once next to the scanner
+// workgroup (more would only queue up behind them), and no more than there are tokens.
 static tsq_status fused_grid(const tsq_plan *plan, uint32_t *grid) {
-    tsq_plan *pl = const_cast<tsq_plan *>(plan);
-    std::call_once(pl->fused_once, [pl] {
-        uint32_t resident = 0;
-        pl->fused_rc = fused_resident_workgroups(pl->p, pl->g, &resident);
-        if (pl->fused_rc != 0) return;
-        uint32_t gmax = resident < kFusedGridCap ? resident : kFusedGridCap;
-        if (gmax > pl->p.tokens) gmax = pl->p.tokens;
-        pl->fused_grid = gmax;
-        pl->p.fused_classes = gmax < kTicketClasses ? gmax : kTicketClasses;
-    });
-    *grid = pl->fused_grid;
-    return hip_rc(pl->fused_rc);
+    uint32_t resident = 0;
+    const int rc = fused_resident_workgroups(plan->p, plan->g, &resident);
+    if (rc != 0) return TSQ_ERR_HIP;
+    uint32_t g = resident > 1 ? resident - 1 : 1;
+    if (g > kFusedGridCap) g = kFusedGridCap;
+    if (g > plan->p.tokens) g = plan->p.tokens;
+    *grid = g;
+    return TSQ_OK;
 }
 
 tsq_status tsq_workspace_reset(const tsq_plan *plan, void *d_ws, void *stream) {
@@ -228,7 +222,7 @@ static tsq_status compress_call(const tsq_plan *plan, const void *d_in, uint32_t
         uint32_t grid = 0;
         st = fused_grid(plan, &grid);
         if (st != TSQ_OK) return st;
-        p = plan->p;                       // fused_grid fills in the ticket classes on its first call
+        p.fused_classes = grid < kTicketClasses ? grid : kTicketClasses;
         p.rows_per_tensor = rows_per_tensor;
         return hip_rc(launch_fused(p, plan->g, grid, d_in, d_blob, d_ws, stream));
     }
@@ -268,7 +262,9 @@ tsq_status tsq_compress_timed(const tsq_plan *plan, const void *d_in, void *d_bl
     if (plan->pipeline == TSQ_PIPE_FUSED) {
         uint32_t grid = 0;
         st = fused_grid(plan, &grid);
-        if (st == TSQ_OK) rc = launch_fused(plan->p, plan->g, grid, d_in, d_blob, d_ws, stream); else rc = 1;
+        Params p = plan->p;
+        p.fused_classes = grid < kTicketClasses ? grid : kTicketClasses;
+        if (st == TSQ_OK) rc = launch_fused(p, plan->g, grid, d_in, d_blob, d_ws, stream); else rc = 1;
         (void)hipEventRecord(ev[1], s);
         n = 1;
     } else {

@@ -73,15 +73,18 @@ __device__ __forceinline__ uint32_t wave_sum_u32(uint32_t v) {
     v += dpp<kDppRowMirror>(v);
     return lane_value(v, 0) + lane_value(v, 16) + lane_value(v, 32) + lane_value(v, 48);
 }
-// Inclusive prefix sum over the lanes of a wave, in lane order.
+// Inclusive prefix sum over the lanes of a wave, in lane order: four shifts inside the rows of 16
+// lanes, then the last lane of row 0 (2) is added to row 1 (3), and the last lane of row 1, by then
+// the total of rows 0 and 1, to rows 2 and 3.
+constexpr int kDppRowBcast15 = 0x142, kDppRowBcast31 = 0x143;
 __device__ __forceinline__ uint32_t wave_incl_scan_u32(uint32_t v) {
     v += dpp<kDppRowShr + 1>(v);    // lanes without a source inside their row add 0
     v += dpp<kDppRowShr + 2>(v);
     v += dpp<kDppRowShr + 4>(v);
     v += dpp<kDppRowShr + 8>(v);
-    const uint32_t r0 = lane_value(v, 15), r1 = lane_value(v, 31), r2 = lane_value(v, 47);
-    const uint32_t row = (threadIdx.x & 63) >> 4;
-    return v + (row > 0 ? r0 : 0u) + (row > 1 ? r1 : 0u) + (row > 2 ? r2 : 0u);
+    v += (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, kDppRowBcast15, 0xA, 0xF, false);
+    v += (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, kDppRowBcast31, 0xC, 0xF, false);
+    return v;
 }
 
 // Exclusive prefix sum of v over the threads of the block, in thread order.
@@ -149,11 +152,12 @@ __device__ __forceinline__ void write_row_part(uint32_t *lrow, uint32_t runs, co
 
 // ---------------------------------------------------------------- Eq. (ts) on one run
 
-// The inlier magnitudes |T_below| of a run in the form the quantizer consumes:
+// The inlier part T_below of a run in the form the quantizer consumes:
 //   bf16: 32 binary32 values;
-//   fp16: 16 dwords of packed half-precision magnitudes (the multiply reads them directly
+//   fp16: 16 dwords of packed half-precision values (the multiply reads them directly
 //         through v_fma_mix_f32).
-// Outlier slots hold 0 in both forms.
+// The values keep their sign (the multiply takes the magnitude through its source modifier, the
+// packing takes the sign bit from here), outlier slots hold +0 in both forms.
 template <int DT> struct Mags;
 template <> struct Mags<kBF16> { float v[32]; };
 template <> struct Mags<kF16> { uint32_t v[16]; };
@@ -168,6 +172,13 @@ __device__ __forceinline__ float masked_low_half_as_bf16(uint32_t w, uint32_t in
         : "v"(w), "v"(inl));
     return __uint_as_float(d);
 }
+// max(|a|, |b|, c) of binary32 values in one instruction; c >= 0.  For finite values the order of the
+// magnitudes is the order of their bit patterns, so the result is the pattern of the largest magnitude.
+__device__ __forceinline__ uint32_t max3_magnitude(float a, float b, uint32_t c) {
+    uint32_t d;
+    asm("v_max3_f32 %0, |%1|, |%2|, %3" : "=v"(d) : "v"(a), "v"(b), "v"(c));
+    return d;
+}
 // Any boolean function of three words in one instruction (v_bitop3_b32): bit i of the result is bit
 // (4 a_i + 2 b_i + c_i) of TABLE, i.e. TABLE is the function applied to a = 0xF0, b = 0xCC, c = 0xAA.
 // On gfx950 it issues at the rate of a plain and / or (twice the rate of v_and_or_b32, v_or3_b32, v_bfi_b32).
@@ -177,6 +188,8 @@ __device__ __forceinline__ uint32_t bitop3(uint32_t a, uint32_t b, uint32_t c) {
 }
 constexpr int kAndOr = (0xF0 & 0xCC) | 0xAA;            // (a & b) | c
 constexpr int kSelect = (0xF0 & 0xCC) | (~0xF0 & 0xAA & 0xFF);   // a ? b : c, bit by bit
+constexpr int kOrAnd = (0xF0 | 0xCC) & 0xAA;            // (a | b) & c
+constexpr int kAnd3 = 0xF0 & 0xCC & 0xAA;               // a & b & c
 
 // bits `sel` of keep into old
 __device__ __forceinline__ uint32_t bit_insert(uint32_t sel, uint32_t keep, uint32_t old) {
@@ -188,12 +201,12 @@ __device__ __forceinline__ uint32_t bit_insert(uint32_t sel, uint32_t keep, uint
 // and NaN lie above every finite one, so
 //   !(|x| < tau)  <=>  (pattern & 0x7FFF) >= thr,
 // thr being the smallest pattern whose value is >= tau (computed on the host).
-//   mg        : |T_below| of the run (see Mags)
+//   mg        : T_below of the run (see Mags)
 //   omask     : outlier flags in column order, bit j = element j
 //   amax_bits : binary32 bit pattern of the largest inlier magnitude of the run (only if WANT_MAX)
 // Per pair of elements: and, subtract, packed arithmetic shift, bit-field insert into the flags;
-// then bf16: two masked widenings and one three-way max (7 instructions), fp16: one and and one
-// packed max (6).  The subtract is a plain 32-bit one (it issues at twice the rate of the packed
+// then bf16: two masked widenings and one three-way max (7 instructions), fp16: two ands and one
+// packed max (7).  The subtract is a plain 32-bit one (it issues at twice the rate of the packed
 // 16-bit form): with g = thr + 0x7FFF = (thr - 1) | 0x8000 in both halves, g - pattern leaves in
 // each half 0x8000 + (thr - 1 - pattern), which is never negative (pattern <= 0x7FFF, thr >= 1),
 // so nothing is borrowed from the upper half, and whose bit 15 is set exactly for the inliers.
@@ -206,19 +219,16 @@ __device__ __forceinline__ void split_regs(const uint32_t (&w)[16], uint32_t thr
     uint32_t im_a = 0, im_b = 0;           // inlier flags of the pairs 0-7 / 8-15, collected bit by bit
     const uint32_t guard_pk = thr_pk + 0x7FFF7FFFu;
     if constexpr (DT == kBF16) {
-        uint32_t mx = 0;                   // non-negative binary32 patterns order like unsigned integers
+        uint32_t mx = 0;
 #pragma unroll
         for (int i = 0; i < 16; ++i) {
             const uint32_t absw = w[i] & 0x7FFF7FFFu;
             const uint32_t inl = pk_ashr15_i16(guard_pk - absw);  // 0xFFFF where |x| < tau
-            const float lo = masked_low_half_as_bf16(absw, inl);
-            const uint32_t hi = absw & inl & 0xFFFF0000u;
+            const float lo = masked_low_half_as_bf16(w[i], inl);
+            const float hi = __uint_as_float(bitop3<kAnd3>(w[i], inl, 0xFFFF0000u));
             mg.v[2 * i] = lo;
-            mg.v[2 * i + 1] = __uint_as_float(hi);
-            if (WANT_MAX) {
-                const uint32_t l = __float_as_uint(lo), t = l > hi ? l : hi;
-                mx = t > mx ? t : mx;                                      // v_max3_u32
-            }
+            mg.v[2 * i + 1] = hi;
+            if (WANT_MAX) mx = max3_magnitude(lo, hi, mx);
             if (i < 8) im_a = bit_insert(0x00020001u << (2 * i), inl, im_a);
             else im_b = bit_insert(0x00020001u << (2 * (i - 8)), inl, im_b);
         }
@@ -229,9 +239,8 @@ __device__ __forceinline__ void split_regs(const uint32_t (&w)[16], uint32_t thr
         for (int i = 0; i < 16; ++i) {
             const uint32_t absw = w[i] & 0x7FFF7FFFu;
             const uint32_t inl = pk_ashr15_i16(guard_pk - absw);
-            const uint32_t a = absw & inl;
-            mg.v[i] = a;
-            if (WANT_MAX) mx = pk_max_u16(mx, a);
+            mg.v[i] = w[i] & inl;
+            if (WANT_MAX) mx = pk_max_u16(mx, absw & inl);
             if (i < 8) im_a = bit_insert(0x00020001u << (2 * i), inl, im_a);
             else im_b = bit_insert(0x00020001u << (2 * (i - 8)), inl, im_b);
         }
@@ -302,20 +311,20 @@ __device__ __forceinline__ float widen16(uint32_t pattern) {
 
 // ---------------------------------------------------------------- Eq. (Proposed) on one run
 
-// fl(a * r) for the low / high half-precision value of a packed pair: v_fma_mix_f32 widens the
+// fl(|a| * r) for the low / high half-precision value of a packed pair: v_fma_mix_f32 widens the
 // half exactly and rounds the product once, which is the binary32 product of the widened value.
 __device__ __forceinline__ float mul_f16_lo(uint32_t pk, float r) {
     float d;
-    asm("v_fma_mix_f32 %0, %1, %2, 0 op_sel_hi:[1,0,0]" : "=v"(d) : "v"(pk), "v"(r));
+    asm("v_fma_mix_f32 %0, |%1|, %2, 0 op_sel_hi:[1,0,0]" : "=v"(d) : "v"(pk), "v"(r));
     return d;
 }
 __device__ __forceinline__ float mul_f16_hi(uint32_t pk, float r) {
     float d;
-    asm("v_fma_mix_f32 %0, %1, %2, 0 op_sel:[1,0,0] op_sel_hi:[1,0,0]" : "=v"(d) : "v"(pk), "v"(r));
+    asm("v_fma_mix_f32 %0, |%1|, %2, 0 op_sel:[1,0,0] op_sel_hi:[1,0,0]" : "=v"(d) : "v"(pk), "v"(r));
     return d;
 }
 
-// m = rint(a * r), one byte per element, element 4g+k in byte k of m[g]: one multiply and one
+// m = rint(|a| * r), one byte per element, element 4g+k in byte k of m[g]: one multiply and one
 // convert per element.  The rounding is done by v_cvt_pk_u8_f32 itself, which converts with
 // round-to-nearest-even (checked on gfx950 on exact halves 0.5, 1.5, 2.5, ... and pinned by the
 // tie rows of the parity tests) and saturates at 255.  A clamp min(., Q) to the code range never
@@ -329,7 +338,7 @@ __device__ __forceinline__ void quantize_run(const Mags<DT> &mg, float r, uint32
         if constexpr (DT == kBF16) {
 #pragma unroll
             for (int k = 0; k < 4; ++k)
-                acc = __builtin_amdgcn_cvt_pk_u8_f32(mg.v[4 * g + k] * r, k, acc);
+                acc = __builtin_amdgcn_cvt_pk_u8_f32(__builtin_fabsf(mg.v[4 * g + k]) * r, k, acc);
         } else {
             acc = __builtin_amdgcn_cvt_pk_u8_f32(mul_f16_lo(mg.v[2 * g], r), 0, acc);
             acc = __builtin_amdgcn_cvt_pk_u8_f32(mul_f16_hi(mg.v[2 * g], r), 1, acc);
@@ -375,21 +384,39 @@ __device__ __forceinline__ float level_count(uint32_t width) { return (float)((1
 
 // ---------------------------------------------------------------- bit packing of one run
 
-// out[0..B) = the run's 32 codes, LSB first.  m: magnitude bytes; w: the run's
-// raw input dwords (sign bits).  The sign is dropped where the magnitude is 0.
-template <int B>
-__device__ __forceinline__ void pack_regs(const uint32_t (&m)[8], const uint32_t (&w)[16], uint32_t (&out)[B]) {
+// The sign bits of elements 4g .. 4g+3 in bit 7 of bytes 0 .. 3 (the other bits are whatever the
+// top bytes of the values hold), and-ed with `keep`.
+template <int DT>
+__device__ __forceinline__ uint32_t sign_bytes_and(const Mags<DT> &mg, int g, uint32_t keep) {
+    if constexpr (DT == kBF16) {
+        // the top byte of two binary32 values per v_perm_b32: bytes 0, 1 from the first pair, 2, 3 from the second
+        const uint32_t p01 = __builtin_amdgcn_perm(__float_as_uint(mg.v[4 * g + 1]), __float_as_uint(mg.v[4 * g]), 0x0c0c0703u);
+        const uint32_t p23 = __builtin_amdgcn_perm(__float_as_uint(mg.v[4 * g + 3]), __float_as_uint(mg.v[4 * g + 2]), 0x07030c0cu);
+        return bitop3<kOrAnd>(p01, p23, keep);
+    } else {
+        // byte k <- high byte of element 4g+k
+        return __builtin_amdgcn_perm(mg.v[2 * g + 1], mg.v[2 * g], 0x07050301u) & keep;
+    }
+}
+
+// out[0..B) = the run's 32 codes, LSB first.  m: magnitude bytes; mg: the run's T_below (sign
+// bits).  The sign is dropped where the magnitude is 0.
+template <int B, int DT>
+__device__ __forceinline__ void pack_regs(const uint32_t (&m)[8], const Mags<DT> &mg, uint32_t (&out)[B]) {
     constexpr uint32_t K = (1u << (B - 1)) - 1u;
     uint64_t acc = 0;
     int filled = 0, od = 0;
 #pragma unroll
     for (int g = 0; g < 8; ++g) {
-        const uint32_t mg = m[g];
-        // byte k <- high byte of element 4g+k (bit 7 of it is the sign)
-        const uint32_t sg = __builtin_amdgcn_perm(w[2 * g + 1], w[2 * g], 0x07050301u);
-        const uint32_t sgb = (B == 8) ? sg : (sg >> (8 - B));            // sign now at bit B-1 of each byte
-        const uint32_t nzb = mg + K * 0x01010101u;                       // bit B-1 of each byte: m > 0
-        const uint32_t code = mg | (sgb & nzb & (0x01010101u << (B - 1)));
+        const uint32_t mb = m[g];
+        const uint32_t nzb = mb + K * 0x01010101u;                       // bit B-1 of each byte: m > 0
+        uint32_t code;
+        if (B == 8) {
+            code = bitop3<kAndOr>(sign_bytes_and<DT>(mg, g, nzb), 0x80808080u, mb);
+        } else {
+            const uint32_t sg = sign_bytes_and<DT>(mg, g, 0x80808080u) >> (8 - B);   // sign now at bit B-1 of each byte
+            code = bitop3<kAndOr>(sg, nzb, mb);
+        }
         uint32_t chunk;
         if (B == 8) {
             chunk = code;
@@ -410,14 +437,7 @@ __device__ __forceinline__ void pack_regs(const uint32_t (&m)[8], const uint32_t
     }
 }
 
-template <int B>
-__device__ __forceinline__ void pack_run(const uint32_t (&m)[8], const uint32_t *lrun, uint32_t (&out)[B]) {
-    uint32_t w[16];
-    load_run_padded(lrun, w);
-    pack_regs<B>(m, w, out);
-}
-
-// Inverse of pack_run followed by Eq. (dequnt) for the inliers: 32 codes ->
+// Inverse of pack_regs followed by Eq. (dequnt) for the inliers: 32 codes ->
 // 16 dwords of 16-bit values sign * (m * s), rounded to nearest even.
 template <int DT>
 __device__ __forceinline__ uint32_t narrow2(float lo, float hi) {
@@ -463,27 +483,43 @@ __device__ __forceinline__ bool token_in_range(const Params &p, uint32_t b, uint
 
 // ---------------------------------------------------------------- Algorithm 1 for the token of this block
 
-struct Choice {
-    uint32_t width;  // b_t
-    float amax;      // inlier absmax
-    uint32_t cnt;    // outliers in the token
+struct RowStats {
+    float amax;           // inlier absmax of the token
+    uint32_t cnt;         // outliers in the token
+    uint32_t cnt_before;  // ... in the waves before this one
+    uint32_t cnt_wave;    // ... in this wave
 };
+struct Choice {
+    uint32_t width;       // b_t
+    float scale;          // s_t = amax / Q_{b_t} (0 for a row coded as zeros)
+};
+
+// Workgroup barrier that orders LDS accesses only (what the cross-wave reductions need): a wave
+// does not wait for its outstanding device-memory operations here, in particular not for a row
+// that is on its way into LDS.
+__device__ __forceinline__ void lds_barrier() {
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup", "local");
+    __builtin_amdgcn_s_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup", "local");
+}
 
 // ---- block collectives for NW waves (known at compile time) ----
 // A reduce area is 2*kMaxWaves dwords; slot w = wave w's first value, kMaxWaves + w its second.
 // The caller rotates over four areas, so a wave that is one barrier ahead never overwrites
 // values another wave still has to read.
 
-// max of mx, sum of sm over the block; pre = sum of sm over the waves before this one
+// max of mx, sum of sm over the block; pre = sum of sm over the waves before this one, own = over this wave
 template <int NW>
-__device__ __forceinline__ void block_max_sum_prefix(uint32_t &mx, uint32_t &sm, uint32_t &pre, uint32_t *red) {
+__device__ __forceinline__ void block_max_sum_prefix(uint32_t &mx, uint32_t &sm, uint32_t &pre, uint32_t &own,
+                                                     uint32_t *red) {
     mx = wave_max_u32(mx);
     sm = wave_sum_u32(sm);
+    own = sm;
     pre = 0;
     if (NW == 1) return;
     const uint32_t lane = threadIdx.x & 63, wv = threadIdx.x >> 6;
     if (lane == 0) { red[wv] = mx; red[kMaxWaves + wv] = sm; }
-    __syncthreads();
+    lds_barrier();
     uint32_t M = 0, S = 0, P = 0;
 #pragma unroll
     for (int w = 0; w < NW; ++w) {
@@ -501,7 +537,7 @@ __device__ __forceinline__ void block_sum2_nw(uint32_t &x, uint32_t &y, uint32_t
     if (NW == 1) return;
     const uint32_t lane = threadIdx.x & 63, wv = threadIdx.x >> 6;
     if (lane == 0) { red[wv] = x; red[kMaxWaves + wv] = y; }
-    __syncthreads();
+    lds_barrier();
     uint32_t X = 0, Y = 0;
 #pragma unroll
     for (int w = 0; w < NW; ++w) { X += red[w]; Y += red[kMaxWaves + w]; }
@@ -513,34 +549,77 @@ __device__ __forceinline__ void block_sum1_nw(uint32_t &x, uint32_t *red) {
     if (NW == 1) return;
     const uint32_t lane = threadIdx.x & 63, wv = threadIdx.x >> 6;
     if (lane == 0) red[wv] = x;
-    __syncthreads();
+    lds_barrier();
     uint32_t X = 0;
 #pragma unroll
     for (int w = 0; w < NW; ++w) X += red[w];
     x = uniform(X);
 }
 
-// Algorithm 1 for the token of this block.  ring: four reduce areas; turn: running count of
-// reductions; live: false for lanes that own no run (they compute on a copy of run 0 and are
-// left out of every sum).  On return m holds the magnitude bytes of the run at the chosen width
-// and cnt_before the outliers of the token in the waves before this one.
-template <int DT, int NW>
-__device__ __forceinline__ Choice choose_width(const Params &p, const Mags<DT> &af, uint32_t omask,
-                                                  uint32_t amax_bits, bool live, uint32_t *ring, uint32_t &turn,
-                                                  uint32_t (&m)[8], uint32_t &cnt_before) {
-    uint32_t mx = live ? amax_bits : 0u;  // non-negative binary32 patterns order like unsigned integers
-    uint32_t cnt = live ? (uint32_t)__builtin_popcount(omask) : 0u;
-    block_max_sum_prefix<NW>(mx, cnt, cnt_before, ring + (turn++ & 3u) * 2 * kMaxWaves);
-    const float amax = __uint_as_float(mx);
+// Inlier absmax and outlier count of the token of this block (one barrier).  ring: four reduce
+// areas; turn: running count of reductions; lanes that own no run pass omask = 0, amax_bits = 0.
+template <int NW>
+__device__ __forceinline__ RowStats reduce_row_stats(uint32_t omask, uint32_t amax_bits, uint32_t *ring,
+                                                     uint32_t &turn) {
+    uint32_t mx = amax_bits;              // non-negative binary32 patterns order like unsigned integers
+    uint32_t cnt = (uint32_t)__builtin_popcount(omask);
+    RowStats st;
+    block_max_sum_prefix<NW>(mx, cnt, st.cnt_before, st.cnt_wave, ring + (turn++ & 3u) * 2 * kMaxWaves);
+    st.amax = __uint_as_float(mx);
+    st.cnt = cnt;
+    return st;
+}
 
+// The same with the wave's outlier count already summed by the caller.
+template <int NW>
+__device__ __forceinline__ RowStats reduce_row_stats_counted(uint32_t amax_bits, uint32_t cnt_wave, uint32_t *ring,
+                                                             uint32_t &turn) {
+    RowStats st;
+    uint32_t mx = wave_max_u32(amax_bits), cnt = cnt_wave, before = 0;
+    if (NW > 1) {
+        uint32_t *red = ring + (turn++ & 3u) * 2 * kMaxWaves;
+        const uint32_t lane = threadIdx.x & 63, wv = threadIdx.x >> 6;
+        if (lane == 0) { red[wv] = mx; red[kMaxWaves + wv] = cnt_wave; }
+        lds_barrier();
+        uint32_t M = 0, S = 0, P = 0;
+#pragma unroll
+        for (int w = 0; w < NW; ++w) {
+            const uint32_t a = red[w], b = red[kMaxWaves + w];
+            M = a > M ? a : M;
+            S += b;
+            P += (uint32_t)w < wv ? b : 0u;
+        }
+        mx = uniform(M); cnt = uniform(S); before = uniform(P);
+    } else {
+        ++turn;
+    }
+    st.amax = __uint_as_float(mx);
+    st.cnt = cnt;
+    st.cnt_before = before;
+    st.cnt_wave = cnt_wave;
+    return st;
+}
+
+// Algorithm 1 for the token of this block, given its inlier absmax.  live: false for lanes that
+// own no run (they compute on a copy of run 0 and are left out of every sum).  On return m holds
+// the magnitude bytes of the run at the chosen width.
+// The divisions of Eq. (Proposed) for all allowed widths are one division per wave: lane k < 8
+// computes Q_k / amax, lane 8 + k computes amax / Q_k (the scale, should width k be chosen).
+template <int DT, int NW>
+__device__ __forceinline__ Choice search_width(const Params &p, const Mags<DT> &af, float amax, bool live,
+                                               uint32_t *ring, uint32_t &turn, uint32_t (&m)[8]) {
     const uint32_t lane = threadIdx.x & 63;
-    float rq = 0.0f;
-    if (lane < p.n_widths && amax >= kAmaxFloor) rq = level_count(width_at(p, lane)) / amax;
+    float quot = 0.0f;
+    if ((lane & 7u) < p.n_widths && lane < 16u && amax >= kAmaxFloor) {
+        const float q = level_count(width_at(p, lane & 7u));
+        quot = lane < 8u ? q / amax : amax / q;
+    }
+    const uint32_t quot_bits = __float_as_uint(quot);
 
     const uint32_t b0 = width_at(p, 0);
     const uint32_t Q0 = (1u << (b0 - 1)) - 1u;
-    quantize_run<DT>(af, __uint_as_float(__builtin_amdgcn_readlane(__float_as_uint(rq), 0)), m);
-    uint32_t sel = b0;
+    quantize_run<DT>(af, __uint_as_float(__builtin_amdgcn_readlane(quot_bits, 0)), m);
+    uint32_t sel = b0, sel_i = 0;
     if (p.n_widths > 1) {
         uint32_t m0[8];
 #pragma unroll
@@ -549,25 +628,21 @@ __device__ __forceinline__ Choice choose_width(const Params &p, const Mags<DT> &
         for (uint32_t i = 1; i < p.n_widths; ++i) {
             const uint32_t bi = width_at(p, i);
             uint32_t mi[8];
-            quantize_run<DT>(af, __uint_as_float(__builtin_amdgcn_readlane(__float_as_uint(rq), (int)i)), mi);
+            quantize_run<DT>(af, __uint_as_float(__builtin_amdgcn_readlane(quot_bits, (int)i)), mi);
             uint32_t sad = live ? sad_run(m0, mi, b0 - bi) : 0u;
             uint32_t *red = ring + (turn++ & 3u) * 2 * kMaxWaves;
             if (i == 1) block_sum2_nw<NW>(sad, ss0, red); else block_sum1_nw<NW>(sad, red);
             if (violates(p.mode, p.budget, p.hidden, Q0, (1u << (bi - 1)) - 1u, sad, ss0)) break;
             sel = bi;
+            sel_i = i;
 #pragma unroll
             for (int g = 0; g < 8; ++g) m[g] = mi[g];
         }
     }
     Choice c;
     c.width = sel;
-    c.amax = amax;
-    c.cnt = cnt;
+    c.scale = __uint_as_float(__builtin_amdgcn_readlane(quot_bits, (int)(8u + sel_i)));
     return c;
-}
-
-__device__ __forceinline__ float scale_of(float amax, uint32_t width) {
-    return amax >= kAmaxFloor ? amax / level_count(width) : 0.0f;
 }
 
 // The 128-byte header at the start of the blob (written by one thread).

@@ -1,69 +1,105 @@
 // Single-pass compress kernel (gfx950): Eq. (ts), Algorithm 1, Eq. (Proposed), bit packing and
 // CSR emission with ONE read of the input.
 //
-// A persistent grid of G workgroups.  Workgroup g starts with token g; every further token comes
-// from a ticket counter.  The workgroups are spread over C classes (g % C), class c owns the
-// tokens t with t % C == c and hands them out in ascending order from its own counter, so that
-// no counter sees more than one atomic per C tokens (atomics on one address are slow across the
-// chip's eight dies) and a workgroup that is slowed down simply takes fewer tokens.
+// Workgroup 0 is the scanner: up to four of its waves turn the per-token sizes, as they are
+// published, into the device-wide exclusive prefix (the exclusive scan that places the
+// variable-length outputs).  Every other workgroup computes tokens.  All tokens are handed
+// out by ticket counters, so a workgroup that has not started yet holds nothing that anybody
+// waits for: any set of resident workgroups that contains workgroup 0 runs the call to its
+// end (workgroups are dispatched in index order, so workgroup 0 is the first to start).
 //
-// Placement of the variable-length outputs (payload words, CSR entries) needs the exclusive
-// prefix over all earlier tokens.  A workgroup publishes, per token, one 32-bit word (words,
-// outliers) in a per-token table.  A workgroup's tokens ascend, so it keeps the sum over the
-// tokens it has already seen and, for each new token of its own, one of its waves reads the
-// table words of the tokens in between (about G of them).  Nobody scans on behalf of the others,
-// nothing forms a serial chain, and apart from the tickets there are no atomic read-modify-write
-// operations (on this chip they cost microseconds when several dies touch one address).
+// Tickets: the computing workgroups are spread over C classes (g % C), class c owns the
+// tokens t with t % C == c and hands them out in ascending order from its own counter, so no
+// counter sees more than one atomic per C tokens (atomics on one address are slow across the
+// chip's eight dies) and a workgroup that is slowed down simply takes fewer tokens.  The
+// counter's top byte carries the call's epoch (mod 3), so the first ticket also tells the
+// workgroup which tag the tables of this call use.
 //
-// To keep the wait for slower neighbours off the critical path a token is stored almost two
-// iterations late: iteration i computes token i, publishes it, stores token i-2, and only then
-// packs token i's codes into the payload
-// image in LDS that token i-2 occupied (two images and two outlier stashes alternate).  All
-// earlier tokens were handed out before token i-2 was, so by then they have been published.  The row of iteration i+1 is fetched into
-// registers in the middle of iteration i; its ticket was requested an iteration earlier.
+// Per token a workgroup publishes one 32-bit word (tag, payload words, outliers) in a table.
+// The scanner reads the table in order, up to 1024 words per round, and for the leading run of
+// published tokens writes (tag, words before, outliers before) into a second table, and the
+// blob's pay_off / row_ptr entries on the way.  Nobody else adds anything up.  (One wave alone
+// does not keep up with 200 tokens per microsecond: its rounds are chains of dependent steps.)
 //
-// Progress: the smallest token that is not stored yet has all its predecessors published, and if
-// nobody has taken it yet, no workgroup of its class is waiting (their pending tokens would be
-// smaller); so some workgroup can always move.  Every wait is bounded by p.spin_limit anyway; an
-// expired wait marks the blob as failed (TSQ_ERR_INTERNAL) instead of hanging.
+// A token is stored two iterations after it was computed: iteration i computes token i,
+// publishes it, stores token i-2 and then packs token i's codes into the payload image in LDS
+// that token i-2 occupied (two images and two outlier stashes alternate).  By then every
+// earlier token was handed out at least two iterations ago, so its prefix is there.  Each
+// wave stores the part of the image and of the stash that it wrote itself: nothing between the
+// width search of one token and that of the next needs a workgroup barrier.  A wave with more
+// outliers than its stash holds (rare) keeps none of them and takes them from the row again
+// when the token is stored.
 //
-// Per-call state: table words carry a 2-bit tag of the call (epoch % 3 + 1), so a word of an
-// earlier call is never taken for a current one; the ticket counters exist in two banks
-// (epoch & 1).  The workgroup that stores the last token waits until every workgroup has
-// drawn its final (failing) ticket, clears the other bank for the next call and advances the epoch.
+// Progress: a workgroup waits (for a prefix) only after it has published its current token,
+// so the smallest unpublished token is always being computed by somebody who is not waiting;
+// the scanner waits for publications only.  Every wait is bounded by p.spin_limit anyway; an
+// expired wait raises the workspace's error word, which ends every other wait quickly, and the
+// scanner then writes status TSQ_ERR_INTERNAL.  The scanner alone writes the header.
+//
+// End of a call: every wave adds one to its class's count of finished waves; the scanner waits
+// for all of them, writes the totals and the header, and puts the counters into the state the
+// next call expects (next epoch, no tickets drawn).
 #include <hip/hip_runtime.h>
+
+#include <mutex>
 
 #include "tsq_device.hpp"
 #include "tsq_internal.hpp"
 
 namespace tsq {
 
-enum { kCtlEpoch = 0, kCtlError = 1 };
+enum { kCtlError = 1 };
 constexpr uint32_t kNoToken = 0xFFFFFFFFu;
+constexpr uint32_t kTicketBits = 24, kTicketMask = (1u << kTicketBits) - 1u;
+enum { kCntTickets = 0, kCntDone = 1 };      // words of a class's counter line
 
-// Table word: bits 31..30 = tag of the call (0 = never written), bits 29..16 = payload words of
-// the token (<= 8192), bits 15..0 = its outliers (<= 32768).
+// Table word: bits 31..30 = tag of the call (0 = never written), bits 29..26 = width of the token,
+// bits 15..0 = its outliers (<= 32768).
+// Prefix word: bits 63..62 = tag, bits 61..32 = payload words before the token, bits 31..0 =
+// outliers before the token.
 __device__ __forceinline__ uint32_t word_load(const uint32_t *p) {
     return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
 __device__ __forceinline__ void word_store(uint32_t *p, uint32_t v) {
     __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
+__device__ __forceinline__ uint64_t prefix_load(const uint64_t *p) {
+    return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ __forceinline__ void prefix_store(uint64_t *p, uint64_t v) {
+    __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+// A zero the compiler knows nothing about, in a vector register: an address formed with it is
+// not provably the same in every lane, so loads and atomics through it stay vector operations
+// that go to memory (a provably uniform one may become a scalar load, or a wave-wide reduction
+// whose result is waited for on the spot).
+__device__ __forceinline__ uint32_t opaque_zero() {
+    uint32_t zero = 0;
+    asm volatile("" : "+v"(zero));
+    return zero;
+}
 
-// One more round of a bounded wait: false when the limit is reached or another workgroup has
-// already given up (checked now and then, so that a broken run ends quickly everywhere).
+// One more round of a bounded wait: false when the limit is reached or somebody has already
+// given up (checked now and then, so that a broken run ends quickly everywhere).
 __device__ __forceinline__ bool keep_waiting(uint32_t &spins, uint32_t limit, const uint32_t *error_flag) {
     if (++spins >= limit) return false;
     if ((spins & 255u) == 0 && __hip_atomic_load(error_flag, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT)) return false;
     __builtin_amdgcn_s_sleep(2);
     return true;
 }
+__device__ __forceinline__ void raise_error(uint32_t *error_flag) {
+    // with its result: the atomic has been performed when the wave goes on
+    const uint32_t old = __hip_atomic_fetch_or(error_flag, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    asm volatile("" ::"v"(old));
+}
 
-struct __attribute__((packed, aligned(4))) Dw4 { uint32_t a, b, c, d; };   // 16 bytes at a 4-byte aligned address
-
-// ---- the row in LDS, fused kernel: 16 dwords per run, no padding.  The four 16-byte chunks of
-// run r are stored in the order k ^ ((r >> 1) & 3), which spreads eight neighbouring runs over
-// all 32 banks for 16-byte accesses. ----
+// ---- the row in LDS: 16 dwords per run, no padding.  The four 16-byte chunks of run r are
+// stored in the order k ^ ((r >> 1) & 3), which spreads eight neighbouring runs over all 32
+// banks for 16-byte accesses.  Every wave moves, reads and overwrites only the 4 KB of the row
+// that its own lanes own (runs 64w .. 64w+63), so the row needs no workgroup barrier.
+// (A row loaded straight into LDS, without the registers in between, does not pay here: the
+// compiler makes every later LDS access of the wave wait for such a load, the reductions of
+// the width search included.) ----
 template <bool FULL>
 __device__ __forceinline__ void write_row_part_sw(uint32_t *lrow, uint32_t runs, const RowPart &pre) {
     const uint32_t lane = threadIdx.x & 63u, wv = threadIdx.x >> 6;
@@ -113,177 +149,243 @@ __device__ __forceinline__ void put_codes(uint32_t *dst, const uint32_t (&o)[8],
             if ((uint32_t)k < nd) dst[k] = o[k];
     }
 }
-template <int B, bool FULL>
-__device__ __forceinline__ void pack_to_image(const uint32_t (&m)[8], const uint32_t (&w)[16], uint32_t *dst,
-                                              uint32_t nd) {
+template <int B, int DT, bool FULL>
+__device__ __forceinline__ void pack_to_image(const uint32_t (&m)[8], const Mags<DT> &mg, uint32_t *dst, uint32_t nd) {
     uint32_t o[8];
     {
         uint32_t t[B];
-        pack_regs<B>(m, w, t);
+        pack_regs<B, DT>(m, mg, t);
 #pragma unroll
         for (int k = 0; k < B; ++k) o[k] = t[k];
     }
     put_codes<B, FULL>(dst, o, nd);
 }
 
-// ---- placement ----
-// What a workgroup knows about the tokens before one of its own.
-struct Place {
-    uint32_t done;           // tokens 0 .. done-1 are contained in base_*
-    uint32_t base_w, base_c; // their payload words / outliers
+// ---------------------------------------------------------------- the scanner (workgroup 0, one wave)
+
+constexpr uint32_t kScanWavesMax = 4;   // waves of workgroup 0 that scan
+constexpr int kScanPerWave = 4;         // groups of 64 table words per wave and round: up to 1024 tokens per round
+
+__device__ __forceinline__ uint64_t prefix_word(uint32_t tag, uint32_t ew, uint32_t ec) {
+    return ((uint64_t)((tag << 30) | ew) << 32) | ec;
+}
+
+// The scanner: R waves of workgroup 0 (this one has index wv) work in rounds.  A round looks at
+// the next 64 * 4R tokens from the frontier on, cut into groups of 64 that are dealt out to the
+// waves in turn (group k to wave k % R).  Every wave sums up its groups' leading runs of
+// published tokens (lane l of a group is its l-th token: loads and stores are contiguous over
+// the wave) and leaves their lengths and totals in LDS; after a barrier every wave knows, from
+// those, which groups are usable (all before the first incomplete one, and that one up to its
+// first gap) and what lies before each of its own, stores the prefixes of its groups, and moves
+// the frontier, which all waves keep in step without exchanging it.
+// lds: 8 + 2 * 3 * 16 dwords of LDS (workgroup 0 uses none otherwise).  waves_total: computing
+// waves of the grid, each of which reports once when it is done.
+template <int R>
+__device__ void scan_tokens(const Params &p, uint8_t *blob, uint8_t *ws, uint32_t waves_total, uint32_t *lds,
+                            uint32_t wv) {
+    constexpr int kGroups = kScanPerWave * R;
+    const uint32_t lane = threadIdx.x & 63u;
+    const uint32_t T = p.tokens, C = p.fused_classes;
+    uint32_t *ctrl = reinterpret_cast<uint32_t *>(ws + p.ws_ctrl);
+    uint32_t *sizes = reinterpret_cast<uint32_t *>(ws + p.ws_sizes);
+    uint64_t *pre = reinterpret_cast<uint64_t *>(ws + p.ws_prefix);
+    uint32_t *tickets = reinterpret_cast<uint32_t *>(ws + p.ws_tickets);
+    uint64_t *pay_off = reinterpret_cast<uint64_t *>(blob + p.off_pay_off);
+    uint64_t *row_ptr = reinterpret_cast<uint64_t *>(blob + p.off_row_ptr);
+    uint32_t *error_flag = ctrl + kCtlError;
+    __builtin_amdgcn_s_setprio(3);
+
+    const uint32_t epoch = (uniform(word_load(tickets + opaque_zero())) >> kTicketBits) % 3u;
+    const uint32_t tag = epoch + 1u, tag3 = tag << 30;
+
+    // Rows of a multiple of 32 elements (the common case) take H/32 payload words per bit of width, so
+    // that one running sum serves both outputs: count + (width << 22) summed over 64 tokens carries
+    // neither into the other (counts <= 2^15 each, widths <= 8).  Other rows get two sums.
+    const bool packed = (p.hidden & 31u) == 0;
+    const uint32_t words_per_bit = p.hidden >> 5;
+    uint32_t pos = 0, bw = 0, bc = 0, idle = 0, round = 0;
+    // wave 0 decides when to give up (its verdict travels with the round's data): a workspace that an
+    // earlier call left in its failed state (or that was never reset) stays failed
+    bool bad = wv == 0 && uniform(word_load(error_flag + opaque_zero())) != 0;
+    while (pos < T) {
+        uint32_t *lead_at = lds + 8 + (round & 1u) * 48u, *sum_at = lead_at + 16, *sum2_at = lead_at + 32;
+        uint32_t w[kScanPerWave];
+#pragma unroll
+        for (int i = 0; i < kScanPerWave; ++i) {
+            const uint32_t j = pos + 64u * (wv + (uint32_t)(R * i)) + lane;
+            w[i] = 0;                                   // past the end: not published
+            if (j < T) w[i] = word_load(sizes + j);
+        }
+        uint32_t before[kScanPerWave], before2[kScanPerWave], lead[kScanPerWave];
+#pragma unroll
+        for (int i = 0; i < kScanPerWave; ++i) {
+            const uint64_t missing = __builtin_amdgcn_ballot_w64((w[i] & 0xC0000000u) != tag3);
+            lead[i] = missing ? (uint32_t)__builtin_ctzll(missing) : 64u;     // published tokens in front of the group
+            const bool mine = lane < lead[i];
+            const uint32_t width = (w[i] >> 26) & 15u, cnt = w[i] & 0xFFFFu;
+            uint32_t total, total2 = 0;
+            if (packed) {
+                const uint32_t v = mine ? cnt | (width << 22) : 0u;
+                const uint32_t upto = wave_incl_scan_u32(v);
+                before[i] = upto - v;
+                before2[i] = 0;
+                total = lane_value(upto, 63);
+            } else {
+                const uint32_t cw = mine ? row_bytes(p.hidden, width) >> 2 : 0u, cc = mine ? cnt : 0u;
+                const uint32_t iw = wave_incl_scan_u32(cw), ic = wave_incl_scan_u32(cc);
+                before[i] = ic - cc;
+                before2[i] = iw - cw;
+                total = lane_value(ic, 63);
+                total2 = lane_value(iw, 63);
+            }
+            if (lane == 0) {
+                const uint32_t k = wv + (uint32_t)(R * i);
+                lead_at[k] = lead[i];
+                sum_at[k] = total;
+                sum2_at[k] = total2;
+            }
+        }
+        if (wv == 0 && lane == 0) lds[0] = bad ? 1u : 0u;
+        lds_barrier();
+        if (uniform(lds[0])) { bad = true; break; }
+        // ---- which groups count, and what lies before each: lane k looks at group k
+        const uint32_t gl = lane < (uint32_t)kGroups ? lead_at[lane] : 64u;
+        const uint64_t gaps = __builtin_amdgcn_ballot_w64(gl != 64u);
+        const uint32_t first_gap = gaps ? (uint32_t)__builtin_ctzll(gaps) : (uint32_t)kGroups;   // groups before it are complete
+        const bool counts = lane <= first_gap && lane < (uint32_t)kGroups;
+        // (a packed group total is taken apart here: the widths of several groups would overflow their field)
+        const uint32_t raw = counts ? sum_at[lane] : 0u;
+        const uint32_t gs = packed ? raw & 0x3FFFFFu : raw;                                 // outliers of group `lane`
+        const uint32_t gs2 = packed ? (raw >> 22) * words_per_bit : (counts ? sum2_at[lane] : 0u);   // its payload words
+        const uint32_t upto = wave_incl_scan_u32(gs), upto2 = wave_incl_scan_u32(gs2);
+        const uint32_t gone = wave_sum_u32(counts ? gl : 0u);                 // tokens the frontier moves by
+#pragma unroll
+        for (int i = 0; i < kScanPerWave; ++i) {
+            const uint32_t k = wv + (uint32_t)(R * i);
+            if (k <= first_gap && lane < lead[i]) {
+                const uint32_t gb = lane_value(upto - gs, (int)k), gb2 = lane_value(upto2 - gs2, (int)k);
+                // payload words / outliers before the lane's token
+                const uint32_t ew = bw + gb2 + (packed ? (before[i] >> 22) * words_per_bit : before2[i]);
+                const uint32_t ec = bc + gb + (packed ? before[i] & 0x3FFFFFu : before[i]);
+                const uint32_t j = pos + 64u * k + lane;
+                prefix_store(pre + j, prefix_word(tag, ew, ec));
+                pay_off[j] = (uint64_t)ew << 2;
+                row_ptr[j] = ec;
+            }
+        }
+        bw += lane_value(upto2, 63);
+        bc += lane_value(upto, 63);
+        pos += gone;
+        ++round;
+        // nothing new for a long time: wave 0 gives up for everybody
+        if (gone) idle = 0;
+        else if (wv == 0 && !keep_waiting(idle, p.spin_limit, error_flag)) bad = true;
+        else if (wv != 0) __builtin_amdgcn_s_sleep(2);
+    }
+    if (wv != 0) return;
+
+    // ---- wave 0 closes the blob
+    uint32_t spins = 0;
+    if (!bad) {
+        // every computing wave reports once, after its last store has been issued
+        for (;;) {
+            uint32_t v = 0;
+            if (lane < C) v = word_load(tickets + lane * kTicketStride + kCntDone);
+            const uint32_t done = wave_sum_u32(v);
+            if (done == waves_total) break;
+            if (!keep_waiting(spins, p.spin_limit, error_flag)) { bad = true; break; }
+        }
+    }
+    if (!bad) bad = uniform(word_load(error_flag + opaque_zero())) != 0;
+    if (bad) {
+        if (lane == 0) {
+            raise_error(error_flag);
+            write_header(p, blob, 0, 0, 6u);
+        }
+        return;
+    }
+    // the counters as the next call expects them
+    if (lane < kTicketClasses) {
+        word_store(tickets + lane * kTicketStride + kCntDone, 0u);
+        word_store(tickets + lane * kTicketStride + kCntTickets, ((epoch + 1u) % 3u) << kTicketBits);
+    }
+    if (lane == 0) {
+        row_ptr[T] = bc;
+        pay_off[T] = (uint64_t)bw << 2;
+        write_header(p, blob, bc, (uint64_t)bw << 2, (uint64_t)bc > p.outlier_capacity ? 3u : 0u);
+    }
+}
+
+// ---------------------------------------------------------------- computing workgroups
+
+// One ticket of a class counter; the caller needs the result an iteration later.
+__device__ __forceinline__ uint32_t draw_ticket(uint32_t *counter) {
+    return __hip_atomic_fetch_add(counter + opaque_zero(), 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+
+// What a wave keeps of a token between computing it and storing it (all uniform in the wave).
+struct Pending {
+    uint32_t width, cnt, words, token;
+    uint32_t parity;     // which payload image and which stash hold it
+    uint32_t cb, nw;     // outliers of the token in the waves before this one / in this wave
 };
 struct Prefix {
-    uint32_t ew, ec;         // payload words / outliers of all tokens before the token
-    uint32_t bad;            // a wait expired
+    uint32_t ew, ec;     // payload words / outliers of all tokens before the token
+    uint32_t bad;        // the wait expired
 };
 
-// Exclusive prefix of token t (t >= pl.done), in two steps so that the memory latency of the
-// table reads overlaps with other work: place_request asks for the table words of the tokens
-// pl.done .. t-1 (kEarly per thread; all waves take part), place_finish waits for those that
-// were not published yet, reads what lies beyond kEarly words per thread, and adds up.
-// area: 3*kMaxWaves dwords.  All threads of the block call both (one barrier, NW > 1).
-constexpr int kEarly = 4;
-__device__ __forceinline__ uint32_t dot_halves(uint32_t v, uint32_t sel, uint32_t acc) {
-    // v.lo * sel.lo + v.hi * sel.hi + acc in one instruction
-    return __builtin_amdgcn_udot2(__builtin_bit_cast(u16x2, v), __builtin_bit_cast(u16x2, sel), acc, false);
-}
-template <int NW>
-__device__ __forceinline__ void place_request(const uint32_t *sizes, uint32_t tag, uint32_t t, const Place &pl,
-                                              uint32_t (&v)[kEarly]) {
-#pragma unroll
-    for (int k = 0; k < kEarly; ++k) {
-        const uint32_t j = pl.done + (uint32_t)k * 64u * NW + threadIdx.x;
-        v[k] = tag << 30;                 // "published, empty" for positions past the range
-        if (j < t) v[k] = word_load(sizes + j);
-    }
-}
-template <int NW>
-__device__ __forceinline__ Prefix place_finish(const Params &p, const uint32_t *sizes, uint32_t tag, uint32_t t,
-                                               Place &pl, const uint32_t (&v)[kEarly], uint32_t *area,
-                                               uint32_t *error_flag) {
-    constexpr uint32_t kThreads = 64u * NW;
-    const uint32_t lane = threadIdx.x & 63u, wv = threadIdx.x >> 6;
-    const uint32_t tag3 = tag << 30;
-    uint32_t w[kEarly];
-    uint32_t differ = 0, bad = 0;
-#pragma unroll
-    for (int k = 0; k < kEarly; ++k) { w[k] = v[k]; differ |= w[k] ^ tag3; }
-    if (differ >> 30) {
-        // some word does not carry this call's tag yet: wait for it
-#pragma unroll
-        for (int k = 0; k < kEarly; ++k) {
-            const uint32_t j = pl.done + (uint32_t)k * kThreads + threadIdx.x;
-            uint32_t spins = 0;
-            while ((w[k] >> 30) != tag && keep_waiting(spins, p.spin_limit, error_flag)) w[k] = word_load(sizes + j);
-            if ((w[k] >> 30) != tag) { bad = 1; w[k] = tag3; }
-        }
-    }
-    // sums of the low halves (outliers) and of the high halves (tag | words): one dot product each
-    uint32_t sc = 0, sh = 0;
-#pragma unroll
-    for (int k = 0; k < kEarly; ++k) {
-        sc = dot_halves(w[k], 0x00000001u, sc);
-        sh = dot_halves(w[k], 0x00010000u, sh);
-    }
-    uint32_t sw = sh - (uint32_t)kEarly * (tag << 14);       // the tags that rode along in the high halves
-    // what lies beyond the early words (narrow workgroups, whose grid is large): four loads in flight
-    for (uint32_t j0 = pl.done + kEarly * kThreads + threadIdx.x; j0 < t; j0 += 4u * kThreads) {
-        uint32_t x[4];
-#pragma unroll
-        for (int k = 0; k < 4; ++k) {
-            const uint32_t j = j0 + (uint32_t)k * kThreads;
-            x[k] = tag3;
-            if (j < t) x[k] = word_load(sizes + j);
-        }
-#pragma unroll
-        for (int k = 0; k < 4; ++k) {
-            const uint32_t j = j0 + (uint32_t)k * kThreads;
-            uint32_t spins = 0;
-            while ((x[k] >> 30) != tag && keep_waiting(spins, p.spin_limit, error_flag)) x[k] = word_load(sizes + j);
-            if ((x[k] >> 30) != tag) { bad = 1; x[k] = 0; }
-            sw += (x[k] >> 16) & 0x3FFFu;
-            sc += x[k] & 0xFFFFu;
-        }
-    }
-
-    uint32_t r0 = wave_sum_u32(sw), r1 = wave_sum_u32(sc);
-    uint32_t r2 = __builtin_amdgcn_ballot_w64(bad != 0) != 0 ? 1u : 0u;
-    if (r2 && lane == 0) __hip_atomic_fetch_or(error_flag, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-    if (NW > 1) {
-        if (lane == 0) { area[wv] = r0; area[kMaxWaves + wv] = r1; area[2 * kMaxWaves + wv] = r2; }
-        __syncthreads();
-        uint32_t a0 = 0, a1 = 0, a2 = 0;
-#pragma unroll
-        for (int w = 0; w < NW; ++w) { a0 += area[w]; a1 += area[kMaxWaves + w]; a2 |= area[2 * kMaxWaves + w]; }
-        r0 = uniform(a0); r1 = uniform(a1); r2 = uniform(a2);
-    }
-    pl.done = t;
-    pl.base_w += r0;
-    pl.base_c += r1;
+// Waits (bounded) until the scanner has published the prefix of `token`; v is what an earlier
+// load of the entry returned.
+__device__ __forceinline__ Prefix prefix_finish(const Params &p, const uint64_t *pre, uint32_t tag, uint32_t token,
+                                                uint64_t v, uint32_t *error_flag) {
+    uint32_t spins = 0;
+    const uint64_t *at = pre + token + opaque_zero();
+    while ((uint32_t)(v >> 62) != tag && keep_waiting(spins, p.spin_limit, error_flag)) v = prefix_load(at);
     Prefix x;
-    x.ew = pl.base_w;
-    x.ec = pl.base_c;
-    x.bad = r2;
+    x.bad = (uint32_t)(v >> 62) != tag ? 1u : 0u;
+    x.ew = uniform((uint32_t)(v >> 32) & 0x3FFFFFFFu);
+    x.ec = uniform((uint32_t)v);
+    x.bad = uniform(x.bad);
     return x;
 }
 
-// One ticket of a class counter; the caller needs the result an iteration later.  The address goes
-// through a register the compiler knows nothing about (the offset is zero): an address that is
-// the same in every lane would have the atomic rewritten into a wave-wide reduction whose result
-// is read, and so waited for, on the spot.
-__device__ __forceinline__ uint32_t draw_ticket(uint32_t *counter) {
-    uint32_t zero = 0;
-    asm volatile("" : "+v"(zero));
-    return __hip_atomic_fetch_add(counter + zero, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-}
-
-// What a workgroup keeps of a token between computing it and storing it.
-struct Pending {
-    uint32_t width, cnt, words, token;
-    uint32_t parity;   // which payload image and which stash hold it
-};
-
 // Where a token's outputs go, and the LDS areas they come from.
 struct StoreTargets {
-    uint64_t *pay_off, *row_ptr;
+    const Params &p;
+    const uint16_t *in;
     uint32_t *payload;
     uint16_t *out_col, *out_val;
     const uint32_t *images, *stashes;
-    uint32_t runs;
+    uint32_t runs, pieces;
     uint64_t payload_words, outlier_capacity;
 };
-// What the workgroup that stores the very last token needs to close the blob.
-struct Tail {
-    uint32_t token, ew, ec, words, cnt;
-};
 
-// Stores a token whose prefix is known: the payload image LDS -> HBM (16 bytes per thread and
-// step, contiguous over the workgroup), its offsets, and (from_stash) its outliers.  The image
-// and the stash were written by all waves: a barrier lies between their writes and this call.
-// Returns false without storing anything if the payload would leave its section, whatever the
-// table said.
-template <int NW>
-__device__ __forceinline__ bool store_token(const StoreTargets &o, const Pending &q, const Prefix &x, bool from_stash,
-                                            Tail &tail) {
-    constexpr uint32_t kThreads = 64u * NW;
-    // the thread index through a register the compiler knows nothing about: the addresses derived
+// Stores this wave's part of a token whose prefix is known: its 64 runs of the payload image
+// LDS -> HBM (16 bytes per lane and step, contiguous over the wave) and its outliers from its
+// stash.  Only what the wave wrote itself is read, so no barrier lies between this call and
+// the writes.  Returns false without storing anything if the payload would leave its section,
+// whatever the tables said.
+template <int DT, int NW>
+__device__ __forceinline__ bool store_wave_part(const StoreTargets &o, const Pending &q, const Prefix &x) {
+    // the lane index through a register the compiler knows nothing about: the addresses derived
     // from it are computed here, not once before the token loop and then kept (or spilled) across it
-    uint32_t tid = threadIdx.x;
-    asm volatile("" : "+v"(tid));
+    uint32_t lane = threadIdx.x & 63u;
+    asm volatile("" : "+v"(lane));
+    const uint32_t wv = uniform(threadIdx.x >> 6);
     if ((uint64_t)x.ew + q.words > o.payload_words) return false;
-    if (tid == 0) {
-        o.pay_off[q.token] = (uint64_t)x.ew << 2;
-        o.row_ptr[q.token] = x.ec;
-    }
+    const uint32_t first = 64u * wv * q.width;                        // the wave's first dword of the image
+    const uint32_t n = q.words > first ? (q.words - first < 64u * q.width ? q.words - first : 64u * q.width) : 0u;
     // Every address below is a uniform base (x is uniform) plus a byte offset of 32 bits: the base
-    // stays in scalar registers and no thread holds a 64-bit pointer of its own.
-    const uint32_t *img = o.images + q.parity * o.runs * 8u;
-    uint8_t *dst = reinterpret_cast<uint8_t *>(o.payload + x.ew);
-    const uint32_t quads = q.words >> 2;      // at most 2 * kThreads: 8 bits x 32 elements per thread = 32 bytes
-    const __amdgpu_buffer_rsrc_t window = raw_window(dst, q.words << 2);
+    // stays in scalar registers and no lane holds a 64-bit pointer of its own.
+    // (in the image every wave's codes start at its own fixed place, whatever the width: the regions
+    // of two tokens of different widths never overlap between waves)
+    const uint32_t *img = o.images + q.parity * o.runs * 8u + wv * (64u * 8u);
+    uint8_t *dst = reinterpret_cast<uint8_t *>(o.payload + x.ew + first);
+    const uint32_t quads = n >> 2;            // at most 128: 8 bits x 32 elements per lane = 32 bytes
+    const __amdgpu_buffer_rsrc_t window = raw_window(dst, n << 2);
 #pragma unroll
     for (uint32_t r = 0; r < 2; ++r) {
-        const uint32_t i = tid + r * kThreads;
+        const uint32_t i = lane + r * 64u;
         if (i < quads) {
             // written through the L2 as it goes (the payload is what decompress reads next: it should stay
             // in the memory-side cache, which a streaming store would bypass; a plain store would leave
@@ -292,114 +394,151 @@ __device__ __forceinline__ bool store_token(const StoreTargets &o, const Pending
             store_quad_through(window, 16u * i, v);
         }
     }
-    const uint32_t rest = q.words & 3u;
-    if (tid < rest) *reinterpret_cast<uint32_t *>(dst + 4u * (4u * quads + tid)) = img[4u * quads + tid];
-    if (from_stash && q.cnt > 0 && (uint64_t)x.ec + q.cnt <= o.outlier_capacity) {
-        const uint32_t *stash = o.stashes + q.parity * kStashCap;
-        uint8_t *col = reinterpret_cast<uint8_t *>(o.out_col + x.ec), *val = reinterpret_cast<uint8_t *>(o.out_val + x.ec);
-        for (uint32_t k = tid; k < q.cnt; k += kThreads) {
-            const uint32_t e = stash[k];
-            *reinterpret_cast<uint16_t *>(col + 2u * k) = (uint16_t)(e >> 16);
-            *reinterpret_cast<uint16_t *>(val + 2u * k) = (uint16_t)e;
+    const uint32_t rest = n & 3u;
+    if (lane < rest) *reinterpret_cast<uint32_t *>(dst + 4u * (4u * quads + lane)) = img[4u * quads + lane];
+    if (q.nw > 0 && (uint64_t)x.ec + q.cnt <= o.outlier_capacity) {
+        uint8_t *col = reinterpret_cast<uint8_t *>(o.out_col + x.ec + q.cb);
+        uint8_t *val = reinterpret_cast<uint8_t *>(o.out_val + x.ec + q.cb);
+        if (q.nw <= kStashWave) {
+            const uint32_t *stash = o.stashes + (q.parity * NW + wv) * kStashWave;
+            for (uint32_t k = lane; k < q.nw; k += 64u) {
+                const uint32_t e = stash[k];
+                *reinterpret_cast<uint16_t *>(col + 2u * k) = (uint16_t)(e >> 16);
+                *reinterpret_cast<uint16_t *>(val + 2u * k) = (uint16_t)e;
+            }
+        } else {
+            // rare: more outliers than the wave's stash holds, so none was kept.  The wave reads its part
+            // of the row once more (it is two iterations old and still in the caches), splits it again
+            // and stores the outliers out of the registers, in column order.
+            const uint32_t r = 64u * wv + lane;                  // the lane's run
+            const uint32_t have = 4u * r < o.pieces ? (o.pieces - 4u * r < 4u ? o.pieces - 4u * r : 4u) : 0u;
+            const GlobalBytes src = (GlobalBytes)row_address(o.p, o.in, q.token, o.p.hidden) + 64u * r;
+            uint32_t w[16];
+#pragma unroll
+            for (uint32_t k = 0; k < 4; ++k) {
+                u32x4 v = {0u, 0u, 0u, 0u};
+                if (k < have) v = *(const __attribute__((address_space(1))) u32x4 *)(src + 16u * k);
+                w[4 * k] = v.x; w[4 * k + 1] = v.y; w[4 * k + 2] = v.z; w[4 * k + 3] = v.w;
+            }
+            Mags<DT> unused;
+            uint32_t omask = 0, amax_bits = 0;
+            split_regs<DT, false>(w, o.p.thr_pk, unused, omask, amax_bits);
+            const uint32_t nl = (uint32_t)__builtin_popcount(omask);
+            uint32_t pos = 2u * (wave_incl_scan_u32(nl) - nl);       // bytes into the wave's CSR slice
+#pragma unroll
+            for (int i = 0; i < 16; ++i) {
+                if (omask & (1u << (2 * i))) {
+                    *reinterpret_cast<uint16_t *>(col + pos) = (uint16_t)(32u * r + 2u * i);
+                    *reinterpret_cast<uint16_t *>(val + pos) = (uint16_t)w[i];
+                    pos += 2u;
+                }
+                if (omask & (2u << (2 * i))) {
+                    *reinterpret_cast<uint16_t *>(col + pos) = (uint16_t)(32u * r + 2u * i + 1u);
+                    *reinterpret_cast<uint16_t *>(val + pos) = (uint16_t)(w[i] >> 16);
+                    pos += 2u;
+                }
+            }
         }
     }
-    tail.token = q.token; tail.ew = x.ew; tail.ec = x.ec; tail.words = q.words; tail.cnt = q.cnt;
     return true;
 }
 
 // LDS map (dynamic): row: runs*16 | two payload images: runs*8 each | ring: 4 reduce areas |
-// 4 placement areas (used in rotation, like the reduce areas) | 2 ticket slots (8 dwords) | two stashes
-constexpr uint32_t kLdsRing = 4 * 2 * kMaxWaves, kLdsPlace = 3 * kMaxWaves;
-static_assert(kFusedScratchDw == kLdsRing + 4 * kLdsPlace + 8 + 2 * kStashCap, "LDS map of the fused kernel");
+// ticket slots (8 dwords) | stashes: 2 x NW x kStashWave dwords
+constexpr uint32_t kLdsRing = 4 * 2 * kMaxWaves;
+static_assert(kFusedScratchDw == kLdsRing + 8, "LDS map of the fused kernel");
+
+// Row t of the input: one tensor, or (BATCH) a device table of tensor pointers, rows_per_tensor rows each.
+template <bool BATCH>
+__device__ __forceinline__ const uint16_t *input_row(const Params &p, const uint16_t *in, uint32_t t, uint32_t hidden) {
+    if (!BATCH) return in + (size_t)t * hidden;
+    return row_address(p, in, t, hidden);
+}
 
 // FULL: the row fills the workgroup exactly (hidden == 2048 * NW), so every lane owns a whole run
 // and none of the range checks of the general case is needed.
-template <int DT, int NW, bool FULL>
+template <int DT, int NW, bool FULL, bool BATCH>
 __global__ void __launch_bounds__(64 * NW, 4)
 k_fused(const Params p, const uint16_t *__restrict__ in, uint8_t *__restrict__ blob, uint8_t *__restrict__ ws) {
     extern __shared__ __align__(16) uint32_t lds[];
-    constexpr uint32_t kThreads = 64 * NW;
+    if (blockIdx.x == 0) {
+        constexpr int kScanWaves = NW < (int)kScanWavesMax ? NW : (int)kScanWavesMax;
+        if (threadIdx.x < 64u * kScanWaves)
+            scan_tokens<kScanWaves>(p, blob, ws, (gridDim.x - 1u) * NW, lds, threadIdx.x >> 6);
+        return;
+    }
     uint32_t *lrow = lds;
     const uint32_t runs = FULL ? 64u * NW : p.runs, pieces = FULL ? 256u * NW : p.pieces;
     uint32_t *images = lds + runs * 16u;                    // packed codes of the current and the pending token
     uint32_t *ring = images + 2u * runs * 8u;
-    uint32_t *areas = ring + kLdsRing;
-    uint32_t *tslot = areas + 4 * kLdsPlace;                // next token, one slot per iteration parity
-    uint32_t *stashes = tslot + 8;                          // 2 x kStashCap dwords: col << 16 | raw value
+    uint32_t *tslot = ring + kLdsRing;                      // next token, one slot per iteration parity; first token, epoch
+    uint32_t *stashes = tslot + 8;                          // 2 x NW x kStashWave dwords: col << 16 | raw value
     const uint32_t tid = threadIdx.x, run = tid;
-    const uint32_t wg = blockIdx.x, G = gridDim.x;
+    const uint32_t wg = blockIdx.x - 1u;
+    const uint32_t wv = uniform(tid >> 6);
     const bool owns = FULL || run < runs;
     const uint32_t left = FULL ? 4u : (owns ? pieces - 4 * run : 0);   // 16-byte pieces of the lane's run inside the row
 
     uint32_t *ctrl = reinterpret_cast<uint32_t *>(ws + p.ws_ctrl);
-    const uint32_t epoch = uniform(ctrl[kCtlEpoch]);
-    const uint32_t bank = epoch & 1u, tag = epoch % 3u + 1u;
+    uint32_t *error_flag = ctrl + kCtlError;
     uint32_t *sizes = reinterpret_cast<uint32_t *>(ws + p.ws_sizes);
-    uint32_t *tickets = reinterpret_cast<uint32_t *>(ws + p.ws_tickets) + (size_t)bank * kTicketClasses * kTicketStride;
+    const uint64_t *pre = reinterpret_cast<const uint64_t *>(ws + p.ws_prefix);
 
-    // ticket class of this workgroup: class c owns the tokens t % C == c; its first Wc tokens go to
-    // its Wc workgroups without a ticket (workgroup g starts with token g)
+    // ticket class of this workgroup: class c owns the tokens t % C == c
     const uint32_t C = p.fused_classes, cls = wg % C;
-    const uint32_t n_cls = (p.tokens - cls + C - 1u) / C;   // tokens of the class
-    const uint32_t w_cls = (G - cls + C - 1u) / C;          // workgroups of the class
-    uint32_t *counter = tickets + cls * kTicketStride;
+    const uint32_t n_cls = (p.tokens - cls + C - 1u) / C;   // tokens of the class (cls < C <= G <= tokens)
+    uint32_t *counter = reinterpret_cast<uint32_t *>(ws + p.ws_tickets) + cls * kTicketStride;
 
     uint8_t *bits = blob + p.off_bits;
     float *scale = reinterpret_cast<float *>(blob + p.off_scale);
-    uint64_t *pay_off = reinterpret_cast<uint64_t *>(blob + p.off_pay_off);
-    uint64_t *row_ptr = reinterpret_cast<uint64_t *>(blob + p.off_row_ptr);
-    uint32_t *payload = reinterpret_cast<uint32_t *>(blob + p.off_payload);
     uint16_t *out_col = reinterpret_cast<uint16_t *>(blob + p.off_out_col);
     uint16_t *out_val = reinterpret_cast<uint16_t *>(blob + p.off_out_val);
-
-    // the row of the next iteration on its way HBM -> registers -> LDS (each wave its own part)
-    RowPart pre;
     const uint32_t hidden = FULL ? 2048u * NW : p.hidden;
 
-    Place pl;
-    pl.done = 0; pl.base_w = 0; pl.base_c = 0;
-    uint32_t failed = 0, turn = 0, pturn = 0;   // turn / pturn: rotation through the reduce / placement areas
+    // ---- the first ticket: this workgroup's first token
+    if (tid == 0) {
+        const uint32_t first = draw_ticket(counter);
+        const uint32_t k = first & kTicketMask;
+        tslot[2] = k < n_cls ? k * C + cls : kNoToken;
+        tslot[3] = (first >> kTicketBits) % 3u + 1u;
+    }
+    __syncthreads();
+    uint32_t t = uniform(tslot[2]);
+    const uint32_t tag = uniform(tslot[3]);
+
+    // the row of the next iteration on its way HBM -> registers -> LDS (each wave its own part)
+    RowPart pre_row;
+    if (t != kNoToken) {
+        fetch_row_part<FULL>(reinterpret_cast<const uint4 *>(input_row<BATCH>(p, in, t, hidden)), pieces, pre_row);
+        write_row_part_sw<FULL>(lrow, runs, pre_row);
+    }
+
+    uint32_t failed = 0, turn = 0;         // turn: rotation through the reduce areas
     // tokens computed but not stored yet: `young` is from the previous iteration, `old` from the one
     // before.  A token's payload image and stash are those of its iteration's parity, so `old` has
     // to leave before the current token's codes are packed into the same image.
     Pending young, old;
     bool have_young = false, have_old = false;
     young.width = 8; young.cnt = 0; young.words = 0; young.token = 0; young.parity = 0;
+    young.cb = 0; young.nw = 0;
     old = young;
-    Tail tail;
-    tail.token = kNoToken; tail.ew = tail.ec = tail.words = tail.cnt = 0;
 
-    const StoreTargets out{pay_off, row_ptr, payload, out_col, out_val, images, stashes, runs,
-                           p.payload_capacity >> 2, p.outlier_capacity};
-
-    // ---- first token: the workgroup's own id; its row; the ticket of the second token
-    uint32_t t = wg;                       // the grid never exceeds the token count
-    fetch_row_part<FULL>(reinterpret_cast<const uint4 *>(row_address(p, in, t, hidden)), pieces, pre);
-    uint32_t req = 0;                      // thread 0: the ticket in flight
-    bool requesting = true;                // uniform: a ticket is in flight
-    if (tid == 0) req = draw_ticket(counter);
-    write_row_part_sw<FULL>(lrow, runs, pre);
+    const StoreTargets out{p, in, reinterpret_cast<uint32_t *>(blob + p.off_payload), out_col, out_val, images, stashes,
+                           runs, pieces, p.payload_capacity >> 2, p.outlier_capacity};
 
     uint32_t it = 0;
     for (; t != kNoToken; ++it) {
-        // ---- the ticket requested an iteration ago: the token after this one; ask for the one after that
-        if (tid == 0) {
-            uint32_t tn = kNoToken;
-            if (requesting) {
-                const uint32_t k = w_cls + req;
-                if (k < n_cls) {
-                    tn = k * C + cls;
-                    req = draw_ticket(counter);
-                }
-            }
-            tslot[it & 1u] = tn;
-        }
+        // ---- the ticket of the token after this one: drawn now, taken after the threshold split.  A
+        //      workgroup holds one token beyond the one it works on, no more, so that the last tokens of
+        //      a call spread evenly over the workgroups.
+        uint32_t req = 0;
+        if (tid == 0) req = draw_ticket(counter);
 
-        // the table words before the older pending token: asked for now, used after the width search
-        uint32_t early[kEarly];
-        if (have_old) place_request<NW>(sizes, tag, old.token, pl, early);
+        // the prefix of the older pending token: asked for now, used after the width search
+        uint64_t early = 0;
+        if (have_old) early = prefix_load(pre + old.token + opaque_zero());
 
-        // ---- Eq. (ts) and Algorithm 1 for token t
+        // ---- Eq. (ts) for token t
         Mags<DT> mg;
         uint32_t omask = 0, amax_bits = 0;
         {
@@ -407,155 +546,104 @@ k_fused(const Params p, const uint16_t *__restrict__ in, uint8_t *__restrict__ b
             load_run_sw(lrow, owns ? run : 0u, w);
             split_regs<DT, true>(w, p.thr_pk, mg, omask, amax_bits);
         }
-        if (!owns) omask = 0;
-        uint32_t m[8], cnt_before;
-        // The width search is where the waves of a workgroup meet at barriers (one per cross-wave
-        // reduction).  A compute unit's SIMDs each hold one wave of several workgroups; with the waves
-        // of the workgroup that is in this phase preferred by the instruction arbiter, they reach
-        // each barrier together instead of each being held up by whatever its SIMD's other waves
-        // happen to do, and less time is lost waiting there (5 % of the kernel on 8192 x 8192).
-        __builtin_amdgcn_s_setprio(1);
-        const Choice c = choose_width<DT, NW>(p, mg, omask, amax_bits, owns, ring, turn, m, cnt_before);
-        __builtin_amdgcn_s_setprio(0);
-        const uint32_t tn = uniform(tslot[it & 1u]);     // written before the barrier inside choose_width
-        requesting = tn != kNoToken;
-        const uint32_t words = row_bytes(p.hidden, c.width) >> 2;
-        if (tid == 0) {
-            word_store(sizes + t, (tag << 30) | (words << 16) | c.cnt);
-            bits[t] = (uint8_t)c.width;
-            scale[t] = scale_of(c.amax, c.width);
-        }
-        // the next row starts its way from HBM now that the registers of the width search are free
-        if (tn != kNoToken)
-            fetch_row_part<FULL>(reinterpret_cast<const uint4 *>(row_address(p, in, tn, hidden)), pieces, pre);
+        if (!owns) { omask = 0; amax_bits = 0; }
 
-        // ---- store the token of two iterations ago: its image and stash are needed now
+        // outliers of the token in this wave, and before each lane
+        const uint32_t nl = (uint32_t)__builtin_popcount(omask);
+        const uint32_t upto = wave_incl_scan_u32(nl);               // outliers of the wave's lanes up to this one
+        const uint32_t cnt_wave = lane_value(upto, 63);
+        // (the ticket is taken here and not earlier: the empty statement ties its first use to a result of
+        // the split, or the wait for it would be placed right behind the draw)
+        asm volatile("" : "+v"(req) : "v"(upto));
+        if (tid == 0) {
+            const uint32_t k = req & kTicketMask;
+            tslot[it & 1u] = k < n_cls ? k * C + cls : kNoToken;      // read behind the barrier of the reduction
+        }
+
+        // ---- Algorithm 1.  The width search is where the waves of a workgroup meet at barriers (one per
+        // cross-wave reduction).  A compute unit's SIMDs each hold one wave of several workgroups; with the
+        // waves of the workgroup that is in this phase preferred by the instruction arbiter, they reach
+        // each barrier together instead of each being held up by whatever its SIMD's other waves
+        // happen to do, and less time is lost waiting there.
+        __builtin_amdgcn_s_setprio(1);
+        const RowStats st = reduce_row_stats_counted<NW>(amax_bits, cnt_wave, ring, turn);
+        const uint32_t tn = uniform(tslot[it & 1u]);
+        // The next row starts its way from HBM (into registers; it goes to LDS at the end of the
+        // iteration).  The loads are issued on every path (without a next token the current row is read
+        // again), so that the number of loads younger than the prefix load is fixed and waiting for the
+        // prefix below does not wait for the row.
+        fetch_row_part<FULL>(reinterpret_cast<const uint4 *>(input_row<BATCH>(p, in, tn != kNoToken ? tn : t, hidden)),
+                             pieces, pre_row);
+        uint32_t m[8];
+        const Choice c = search_width<DT, NW>(p, mg, st.amax, owns, ring, turn, m);
+        __builtin_amdgcn_s_setprio(0);
+        const uint32_t words = row_bytes(p.hidden, c.width) >> 2;
+        // the prefix asked for at the top: taken as late as the stores allow
+        Prefix xo;
+        xo.ew = xo.ec = xo.bad = 0;
+        if (have_old) xo = prefix_finish(p, pre, tag, old.token, early, error_flag);
+        if (tid == 0) {
+            word_store(sizes + t, (tag << 30) | (c.width << 26) | st.cnt);
+            bits[t] = (uint8_t)c.width;
+            scale[t] = c.scale;
+        }
+
+        // ---- store this wave's part of the token of two iterations ago: its image and stash are needed now
         if (have_old) {
-            const Prefix x = place_finish<NW>(p, sizes, tag, old.token, pl, early, areas + (pturn++ & 3u) * kLdsPlace,
-                                              ctrl + kCtlError);
-            failed |= x.bad;
-            if (!x.bad && !store_token<NW>(out, old, x, true, tail)) failed = 1;
+            if (xo.bad || !store_wave_part<DT, NW>(out, old, xo)) failed = 1;
             have_old = false;
-            if (NW > 1) __syncthreads();      // the image and the stash of this parity are free again
         }
 
         // ---- codes of the lane's run at the chosen width, into this iteration's payload image
         Pending cur;
-        cur.width = c.width; cur.cnt = c.cnt; cur.words = words; cur.token = t; cur.parity = it & 1u;
+        cur.width = c.width; cur.cnt = st.cnt; cur.words = words; cur.token = t; cur.parity = it & 1u;
+        cur.cb = st.cnt_before; cur.nw = cnt_wave;
         if (owns) {
-            uint32_t wr[16];
-            load_run_sw(lrow, run, wr);
-            uint32_t *dst = images + cur.parity * runs * 8u + run * c.width;
+            uint32_t *dst = images + cur.parity * runs * 8u + wv * (64u * 8u) + (run & 63u) * c.width;
             const uint32_t nd = (FULL || left >= 4) ? c.width : ((left * c.width + 3u) >> 2);
             switch (c.width) {
-                case 2: pack_to_image<2, FULL>(m, wr, dst, nd); break;
-                case 3: pack_to_image<3, FULL>(m, wr, dst, nd); break;
-                case 4: pack_to_image<4, FULL>(m, wr, dst, nd); break;
-                case 5: pack_to_image<5, FULL>(m, wr, dst, nd); break;
-                case 6: pack_to_image<6, FULL>(m, wr, dst, nd); break;
-                case 7: pack_to_image<7, FULL>(m, wr, dst, nd); break;
-                default: pack_to_image<8, FULL>(m, wr, dst, nd); break;
+                case 2: pack_to_image<2, DT, FULL>(m, mg, dst, nd); break;
+                case 3: pack_to_image<3, DT, FULL>(m, mg, dst, nd); break;
+                case 4: pack_to_image<4, DT, FULL>(m, mg, dst, nd); break;
+                case 5: pack_to_image<5, DT, FULL>(m, mg, dst, nd); break;
+                case 6: pack_to_image<6, DT, FULL>(m, mg, dst, nd); break;
+                case 7: pack_to_image<7, DT, FULL>(m, mg, dst, nd); break;
+                default: pack_to_image<8, DT, FULL>(m, mg, dst, nd); break;
             }
         }
-
-        // ---- T_above of token t: into this iteration's stash in column order, or straight out if
-        //      it is too long for the stash
-        bool placed = false;
-        if (c.cnt > 0) {
-            const uint32_t nl = (uint32_t)__builtin_popcount(omask);
-            const uint32_t loff = cnt_before + wave_incl_scan_u32(nl) - nl;
-            const bool stashed = c.cnt <= kStashCap;
-            Prefix x;
-            x.ew = x.ec = x.bad = 0;
-            bool direct_ok = false;
-            if (!stashed) {
-                // rare: more outliers than the stash holds.  Place everything that is pending, then
-                // this token, now.
-                uint32_t now[kEarly];
-                if (have_young) {
-                    place_request<NW>(sizes, tag, young.token, pl, now);
-                    const Prefix y = place_finish<NW>(p, sizes, tag, young.token, pl, now,
-                                                      areas + (pturn++ & 3u) * kLdsPlace, ctrl + kCtlError);
-                    failed |= y.bad;
-                    if (!y.bad && !store_token<NW>(out, young, y, true, tail)) failed = 1;
-                    have_young = false;
-                }
-                place_request<NW>(sizes, tag, t, pl, now);
-                x = place_finish<NW>(p, sizes, tag, t, pl, now, areas + (pturn++ & 3u) * kLdsPlace, ctrl + kCtlError);
-                failed |= x.bad;
-                direct_ok = !x.bad && (uint64_t)x.ec + c.cnt <= p.outlier_capacity;
-            }
-            if (omask && (stashed || direct_ok)) {
-                uint32_t *stash = stashes + (it & 1u) * kStashCap;
-                uint32_t pos = loff;
-                for (uint32_t rest = omask; rest; rest &= rest - 1u) {
-                    const uint32_t j = (uint32_t)__builtin_ctz(rest);
-                    const uint32_t col = run * kRun + j;
-                    if (stashed) {
-                        stash[pos] = (col << 16) | raw_element_sw(lrow, run, j);
-                    } else {
-                        out_col[(size_t)x.ec + pos] = (uint16_t)col;
-                        out_val[(size_t)x.ec + pos] = (uint16_t)raw_element_sw(lrow, run, j);
-                    }
-                    ++pos;
-                }
-            }
-            if (!stashed) {
-                if (!x.bad && !store_token<NW>(out, cur, x, false, tail)) failed = 1;
-                placed = true;
+        // ---- T_above of token t, this wave's part: into the wave's stash of this parity (free since the
+        //      store above) in column order; a wave with more outliers than its stash holds keeps
+        //      nothing (see store_wave_part)
+        if (cnt_wave > 0 && cnt_wave <= kStashWave) {
+            uint32_t *stash = stashes + ((it & 1u) * NW + wv) * kStashWave;
+            uint32_t pos = upto - nl;
+            for (uint32_t rest = omask; rest; rest &= rest - 1u) {
+                const uint32_t j = (uint32_t)__builtin_ctz(rest);
+                stash[pos++] = ((run * kRun + j) << 16) | raw_element_sw(lrow, run, j);
             }
         }
         old = young; have_old = have_young;
-        young = cur; have_young = !placed;
-
-        if (tn != kNoToken) write_row_part_sw<FULL>(lrow, runs, pre);   // this wave is done with its part of the row
+        young = cur; have_young = true;
+        if (tn != kNoToken) write_row_part_sw<FULL>(lrow, runs, pre_row);   // this wave is done with its part of the row
         t = tn;
     }
 
-    // ---- the tokens still pending, oldest first
+    // ---- the tokens still pending, oldest first (both prefixes are asked for at once)
+    uint64_t last_old = 0, last_young = 0;
+    if (have_old) last_old = prefix_load(pre + old.token + opaque_zero());
+    if (have_young) last_young = prefix_load(pre + young.token + opaque_zero());
     if (have_old) {
-        uint32_t now[kEarly];
-        place_request<NW>(sizes, tag, old.token, pl, now);
-        const Prefix x = place_finish<NW>(p, sizes, tag, old.token, pl, now, areas + (pturn++ & 3u) * kLdsPlace,
-                                          ctrl + kCtlError);
-        failed |= x.bad;
-        if (!x.bad && !store_token<NW>(out, old, x, true, tail)) failed = 1;
+        const Prefix x = prefix_finish(p, pre, tag, old.token, last_old, error_flag);
+        if (x.bad || !store_wave_part<DT, NW>(out, old, x)) failed = 1;
     }
     if (have_young) {
-        uint32_t now[kEarly];
-        place_request<NW>(sizes, tag, young.token, pl, now);
-        const Prefix x = place_finish<NW>(p, sizes, tag, young.token, pl, now, areas + (pturn++ & 3u) * kLdsPlace,
-                                          ctrl + kCtlError);
-        failed |= x.bad;
-        if (!x.bad && !store_token<NW>(out, young, x, true, tail)) failed = 1;
+        const Prefix x = prefix_finish(p, pre, tag, young.token, last_young, error_flag);
+        if (x.bad || !store_wave_part<DT, NW>(out, young, x)) failed = 1;
     }
-    if (failed && tid == 0) write_header(p, blob, 0, 0, 6u);   // the header may already be final: overwrite it
-
-    // ---- the workgroup that stored the last token closes the blob and prepares the next call
-    if (tail.token == p.tokens - 1u) {
-        const uint64_t nnz = (uint64_t)tail.ec + tail.cnt, wordsum = (uint64_t)tail.ew + tail.words;
-        // every workgroup draws exactly one failing ticket, after which all counters add up to the
-        // token count; until then somebody may not even have read the epoch yet
-        uint32_t spins = 0, drawn = 0;
-        for (;;) {
-            uint32_t v = 0;
-            if ((tid & 63u) < C) v = word_load(tickets + (tid & 63u) * kTicketStride);
-            drawn = wave_sum_u32(v);                          // C <= 64 classes: one lane each
-            if (drawn == p.tokens || !keep_waiting(spins, p.spin_limit, ctrl + kCtlError)) break;
-        }
-        const bool late = drawn != p.tokens;
-        uint32_t *tickets_next =
-            reinterpret_cast<uint32_t *>(ws + p.ws_tickets) + (size_t)(1u - bank) * kTicketClasses * kTicketStride;
-        for (uint32_t i = tid; i < kTicketClasses; i += kThreads) tickets_next[i * kTicketStride] = 0;
-        if (tid == 0) {
-            row_ptr[p.tokens] = nnz;
-            pay_off[p.tokens] = wordsum << 2;
-            const uint32_t err = failed | (late ? 1u : 0u) |
-                                 __hip_atomic_load(ctrl + kCtlError, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-            write_header(p, blob, nnz, wordsum << 2, err ? 6u : (nnz > p.outlier_capacity ? 3u : 0u));
-            __hip_atomic_store(ctrl + kCtlError, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-            __hip_atomic_store(ctrl + kCtlEpoch, epoch + 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        }
+    // ---- this wave is done
+    if ((tid & 63u) == 0) {
+        if (failed) raise_error(error_flag);
+        __hip_atomic_fetch_add(counter + kCntDone + opaque_zero(), 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     }
 }
 
@@ -565,21 +653,24 @@ static hipStream_t as_stream(void *s) { return reinterpret_cast<hipStream_t>(s);
 
 typedef void (*FusedKernel)(const Params, const uint16_t *, uint8_t *, uint8_t *);
 
-template <int DT, bool FULL>
+template <int DT, bool FULL, bool BATCH>
 static FusedKernel fused_kernel_for(uint32_t nw) {
     switch (nw) {
-        case 1: return k_fused<DT, 1, FULL>;
-        case 2: return k_fused<DT, 2, FULL>;
-        case 3: return k_fused<DT, 3, FULL>;
-        case 4: return k_fused<DT, 4, FULL>;
-        case 8: return k_fused<DT, 8, FULL>;
-        default: return k_fused<DT, 16, FULL>;
+        case 1: return k_fused<DT, 1, FULL, BATCH>;
+        case 2: return k_fused<DT, 2, FULL, BATCH>;
+        case 3: return k_fused<DT, 3, FULL, BATCH>;
+        case 4: return k_fused<DT, 4, FULL, BATCH>;
+        case 8: return k_fused<DT, 8, FULL, BATCH>;
+        default: return k_fused<DT, 16, FULL, BATCH>;
     }
 }
-
-static FusedKernel fused_kernel(uint32_t dtype, uint32_t nw, bool full) {
-    if (full) return dtype == (uint32_t)kF16 ? fused_kernel_for<kF16, true>(nw) : fused_kernel_for<kBF16, true>(nw);
-    return dtype == (uint32_t)kF16 ? fused_kernel_for<kF16, false>(nw) : fused_kernel_for<kBF16, false>(nw);
+template <int DT>
+static FusedKernel fused_kernel_dt(uint32_t nw, bool full, bool batch) {
+    if (full) return batch ? fused_kernel_for<DT, true, true>(nw) : fused_kernel_for<DT, true, false>(nw);
+    return batch ? fused_kernel_for<DT, false, true>(nw) : fused_kernel_for<DT, false, false>(nw);
+}
+static FusedKernel fused_kernel(uint32_t dtype, uint32_t nw, bool full, bool batch) {
+    return dtype == (uint32_t)kF16 ? fused_kernel_dt<kF16>(nw, full, batch) : fused_kernel_dt<kBF16>(nw, full, batch);
 }
 static bool fills_workgroup(const Params &p, const Geometry &g) { return p.hidden == 2048u * g.waves; }
 
@@ -591,37 +682,53 @@ uint32_t compress_waves(uint32_t runs) {
 }
 
 int prepare_fused_kernels() {
-    const int big = (int)(((kMaxHidden / kRun) * 32u + kFusedScratchDw) * 4);
+    const int big = (int)(((kMaxHidden / kRun) * 32u + kFusedScratchDw + 2u * kMaxWaves * kStashWave) * 4);
     static const uint32_t sizes[] = {1, 2, 3, 4, 8, 16};
     for (uint32_t dt = 0; dt < 2; ++dt)
         for (uint32_t nw : sizes)
-            for (int full = 0; full < 2; ++full) {
-                hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(fused_kernel(dt, nw, full != 0)),
+            for (int v = 0; v < 4; ++v) {
+                hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(fused_kernel(dt, nw, (v & 1) != 0, (v & 2) != 0)),
                                                    hipFuncAttributeMaxDynamicSharedMemorySize, big);
                 if (e != hipSuccess) return (int)e;
             }
     return 0;
 }
 
-// Largest grid whose workgroups are all resident at once on the current device, for this plan.
+// Workgroups of this plan's kernel that the current device holds at once.  The answer depends on
+// the device, the kernel and its LDS size only; it is looked up once per such combination.
 int fused_resident_workgroups(const Params &p, const Geometry &g, uint32_t *out) {
-    int dev = 0, cus = 0, per_cu = 0;
+    struct Entry { int dev; const void *fn; uint32_t lds; uint32_t resident; };
+    static std::mutex mutex;
+    static Entry cache[64];
+    static int used = 0;
+    int dev = 0;
     hipError_t e = hipGetDevice(&dev);
-    if (e == hipSuccess) e = hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev);
+    if (e != hipSuccess) return (int)e;
+    const void *fn = reinterpret_cast<const void *>(fused_kernel(p.dtype, g.waves, fills_workgroup(p, g), p.rows_per_tensor != 0));
+    std::lock_guard<std::mutex> lock(mutex);
+    for (int i = 0; i < used; ++i)
+        if (cache[i].dev == dev && cache[i].fn == fn && cache[i].lds == g.lds_fused_bytes) {
+            *out = cache[i].resident;
+            return 0;
+        }
+    int cus = 0, per_cu = 0;
+    e = hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev);
     if (e == hipSuccess)
-        e = hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, reinterpret_cast<const void *>(fused_kernel(p.dtype, g.waves, fills_workgroup(p, g))),
-                                                         (int)(64u * g.waves), g.lds_fused_bytes);
+        e = hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, fn, (int)(64u * g.waves), g.lds_fused_bytes);
     if (e != hipSuccess) return (int)e;
     if (per_cu < 1 || cus < 1) return (int)hipErrorInvalidConfiguration;
     *out = (uint32_t)per_cu * (uint32_t)cus;
+    if (used < 64) cache[used++] = Entry{dev, fn, g.lds_fused_bytes, *out};
     return 0;
 }
 
+// grid: computing workgroups (the scanner is added here)
 int launch_fused(const Params &p, const Geometry &g, uint32_t grid, const void *d_in, void *d_blob, void *d_ws,
                  void *stream) {
-    hipLaunchKernelGGL(fused_kernel(p.dtype, g.waves, fills_workgroup(p, g)), dim3(grid), dim3(64u * g.waves), g.lds_fused_bytes,
-                       as_stream(stream), p, static_cast<const uint16_t *>(d_in), static_cast<uint8_t *>(d_blob),
-                       static_cast<uint8_t *>(d_ws));
+    hipLaunchKernelGGL(fused_kernel(p.dtype, g.waves, fills_workgroup(p, g), p.rows_per_tensor != 0), dim3(grid + 1u),
+                       dim3(64u * g.waves),
+                       g.lds_fused_bytes, as_stream(stream), p, static_cast<const uint16_t *>(d_in),
+                       static_cast<uint8_t *>(d_blob), static_cast<uint8_t *>(d_ws));
     return (int)hipGetLastError();
 }
 
@@ -629,12 +736,13 @@ int launch_fused(const Params &p, const Geometry &g, uint32_t grid, const void *
 
 __global__ void k_ws_reset(const Params p, uint8_t *__restrict__ ws) {
     uint32_t *sizes = reinterpret_cast<uint32_t *>(ws + p.ws_sizes);
+    uint32_t *pre = reinterpret_cast<uint32_t *>(ws + p.ws_prefix);
     uint32_t *tickets = reinterpret_cast<uint32_t *>(ws + p.ws_tickets);
     uint32_t *ctrl = reinterpret_cast<uint32_t *>(ws + p.ws_ctrl);
-    const uint32_t stride = gridDim.x * blockDim.x;
-    for (uint32_t i = blockIdx.x * blockDim.x + threadIdx.x; i < p.tokens; i += stride) sizes[i] = 0;
-    for (uint32_t i = blockIdx.x * blockDim.x + threadIdx.x; i < 2u * kTicketClasses * kTicketStride; i += stride)
-        tickets[i] = 0;
+    const uint32_t stride = gridDim.x * blockDim.x, first = blockIdx.x * blockDim.x + threadIdx.x;
+    for (uint32_t i = first; i < p.tokens; i += stride) sizes[i] = 0;
+    for (uint64_t i = first; i < 2ull * (p.tokens + 1ull); i += stride) pre[i] = 0;
+    for (uint32_t i = first; i < kTicketClasses * kTicketStride; i += stride) tickets[i] = 0;
     if (blockIdx.x == 0 && threadIdx.x < 64) ctrl[threadIdx.x] = 0;
 }
 

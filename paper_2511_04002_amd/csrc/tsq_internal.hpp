@@ -18,14 +18,14 @@ constexpr int kMaxWaves = 16;   // 1024 threads per workgroup at most
 // each) and one scan area
 constexpr uint32_t kScratchDw = 4 * 2 * kMaxWaves + kMaxWaves;
 constexpr uint32_t kMaxHidden = 32768;
-// fused kernel: outliers of one token that fit an LDS stash (longer tokens take a slower path),
-// the largest persistent grid, the ticket classes (one counter each, kTicketStride dwords apart
-// so that no two share a 256-byte line), and its LDS behind the row in dwords (four reduce
-// areas, four placement areas, ticket slots, two stashes)
-constexpr uint32_t kStashCap = 512;
+// fused kernel: outliers of one token and wave that fit the wave's LDS stash (a wave with more takes
+// a slower path), the largest grid, the ticket classes (one counter line each, kTicketStride
+// dwords apart so that no two share a 256-byte line), and its LDS behind the row and the two
+// payload images in dwords (four reduce areas, ticket slots; the stashes follow: 2 per wave)
+constexpr uint32_t kStashWave = 232;
 constexpr uint32_t kFusedGridCap = 4096;
 constexpr uint32_t kTicketClasses = 64, kTicketStride = 64;
-constexpr uint32_t kFusedScratchDw = 4 * 2 * kMaxWaves + 4 * 3 * kMaxWaves + 8 + 2 * kStashCap;
+constexpr uint32_t kFusedScratchDw = 4 * 2 * kMaxWaves + 8;
 
 // 128-byte header at the start of every blob.
 struct BlobHeader {
@@ -84,9 +84,10 @@ struct Params {
     uint64_t ws_cnt;        // u32[T]  outliers per token           (staged)
     uint64_t ws_amax;       // f32[T]  inlier absmax per token      (staged)
     uint64_t ws_sizes;      // u32[T]   published (tag, words, count) of every token   (fused)
-    uint64_t ws_tickets;    // u32[2][kTicketClasses][kTicketStride] ticket counters, two banks (fused)
-    uint64_t ws_ctrl;       // u32[64]  epoch (calls completed), error flag            (fused)
-    uint32_t fused_classes; // ticket classes in use: min(kTicketClasses, grid)        (fused)
+    uint64_t ws_prefix;     // u64[T+1] (tag, words before, outliers before) of every token, from the scanner (fused)
+    uint64_t ws_tickets;    // u32[kTicketClasses][kTicketStride] per class: epoch << 24 | tickets drawn, waves done (fused)
+    uint64_t ws_ctrl;       // u32[64]  word 1: error flag                             (fused)
+    uint32_t fused_classes; // ticket classes in use: min(kTicketClasses, computing workgroups; set per call) (fused)
     uint32_t rows_per_tensor;  // 0: the rows form one contiguous tensor.  Otherwise the data pointer of a
                                // call is a device table of tensor pointers, rows_per_tensor rows each
                                // (set per call from a copy of the plan's block)

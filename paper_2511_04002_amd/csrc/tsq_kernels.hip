@@ -16,11 +16,11 @@ namespace tsq {
 
 // ---------------------------------------------------------------- payload + CSR output of one token
 
-template <int B>
-__device__ __forceinline__ void store_codes(const uint32_t (&m)[8], const uint32_t *lrun, uint32_t *dst_row,
+template <int B, int DT>
+__device__ __forceinline__ void store_codes(const uint32_t (&m)[8], const Mags<DT> &mg, uint32_t *dst_row,
                                             uint32_t run, uint32_t valid_pieces) {
     uint32_t out[B];
-    pack_run<B>(m, lrun, out);
+    pack_regs<B, DT>(m, mg, out);
     uint32_t *dst = dst_row + run * B;
     if (valid_pieces >= 4) {
 #pragma unroll
@@ -33,16 +33,17 @@ __device__ __forceinline__ void store_codes(const uint32_t (&m)[8], const uint32
     }
 }
 
-__device__ __forceinline__ void store_codes_any(uint32_t width, const uint32_t (&m)[8], const uint32_t *lrun,
+template <int DT>
+__device__ __forceinline__ void store_codes_any(uint32_t width, const uint32_t (&m)[8], const Mags<DT> &mg,
                                                 uint32_t *dst_row, uint32_t run, uint32_t valid_pieces) {
     switch (width) {
-        case 2: store_codes<2>(m, lrun, dst_row, run, valid_pieces); break;
-        case 3: store_codes<3>(m, lrun, dst_row, run, valid_pieces); break;
-        case 4: store_codes<4>(m, lrun, dst_row, run, valid_pieces); break;
-        case 5: store_codes<5>(m, lrun, dst_row, run, valid_pieces); break;
-        case 6: store_codes<6>(m, lrun, dst_row, run, valid_pieces); break;
-        case 7: store_codes<7>(m, lrun, dst_row, run, valid_pieces); break;
-        default: store_codes<8>(m, lrun, dst_row, run, valid_pieces); break;
+        case 2: store_codes<2, DT>(m, mg, dst_row, run, valid_pieces); break;
+        case 3: store_codes<3, DT>(m, mg, dst_row, run, valid_pieces); break;
+        case 4: store_codes<4, DT>(m, mg, dst_row, run, valid_pieces); break;
+        case 5: store_codes<5, DT>(m, mg, dst_row, run, valid_pieces); break;
+        case 6: store_codes<6, DT>(m, mg, dst_row, run, valid_pieces); break;
+        case 7: store_codes<7, DT>(m, mg, dst_row, run, valid_pieces); break;
+        default: store_codes<8, DT>(m, mg, dst_row, run, valid_pieces); break;
     }
 }
 
@@ -79,15 +80,17 @@ k_row_stats(const Params p, const uint16_t *__restrict__ in, uint8_t *__restrict
     write_row_part(lrow, p.runs, pre);
 
     Mags<DT> mg;
-    uint32_t omask = 0, amax_bits = 0, turn = 0, cnt_before;
+    uint32_t omask = 0, amax_bits = 0, turn = 0;
     split_run<DT, true>(lrow + (owns ? run : 0u) * kRunLdsDw, p.thr_pk, mg, omask, amax_bits);
+    if (!owns) { omask = 0; amax_bits = 0; }
     uint32_t m[8];
-    const Choice c = choose_width<DT, NW>(p, mg, omask, amax_bits, owns, ring, turn, m, cnt_before);
+    const RowStats st = reduce_row_stats<NW>(omask, amax_bits, ring, turn);
+    const Choice c = search_width<DT, NW>(p, mg, st.amax, owns, ring, turn, m);
     if (threadIdx.x == 0) {
         blob[p.off_bits + t] = (uint8_t)c.width;
-        reinterpret_cast<float *>(blob + p.off_scale)[t] = scale_of(c.amax, c.width);
-        reinterpret_cast<uint32_t *>(ws + p.ws_cnt)[t] = c.cnt;
-        reinterpret_cast<float *>(ws + p.ws_amax)[t] = c.amax;
+        reinterpret_cast<float *>(blob + p.off_scale)[t] = c.scale;
+        reinterpret_cast<uint32_t *>(ws + p.ws_cnt)[t] = st.cnt;
+        reinterpret_cast<float *>(ws + p.ws_amax)[t] = st.amax;
     }
 }
 
@@ -179,8 +182,8 @@ k_pack(const Params p, const uint16_t *__restrict__ in, uint8_t *__restrict__ bl
             uint32_t m[8];
             quantize_run<DT>(mg, r, m);
             const uint32_t left = p.pieces - 4 * run;
-            store_codes_any(width, m, lrow + run * kRunLdsDw, reinterpret_cast<uint32_t *>(blob + p.off_payload + po),
-                            run, left < 4 ? left : 4);
+            store_codes_any<DT>(width, m, mg, reinterpret_cast<uint32_t *>(blob + p.off_payload + po), run,
+                                left < 4 ? left : 4);
         }
     }
     // side stream: only tokens that fit entirely below the capacity are stored
