@@ -141,6 +141,22 @@ tsq_status tsq_compress(const tsq_plan *plan, const void *d_in, void *d_blob, vo
                         void *stream);
 
 /*
+ * tsq_compress for callers that cannot allocate device memory and have no workspace to pass:
+ * code under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  The
+ * workspace is a static device array inside the library, tsq_static_workspace_bytes() = 4 MiB
+ * per GPU the library runs on, held until the process ends.  A plan whose
+ * tsq_plan_workspace_bytes() exceeds that (about 200 000 tokens) is refused with
+ * TSQ_ERR_UNSUPPORTED before anything is enqueued.  The call allocates and frees nothing, needs no
+ * tsq_workspace_reset (it enqueues a small fill kernel ahead of the compress kernels, so any plan
+ * may follow any other), and writes the same blob as tsq_compress.  All calls on one GPU share
+ * that GPU's array: calls that overlap in time on one GPU (different streams, different threads)
+ * race; calls on one stream are safe.  Arguments, asynchrony and errors otherwise as for
+ * tsq_compress.
+ */
+tsq_status tsq_compress_static(const tsq_plan *plan, const void *d_in, void *d_blob, void *stream);
+size_t     tsq_static_workspace_bytes(void);
+
+/*
  * Measurement aid: tsq_compress with every kernel of the call bracketed by HIP
  * events on `stream`.  SYNCHRONIZES `stream`.  ms_out (host, 4 floats) receives
  * the kernels' durations in milliseconds: staged pipeline {row statistics, scan,

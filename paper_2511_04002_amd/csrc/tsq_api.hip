@@ -239,6 +239,45 @@ tsq_status tsq_compress(const tsq_plan *plan, const void *d_in, void *d_blob, vo
     return compress_call(plan, d_in, 0, d_blob, d_ws, stream);
 }
 
+// ---- tsq_compress for callers that cannot allocate: the workspace is a static device array.
+// `scratch` is a host-side stand-in for the array, not a device address: every use below goes
+// through the pointer that hipGetSymbolAddress returned for the device at hand.
+constexpr size_t kStaticWorkspaceBytes = 4u << 20;
+constexpr int kStaticMaxDevices = 64;
+static __device__ __align__(256) uint8_t scratch[kStaticWorkspaceBytes];
+static std::mutex g_static_mutex;
+static void *g_static_ws[kStaticMaxDevices];        // per device: where that device holds its copy of `scratch`
+
+// The current device's copy of the array (looked up once per device, with that device current).
+static tsq_status static_workspace(void **out) {
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess) return TSQ_ERR_HIP;
+    if (dev < 0 || dev >= kStaticMaxDevices) return TSQ_ERR_UNSUPPORTED;
+    std::lock_guard<std::mutex> lock(g_static_mutex);
+    if (!g_static_ws[dev]) {
+        void *ptr = nullptr;
+        if (hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)) != hipSuccess || !ptr) return TSQ_ERR_HIP;
+        g_static_ws[dev] = ptr;
+    }
+    *out = g_static_ws[dev];
+    return TSQ_OK;
+}
+
+size_t tsq_static_workspace_bytes(void) { return kStaticWorkspaceBytes; }
+
+tsq_status tsq_compress_static(const tsq_plan *plan, const void *d_in, void *d_blob, void *stream) {
+    if (!plan || !d_in || !d_blob) return TSQ_ERR_INVALID_ARG;
+    if (((uintptr_t)d_in & 15u) || ((uintptr_t)d_blob & 255u)) return TSQ_ERR_INVALID_ARG;
+    if (plan->layout.workspace_bytes > kStaticWorkspaceBytes) return TSQ_ERR_UNSUPPORTED;
+    void *ws = nullptr;
+    tsq_status st = static_workspace(&ws);
+    if (st != TSQ_OK) return st;
+    // the array keeps what the last call (of any plan) left in it: a small fill kernel puts the part this
+    // plan uses back into its initial state (a kernel, not a memset, so that the call can be captured)
+    if (launch_ws_reset(plan->p, ws, stream) != 0) return TSQ_ERR_HIP;
+    return compress_call(plan, d_in, 0, d_blob, ws, stream);
+}
+
 tsq_status tsq_compress_batch(const tsq_plan *plan, const void *const *d_in_ptrs, uint32_t rows_per_tensor,
                               void *d_blob, void *d_ws, void *stream) {
     if (!plan || !d_in_ptrs || !d_blob || !d_ws) return TSQ_ERR_INVALID_ARG;

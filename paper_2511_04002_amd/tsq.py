@@ -22,6 +22,7 @@ TSQ_PIPE_AUTO, TSQ_PIPE_STAGED, TSQ_PIPE_FUSED = 0, 1, 2
 
 EXPORTS = ("tsq_plan_create", "tsq_plan_destroy", "tsq_plan_layout", "tsq_plan_blob_bytes",
            "tsq_plan_workspace_bytes", "tsq_workspace_reset", "tsq_compress", "tsq_compress_timed",
+           "tsq_compress_static", "tsq_static_workspace_bytes",
            "tsq_decompress", "tsq_compress_batch", "tsq_decompress_batch",
            "tsq_code_histogram", "tsq_blob_info", "tsq_status_string",
            "tsq_entropy_blob_bytes", "tsq_entropy_workspace_bytes", "tsq_entropy_encode", "tsq_entropy_decode",
@@ -100,6 +101,10 @@ def lib():
         L.tsq_workspace_reset.argtypes = [vp, vp, vp]
         L.tsq_compress.restype = u
         L.tsq_compress.argtypes = [vp, vp, vp, vp, vp]
+        L.tsq_compress_static.restype = u
+        L.tsq_compress_static.argtypes = [vp, vp, vp, vp]
+        L.tsq_static_workspace_bytes.restype = C.c_size_t
+        L.tsq_static_workspace_bytes.argtypes = []
         L.tsq_compress_timed.restype = u
         L.tsq_compress_timed.argtypes = [vp, vp, vp, vp, vp, C.POINTER(C.c_float)]
         L.tsq_decompress.restype = u
@@ -181,6 +186,16 @@ def tsq_compress(plan: int, d_in: int, d_blob: int, d_ws: int, stream: int = 0) 
     st = lib().tsq_compress(plan, d_in, d_blob, d_ws, stream)
     if st != TSQ_OK:
         raise TsqError(st, "tsq_compress")
+
+
+def tsq_compress_static(plan: int, d_in: int, d_blob: int, stream: int = 0) -> None:
+    st = lib().tsq_compress_static(plan, d_in, d_blob, stream)
+    if st != TSQ_OK:
+        raise TsqError(st, "tsq_compress_static")
+
+
+def tsq_static_workspace_bytes() -> int:
+    return int(lib().tsq_static_workspace_bytes())
 
 
 def tsq_compress_timed(plan: int, d_in: int, d_blob: int, d_ws: int, stream: int = 0):
