@@ -365,8 +365,25 @@ struct StoreTargets {
 // stash.  Only what the wave wrote itself is read, so no barrier lies between this call and
 // the writes.  Returns false without storing anything if the payload would leave its section,
 // whatever the tables said.
+// The lane's run of a token's row, read from memory again (see the rare case in store_wave_part).
+__device__ __forceinline__ void reread_run(const StoreTargets &o, uint32_t token, uint32_t (&w)[16]) {
+    const uint32_t r = threadIdx.x;                          // the lane's run
+    const uint32_t have = 4u * r < o.pieces ? (o.pieces - 4u * r < 4u ? o.pieces - 4u * r : 4u) : 0u;
+    const GlobalBytes src = (GlobalBytes)row_address(o.p, o.in, token, o.p.hidden) + 64u * r;
+#pragma unroll
+    for (uint32_t k = 0; k < 4; ++k) {
+        u32x4 v = {0u, 0u, 0u, 0u};
+        if (k < have) v = *(const __attribute__((address_space(1))) u32x4 *)(src + 16u * k);
+        w[4 * k] = v.x; w[4 * k + 1] = v.y; w[4 * k + 2] = v.z; w[4 * k + 3] = v.w;
+    }
+}
+
+// row_in_lds: the token's row is still in the LDS row buffer (the workgroup's last token).
+// reread: the lane's run of the row as reread_run delivered it (asked for ahead of time), or null.
 template <int DT, int NW>
-__device__ __forceinline__ bool store_wave_part(const StoreTargets &o, const Pending &q, const Prefix &x) {
+__device__ __forceinline__ bool store_wave_part(const StoreTargets &o, const Pending &q, const Prefix &x,
+                                                const uint32_t *row_in_lds = nullptr,
+                                                const uint32_t (*reread)[16] = nullptr) {
     // the lane index through a register the compiler knows nothing about: the addresses derived
     // from it are computed here, not once before the token loop and then kept (or spilled) across it
     uint32_t lane = threadIdx.x & 63u;
@@ -407,18 +424,24 @@ __device__ __forceinline__ bool store_wave_part(const StoreTargets &o, const Pen
                 *reinterpret_cast<uint16_t *>(val + 2u * k) = (uint16_t)e;
             }
         } else {
-            // rare: more outliers than the wave's stash holds, so none was kept.  The wave reads its part
-            // of the row once more (it is two iterations old and still in the caches), splits it again
-            // and stores the outliers out of the registers, in column order.
+            // rare: more outliers than the wave's stash holds, so none was kept.  The wave takes its part
+            // of the row once more (from LDS if it is still there, else from memory: it is two
+            // iterations old and still in the caches), splits it again and stores the outliers out of
+            // the registers, in column order.
             const uint32_t r = 64u * wv + lane;                  // the lane's run
             const uint32_t have = 4u * r < o.pieces ? (o.pieces - 4u * r < 4u ? o.pieces - 4u * r : 4u) : 0u;
-            const GlobalBytes src = (GlobalBytes)row_address(o.p, o.in, q.token, o.p.hidden) + 64u * r;
             uint32_t w[16];
+            if (row_in_lds) {
+                load_run_sw(row_in_lds, have ? r : 0u, w);       // pieces beyond the row were written as zeros
+                if (!have) {
 #pragma unroll
-            for (uint32_t k = 0; k < 4; ++k) {
-                u32x4 v = {0u, 0u, 0u, 0u};
-                if (k < have) v = *(const __attribute__((address_space(1))) u32x4 *)(src + 16u * k);
-                w[4 * k] = v.x; w[4 * k + 1] = v.y; w[4 * k + 2] = v.z; w[4 * k + 3] = v.w;
+                    for (int k = 0; k < 16; ++k) w[k] = 0;
+                }
+            } else if (reread) {
+#pragma unroll
+                for (int k = 0; k < 16; ++k) w[k] = (*reread)[k];
+            } else {
+                reread_run(o, q.token, w);
             }
             Mags<DT> unused;
             uint32_t omask = 0, amax_bits = 0;
@@ -526,17 +549,27 @@ k_fused(const Params p, const uint16_t *__restrict__ in, uint8_t *__restrict__ b
     const StoreTargets out{p, in, reinterpret_cast<uint32_t *>(blob + p.off_payload), out_col, out_val, images, stashes,
                            runs, pieces, p.payload_capacity >> 2, p.outlier_capacity};
 
+    // The end of a call: workgroups that were dispatched later run slower (the instruction arbiter of
+    // a SIMD prefers its older waves), and whoever starts a token among the last ones keeps everybody
+    // waiting for it.  So the later half of the workgroups stops drawing tickets a little before the
+    // tokens run out (the last quarter 1.25 generations before, the third quarter half a generation
+    // before; a generation = one token per workgroup) and leaves the rest to the faster ones, which then
+    // have their compute units more to themselves.  Only for calls of at least six generations, and
+    // never for the first quarter of a class, so every token is still drawn.
+    uint32_t kmine = t != kNoToken ? (t - cls) / C : 0u;     // thread 0: the class's number of the workgroup's newest token
+    const uint32_t n_wg = gridDim.x - 1u, w_cls = (n_wg - cls + C - 1u) / C;
+    const uint32_t quarter = n_wg >= 4u * C && n_cls >= 6u * w_cls ? (4u * wg) / n_wg : 0u;
+    const uint32_t stop_margin = (w_cls * (quarter == 3u ? 5u : quarter == 2u ? 2u : 0u)) / 4u;
     uint32_t it = 0;
     for (; t != kNoToken; ++it) {
         // ---- the ticket of the token after this one: drawn now, taken after the threshold split.  A
         //      workgroup holds one token beyond the one it works on, no more, so that the last tokens of
         //      a call spread evenly over the workgroups.
         uint32_t req = 0;
-        if (tid == 0) req = draw_ticket(counter);
-
-        // the prefix of the older pending token: asked for now, used after the width search
-        uint64_t early = 0;
-        if (have_old) early = prefix_load(pre + old.token + opaque_zero());
+        if (tid == 0) {
+            if (n_cls - 1u - kmine < stop_margin) req = kTicketMask;       // leave the last tokens to the faster workgroups
+            else req = draw_ticket(counter);
+        }
 
         // ---- Eq. (ts) for token t
         Mags<DT> mg;
@@ -558,6 +591,7 @@ k_fused(const Params p, const uint16_t *__restrict__ in, uint8_t *__restrict__ b
         if (tid == 0) {
             const uint32_t k = req & kTicketMask;
             tslot[it & 1u] = k < n_cls ? k * C + cls : kNoToken;      // read behind the barrier of the reduction
+            kmine = k;
         }
 
         // ---- Algorithm 1.  The width search is where the waves of a workgroup meet at barriers (one per
@@ -568,6 +602,10 @@ k_fused(const Params p, const uint16_t *__restrict__ in, uint8_t *__restrict__ b
         __builtin_amdgcn_s_setprio(1);
         const RowStats st = reduce_row_stats_counted<NW>(amax_bits, cnt_wave, ring, turn);
         const uint32_t tn = uniform(tslot[it & 1u]);
+        // the prefix of the older pending token: asked for now (as late as it can be and still arrive
+        // behind the width search), used after the search
+        uint64_t early = 0;
+        if (have_old) early = prefix_load(pre + old.token + opaque_zero());
         // The next row starts its way from HBM (into registers; it goes to LDS at the end of the
         // iteration).  The loads are issued on every path (without a next token the current row is read
         // again), so that the number of loads younger than the prefix load is fixed and waiting for the
@@ -632,13 +670,19 @@ k_fused(const Params p, const uint16_t *__restrict__ in, uint8_t *__restrict__ b
     uint64_t last_old = 0, last_young = 0;
     if (have_old) last_old = prefix_load(pre + old.token + opaque_zero());
     if (have_young) last_young = prefix_load(pre + young.token + opaque_zero());
+    // (a wave that kept none of the older token's outliers asks for its part of that row now, not
+    // when the prefix has arrived)
+    uint32_t again[16];
+    const bool old_reread = have_old && old.nw > kStashWave;
+    if (old_reread) reread_run(out, old.token, again);
     if (have_old) {
         const Prefix x = prefix_finish(p, pre, tag, old.token, last_old, error_flag);
-        if (x.bad || !store_wave_part<DT, NW>(out, old, x)) failed = 1;
+        if (x.bad || !store_wave_part<DT, NW>(out, old, x, nullptr, old_reread ? &again : nullptr)) failed = 1;
     }
     if (have_young) {
+        // the row of the workgroup's last token was not overwritten by a next one
         const Prefix x = prefix_finish(p, pre, tag, young.token, last_young, error_flag);
-        if (x.bad || !store_wave_part<DT, NW>(out, young, x)) failed = 1;
+        if (x.bad || !store_wave_part<DT, NW>(out, young, x, lrow)) failed = 1;
     }
     // ---- this wave is done
     if ((tid & 63u) == 0) {
