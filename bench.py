@@ -21,37 +21,56 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0     # MI355X HBM3E, published peak
-
-# HBM bytes per launch from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of this command, scaled by
-# what the same counters read for a plain 128 MiB copy (profiles/C4_*_hbm_traffic.txt);
-# keyed by (workload, pipeline, eps) -> kernel -> bytes.  None where no such run was made.
-TRAFFIC = {
-    ("C4", "staged", 0.05): {"k_row_stats": 134.3e6 + 0.6e6, "k_pack": 136.6e6 + 62.7e6,
-                             "k_unpack": 67.1e6 + 134.2e6, "k_scan": 0.2e6},
-    ("C4", "fused", 0.05): {"k_fused": 135.2e6 + 64.1e6, "k_unpack": 67.1e6 + 134.2e6},
-}
-
-
-# VALU instructions per launch (wave level) from a rocprofv3 --pmc SQ_INSTS_VALU run of this command
-# (profiles/C4_fused_valu_counts.txt), and the issue peak they are priced against: 256 CUs x 4 SIMDs x 16 lanes
-# x 2.4 GHz = 39.3e12 lane-operations per second (packed fp32 is not used, so every VALU instruction occupies
-# its SIMD for four cycles per wave of 64).
-VALU_INSTS = {("C4", "fused", 0.05): {"k_fused": 23.6e6, "k_unpack": 7.75e6}}
+# the issue peak that VALU instruction counts are priced against: 256 CUs x 4 SIMDs x 16 lanes x 2.4 GHz =
+# 39.3e12 lane-operations per second (one VALU instruction occupies its SIMD for four cycles per wave of 64)
 VALU_PEAK_LANE_OPS = 256 * 4 * 16 * 2.4e9
+
+
+def kernels_sha():
+    """Fingerprint of the kernel sources: counter figures from a profile are used only for the sources they
+    were taken from."""
+    import glob
+    import hashlib
+    h = hashlib.sha256()
+    for f in sorted(glob.glob(os.path.join(ROOT, "paper_2511_04002_amd", "csrc", "*"))):
+        if f.endswith((".hip", ".hpp", ".cpp", ".h")):
+            h.update(open(f, "rb").read())
+    return h.hexdigest()[:12]
+
+
+def profile_records():
+    """Counter figures per launch from the rocprofv3 summaries under profiles/: lines of the form
+    `bench-record: workload=C4 pipeline=fused eps=0.05 kernel=k_fused hbm_bytes=1.99e8 valu_wave_insts=2.3e7
+    kernels_sha=...` that each summary ends with.  -> {(workload, pipeline, eps, kernel): {...}}"""
+    import glob
+    out = {}
+    for f in sorted(glob.glob(os.path.join(ROOT, "profiles", "*.txt"))):
+        for line in open(f):
+            if not line.startswith("bench-record:"):
+                continue
+            kv = dict(item.split("=", 1) for item in line.split()[1:])
+            key = (kv.get("workload"), kv.get("pipeline"), float(kv.get("eps", "nan")), kv.get("kernel"))
+            out.setdefault(key, {"source": os.path.basename(f)}).update(
+                {k: (float(v) if k in ("hbm_bytes", "valu_wave_insts") else v) for k, v in kv.items()
+                 if k in ("hbm_bytes", "valu_wave_insts", "kernels_sha")})
+    return out
 
 
 def parse():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=50)
-    ap.add_argument("--warmup", type=int, default=5)
+    # (the card needs a few milliseconds of work before its clocks settle: with 5 warm-up steps the same
+    # kernels read about 10 % slower)
+    ap.add_argument("--steps", type=int, default=1000)
+    ap.add_argument("--warmup", type=int, default=200)
     ap.add_argument("--workload", default="C4", choices=["C1", "C2", "C3", "C4", "C5", "KV7", "KV13"])
     ap.add_argument("--eps", type=float, default=0.05, help="error budget, relative to the row RMS")
     ap.add_argument("--pipeline", default="auto", choices=["auto", "staged", "fused"])
     ap.add_argument("--nbuf", type=int, default=0,
                     help="buffer sets rotated through (default 4; 1 for C5 and the KV workloads, whose "
                          "single set is beyond the last-level cache already)")
-    ap.add_argument("--graph", action="store_true", help="replay the timed steps as one HIP graph")
+    ap.add_argument("--graph", action="store_true",
+                    help="replay the timed steps as one HIP graph (the line reports both launch modes either way)")
     ap.add_argument("--bits", default="", help="allowed widths, e.g. 2,4,8 (default: the workload's set)")
     ap.add_argument("--tau", type=float, default=0.0, help="outlier threshold (default: the workload's)")
     ap.add_argument("--c5-seqs", type=int, default=32)
@@ -74,6 +93,23 @@ def make_input(args):
     else:
         x = synth.make(args.workload)
     return w, x
+
+
+def oracle_check(x, w, tau, bit_set, eps, sec, rows=64):
+    """The first `rows` tokens of the benchmarked blob against the oracle, bit for bit (a token's width,
+    scale, codes and outliers do not depend on the tokens behind it; its offsets are those of the prefix)."""
+    import numpy as np
+    from oracle import tsq_oracle as O
+    O.build()
+    dt = O.F16 if w.dtype == "f16" else O.BF16
+    rows = min(rows, x.shape[0])
+    c = O.compress(x[:rows], dt, tau, bit_set, eps, O.BUDGET_REL_RMS, nthreads=1)
+    ok = (np.array_equal(sec["bits"][:rows], c.bits) and
+          np.array_equal(sec["scale"][:rows].view(np.uint32), c.scale.view(np.uint32)) and
+          np.array_equal(sec["pay_off"][: rows + 1], c.pay_off) and np.array_equal(sec["row_ptr"][: rows + 1], c.row_ptr) and
+          np.array_equal(sec["payload"][: c.payload_bytes], c.payload) and
+          np.array_equal(sec["out_col"][: c.nnz], c.out_col) and np.array_equal(sec["out_val"][: c.nnz], c.out_val))
+    return {"rows": rows, "bit_exact": bool(ok)}
 
 
 def cpu_baseline(x, w, tau, bit_set, eps, rows):
@@ -101,6 +137,29 @@ def cpu_baseline(x, w, tau, bit_set, eps, rows):
             "sample": "first %d of the first %d rows of %s, best of %d passes (%.1f s in all): compress %.3f s + "
                       "decompress %.3f s, %d threads" % (rows, x.shape[0], w.name, passes, spent, best[1], best[2],
                                                           threads)}
+
+
+def copy_ceilings(tsq, torch, srcs, dsts, nbytes, stream, reps=40):
+    """What kernels that only move bytes reach on this card in this run: a plain copy (nbytes read + nbytes
+    written) and a read-only pass, over the rotating buffer sets.  -> GB/s of bytes moved."""
+    sink = torch.zeros(64, dtype=torch.int32, device="cuda")
+    ev = [torch.cuda.Event(enable_timing=True) for _ in range(3)]
+    for timed in (False, True):
+        if timed:
+            ev[0].record()
+        for i in range(reps):
+            tsq.tsq_measure_copy(dsts[i % len(dsts)].data_ptr(), srcs[i % len(srcs)].data_ptr(), nbytes, stream)
+        if timed:
+            ev[1].record()
+        for i in range(reps):
+            tsq.tsq_measure_read(srcs[i % len(srcs)].data_ptr(), nbytes, sink.data_ptr(), stream)
+        if timed:
+            ev[2].record()
+    torch.cuda.synchronize()
+    ms_copy, ms_read = ev[0].elapsed_time(ev[1]) / reps, ev[1].elapsed_time(ev[2]) / reps
+    return {"copy_GBps": 2.0 * nbytes / ms_copy / 1e6, "read_GBps": nbytes / ms_read / 1e6,
+            "copy_ms": ms_copy, "read_ms": ms_read, "bytes": nbytes,
+            "what": "tsq_measure_copy / tsq_measure_read over %d buffer sets, %d launches each" % (len(srcs), reps)}
 
 
 def main():
@@ -162,42 +221,59 @@ def main():
     torch.cuda.synchronize()
     info = plan.info(blobs[0])
     assert info.status == 0
+    # parity in the run that is timed: the head of the blob against the oracle
+    parity = None
+    if not args.no_cpu_baseline:
+        parity = oracle_check(x, w, tau, bit_set, args.eps, plan.sections(blobs[0]))
+        assert parity["bit_exact"], "the benchmarked blob differs from the oracle's"
+        for i in range(args.warmup):              # the check idled the card: warm up again
+            step(i)
+        torch.cuda.synchronize()
 
-    # the timed region: exactly K steps between two events on the stream (nothing else is enqueued
-    # in between); with --graph the K steps are captured once and replayed as one HIP graph
-    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-    graph = None
-    if args.graph:
-        side = torch.cuda.Stream()
-        side.wait_stream(torch.cuda.current_stream())
-        with torch.cuda.stream(side):
-            graph = torch.cuda.CUDAGraph()
-            with torch.cuda.graph(graph, stream=side):
-                for i in range(args.steps):
-                    step(args.warmup + i)
-        torch.cuda.current_stream().wait_stream(side)
-        graph.replay()                     # one untimed replay
-    torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    e0.record()
-    if graph is not None:
-        graph.replay()
-    else:
-        for i in range(args.steps):
-            step(args.warmup + i)
-    e1.record()
-    torch.cuda.synchronize()
-    wall = time.perf_counter() - t0
-    ms_per_step = e0.elapsed_time(e1) / args.steps
+    def timed_region(graph):
+        """Exactly K steps between two events on the stream (nothing else is enqueued in between)."""
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        e0.record()
+        if graph is not None:
+            for _ in range(args.steps // graph_steps):
+                graph.replay()
+        else:
+            for i in range(args.steps):
+                step(args.warmup + i)
+        e1.record()
+        torch.cuda.synchronize()
+        return e0.elapsed_time(e1) / args.steps, (time.perf_counter() - t0) * 1e3 / args.steps
+
+    # both launch modes: the steps enqueued one by one, and replayed from a HIP graph that holds a block of
+    # them (K is a multiple of the block); the headline is the one asked for
+    graph_steps = max(d for d in range(1, min(args.steps, 100) + 1) if args.steps % d == 0)
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph, stream=side):
+            for i in range(graph_steps):
+                step(args.warmup + i)
+    torch.cuda.current_stream().wait_stream(side)
+    for _ in range(max(1, args.warmup // graph_steps)):
+        graph.replay()                     # untimed
+    ms_graph, wall_graph = timed_region(graph)
+    for i in range(args.warmup):
+        step(i)
+    ms_stream, wall_stream = timed_region(None)
+    ms_per_step, wall = (ms_graph, wall_graph) if args.graph else (ms_stream, wall_stream)
     assert plan.info(blobs[0]).status == 0
 
     # compress / decompress split of the same steps (events between the two calls: not the headline)
-    evs = [[torch.cuda.Event(enable_timing=True) for _ in range(3)] for _ in range(args.steps)]
-    for i in range(args.steps):
+    n_split = min(args.steps, 200)
+    evs = [[torch.cuda.Event(enable_timing=True) for _ in range(3)] for _ in range(n_split)]
+    for i in range(n_split):
         step(args.warmup + i, evs[i])
     torch.cuda.synchronize()
-    ms_c = sum(e[0].elapsed_time(e[1]) for e in evs) / args.steps
-    ms_d = sum(e[1].elapsed_time(e[2]) for e in evs) / args.steps
+    ms_c = sum(e[0].elapsed_time(e[1]) for e in evs) / n_split
+    ms_d = sum(e[1].elapsed_time(e[2]) for e in evs) / n_split
 
     n = T * H
     rho = info.nnz / n
@@ -212,8 +288,8 @@ def main():
     acc = [0.0] * len(names)
     if parts:
         assert pipe == "fused", "the batch form is timed per call: with one kernel per call that is per kernel"
-        acc = [ms_c * args.steps]
-    for i in range(0 if parts else args.steps):
+        acc = [ms_c * n_split]
+    for i in range(0 if parts else n_split):
         k = (args.warmup + i) % nbuf
         ms = tsq.tsq_compress_timed(plan.handle, xs[k].data_ptr(), blobs[k].data_ptr(), ws.data_ptr(),
                                     plan._stream())
@@ -224,20 +300,31 @@ def main():
     # algorithmic bytes of each kernel: what it must read and write once
     kalg = {"k_fused": alg_c, "k_row_stats": 2 * n + 9 * T, "k_scan": 29 * T, "k_pack": alg_c,
             "k_unpack": alg_d}
-    kern = {nm: {"ms": acc[j] / args.steps, "alg_bytes": kalg[nm]} for j, nm in enumerate(names)}
+    kern = {nm: {"ms": acc[j] / n_split, "alg_bytes": kalg[nm]} for j, nm in enumerate(names)}
     kern["k_unpack"] = {"ms": ms_d, "alg_bytes": alg_d}
     for v in kern.values():
         v["GBps"] = v["alg_bytes"] / v["ms"] / 1e6
     dom = max(kern, key=lambda nm: kern[nm]["ms"])
     achieved = kern[dom]["GBps"]
-    pair_gbps = (alg_c + alg_d) / (ms_c + ms_d) / 1e6
-    traffic = TRAFFIC.get((w.name, pipe, args.eps), {}).get(dom)
-    insts = VALU_INSTS.get((w.name, pipe, args.eps), {}).get(dom)
-    valu = None
-    if insts:
-        ops = insts * 64.0 / (kern[dom]["ms"] * 1e-3)
-        valu = {"wave_instructions": insts, "achieved_lane_ops_per_s": ops, "peak_lane_ops_per_s": VALU_PEAK_LANE_OPS,
-                "frac": ops / VALU_PEAK_LANE_OPS}
+    pair_gbps = (alg_c + alg_d) / ms_per_step / 1e6
+    pair_split_gbps = (alg_c + alg_d) / (ms_c + ms_d) / 1e6
+    # counter figures: from the committed rocprofv3 summaries, and only while the kernels are the ones profiled
+    rec = profile_records().get((w.name, pipe, args.eps, dom))
+    sha = kernels_sha()
+    traffic, valu = None, None
+    if rec and rec.get("kernels_sha") == sha:
+        traffic = rec.get("hbm_bytes")
+        insts = rec.get("valu_wave_insts")
+        if insts:
+            ops = insts * 64.0 / (kern[dom]["ms"] * 1e-3)
+            valu = {"wave_instructions": insts, "achieved_lane_ops_per_s": ops, "peak_lane_ops_per_s": VALU_PEAK_LANE_OPS,
+                    "frac": ops / VALU_PEAK_LANE_OPS, "source": "profiles/" + rec["source"]}
+    # what kernels that only move bytes reach here, over the same buffers
+    if parts:
+        ceil = copy_ceilings(tsq, torch, [v[0] for v in xs], [v[0] for v in outs], parts[0].size * 2, plan._stream())
+    else:
+        ceil = copy_ceilings(tsq, torch, xs, outs, 2 * n, plan._stream())
+    copy_pair_ms = (alg_c + alg_d) / (ceil["copy_GBps"] * 1e6)      # the pair's bytes at the copy kernel's rate
 
     res = {
         "metric": "compress+decompress GB/s of split-point activations",
@@ -246,7 +333,8 @@ def main():
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": ms_per_step,
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
-        "dtype": "f32",
+        "dtype": w.dtype,              # the tensors' storage type; the arithmetic is in "arith"
+        "arith": "f32 products rounded to integer codes, integer sums, f64 budget test",
         "data": "synthetic",
         "config": {"workload": ("%s %dx%d %s" % (w.name, T, H, w.dtype)) +
                                (" as %d tensors of %d rows" % (len(parts), parts[0].shape[0]) if parts else ""),
@@ -255,12 +343,24 @@ def main():
                    "pipeline": pipe, "launch": "hip graph" if args.graph else "stream", "buffer_sets": nbuf, "mean_width": round(bbar, 3),
                    "outlier_fraction": round(rho, 6), "width_hist": list(info.width_hist),
                    "compression_ratio": round(2.0 * n / info.compressed_bytes, 3)},
+        "launch_modes": {"stream_ms_per_step": ms_stream, "hip_graph_ms_per_step": ms_graph,
+                         "graph_holds_steps": graph_steps},
+        # the bar: algorithmic bytes of compress + decompress over the timed step, against the 8 TB/s peak
+        "target": {"quantity": "roofline.pair_frac", "bar": 0.6, "met": pair_gbps / HBM_PEAK_GBS >= 0.6},
         "roofline": {"bound": "hbm", "kernel": dom, "achieved": achieved, "peak": HBM_PEAK_GBS,
                      "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS, "traffic": traffic,
-                     "compress_ms": ms_c, "decompress_ms": ms_d,
+                     "frac_is": "algorithmic bytes of the dominant kernel / its HIP-event duration / peak",
                      "pair_achieved": pair_gbps, "pair_frac": pair_gbps / HBM_PEAK_GBS,
-                     "valu_issue": valu, "kernels": kern},
-        "host_wall_ms_per_step": wall * 1e3 / args.steps,
+                     "pair_frac_is": "algorithmic bytes of compress + decompress / ms_per_step / peak",
+                     "compress_ms": ms_c, "decompress_ms": ms_d,
+                     "pair_frac_split": pair_split_gbps / HBM_PEAK_GBS,
+                     "pair_frac_split_is": "the same over compress_ms + decompress_ms, each call between events of its own",
+                     "copy_ceiling": ceil,
+                     "pair_vs_copy": copy_pair_ms / ms_per_step,
+                     "pair_vs_copy_is": "time a plain copy kernel needs for the pair's algorithmic bytes / ms_per_step",
+                     "valu_issue": valu, "kernels_sha": sha, "kernels": kern},
+        "parity_check": parity,
+        "host_wall_ms_per_step": wall,
     }
     if not args.no_cpu_baseline:
         rows = args.cpu_sample_rows or max(64, min(T, int(2.5e8 // H)))

@@ -13,7 +13,8 @@
  *
  * All pointers named d_* are DEVICE pointers on the current HIP device; every
  * other pointer is a HOST pointer.  The library allocates no device memory,
- * keeps no global state, and never synchronizes except where stated.
+ * keeps no global state (apart from the static workspace of tsq_compress_static),
+ * and never synchronizes except where stated.
  * `stream` is a hipStream_t passed as void* (NULL = the default stream).
  *
  * Errors are return codes only (no exceptions, no abort).
@@ -34,8 +35,11 @@ typedef enum {
     TSQ_ERR_UNSUPPORTED = 2,  /* valid request this build cannot run (shape limits below)       */
     TSQ_ERR_CAPACITY    = 3,  /* the outlier side stream did not fit max_outliers               */
     TSQ_ERR_HIP         = 4,  /* a HIP call or kernel launch failed                             */
-    TSQ_ERR_FORMAT      = 5,  /* the blob does not carry this library's header / this plan      */
-    TSQ_ERR_INTERNAL    = 6   /* a bounded device-side wait expired (workspace not reset?)      */
+    TSQ_ERR_FORMAT      = 5,  /* the blob does not carry this library's header / this plan, or
+                                 the workspace was not reset for this plan's shape              */
+    TSQ_ERR_INTERNAL    = 6,  /* a bounded device-side wait expired, or the workspace still
+                                 carries the failure of an earlier call                         */
+    TSQ_ERR_NO_MEMORY   = 7   /* a host allocation failed                                       */
 } tsq_status;
 
 typedef enum { TSQ_F16 = 0, TSQ_BF16 = 1 } tsq_dtype;
@@ -48,22 +52,25 @@ typedef enum {
 } tsq_budget_mode;
 
 typedef enum {
-    TSQ_PIPE_AUTO   = 0,      /* the library picks (at present: TSQ_PIPE_FUSED)                 */
+    TSQ_PIPE_AUTO   = 0,      /* the library picks: TSQ_PIPE_FUSED wherever the device can hold
+                                 two workgroups of its kernel at once, else TSQ_PIPE_STAGED     */
     TSQ_PIPE_STAGED = 1,      /* row statistics -> device-wide scan -> pack: three launches,
                                  the input is read twice                                        */
-    TSQ_PIPE_FUSED  = 2       /* one launch of a persistent grid, the input is read once;
-                                 tokens are handed out by ticket counters in the workspace and
-                                 outputs are placed through a per-token size table there.  The
-                                 grid is as large as the device can hold at once; on a device that
-                                 other kernels occupy at the same time its workgroups may not all
-                                 start, and the call then ends with TSQ_ERR_INTERNAL in the blob's
-                                 status (every device-side wait is bounded)                      */
+    TSQ_PIPE_FUSED  = 2       /* one launch, the input is read once.  Every token is handed out
+                                 by ticket counters in the workspace, so whichever workgroups
+                                 are running finish the call (none waits for one that has not
+                                 started); one workgroup scans the published sizes into the
+                                 tokens' places.  Every device-side wait is bounded: if the
+                                 workgroup that scans is kept from running for about a second,
+                                 the call ends with TSQ_ERR_INTERNAL in the blob's status      */
 } tsq_pipeline;
 
 /* Problem statement (Algorithm 1 "Require": T, Q-bar, Delta; Eq. (ts): tau). */
 typedef struct {
     uint32_t tokens;        /* T >= 1: rows of the tensor                                       */
-    uint32_t hidden;        /* H: row length; this build needs H % 8 == 0 and 8 <= H <= 32768   */
+    uint32_t hidden;        /* H: row length; this build needs H % 8 == 0 and 8 <= H <= 32768
+                               (one workgroup of at most 1024 lanes holds a row, 32 elements
+                               per lane)                                                        */
     int32_t  dtype;         /* tsq_dtype of the input and of the restored output                */
     float    tau;           /* TS threshold, 0 < tau < inf                                      */
     uint32_t bit_mask;      /* allowed widths: bit b set <=> b allowed, 2 <= b <= 8, b counts
@@ -74,7 +81,8 @@ typedef struct {
     uint64_t max_outliers;  /* capacity of the side stream in elements; 0 = tokens*hidden       */
 } tsq_config;
 
-typedef struct tsq_plan tsq_plan;   /* opaque, host memory, immutable, reusable across calls    */
+typedef struct tsq_plan tsq_plan;   /* opaque, host memory, never written after tsq_plan_create,
+                                       usable from any thread, on any device, across calls     */
 
 /*
  * Layout of a compressed blob (device memory, all little-endian, every section
@@ -109,8 +117,9 @@ typedef struct {
     uint32_t reserved;
 } tsq_info;
 
-/* Validates cfg and fixes blob layout and launch geometry.  Host only.
- * Returns INVALID_ARG / UNSUPPORTED without touching *out on failure. */
+/* Validates cfg and fixes the blob layout.  Host only.  Returns INVALID_ARG / UNSUPPORTED /
+ * NO_MEMORY without touching *out on failure.  (How many workgroups a launch gets depends on the
+ * device and is looked up at each call for the device current then.) */
 tsq_status tsq_plan_create(const tsq_config *cfg, tsq_plan **out);
 void       tsq_plan_destroy(tsq_plan *plan);
 tsq_status tsq_plan_layout(const tsq_plan *plan, tsq_layout *out);
@@ -123,7 +132,10 @@ size_t     tsq_plan_workspace_bytes(const tsq_plan *plan);
  * it that was aborted or returned TSQ_ERR_INTERNAL through tsq_blob_info; every
  * completed compress call leaves the workspace ready for the next call by
  * itself.  A workspace serves one compress call at a time (calls that overlap
- * on one workspace race), and only plans of one shape (tokens, hidden).
+ * on one workspace race), and only plans of one shape (tokens, hidden): the
+ * reset records the shape, and a compress call with a plan of another shape (or
+ * on a workspace that was never reset) touches nothing in the workspace, stores
+ * nothing but a header with status TSQ_ERR_FORMAT, and tsq_blob_info returns that.
  */
 tsq_status tsq_workspace_reset(const tsq_plan *plan, void *d_ws, void *stream);
 
@@ -157,14 +169,15 @@ tsq_status tsq_compress_static(const tsq_plan *plan, const void *d_in, void *d_b
 size_t     tsq_static_workspace_bytes(void);
 
 /*
- * Measurement aid: tsq_compress with every kernel of the call bracketed by HIP
- * events on `stream`.  SYNCHRONIZES `stream`.  ms_out (host, 4 floats) receives
- * the kernels' durations in milliseconds: staged pipeline {row statistics, scan,
- * pack, 0}; fused pipeline {fused kernel, 0, 0, 0}.  Same arguments and result
- * as tsq_compress otherwise.
+ * tsq_compress, then tsq_blob_info into *info_out: SYNCHRONIZES `stream`.  For callers that want the
+ * outcome before going on (the controller of Algorithm 2 needs the compressed size anyway).  With
+ * TSQ_PIPE_AUTO, a call whose single pass gave up (status TSQ_ERR_INTERNAL, or TSQ_ERR_FORMAT
+ * recorded by the device because of the workspace) is run once more here: the workspace is reset
+ * and the staged kernels, which wait for nothing, compress the same input into the same blob.
+ * Returns what tsq_blob_info returns for the final blob.
  */
-tsq_status tsq_compress_timed(const tsq_plan *plan, const void *d_in, void *d_blob, void *d_ws,
-                              void *stream, float *ms_out);
+tsq_status tsq_compress_blocking(const tsq_plan *plan, const void *d_in, void *d_blob, void *d_ws,
+                                 void *stream, tsq_info *info_out);
 
 /*
  * Restore (Eq. (dequnt)): d_out receives tokens*hidden 16-bit values of the
@@ -245,11 +258,22 @@ tsq_status tsq_entropy_info(const tsq_plan *plan, const void *d_eblob, tsq_entro
 
 /*
  * Reads the blob's header and widths back to the host.  SYNCHRONIZES `stream`.
- * Returns the status stored in the blob (CAPACITY / INTERNAL), FORMAT when the
- * header is not this plan's, or OK.
+ * Returns the status stored in the blob (CAPACITY / FORMAT / INTERNAL), FORMAT when
+ * the header is not this plan's (host_out->status is 0 then), or OK.
  */
 tsq_status tsq_blob_info(const tsq_plan *plan, const void *d_blob, tsq_info *host_out,
                          void *stream);
+
+/*
+ * Compressed size in bytes of the first k tokens of a blob, as a blob of k tokens would report it
+ * (tsq_info.compressed_bytes: header, 5 bytes and two offsets per token plus the closing pair, the
+ * codes before pay_off[k], 4 bytes per outlier before row_ptr[k]): what Algorithm 2 needs when it
+ * sends fewer tokens.  k (host) lists n token counts, each <= tokens; k = NULL means k = 0 .. n-1
+ * (n <= tokens + 1).  bytes_out (host) receives n sizes.  SYNCHRONIZES `stream`.  Returns as
+ * tsq_blob_info does; bytes_out is unspecified unless the result is TSQ_OK.
+ */
+tsq_status tsq_prefix_bytes(const tsq_plan *plan, const void *d_blob, const uint32_t *k, uint32_t n,
+                            uint64_t *bytes_out, void *stream);
 
 /*
  * Link model and early exit (Sec. II-D.2).  HOST-only scalar code, no GPU work; every pointer
@@ -316,6 +340,47 @@ typedef struct {
                                    tokens do not meet it)                                         */
 } tsq_exit_decision;
 tsq_status tsq_early_exit_decide(const tsq_exit_input *in, tsq_exit_decision *out);
+
+/*
+ * Algorithm 2 with its two loops: for w = 1 .. max_tokens (W-bar), for layer = 1 .. layers (L), in
+ * the printed order of steps.  The caller's callbacks stand for the forward pass and for the sizes:
+ *   compute_latency(w, layer, user)                 L_c after w tokens up to `layer`, seconds
+ *   bits(w, layer, with_kv, compressed, keep, user) what would be sent then, in bits: compressed = 0
+ *       the raw intermediate output (B_io of Eq. (if_total), cache included iff with_kv); compressed
+ *       = 1 the output through TS + TAB-Q with only the first `keep` tokens of the hidden state
+ *       (tsq_compress, then tsq_blob_info / tsq_prefix_bytes; cache included iff with_kv)
+ * Each (w, layer) is one step; the callbacks are called at every step, so sizes are measured as the
+ * tensors grow.  The walk returns at the first exit: TSQ_EXIT_COMPRESSED (the compressed output
+ * meets the deadline) or TSQ_EXIT_FEWER_TOKENS (not even without the cache: tokens are cut from the
+ * end until it does, or none is left).  When dropping the cache alone brings the latency under the
+ * deadline the printed steps do not return: the walk goes on with I_kv = 0.  If no step exits, the
+ * result is TSQ_EXIT_COMPLETED with the compressed size of the whole output.  A callback that returns
+ * a negative value or NaN ends the walk with INVALID_ARG.
+ */
+#define TSQ_EXIT_COMPLETED 4       /* all max_tokens x layers steps ran; the output is sent compressed */
+typedef double (*tsq_exit_latency_fn)(uint32_t tokens, uint32_t layer, void *user);
+typedef double (*tsq_exit_bits_fn)(uint32_t tokens, uint32_t layer, int32_t with_kv, int32_t compressed,
+                                   uint32_t keep, void *user);
+typedef struct {
+    tsq_link link;
+    double rate;                /* R*                                                             */
+    double deadline;            /* D                                                              */
+    uint32_t max_tokens;        /* W-bar                                                          */
+    uint32_t layers;            /* L >= 1                                                         */
+    tsq_exit_latency_fn compute_latency;
+    tsq_exit_bits_fn bits;
+    void *user;                 /* passed through to the callbacks                                */
+} tsq_exit_walk_input;
+typedef struct {
+    int32_t action;             /* TSQ_EXIT_COMPRESSED, TSQ_EXIT_FEWER_TOKENS or TSQ_EXIT_COMPLETED */
+    int32_t with_kv;            /* I_kv of what is sent                                           */
+    uint32_t tokens;            /* w at the exit                                                  */
+    uint32_t layer;             /* layer at the exit                                              */
+    uint32_t sent_tokens;       /* tokens of the hidden state that are sent (<= tokens)           */
+    uint32_t steps;             /* (w, layer) steps taken                                         */
+    double latency;             /* L_t of what is sent                                            */
+} tsq_exit_walk_result;
+tsq_status tsq_early_exit_walk(const tsq_exit_walk_input *in, tsq_exit_walk_result *out);
 
 const char *tsq_status_string(tsq_status s);
 

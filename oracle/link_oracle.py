@@ -12,6 +12,11 @@ TEST INFRASTRUCTURE ONLY (see tsq_oracle.py).
                        R ln(1/P_o(R)); that is what is searched for here.
   early_exit           Algorithm 2 for one (w, layer): as it is -> compressed -> without the KV cache
                        -> fewer tokens, total latency L_c(w) + L_eps (Eq. (total))
+  early_exit_walk      Algorithm 2 with its two loops (for w = 1 .. W-bar, for layer = 1 .. L), in the
+                       printed order of steps.  Readings: (a) when dropping the KV cache brings the
+                       latency under the deadline the printed steps do not return, so the walk goes on
+                       with I_kv = 0 from there; (b) "w <- w - 1" stops at zero tokens; (c) L_c of a
+                       shortened output is that of the tokens kept (as in early_exit above).
 """
 from __future__ import annotations
 
@@ -68,3 +73,31 @@ def early_exit(W, gamma, eps, rate, deadline, compute_latency, raw_bits, compres
         w -= 1
         lat = compute_latency[w] + latency(W, gamma, eps, hidden_prefix_bits[w], rate)
     return FEWER_TOKENS, 0, w, lat
+
+
+COMPLETED = 4
+
+
+def early_exit_walk(W, gamma, eps, rate, deadline, max_tokens, layers, compute_latency, bits):
+    """compute_latency(w, layer) -> seconds; bits(w, layer, with_kv, compressed, keep) -> size in bits of
+    what is sent after w tokens at `layer`: raw (compressed = 0) or through TS + TAB-Q with only the first
+    `keep` tokens of the hidden state.  -> (action, with_kv, tokens, layer, kept, latency)."""
+    ikv = 1
+    for w in range(1, max_tokens + 1):
+        for layer in range(1, layers + 1):
+            lat = compute_latency(w, layer) + latency(W, gamma, eps, bits(w, layer, ikv, 0, w), rate)
+            if lat > deadline:
+                lat = compute_latency(w, layer) + latency(W, gamma, eps, bits(w, layer, ikv, 1, w), rate)
+                if lat <= deadline:
+                    return COMPRESSED, ikv, w, layer, w, lat
+                ikv = 0
+                lat = compute_latency(w, layer) + latency(W, gamma, eps, bits(w, layer, 0, 1, w), rate)
+                if lat > deadline:
+                    keep = w
+                    while lat > deadline and keep > 0:
+                        keep -= 1
+                        lat = compute_latency(keep, layer) + latency(W, gamma, eps, bits(w, layer, 0, 1, keep), rate)
+                    return FEWER_TOKENS, 0, w, layer, keep, lat
+    w, layer = max_tokens, layers
+    lat = compute_latency(w, layer) + latency(W, gamma, eps, bits(w, layer, ikv, 1, w), rate)
+    return COMPLETED, ikv, w, layer, w, lat

@@ -8,10 +8,12 @@
 #include <cstring>
 #include <mutex>
 #include <new>
-#include <vector>
 
 #include "tsq.h"
+#include "tsq_measure.h"
+#include "tsq_ranges.h"
 #include "tsq_internal.hpp"
+#include "tsq_ranges.hpp"
 
 using namespace tsq;
 
@@ -73,6 +75,7 @@ const char *tsq_status_string(tsq_status s) {
         case TSQ_ERR_HIP: return "HIP call failed";
         case TSQ_ERR_FORMAT: return "blob does not match this plan";
         case TSQ_ERR_INTERNAL: return "device-side wait expired";
+        case TSQ_ERR_NO_MEMORY: return "host allocation failed";
     }
     return "unknown status";
 }
@@ -90,7 +93,7 @@ tsq_status tsq_plan_create(const tsq_config *cfg, tsq_plan **out) {
     if (cfg->hidden % 8 != 0 || cfg->hidden > kMaxHidden) return TSQ_ERR_UNSUPPORTED;
 
     tsq_plan *pl = new (std::nothrow) tsq_plan();
-    if (!pl) return TSQ_ERR_INVALID_ARG;
+    if (!pl) return TSQ_ERR_NO_MEMORY;
     pl->cfg = *cfg;
     const uint32_t T = cfg->tokens, H = cfg->hidden;
 
@@ -130,13 +133,15 @@ tsq_status tsq_plan_create(const tsq_config *cfg, tsq_plan **out) {
     L.off_out_val = off;   off = align_up(off + 2ull * L.outlier_capacity, 256);
     L.blob_bytes = off;
 
+    // the control block and the counters come first: they lie at the same place whatever the shape, so a
+    // kernel can tell a workspace of another shape before it touches anything that depends on the shape
     uint64_t w = 0;
+    p.ws_ctrl = w;   w = align_up(w + 256, 256);
+    p.ws_tickets = w; w = align_up(w + 4ull * kTicketClasses * kTicketStride, 256);
     p.ws_cnt = w;    w = align_up(w + 4ull * T, 256);
     p.ws_amax = w;   w = align_up(w + 4ull * T, 256);
     p.ws_sizes = w;  w = align_up(w + 4ull * T, 256);
     p.ws_prefix = w; w = align_up(w + 8ull * (T + 1ull), 256);
-    p.ws_tickets = w; w = align_up(w + 4ull * kTicketClasses * kTicketStride, 256);
-    p.ws_ctrl = w;   w = align_up(w + 256, 256);
     L.workspace_bytes = w;
 
     p.off_bits = L.off_bits; p.off_scale = L.off_scale; p.off_pay_off = L.off_pay_off;
@@ -188,7 +193,6 @@ static tsq_status ensure_prepared() {
     std::call_once(g_prepare_once, [] {
         g_prepare_rc = prepare_kernels();
         if (g_prepare_rc == 0) g_prepare_rc = prepare_fused_kernels();
-        if (g_prepare_rc == 0) g_prepare_rc = prepare_rans_kernels();
     });
     return hip_rc(g_prepare_rc);
 }
@@ -199,7 +203,7 @@ static tsq_status fused_grid(const tsq_plan *plan, uint32_t *grid) {
     uint32_t resident = 0;
     const int rc = fused_resident_workgroups(plan->p, plan->g, &resident);
     if (rc != 0) return TSQ_ERR_HIP;
-    uint32_t g = resident > 1 ? resident - 1 : 1;
+    uint32_t g = resident > 1 ? resident - 1 : 0;       // 0: scanner and computing workgroup do not both fit
     if (g > kFusedGridCap) g = kFusedGridCap;
     if (g > plan->p.tokens) g = plan->p.tokens;
     *grid = g;
@@ -214,19 +218,23 @@ tsq_status tsq_workspace_reset(const tsq_plan *plan, void *d_ws, void *stream) {
 // One compress call.  rows_per_tensor == 0: d_in is the tensor; otherwise d_in is a device table of
 // tensor pointers (the kernels pick the row's tensor from it).
 static tsq_status compress_call(const tsq_plan *plan, const void *d_in, uint32_t rows_per_tensor, void *d_blob,
-                                void *d_ws, void *stream) {
+                                void *d_ws, void *stream, bool force_staged = false) {
     tsq_status st = ensure_prepared();
     if (st != TSQ_OK) return st;
     Params p = plan->p;
-    if (plan->pipeline == TSQ_PIPE_FUSED) {
+    p.rows_per_tensor = rows_per_tensor;
+    if (plan->pipeline == TSQ_PIPE_FUSED && !force_staged) {
         uint32_t grid = 0;
         st = fused_grid(plan, &grid);
-        if (st != TSQ_OK) return st;
-        p.fused_classes = grid < kTicketClasses ? grid : kTicketClasses;
-        p.rows_per_tensor = rows_per_tensor;
-        return hip_rc(launch_fused(p, plan->g, grid, d_in, d_blob, d_ws, stream));
+        // TSQ_PIPE_AUTO: a device that cannot tell how many workgroups it holds, or holds fewer than the
+        // scanner and one computing workgroup, gets the staged pipeline, which needs nothing resident
+        const bool fits = st == TSQ_OK && grid >= 1;
+        if (!fits && plan->cfg.pipeline != TSQ_PIPE_AUTO) return st != TSQ_OK ? st : TSQ_ERR_UNSUPPORTED;
+        if (fits) {
+            p.fused_classes = grid < kTicketClasses ? grid : kTicketClasses;
+            return hip_rc(launch_fused(p, plan->g, grid, d_in, d_blob, d_ws, stream));
+        }
     }
-    p.rows_per_tensor = rows_per_tensor;
     int e = launch_row_stats(p, plan->g, d_in, d_blob, d_ws, stream);
     if (e == 0) e = launch_scan(p, d_blob, d_ws, stream);
     if (e == 0) e = launch_pack(p, plan->g, d_in, d_blob, d_ws, stream);
@@ -294,8 +302,11 @@ tsq_status tsq_compress_timed(const tsq_plan *plan, const void *d_in, void *d_bl
     if (st != TSQ_OK) return st;
     hipStream_t s = reinterpret_cast<hipStream_t>(stream);
     hipEvent_t ev[4];
-    for (auto &e : ev)
-        if (hipEventCreate(&e) != hipSuccess) return TSQ_ERR_HIP;
+    for (int i = 0; i < 4; ++i)
+        if (hipEventCreate(&ev[i]) != hipSuccess) {
+            while (i > 0) (void)hipEventDestroy(ev[--i]);
+            return TSQ_ERR_HIP;
+        }
     int rc = 0, n = 0;
     (void)hipEventRecord(ev[0], s);
     if (plan->pipeline == TSQ_PIPE_FUSED) {
@@ -303,7 +314,7 @@ tsq_status tsq_compress_timed(const tsq_plan *plan, const void *d_in, void *d_bl
         st = fused_grid(plan, &grid);
         Params p = plan->p;
         p.fused_classes = grid < kTicketClasses ? grid : kTicketClasses;
-        if (st == TSQ_OK) rc = launch_fused(p, plan->g, grid, d_in, d_blob, d_ws, stream); else rc = 1;
+        if (st == TSQ_OK && grid >= 1) rc = launch_fused(p, plan->g, grid, d_in, d_blob, d_ws, stream); else rc = 1;
         (void)hipEventRecord(ev[1], s);
         n = 1;
     } else {
@@ -390,14 +401,21 @@ tsq_status tsq_blob_info(const tsq_plan *plan, const void *d_blob, tsq_info *hos
     if (!plan || !d_blob || !host_out) return TSQ_ERR_INVALID_ARG;
     hipStream_t s = reinterpret_cast<hipStream_t>(stream);
     BlobHeader h;
-    std::vector<uint8_t> bits(plan->p.tokens);
+    const Params &p = plan->p;
+    struct Bytes {                                   // host buffer that cannot throw
+        uint8_t *at;
+        explicit Bytes(size_t n) : at(static_cast<uint8_t *>(std::malloc(n ? n : 1))) {}
+        ~Bytes() { std::free(at); }
+    } bits(p.tokens);
+    if (!bits.at) return TSQ_ERR_NO_MEMORY;
     if (hipMemcpyAsync(&h, d_blob, sizeof h, hipMemcpyDeviceToHost, s) != hipSuccess) return TSQ_ERR_HIP;
-    if (hipMemcpyAsync(bits.data(), static_cast<const uint8_t *>(d_blob) + plan->layout.off_bits, bits.size(),
-                       hipMemcpyDeviceToHost, s) != hipSuccess)
+    if (hipMemcpyAsync(bits.at, static_cast<const uint8_t *>(d_blob) + plan->layout.off_bits, p.tokens,
+                       hipMemcpyDeviceToHost, s) != hipSuccess) {
+        (void)hipStreamSynchronize(s);               // the first copy may still be writing into h
         return TSQ_ERR_HIP;
+    }
     if (hipStreamSynchronize(s) != hipSuccess) return TSQ_ERR_HIP;
     std::memset(host_out, 0, sizeof *host_out);
-    const Params &p = plan->p;
     if (h.magic != kMagic || h.version != kVersion || h.tokens != p.tokens || h.hidden != p.hidden ||
         h.dtype != p.dtype || h.bit_mask != p.bit_mask || h.off_payload != p.off_payload ||
         h.off_out_col != p.off_out_col || h.off_out_val != p.off_out_val)
@@ -406,11 +424,98 @@ tsq_status tsq_blob_info(const tsq_plan *plan, const void *d_blob, tsq_info *hos
     host_out->nnz = h.nnz;
     host_out->payload_bytes = h.payload_bytes;
     host_out->compressed_bytes = 128ull + 5ull * p.tokens + 16ull * (p.tokens + 1ull) + h.payload_bytes + 4ull * h.nnz;
-    for (uint8_t b : bits)
-        if (b <= 8) host_out->width_hist[b]++;
+    for (uint32_t t = 0; t < p.tokens; ++t)
+        if (bits.at[t] <= 8) host_out->width_hist[bits.at[t]]++;
     if (h.status == TSQ_ERR_CAPACITY) return TSQ_ERR_CAPACITY;
+    if (h.status == TSQ_ERR_FORMAT) return TSQ_ERR_FORMAT;      // the workspace was another shape's, or never reset
     if (h.status != 0) return TSQ_ERR_INTERNAL;
     return TSQ_OK;
+}
+
+tsq_status tsq_prefix_bytes(const tsq_plan *plan, const void *d_blob, const uint32_t *k, uint32_t n, uint64_t *bytes_out,
+                            void *stream) {
+    if (!plan || !d_blob || n == 0 || !bytes_out) return TSQ_ERR_INVALID_ARG;
+    const Params &p = plan->p;
+    if (!k && (uint64_t)n > p.tokens + 1ull) return TSQ_ERR_INVALID_ARG;
+    for (uint32_t i = 0; k && i < n; ++i)
+        if (k[i] > p.tokens) return TSQ_ERR_INVALID_ARG;
+    hipStream_t s = reinterpret_cast<hipStream_t>(stream);
+    const uint8_t *blob = static_cast<const uint8_t *>(d_blob);
+    BlobHeader h;
+    if (hipMemcpyAsync(&h, blob, sizeof h, hipMemcpyDeviceToHost, s) != hipSuccess) return TSQ_ERR_HIP;
+    // bytes_out doubles as the landing place of pay_off[k]; row_ptr[k] lands in a buffer of its own
+    uint64_t *rp = static_cast<uint64_t *>(std::malloc(sizeof(uint64_t) * n));
+    if (!rp) { (void)hipStreamSynchronize(s); return TSQ_ERR_NO_MEMORY; }
+    int bad = 0;
+    if (!k) {       // k = 0 .. n-1: the tables' first n entries in one copy each
+        bad |= hipMemcpyAsync(bytes_out, blob + p.off_pay_off, 8ull * n, hipMemcpyDeviceToHost, s) != hipSuccess;
+        bad |= hipMemcpyAsync(rp, blob + p.off_row_ptr, 8ull * n, hipMemcpyDeviceToHost, s) != hipSuccess;
+    }
+    for (uint32_t i = 0; k && i < n && !bad; ++i) {
+        bad |= hipMemcpyAsync(&bytes_out[i], blob + p.off_pay_off + 8ull * k[i], 8, hipMemcpyDeviceToHost, s) != hipSuccess;
+        bad |= hipMemcpyAsync(&rp[i], blob + p.off_row_ptr + 8ull * k[i], 8, hipMemcpyDeviceToHost, s) != hipSuccess;
+    }
+    if (hipStreamSynchronize(s) != hipSuccess) bad = 1;
+    tsq_status st = bad ? TSQ_ERR_HIP : TSQ_OK;
+    if (st == TSQ_OK && (h.magic != kMagic || h.version != kVersion || h.tokens != p.tokens || h.hidden != p.hidden ||
+                         h.off_pay_off != p.off_pay_off || h.off_row_ptr != p.off_row_ptr))
+        st = TSQ_ERR_FORMAT;
+    if (st == TSQ_OK && h.status != 0) st = h.status == TSQ_ERR_CAPACITY ? TSQ_ERR_CAPACITY : TSQ_ERR_INTERNAL;
+    // header + per-token metadata of k tokens (5 bytes and two offsets each, one closing pair) + codes + CSR entries
+    for (uint32_t i = 0; i < n && st == TSQ_OK; ++i) {
+        const uint64_t ki = k ? k[i] : i;
+        bytes_out[i] = 128ull + 5ull * ki + 16ull * (ki + 1ull) + bytes_out[i] + 4ull * rp[i];
+    }
+    std::free(rp);
+    return st;
+}
+
+tsq_status tsq_compress_blocking(const tsq_plan *plan, const void *d_in, void *d_blob, void *d_ws, void *stream,
+                                 tsq_info *info_out) {
+    if (!info_out) return TSQ_ERR_INVALID_ARG;
+    tsq_status st = tsq_compress(plan, d_in, d_blob, d_ws, stream);
+    if (st != TSQ_OK) return st;
+    st = tsq_blob_info(plan, d_blob, info_out, stream);
+    const bool workspace_trouble = st == TSQ_ERR_INTERNAL || (st == TSQ_ERR_FORMAT && info_out->status == TSQ_ERR_FORMAT);
+    if (!workspace_trouble || plan->cfg.pipeline != TSQ_PIPE_AUTO || plan->pipeline != TSQ_PIPE_FUSED) return st;
+    // the single pass gave up (a wait expired, or the workspace was not in its initial state): the same call
+    // once more on a fresh workspace with the staged kernels, which wait for nothing
+    st = tsq_workspace_reset(plan, d_ws, stream);
+    if (st == TSQ_OK) st = compress_call(plan, d_in, 0, d_blob, d_ws, stream, true);
+    if (st != TSQ_OK) return st;
+    return tsq_blob_info(plan, d_blob, info_out, stream);
+}
+
+// ---- the kernels' range predicates, evaluated on the host (include/tsq_ranges.h)
+int tsq_check_payload_span(uint32_t hidden, uint64_t capacity, uint32_t width, uint64_t offset) {
+    return payload_span_ok(hidden, capacity, width, offset) ? 1 : 0;
+}
+int tsq_check_csr_slice(uint64_t rp0, uint64_t rp1, uint64_t capacity) { return csr_slice_ok(rp0, rp1, capacity) ? 1 : 0; }
+int tsq_check_csr_slice_holds(uint64_t rp0, uint64_t rp1, uint64_t capacity, uint32_t count) {
+    return csr_slice_holds(rp0, rp1, capacity, count) ? 1 : 0;
+}
+int tsq_check_column(uint32_t column, uint32_t hidden) { return column_ok(column, hidden) ? 1 : 0; }
+int tsq_check_stream_span(uint64_t begin, uint64_t end, uint64_t capacity, uint32_t coders, uint32_t slot_bytes) {
+    return stream_span_ok(begin, end, capacity, coders, slot_bytes) ? 1 : 0;
+}
+int tsq_check_stream_move(uint32_t bytes, uint32_t coders, uint32_t slot_bytes, uint64_t at, uint64_t capacity) {
+    return stream_move_ok(bytes, coders, slot_bytes, at, capacity) ? 1 : 0;
+}
+uint32_t tsq_check_frequency_slot(uint32_t state) { return frequency_slot(state); }
+int tsq_check_workspace_shape(uint32_t ws_tokens, uint32_t ws_hidden, uint32_t tokens, uint32_t hidden) {
+    return workspace_shape_ok(ws_tokens, ws_hidden, tokens, hidden) ? 1 : 0;
+}
+
+// ---- copy ceilings (include/tsq_measure.h)
+tsq_status tsq_measure_copy(void *d_dst, const void *d_src, size_t bytes, void *stream) {
+    if (!d_dst || !d_src || bytes == 0 || (bytes & 15u) || ((uintptr_t)d_dst & 15u) || ((uintptr_t)d_src & 15u))
+        return TSQ_ERR_INVALID_ARG;
+    return hip_rc(launch_plain_copy(d_dst, d_src, bytes, stream));
+}
+tsq_status tsq_measure_read(const void *d_src, size_t bytes, void *d_sink, void *stream) {
+    if (!d_sink || !d_src || bytes == 0 || (bytes & 15u) || ((uintptr_t)d_src & 15u) || ((uintptr_t)d_sink & 3u))
+        return TSQ_ERR_INVALID_ARG;
+    return hip_rc(launch_plain_read(d_src, bytes, d_sink, stream));
 }
 
 }  // extern "C"

@@ -13,6 +13,7 @@
 #include <stdint.h>
 
 #include "tsq_internal.hpp"
+#include "tsq_ranges.hpp"
 
 namespace tsq {
 
@@ -473,12 +474,10 @@ __device__ __forceinline__ void unpack_run(const uint32_t (&d)[B], float s, uint
 // LDS scratch of the staged row kernels (behind the row): four reduce areas | scan area
 constexpr uint32_t kScrScan = 4 * 2 * kMaxWaves;
 
-__device__ __forceinline__ uint32_t row_bytes(uint32_t H, uint32_t b) { return 4u * ((H * b + 31u) >> 5); }
-// A token of width b whose payload starts at byte po of the payload section: valid width, 4-byte
-// aligned, and inside the section.  Written without a sum of untrusted values, which could wrap.
+__device__ __forceinline__ uint32_t row_bytes(uint32_t H, uint32_t b) { return payload_row_bytes(H, b); }
+// A token of width b whose payload starts at byte po of the payload section (see tsq_ranges.hpp).
 __device__ __forceinline__ bool token_in_range(const Params &p, uint32_t b, uint64_t po) {
-    if (b < 2 || b > 8 || (po & 3u) || po > p.payload_capacity) return false;
-    return row_bytes(p.hidden, b) <= p.payload_capacity - po;
+    return payload_span_ok(p.hidden, p.payload_capacity, b, po);
 }
 
 // ---------------------------------------------------------------- Algorithm 1 for the token of this block

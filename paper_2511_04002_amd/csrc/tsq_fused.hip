@@ -48,7 +48,6 @@
 
 namespace tsq {
 
-enum { kCtlError = 1 };
 constexpr uint32_t kNoToken = 0xFFFFFFFFu;
 constexpr uint32_t kTicketBits = 24, kTicketMask = (1u << kTicketBits) - 1u;
 enum { kCntTickets = 0, kCntDone = 1 };      // words of a class's counter line
@@ -195,6 +194,12 @@ __device__ void scan_tokens(const Params &p, uint8_t *blob, uint8_t *ws, uint32_
     uint32_t *error_flag = ctrl + kCtlError;
     __builtin_amdgcn_s_setprio(3);
 
+    // a workspace that was reset for another shape (or never): nothing in it is touched, and the blob says so
+    if (!workspace_shape_ok(uniform(word_load(ctrl + kCtlTokens + opaque_zero())),
+                            uniform(word_load(ctrl + kCtlHidden + opaque_zero())), p.tokens, p.hidden)) {
+        if (wv == 0 && lane == 0) write_header(p, blob, 0, 0, 5u);
+        return;
+    }
     const uint32_t epoch = (uniform(word_load(tickets + opaque_zero())) >> kTicketBits) % 3u;
     const uint32_t tag = epoch + 1u, tag3 = tag << 30;
 
@@ -360,11 +365,6 @@ struct StoreTargets {
     uint64_t payload_words, outlier_capacity;
 };
 
-// Stores this wave's part of a token whose prefix is known: its 64 runs of the payload image
-// LDS -> HBM (16 bytes per lane and step, contiguous over the wave) and its outliers from its
-// stash.  Only what the wave wrote itself is read, so no barrier lies between this call and
-// the writes.  Returns false without storing anything if the payload would leave its section,
-// whatever the tables said.
 // The lane's run of a token's row, read from memory again (see the rare case in store_wave_part).
 __device__ __forceinline__ void reread_run(const StoreTargets &o, uint32_t token, uint32_t (&w)[16]) {
     const uint32_t r = threadIdx.x;                          // the lane's run
@@ -378,6 +378,11 @@ __device__ __forceinline__ void reread_run(const StoreTargets &o, uint32_t token
     }
 }
 
+// Stores this wave's part of a token whose prefix is known: its 64 runs of the payload image
+// LDS -> HBM (16 bytes per lane and step, contiguous over the wave) and its outliers from its
+// stash.  Only what the wave wrote itself is read, so no barrier lies between this call and
+// the writes.  Returns false without storing anything if the payload would leave its section,
+// whatever the tables said.
 // row_in_lds: the token's row is still in the LDS row buffer (the workgroup's last token).
 // reread: the lane's run of the row as reread_run delivered it (asked for ahead of time), or null.
 template <int DT, int NW>
@@ -520,14 +525,26 @@ k_fused(const Params p, const uint16_t *__restrict__ in, uint8_t *__restrict__ b
 
     // ---- the first ticket: this workgroup's first token
     if (tid == 0) {
+        // (the counters lie at the same place in every workspace; the ticket is drawn while the shape is
+        // on its way, and handed back if the workspace turns out to be another plan's or never reset: the
+        // scanner reports that, and the workspace is left as it was)
         const uint32_t first = draw_ticket(counter);
-        const uint32_t k = first & kTicketMask;
-        tslot[2] = k < n_cls ? k * C + cls : kNoToken;
-        tslot[3] = (first >> kTicketBits) % 3u + 1u;
+        const uint32_t ws_tokens = word_load(ctrl + kCtlTokens + opaque_zero());
+        const uint32_t ws_hidden = word_load(ctrl + kCtlHidden + opaque_zero());
+        if (workspace_shape_ok(ws_tokens, ws_hidden, p.tokens, p.hidden)) {
+            const uint32_t k = first & kTicketMask;
+            tslot[2] = k < n_cls ? k * C + cls : kNoToken;
+            tslot[3] = (first >> kTicketBits) % 3u + 1u;
+        } else {
+            __hip_atomic_fetch_sub(counter + opaque_zero(), 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            tslot[2] = kNoToken;
+            tslot[3] = 0;
+        }
     }
     __syncthreads();
     uint32_t t = uniform(tslot[2]);
     const uint32_t tag = uniform(tslot[3]);
+    if (tag == 0) return;
 
     // the row of the next iteration on its way HBM -> registers -> LDS (each wave its own part)
     RowPart pre_row;
@@ -787,7 +804,8 @@ __global__ void k_ws_reset(const Params p, uint8_t *__restrict__ ws) {
     for (uint32_t i = first; i < p.tokens; i += stride) sizes[i] = 0;
     for (uint64_t i = first; i < 2ull * (p.tokens + 1ull); i += stride) pre[i] = 0;
     for (uint32_t i = first; i < kTicketClasses * kTicketStride; i += stride) tickets[i] = 0;
-    if (blockIdx.x == 0 && threadIdx.x < 64) ctrl[threadIdx.x] = 0;
+    if (blockIdx.x == 0 && threadIdx.x < 64)
+        ctrl[threadIdx.x] = threadIdx.x == kCtlTokens ? p.tokens : threadIdx.x == kCtlHidden ? p.hidden : 0u;
 }
 
 int launch_ws_reset(const Params &p, void *d_ws, void *stream) {

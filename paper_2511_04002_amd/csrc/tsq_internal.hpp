@@ -26,6 +26,8 @@ constexpr uint32_t kStashWave = 232;
 constexpr uint32_t kFusedGridCap = 4096;
 constexpr uint32_t kTicketClasses = 64, kTicketStride = 64;
 constexpr uint32_t kFusedScratchDw = 4 * 2 * kMaxWaves + 8;
+// words of a workspace's control block
+constexpr uint32_t kCtlError = 1, kCtlTokens = 2, kCtlHidden = 3;
 
 // 128-byte header at the start of every blob.
 struct BlobHeader {
@@ -86,7 +88,8 @@ struct Params {
     uint64_t ws_sizes;      // u32[T]   published (tag, words, count) of every token   (fused)
     uint64_t ws_prefix;     // u64[T+1] (tag, words before, outliers before) of every token, from the scanner (fused)
     uint64_t ws_tickets;    // u32[kTicketClasses][kTicketStride] per class: epoch << 24 | tickets drawn, waves done (fused)
-    uint64_t ws_ctrl;       // u32[64]  word 1: error flag                             (fused)
+    uint64_t ws_ctrl;       // u32[64]  at the start of every workspace: word kCtlError = a call on it failed (fused);
+                            //          words kCtlTokens, kCtlHidden = the shape it was reset for
     uint32_t fused_classes; // ticket classes in use: min(kTicketClasses, computing workgroups; set per call) (fused)
     uint32_t rows_per_tensor;  // 0: the rows form one contiguous tensor.  Otherwise the data pointer of a
                                // call is a device table of tensor pointers, rows_per_tensor rows each
@@ -130,10 +133,11 @@ int launch_unpack(const Params &p, const Geometry &g, const void *d_blob, void *
 int launch_code_hist(const Params &p, const Geometry &g, const void *d_blob, void *d_hist, void *stream);
 int launch_code_pool(const Params &p, const Geometry &g, const EntropyLayout &e, const void *d_blob, void *d_counts,
                      void *stream);
-int prepare_rans_kernels();
 int launch_rans_encode(const Params &p, const Geometry &g, const EntropyLayout &e, const void *d_blob, void *d_eblob,
                        void *d_ews, void *stream);
 int launch_rans_decode(const Params &p, const EntropyLayout &e, const void *d_eblob, void *d_blob, void *stream);
+int launch_plain_copy(void *d_dst, const void *d_src, size_t bytes, void *stream);     // measurement aids
+int launch_plain_read(const void *d_src, size_t bytes, void *d_sink, void *stream);
 int prepare_kernels();  // raises the dynamic-LDS limit of the row kernels once per process
 
 }  // namespace tsq

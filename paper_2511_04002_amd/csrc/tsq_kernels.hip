@@ -63,6 +63,12 @@ __device__ __forceinline__ void emit_outliers(uint32_t omask, const uint32_t *lr
     }
 }
 
+// The workspace was reset for this plan's shape (its sections lie where this plan expects them).
+__device__ __forceinline__ bool workspace_is_plans(const Params &p, const uint8_t *ws) {
+    const uint32_t *ctrl = reinterpret_cast<const uint32_t *>(ws + p.ws_ctrl);
+    return workspace_shape_ok(ctrl[kCtlTokens], ctrl[kCtlHidden], p.tokens, p.hidden);
+}
+
 // ---------------------------------------------------------------- k_row_stats
 
 template <int DT, int NW>
@@ -74,6 +80,7 @@ k_row_stats(const Params p, const uint16_t *__restrict__ in, uint8_t *__restrict
     const uint32_t t = blockIdx.x;
     const uint32_t run = threadIdx.x;
     const bool owns = run < p.runs;
+    if (!workspace_is_plans(p, ws)) return;       // k_scan reports
 
     RowPart pre;
     fetch_row_part(reinterpret_cast<const uint4 *>(row_address(p, in, t, p.hidden)), p.pieces, pre);
@@ -105,6 +112,10 @@ k_scan(const Params p, uint8_t *__restrict__ blob, const uint8_t *__restrict__ w
     uint64_t *pay_off = reinterpret_cast<uint64_t *>(blob + p.off_pay_off);
     const uint32_t tid = threadIdx.x, lane = tid & 63, wv = tid >> 6, nw = blockDim.x >> 6;
     constexpr uint32_t kItems = 4;
+    if (!workspace_is_plans(p, ws)) {
+        if (tid == 0) write_header(p, blob, 0, 0, 5u);
+        return;
+    }
 
     uint64_t carry_c = 0, carry_b = 0;
     uint32_t it = 0;
@@ -156,6 +167,7 @@ k_pack(const Params p, const uint16_t *__restrict__ in, uint8_t *__restrict__ bl
     uint32_t *scratch = lds + p.runs * kRunLdsDw;
     const uint32_t t = blockIdx.x;
     const uint32_t run = threadIdx.x;
+    if (!workspace_is_plans(p, ws)) return;
 
     RowPart pre;
     fetch_row_part(reinterpret_cast<const uint4 *>(row_address(p, in, t, p.hidden)), p.pieces, pre);
@@ -187,7 +199,7 @@ k_pack(const Params p, const uint16_t *__restrict__ in, uint8_t *__restrict__ bl
         }
     }
     // side stream: only tokens that fit entirely below the capacity are stored
-    if (cnt > 0 && rp1 <= p.outlier_capacity && rp1 - rp0 == cnt) {
+    if (cnt > 0 && csr_slice_holds(rp0, rp1, p.outlier_capacity, cnt)) {
         emit_outliers(omask, lrow, run, reinterpret_cast<uint16_t *>(blob + p.off_out_col),
                       reinterpret_cast<uint16_t *>(blob + p.off_out_val), rp0, scratch + kScrScan);
     }
@@ -236,7 +248,7 @@ k_unpack(const Params p, const uint8_t *__restrict__ blob, uint16_t *__restrict_
     const uint64_t rp0 = reinterpret_cast<const uint64_t *>(blob + p.off_row_ptr)[t];
     const uint64_t rp1 = reinterpret_cast<const uint64_t *>(blob + p.off_row_ptr)[t + 1];
     // a damaged token is skipped rather than read out of bounds
-    if (!token_in_range(p, width, po) || rp0 > rp1 || rp1 > p.outlier_capacity)
+    if (!token_in_range(p, width, po) || !csr_slice_ok(rp0, rp1, p.outlier_capacity))
         return;
 
     if (run < p.runs) {
@@ -262,7 +274,7 @@ k_unpack(const Params p, const uint8_t *__restrict__ blob, uint16_t *__restrict_
         uint16_t *lrow16 = reinterpret_cast<uint16_t *>(lrow);
         for (uint64_t k = rp0 + threadIdx.x; k < rp1; k += blockDim.x) {
             const uint32_t c = col[k];
-            if (c < p.hidden) lrow16[(c >> 5) * (2 * kRunLdsDw) + (c & 31u)] = val[k];
+            if (column_ok(c, p.hidden)) lrow16[(c >> 5) * (2 * kRunLdsDw) + (c & 31u)] = val[k];
         }
     }
     __syncthreads();
@@ -278,9 +290,58 @@ k_unpack(const Params p, const uint8_t *__restrict__ blob, uint16_t *__restrict_
     }
 }
 
+// ---------------------------------------------------------------- copy ceilings (measurement aids)
+
+// What the memory system gives a kernel that only moves bytes, with this library's access shape: 16
+// bytes per lane, four pieces in flight per thread, 256 threads per workgroup, streaming stores.
+constexpr uint32_t kCopyPieces = 4, kCopyThreads = 256;
+
+__global__ void __launch_bounds__(kCopyThreads)
+k_plain_copy(u32x4 *__restrict__ dst, const u32x4 *__restrict__ src, uint64_t pieces) {
+    const uint64_t base = (uint64_t)blockIdx.x * (kCopyThreads * kCopyPieces) + threadIdx.x;
+    u32x4 v[kCopyPieces];
+#pragma unroll
+    for (uint32_t k = 0; k < kCopyPieces; ++k)
+        if (base + k * kCopyThreads < pieces) v[k] = __builtin_nontemporal_load(src + base + k * kCopyThreads);
+#pragma unroll
+    for (uint32_t k = 0; k < kCopyPieces; ++k)
+        if (base + k * kCopyThreads < pieces) __builtin_nontemporal_store(v[k], dst + base + k * kCopyThreads);
+}
+
+__global__ void __launch_bounds__(kCopyThreads)
+k_plain_read(const u32x4 *__restrict__ src, uint64_t pieces, uint32_t *__restrict__ sink) {
+    const uint64_t base = (uint64_t)blockIdx.x * (kCopyThreads * kCopyPieces) + threadIdx.x;
+    uint32_t acc = 0;
+#pragma unroll
+    for (uint32_t k = 0; k < kCopyPieces; ++k)
+        if (base + k * kCopyThreads < pieces) {
+            const u32x4 v = __builtin_nontemporal_load(src + base + k * kCopyThreads);
+            acc |= v.x ^ v.y ^ v.z ^ v.w;
+        }
+    // every load feeds a result that may be stored, so none is dropped; in practice almost nothing is written
+    if (acc == 0x9E3779B9u) sink[0] = acc;
+}
+
 // ---------------------------------------------------------------- launchers
 
 static hipStream_t as_stream(void *s) { return reinterpret_cast<hipStream_t>(s); }
+
+int launch_plain_copy(void *d_dst, const void *d_src, size_t bytes, void *stream) {
+    const uint64_t pieces = bytes / 16u, per_wg = kCopyThreads * kCopyPieces;
+    const uint64_t wgs = (pieces + per_wg - 1) / per_wg;
+    if (wgs == 0 || wgs > 0x7FFFFFFFull) return (int)hipErrorInvalidValue;
+    hipLaunchKernelGGL(k_plain_copy, dim3((uint32_t)wgs), dim3(kCopyThreads), 0, as_stream(stream),
+                       static_cast<u32x4 *>(d_dst), static_cast<const u32x4 *>(d_src), pieces);
+    return (int)hipGetLastError();
+}
+int launch_plain_read(const void *d_src, size_t bytes, void *d_sink, void *stream) {
+    const uint64_t pieces = bytes / 16u, per_wg = kCopyThreads * kCopyPieces;
+    const uint64_t wgs = (pieces + per_wg - 1) / per_wg;
+    if (wgs == 0 || wgs > 0x7FFFFFFFull) return (int)hipErrorInvalidValue;
+    hipLaunchKernelGGL(k_plain_read, dim3((uint32_t)wgs), dim3(kCopyThreads), 0, as_stream(stream),
+                       static_cast<const u32x4 *>(d_src), pieces, static_cast<uint32_t *>(d_sink));
+    return (int)hipGetLastError();
+}
 
 typedef void (*StatsKernel)(const Params, const uint16_t *, uint8_t *, uint8_t *);
 typedef void (*PackKernel)(const Params, const uint16_t *, uint8_t *, const uint8_t *);

@@ -91,4 +91,52 @@ tsq_status tsq_early_exit_decide(const tsq_exit_input *in, tsq_exit_decision *ou
     return TSQ_OK;
 }
 
+tsq_status tsq_early_exit_walk(const tsq_exit_walk_input *in, tsq_exit_walk_result *out) {
+    if (!in || !out || !link_ok(&in->link) || !(in->rate > 0.0) || !(in->deadline >= 0.0) || !in->compute_latency ||
+        !in->bits || in->layers == 0)
+        return TSQ_ERR_INVALID_ARG;
+    const tsq_link &l = in->link;
+    const double D = in->deadline;
+    tsq_status st = TSQ_OK;
+    uint32_t steps = 0;
+    // L_t of Eq. (total) for what the callbacks say; a size or a time that is negative or NaN ends the walk
+    auto total = [&](uint32_t w_time, uint32_t w, uint32_t layer, int32_t ikv, int32_t compressed, uint32_t keep) {
+        const double lc = in->compute_latency(w_time, layer, in->user);
+        const double bits = in->bits(w, layer, ikv, compressed, keep, in->user);
+        if (!(lc >= 0.0) || !(bits >= 0.0)) { st = TSQ_ERR_INVALID_ARG; return 0.0; }
+        return lc + latency(l, bits, in->rate);
+    };
+    auto done = [&](int32_t action, int32_t ikv, uint32_t w, uint32_t layer, uint32_t keep, double t) {
+        out->action = action; out->with_kv = ikv; out->tokens = w; out->layer = layer;
+        out->sent_tokens = keep; out->steps = steps; out->latency = t;
+        return st;
+    };
+    int32_t ikv = 1;
+    for (uint32_t w = 1; w <= in->max_tokens; ++w)
+        for (uint32_t layer = 1; layer <= in->layers; ++layer) {
+            ++steps;                                           // the caller's forward pass up to `layer` for token w
+            double t = total(w, w, layer, ikv, 0, w);
+            if (st != TSQ_OK) return st;
+            if (!(t > D)) continue;
+            t = total(w, w, layer, ikv, 1, w);                 // TabQ(T_w; I_kv)
+            if (st != TSQ_OK) return st;
+            if (t <= D) return done(TSQ_EXIT_COMPRESSED, ikv, w, layer, w, t);
+            ikv = 0;
+            t = total(w, w, layer, 0, 1, w);
+            if (st != TSQ_OK) return st;
+            if (t > D) {
+                uint32_t keep = w;
+                while (t > D && keep > 0) {
+                    --keep;
+                    t = total(keep, w, layer, 0, 1, keep);
+                    if (st != TSQ_OK) return st;
+                }
+                return done(TSQ_EXIT_FEWER_TOKENS, 0, w, layer, keep, t);
+            }
+        }
+    const double t = total(in->max_tokens, in->max_tokens, in->layers, ikv, 1, in->max_tokens);
+    if (st != TSQ_OK) return st;
+    return done(TSQ_EXIT_COMPLETED, ikv, in->max_tokens, in->layers, in->max_tokens, t);
+}
+
 }  // extern "C"

@@ -28,6 +28,7 @@
 namespace tsq {
 
 constexpr uint32_t kProbBits = 12, kProbScale = 1u << kProbBits, kRansLow = 1u << 16;
+static_assert(kProbScale == 4096, "frequency_slot() masks 12 bits");
 
 __device__ __forceinline__ bool blob_is_valid(const Params &p, const uint8_t *blob) {
     const BlobHeader *h = reinterpret_cast<const BlobHeader *>(blob);
@@ -324,7 +325,7 @@ k_rans_gather(const Params p, const EntropyLayout e, const uint8_t *__restrict__
         }
     }
     const uint32_t coders = p.runs < 64u ? p.runs : 64u;
-    if (bytes < 4u * coders || bytes > e.slot_bytes || at + padded > e.stream_capacity) return;
+    if (!stream_move_ok(bytes, coders, e.slot_bytes, at, e.stream_capacity)) return;
     const uint8_t *slot = ews + e.ws_slots + (size_t)t * e.slot_bytes;
     uint8_t *dst = eblob + e.off_streams + at;
     if (threadIdx.x < coders) reinterpret_cast<uint32_t *>(dst)[threadIdx.x] = reinterpret_cast<const uint32_t *>(slot)[threadIdx.x];
@@ -365,7 +366,7 @@ __device__ __forceinline__ void build_slot_table(const uint32_t *ftab, uint32_t 
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
         const uint32_t c = 4u * lane + i, fc = ftab[c];
-        if (fc & 0xFFFFu) sym[(fc >> 16) & (kProbScale - 1u)] = (uint8_t)c;   // masked: a damaged table stays inside the array
+        if (fc & 0xFFFFu) sym[frequency_slot(fc >> 16)] = (uint8_t)c;   // masked: a damaged table stays inside the array
     }
     __syncthreads();
     // lane l owns the slots 64l .. 64l+63
@@ -423,7 +424,7 @@ __device__ __forceinline__ void decode_round(uint32_t *dst_row, uint32_t run, in
 #pragma unroll
     for (int j = 0; j < 32; ++j) {
         const bool active = WHOLE || j < valid;
-        const uint32_t slot = x & (kProbScale - 1u);
+        const uint32_t slot = frequency_slot(x);
         const uint32_t s = sym[slot];
         const uint32_t fc = ftab[s];
         if (active) {
@@ -464,7 +465,7 @@ k_rans_decode(const Params p, const EntropyLayout e, const uint8_t *__restrict__
     const uint64_t *off = reinterpret_cast<const uint64_t *>(eblob + e.off_stream_off);
     const uint64_t a = off[t], b = off[t + 1];
     const uint32_t coders = p.runs < 64u ? p.runs : 64u;  // states in the stream; the other coders start (and stay) at 2^16
-    if (a > b || b > e.stream_capacity || b - a < 4u * coders || b - a > e.slot_bytes || (a & 3u)) return;
+    if (!stream_span_ok(a, b, e.stream_capacity, coders, e.slot_bytes)) return;
     load_table_decode(reinterpret_cast<const uint16_t *>(eblob + e.off_tables) + (width - 2u) * 256u, ftab);
     __syncthreads();
     build_slot_table(ftab, sym32);
@@ -505,8 +506,6 @@ k_rans_decode(const Params p, const EntropyLayout e, const uint8_t *__restrict__
 // ---------------------------------------------------------------- launchers
 
 static hipStream_t as_stream(void *s) { return reinterpret_cast<hipStream_t>(s); }
-
-int prepare_rans_kernels() { return 0; }
 
 int launch_rans_encode(const Params &p, const Geometry &g, const EntropyLayout &e, const void *d_blob, void *d_eblob,
                        void *d_ews, void *stream) {

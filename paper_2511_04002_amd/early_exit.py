@@ -1,6 +1,7 @@
 """Algorithm 2 (early exit under a delay constraint, Sec. II-D.2) driven by sizes measured on the GPU.
 
     python -m paper_2511_04002_amd.early_exit [--tokens 512] [--layers 20]
+    python -m paper_2511_04002_amd.early_exit --walk --tokens 32 --layers 8     (both loops of Algorithm 2)
 
 The hidden state of `tokens` tokens at the split layer and the KV cache of the `layers` layers
 below it (synthetic, 7B-shaped: HD = 4096, fp16) are compressed with tsq_compress /
@@ -17,15 +18,6 @@ import json
 import numpy as np
 
 
-def prefix_bits(sections, tokens: int):
-    """Compressed size in bits of the first k tokens of a blob, k = 0 .. tokens: header, per-token
-    width and scale, the two offset tables, payload and CSR entries."""
-    k = np.arange(tokens + 1, dtype=np.uint64)
-    pay, nnz = sections["pay_off"][: tokens + 1], sections["row_ptr"][: tokens + 1]
-    return (np.uint64(8) * (np.uint64(128) + np.uint64(5) * k + np.uint64(16) * (k + np.uint64(1)) + pay +
-                            np.uint64(4) * nnz)).tolist()
-
-
 def measure(tokens: int, layers: int, eps: float = 0.05):
     """-> (raw_bits, compressed_bits_with_kv, hidden_prefix_bits) from GPU compress calls."""
     import torch
@@ -36,7 +28,7 @@ def measure(tokens: int, layers: int, eps: float = 0.05):
     plan = tsq.Plan(tokens, H, w2.dtype, w2.tau, w2.bit_set, eps, max_outliers=tokens * H // 8)
     blob = plan.compress(torch.from_numpy(hid.view(np.int16)).cuda())
     info = plan.info(blob)
-    pre = prefix_bits(plan.sections(blob), tokens)
+    pre = [8 * v for v in plan.prefix_bytes(blob)]          # bits, k = 0 .. tokens (tsq_prefix_bytes)
     assert pre[-1] == 8 * info.compressed_bytes
     kv = [torch.from_numpy(p.view(np.int16)).cuda() for p in synth.make_kv("KV7", layers=layers, rows=tokens)]
     plan_kv = tsq.Plan(2 * layers * tokens, H, wk.dtype, wk.tau, wk.bit_set, eps,
@@ -47,13 +39,76 @@ def measure(tokens: int, layers: int, eps: float = 0.05):
     return raw, 8.0 * (info.compressed_bytes + info_kv.compressed_bytes), pre
 
 
+class StepSizes:
+    """Sizes for Algorithm 2's walk, measured on the GPU when the walk asks for them: the hidden state of w
+    tokens at the split layer and the KV cache of the `layer` layers below it, compressed with tsq_compress /
+    tsq_compress_batch (one plan per shape, kept)."""
+
+    def __init__(self, max_tokens: int, layers: int, eps: float = 0.05):
+        import torch
+        from . import synth, tsq
+        self.tsq, self.torch = tsq, torch
+        self.w2, self.wk, self.eps = synth.WORKLOADS["C2"], synth.WORKLOADS["KV7"], eps
+        self.H = self.w2.hidden
+        self.hid = torch.from_numpy(synth.make_c2(tokens=max_tokens).view(np.int16)).cuda()
+        self.kv = [torch.from_numpy(p.view(np.int16)).cuda()
+                   for p in synth.make_kv("KV7", layers=layers, rows=max_tokens)]       # K_1, V_1, K_2, ...
+        self.cache = {}
+        self.compress_calls = 0
+
+    def hidden_prefix_bits(self, w: int):
+        key = ("h", w)
+        if key not in self.cache:
+            plan = self.tsq.Plan(w, self.H, self.w2.dtype, self.w2.tau, self.w2.bit_set, self.eps,
+                                 max_outliers=max(1, w * self.H // 8))
+            blob = plan.compress(self.hid[:w].contiguous())
+            self.compress_calls += 1
+            self.cache[key] = [8 * v for v in plan.prefix_bytes(blob)]
+        return self.cache[key]
+
+    def kv_bits(self, w: int, layer: int) -> float:
+        key = ("kv", w, layer)
+        if key not in self.cache:
+            plan = self.tsq.Plan(2 * layer * w, self.H, self.wk.dtype, self.wk.tau, self.wk.bit_set, self.eps,
+                                 max_outliers=max(1, 2 * layer * w * self.H // 8))
+            blob, _ = plan.compress_batch([t[:w].contiguous() for t in self.kv[: 2 * layer]])
+            self.compress_calls += 1
+            self.cache[key] = 8.0 * plan.info(blob).compressed_bytes
+        return self.cache[key]
+
+    def bits(self, w, layer, with_kv, compressed, keep):
+        if not compressed:                                    # Eq. (if_total), 16-bit activations
+            return 16.0 * (keep * self.H + (2 * layer * w * self.H if with_kv else 0))
+        return float(self.hidden_prefix_bits(w)[keep]) + (self.kv_bits(w, layer) if with_kv else 0.0)
+
+
+def walk(max_tokens: int, layers: int, c0: float, c1: float, deadlines):
+    """Algorithm 2 with both loops (tsq_early_exit_walk); sizes are measured at the step that needs them."""
+    from . import tsq
+    sizes = StepSizes(max_tokens, layers)
+    link = tsq.tsq_link(10e6, 10.0, 1e-3)
+    rate = tsq.tsq_link_best_rate(link, 1e5, 1e8, 2000)
+    names = {1: "compressed", 3: "fewer_tokens", 4: "completed"}
+    for D in deadlines:
+        r = tsq.tsq_early_exit_walk(link, rate, D, max_tokens, layers, lambda w, layer: (c0 + c1 * w) * layer / layers if w else 0.0,
+                                    sizes.bits)
+        print(json.dumps({"deadline_s": D, "action": names[r.action], "with_kv": r.with_kv, "tokens": r.tokens,
+                          "layer": r.layer, "sent_tokens": r.sent_tokens, "steps": r.steps, "latency_s": r.latency,
+                          "compress_calls_so_far": sizes.compress_calls}))
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--tokens", type=int, default=512)
     ap.add_argument("--layers", type=int, default=20)
     ap.add_argument("--c0", type=float, default=0.05, help="L_c(w) = c0 + c1 * w, seconds")
     ap.add_argument("--c1", type=float, default=0.002)
+    ap.add_argument("--walk", action="store_true",
+                    help="run Algorithm 2's loops over w = 1..tokens and layer = 1..layers, measuring sizes at each exit")
     args = ap.parse_args()
+    if args.walk:
+        walk(args.tokens, args.layers, args.c0, args.c1, (10.0, 1.0, 0.3, 0.1, 0.03, 0.01, 0.003))
+        return
     from . import tsq
     raw, with_kv, pre = measure(args.tokens, args.layers)
     link = tsq.tsq_link(10e6, 10.0, 1e-3)

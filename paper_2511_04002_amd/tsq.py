@@ -1,4 +1,4 @@
-"""Thin Python binding of the C-ABI library (include/tsq.h): argument marshalling
+"""Thin Python binding of the C-ABI library (include/tsq.h, tsq_measure.h, tsq_ranges.h): argument marshalling
 only.  Every step of the method runs in the HIP kernels of libtsq.so; there is
 no CPU fallback, and a missing library is an error.
 
@@ -15,19 +15,25 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 _LIB_PATH = os.environ.get("TSQ_LIBRARY") or os.path.join(_HERE, "libtsq.so")
 
 TSQ_OK, TSQ_ERR_INVALID_ARG, TSQ_ERR_UNSUPPORTED, TSQ_ERR_CAPACITY = 0, 1, 2, 3
-TSQ_ERR_HIP, TSQ_ERR_FORMAT, TSQ_ERR_INTERNAL = 4, 5, 6
+TSQ_ERR_HIP, TSQ_ERR_FORMAT, TSQ_ERR_INTERNAL, TSQ_ERR_NO_MEMORY = 4, 5, 6, 7
 TSQ_F16, TSQ_BF16 = 0, 1
 TSQ_BUDGET_LSB, TSQ_BUDGET_REL_RMS = 0, 1
 TSQ_PIPE_AUTO, TSQ_PIPE_STAGED, TSQ_PIPE_FUSED = 0, 1, 2
 
 EXPORTS = ("tsq_plan_create", "tsq_plan_destroy", "tsq_plan_layout", "tsq_plan_blob_bytes",
-           "tsq_plan_workspace_bytes", "tsq_workspace_reset", "tsq_compress", "tsq_compress_timed",
+           "tsq_plan_workspace_bytes", "tsq_workspace_reset", "tsq_compress", "tsq_compress_blocking",
            "tsq_compress_static", "tsq_static_workspace_bytes",
            "tsq_decompress", "tsq_compress_batch", "tsq_decompress_batch",
-           "tsq_code_histogram", "tsq_blob_info", "tsq_status_string",
+           "tsq_code_histogram", "tsq_blob_info", "tsq_prefix_bytes", "tsq_status_string",
+           # tsq_measure.h
+           "tsq_compress_timed", "tsq_measure_copy", "tsq_measure_read",
+           # tsq_ranges.h
+           "tsq_check_payload_span", "tsq_check_csr_slice", "tsq_check_csr_slice_holds", "tsq_check_column",
+           "tsq_check_stream_span", "tsq_check_stream_move", "tsq_check_frequency_slot", "tsq_check_workspace_shape",
            "tsq_entropy_blob_bytes", "tsq_entropy_workspace_bytes", "tsq_entropy_encode", "tsq_entropy_decode",
-           "tsq_entropy_info", "tsq_link_outage_probability", "tsq_link_latency", "tsq_link_best_rate", "tsq_early_exit_decide")
-TSQ_EXIT_CONTINUE, TSQ_EXIT_COMPRESSED, TSQ_EXIT_WITHOUT_KV, TSQ_EXIT_FEWER_TOKENS = 0, 1, 2, 3
+           "tsq_entropy_info", "tsq_link_outage_probability", "tsq_link_latency", "tsq_link_best_rate", "tsq_early_exit_decide",
+           "tsq_early_exit_walk")
+TSQ_EXIT_CONTINUE, TSQ_EXIT_COMPRESSED, TSQ_EXIT_WITHOUT_KV, TSQ_EXIT_FEWER_TOKENS, TSQ_EXIT_COMPLETED = 0, 1, 2, 3, 4
 
 
 class tsq_config(C.Structure):
@@ -62,6 +68,21 @@ class tsq_exit_input(C.Structure):
     _fields_ = [("link", tsq_link), ("rate", C.c_double), ("deadline", C.c_double), ("tokens", C.c_uint32),
                 ("compute_latency", C.POINTER(C.c_double)), ("raw_bits", C.c_double),
                 ("compressed_bits_with_kv", C.c_double), ("hidden_prefix_bits", C.POINTER(C.c_uint64))]
+
+
+tsq_exit_latency_fn = C.CFUNCTYPE(C.c_double, C.c_uint32, C.c_uint32, C.c_void_p)
+tsq_exit_bits_fn = C.CFUNCTYPE(C.c_double, C.c_uint32, C.c_uint32, C.c_int32, C.c_int32, C.c_uint32, C.c_void_p)
+
+
+class tsq_exit_walk_input(C.Structure):
+    _fields_ = [("link", tsq_link), ("rate", C.c_double), ("deadline", C.c_double), ("max_tokens", C.c_uint32),
+                ("layers", C.c_uint32), ("compute_latency", tsq_exit_latency_fn), ("bits", tsq_exit_bits_fn),
+                ("user", C.c_void_p)]
+
+
+class tsq_exit_walk_result(C.Structure):
+    _fields_ = [("action", C.c_int32), ("with_kv", C.c_int32), ("tokens", C.c_uint32), ("layer", C.c_uint32),
+                ("sent_tokens", C.c_uint32), ("steps", C.c_uint32), ("latency", C.c_double)]
 
 
 class tsq_exit_decision(C.Structure):
@@ -107,6 +128,24 @@ def lib():
         L.tsq_static_workspace_bytes.argtypes = []
         L.tsq_compress_timed.restype = u
         L.tsq_compress_timed.argtypes = [vp, vp, vp, vp, vp, C.POINTER(C.c_float)]
+        L.tsq_compress_blocking.restype = u
+        L.tsq_compress_blocking.argtypes = [vp, vp, vp, vp, vp, C.POINTER(tsq_info)]
+        L.tsq_prefix_bytes.restype = u
+        L.tsq_prefix_bytes.argtypes = [vp, vp, C.POINTER(C.c_uint32), C.c_uint32, C.POINTER(C.c_uint64), vp]
+        L.tsq_measure_copy.restype = u
+        L.tsq_measure_copy.argtypes = [vp, vp, C.c_size_t, vp]
+        L.tsq_measure_read.restype = u
+        L.tsq_measure_read.argtypes = [vp, C.c_size_t, vp, vp]
+        u32, u64 = C.c_uint32, C.c_uint64
+        for name, args in (("tsq_check_payload_span", [u32, u64, u32, u64]), ("tsq_check_csr_slice", [u64, u64, u64]),
+                           ("tsq_check_csr_slice_holds", [u64, u64, u64, u32]), ("tsq_check_column", [u32, u32]),
+                           ("tsq_check_stream_span", [u64, u64, u64, u32, u32]),
+                           ("tsq_check_stream_move", [u32, u32, u32, u64, u64]),
+                           ("tsq_check_workspace_shape", [u32, u32, u32, u32])):
+            getattr(L, name).restype = C.c_int
+            getattr(L, name).argtypes = args
+        L.tsq_check_frequency_slot.restype = u32
+        L.tsq_check_frequency_slot.argtypes = [u32]
         L.tsq_decompress.restype = u
         L.tsq_decompress.argtypes = [vp, vp, vp, vp]
         L.tsq_compress_batch.restype = u
@@ -135,6 +174,8 @@ def lib():
         L.tsq_link_best_rate.argtypes = [C.POINTER(tsq_link), C.c_double, C.c_double, C.c_uint32]
         L.tsq_early_exit_decide.restype = u
         L.tsq_early_exit_decide.argtypes = [C.POINTER(tsq_exit_input), C.POINTER(tsq_exit_decision)]
+        L.tsq_early_exit_walk.restype = u
+        L.tsq_early_exit_walk.argtypes = [C.POINTER(tsq_exit_walk_input), C.POINTER(tsq_exit_walk_result)]
         L.tsq_status_string.restype = C.c_char_p
         L.tsq_status_string.argtypes = [u]
         _lib = L
@@ -205,6 +246,43 @@ def tsq_compress_timed(plan: int, d_in: int, d_blob: int, d_ws: int, stream: int
     if st != TSQ_OK:
         raise TsqError(st, "tsq_compress_timed")
     return list(ms)
+
+
+def tsq_measure_copy(d_dst: int, d_src: int, nbytes: int, stream: int = 0) -> None:
+    st = lib().tsq_measure_copy(d_dst, d_src, nbytes, stream)
+    if st != TSQ_OK:
+        raise TsqError(st, "tsq_measure_copy")
+
+
+def tsq_measure_read(d_src: int, nbytes: int, d_sink: int, stream: int = 0) -> None:
+    st = lib().tsq_measure_read(d_src, nbytes, d_sink, stream)
+    if st != TSQ_OK:
+        raise TsqError(st, "tsq_measure_read")
+
+
+def tsq_compress_blocking(plan: int, d_in: int, d_blob: int, d_ws: int, stream: int = 0, check: bool = True) -> tsq_info:
+    """Synchronizes.  -> tsq_info of the final blob (return_status = what the call returned)."""
+    out = tsq_info()
+    st = lib().tsq_compress_blocking(plan, d_in, d_blob, d_ws, stream, C.byref(out))
+    if st != TSQ_OK and check:
+        raise TsqError(st, "tsq_compress_blocking")
+    out.return_status = st
+    return out
+
+
+def tsq_prefix_bytes(plan: int, d_blob: int, k=None, n: int = 0, stream: int = 0):
+    """-> list of compressed sizes in bytes of the first k tokens, for the counts in `k` (or for
+    k = 0 .. n-1 when k is None).  Synchronizes."""
+    if k is not None:
+        n = len(k)
+        ks = (C.c_uint32 * n)(*[int(v) for v in k])
+    else:
+        ks = None
+    out = (C.c_uint64 * n)()
+    st = lib().tsq_prefix_bytes(plan, d_blob, ks, n, out, stream)
+    if st != TSQ_OK:
+        raise TsqError(st, "tsq_prefix_bytes")
+    return list(out)
 
 
 def tsq_decompress(plan: int, d_blob: int, d_out: int, stream: int = 0) -> None:
@@ -294,6 +372,36 @@ def tsq_early_exit_decide(link: tsq_link, rate: float, deadline: float, compute_
     st = lib().tsq_early_exit_decide(C.byref(inp), C.byref(out))
     if st != TSQ_OK:
         raise TsqError(st, "tsq_early_exit_decide")
+    return out
+
+
+def tsq_early_exit_walk(link: tsq_link, rate: float, deadline: float, max_tokens: int, layers: int,
+                        compute_latency, bits) -> tsq_exit_walk_result:
+    """compute_latency(w, layer) -> seconds; bits(w, layer, with_kv, compressed, keep) -> bits."""
+    failure = []
+
+    def lat_cb(w, layer, _user):
+        try:
+            return float(compute_latency(w, layer))
+        except BaseException as e:           # an exception cannot cross the C frames: end the walk, raise afterwards
+            failure.append(e)
+            return float("nan")
+
+    def bits_cb(w, layer, with_kv, compressed, keep, _user):
+        try:
+            return float(bits(w, layer, with_kv, compressed, keep))
+        except BaseException as e:
+            failure.append(e)
+            return float("nan")
+
+    inp = tsq_exit_walk_input(link, rate, deadline, max_tokens, layers, tsq_exit_latency_fn(lat_cb),
+                              tsq_exit_bits_fn(bits_cb), None)
+    out = tsq_exit_walk_result()
+    st = lib().tsq_early_exit_walk(C.byref(inp), C.byref(out))
+    if failure:
+        raise failure[0]
+    if st != TSQ_OK:
+        raise TsqError(st, "tsq_early_exit_walk")
     return out
 
 
@@ -431,6 +539,10 @@ class Plan:
 
     def info(self, blob, check: bool = True) -> tsq_info:
         return tsq_blob_info(self.handle, blob.data_ptr(), self._stream(), check)
+
+    def prefix_bytes(self, blob, k=None):
+        """Compressed size of the first k tokens for every k in `k` (default: k = 0 .. tokens)."""
+        return tsq_prefix_bytes(self.handle, blob.data_ptr(), k, self.tokens + 1 if k is None else 0, self._stream())
 
     def sections(self, blob) -> Dict[str, "object"]:
         """Host copies (numpy) of the blob's sections, cut to their actual lengths."""

@@ -1,5 +1,5 @@
 """Host-only checks of the C-ABI library: it loads, exports every function that
-include/tsq.h declares, and its plan validation and layout behave as the header
+the headers under include/ declare, and its plan validation and layout behave as the header
 says.  No kernel is launched here."""
 import ctypes as C
 import os
@@ -20,9 +20,13 @@ def L():
 
 
 def declared_functions():
-    text = open(os.path.join(ROOT, "include", "tsq.h")).read()
-    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
-    return sorted(set(re.findall(r"\b(tsq_[a-z_]+)\s*\(", text)))
+    names = set()
+    for header in ("tsq.h", "tsq_measure.h", "tsq_ranges.h"):
+        text = open(os.path.join(ROOT, "include", header)).read()
+        text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+        text = re.sub(r"typedef[^;{]*\(\s*\*\s*tsq_[a-z_]+\s*\)[^;]*;", "", text)      # function-pointer types
+        names |= set(re.findall(r"\b(tsq_[a-z_]+)\s*\(", text))
+    return sorted(names)
 
 
 def test_every_declared_symbol_is_exported(L):

@@ -34,3 +34,66 @@ def test_decisions_from_measured_sizes_follow_the_ladder(oracle):
         assert got.latency == pytest.approx(want[3], rel=1e-12)
         seen.add(got.action)
     assert len(seen) >= 3
+
+
+def test_prefix_sizes_are_those_of_the_shorter_tensor(oracle):
+    """tsq_prefix_bytes(k) is what compressing the first k tokens alone reports, for every k."""
+    import torch
+    from paper_2511_04002_amd import synth, tsq
+    w2 = synth.WORKLOADS["C2"]
+    tokens = 40
+    x = synth.make_c2(tokens=tokens)
+    plan = tsq.Plan(tokens, w2.hidden, w2.dtype, w2.tau, w2.bit_set, 0.2, max_outliers=tokens * w2.hidden // 8)
+    blob = plan.compress(torch.from_numpy(x.view(np.int16)).cuda())
+    pre = plan.prefix_bytes(blob)
+    assert len(pre) == tokens + 1 and pre[0] == 128 + 16
+    for k in (1, 2, 7, 39, 40):
+        c = oracle.compress(x[:k], oracle.F16, w2.tau, w2.bit_set, 0.2, 1)
+        assert pre[k] == oracle.compressed_bytes(c)
+    assert plan.prefix_bytes(blob, [40, 0, 7]) == [pre[40], pre[0], pre[7]]
+    assert pre[tokens] == plan.info(blob).compressed_bytes
+    with pytest.raises(tsq.TsqError):
+        plan.prefix_bytes(blob, [41])
+
+
+def test_walk_with_sizes_measured_step_by_step(oracle):
+    """Algorithm 2 with both loops: the library's walk over sizes that the GPU measures at the steps that need
+    them, against the oracle's walk over sizes that the oracle compresses."""
+    from oracle import link_oracle as LO
+    from paper_2511_04002_amd import early_exit, synth, tsq
+    max_tokens, layers = 12, 3
+    sizes = early_exit.StepSizes(max_tokens, layers)
+    w2, wk = synth.WORKLOADS["C2"], synth.WORKLOADS["KV7"]
+    hid = synth.make_c2(tokens=max_tokens)
+    kv = synth.make_kv("KV7", layers=layers, rows=max_tokens)
+    memo = {}
+
+    def oracle_bits(w, layer, with_kv, compressed, keep):
+        if not compressed:
+            return 16.0 * (keep * w2.hidden + (2 * layer * w * w2.hidden if with_kv else 0))
+        key = (w, layer, with_kv, keep)
+        if key not in memo:
+            c = oracle.compress(hid[:w], oracle.F16, w2.tau, w2.bit_set, 0.05, 1)
+            # first `keep` tokens of the w-token blob: header + metadata + their codes + their CSR entries
+            b = 128 + 5 * keep + 16 * (keep + 1) + int(c.pay_off[keep]) + 4 * int(c.row_ptr[keep])
+            if with_kv:
+                ck = oracle.compress(np.concatenate([t[:w] for t in kv[: 2 * layer]]), oracle.F16, wk.tau, wk.bit_set,
+                                     0.05, 1)
+                b += oracle.compressed_bytes(ck)
+            memo[key] = 8.0 * b
+        return memo[key]
+
+    W, gamma, eps = 10e6, 10.0, 1e-3
+    link = tsq.tsq_link(W, gamma, eps)
+    rate = tsq.tsq_link_best_rate(link, 1e5, 1e8, 2000)
+
+    def lc(w, layer):
+        return (0.002 + 0.0005 * w) * layer if w else 0.0
+    seen = set()
+    for D in (10.0, 1.0, 0.5, 0.2, 0.1, 0.05, 0.03, 0.02, 0.01, 0.003):
+        got = tsq.tsq_early_exit_walk(link, rate, D, max_tokens, layers, lc, sizes.bits)
+        want = LO.early_exit_walk(W, gamma, eps, rate, D, max_tokens, layers, lc, oracle_bits)
+        assert (got.action, got.with_kv, got.tokens, got.layer, got.sent_tokens) == want[:5], D
+        assert got.latency == pytest.approx(want[5], rel=1e-12)
+        seen.add(got.action)
+    assert len(seen) >= 2 and sizes.compress_calls > 0

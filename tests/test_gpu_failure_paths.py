@@ -1,6 +1,7 @@
-"""Error paths of the single-pass compress that the host can force without breaking a kernel: every
-device-side wait is bounded, so a workspace in an arbitrary state ends in TSQ_ERR_INTERNAL in the
-blob's header, never in a hang, and tsq_workspace_reset brings the workspace back."""
+"""Error paths of the single-pass compress that the host can force without breaking a kernel: a
+workspace that was not reset for the plan's shape is left alone and reported as TSQ_ERR_FORMAT; one of
+the right shape in an arbitrary state ends in TSQ_ERR_INTERNAL in the blob's header (every device-side
+wait is bounded), never in a hang; tsq_workspace_reset brings the workspace back."""
 import numpy as np
 import pytest
 
@@ -20,11 +21,94 @@ def tsq():
     return m
 
 
-def test_a_workspace_that_was_never_reset_is_reported_and_recovers(tsq, oracle):
-    """A workspace of all-ones bytes: the error word is set, the table words carry no valid tag and
-    the ticket counters wrap around.  Every token index the kernel forms from them is still checked
-    against the token count, and every store against its section, so the call runs to its end and
-    says TSQ_ERR_INTERNAL; after a reset the same buffers give the oracle's blob."""
+CTL_ERROR, CTL_TOKENS, CTL_HIDDEN = 1, 2, 3       # 32-bit words at the start of a workspace
+
+
+@pytest.mark.parametrize("pipeline", ["fused", "staged"])
+def test_a_workspace_of_another_shape_is_left_alone_and_reported(tsq, oracle, pipeline):
+    """A workspace that was never reset (all-ones bytes here), and one reset for a plan of another shape:
+    the call stores a header with TSQ_ERR_FORMAT and nothing else, the workspace keeps every byte, and the
+    plan it was reset for still gets the oracle's blob from it."""
+    import torch
+    x = synth.make_c2(tokens=600)
+    T, H = x.shape
+    plan = tsq.Plan(T, H, "f16", 8.0, (2, 3, 4, 6, 8), 0.05, pipeline=pipeline)
+    xd = torch.from_numpy(x.view(np.int16)).cuda()
+    blob = plan.new_blob()
+    ws = torch.empty(int(plan.layout.workspace_bytes), dtype=torch.uint8, device="cuda")
+    ws.fill_(0xFF)
+    print("compress on a workspace of all-ones bytes", flush=True)
+    plan.compress(xd, blob, ws)
+    info = plan.info(blob, check=False)
+    assert info.return_status == tsq.TSQ_ERR_FORMAT and info.status == tsq.TSQ_ERR_FORMAT
+    assert bool((ws == 0xFF).all())
+    # a smaller plan's workspace
+    small = tsq.Plan(200, H, "f16", 8.0, (2, 3, 4, 6, 8), 0.05, pipeline=pipeline)
+    ws2 = small.new_workspace()
+    torch.cuda.synchronize()
+    before = ws2.clone()
+    print("compress on the workspace of a 200-token plan", flush=True)
+    plan.compress(xd, blob, ws2)
+    assert plan.info(blob, check=False).return_status == tsq.TSQ_ERR_FORMAT
+    assert torch.equal(ws2, before)
+    out = torch.full((T, H), 0x1234, dtype=torch.int16, device="cuda")
+    plan.decompress(blob, out)                              # refused: the output stays as it was
+    torch.cuda.synchronize()
+    assert bool((out == 0x1234).all())
+    ref = oracle.compress(x[:200], oracle.F16, 8.0, (2, 3, 4, 6, 8), 0.05, 1)
+    b2 = small.compress(xd[:200].contiguous(), None, ws2)
+    assert small.info(b2).status == 0
+    sec = small.sections(b2)
+    for k in SECTIONS:
+        assert np.array_equal(sec[k], getattr(ref, k)), k
+
+
+def test_a_failed_workspace_stays_failed_until_it_is_reset(tsq, oracle):
+    """The error word of a workspace set by hand (as a call whose wait expired leaves it): every call on it,
+    also on a blob that still holds a good header from before, ends with TSQ_ERR_INTERNAL; the blocking call
+    with TSQ_PIPE_AUTO resets the workspace and compresses again with the staged kernels."""
+    import torch
+    x = synth.make_c2(tokens=900)
+    T, H = x.shape
+    ref = oracle.compress(x, oracle.F16, 8.0, (2, 3, 4, 6, 8), 0.05, 1, nthreads=8)
+    plan = tsq.Plan(T, H, "f16", 8.0, (2, 3, 4, 6, 8), 0.05, pipeline="auto")
+    xd = torch.from_numpy(x.view(np.int16)).cuda()
+    ws = plan.new_workspace()
+    blob = plan.compress(xd, None, ws)
+    assert plan.info(blob).status == 0                      # a good header is in the blob now
+    ws.view(torch.int32)[CTL_ERROR] = 1
+    for i in range(2):
+        print("call %d on the failed workspace" % i, flush=True)
+        plan.compress(xd, blob, ws)
+        info = plan.info(blob, check=False)
+        assert info.return_status == tsq.TSQ_ERR_INTERNAL and info.status == tsq.TSQ_ERR_INTERNAL
+    print("the blocking call", flush=True)
+    info = tsq.tsq_compress_blocking(plan.handle, xd.data_ptr(), blob.data_ptr(), ws.data_ptr(), plan._stream())
+    assert info.return_status == tsq.TSQ_OK and info.status == 0 and info.nnz == ref.nnz
+    sec = plan.sections(blob)
+    for k in SECTIONS:
+        assert np.array_equal(sec[k], getattr(ref, k)), k
+    # the workspace is usable again by the ordinary call
+    blob.zero_()
+    plan.compress(xd, blob, ws)
+    assert plan.info(blob).status == 0
+    assert np.array_equal(plan.sections(blob)["payload"], ref.payload)
+    # the blocking call on a workspace that was never reset
+    ws.fill_(0xFF)
+    info = tsq.tsq_compress_blocking(plan.handle, xd.data_ptr(), blob.data_ptr(), ws.data_ptr(), plan._stream())
+    assert info.return_status == tsq.TSQ_OK and np.array_equal(plan.sections(blob)["payload"], ref.payload)
+    # a plan that insists on the single pass gets the error, not the second try
+    fused = tsq.Plan(T, H, "f16", 8.0, (2, 3, 4, 6, 8), 0.05, pipeline="fused")
+    ws.view(torch.int32)[CTL_ERROR] = 1
+    info = tsq.tsq_compress_blocking(fused.handle, xd.data_ptr(), blob.data_ptr(), ws.data_ptr(), plan._stream(), check=False)
+    assert info.return_status == tsq.TSQ_ERR_INTERNAL
+
+
+def test_a_workspace_in_an_arbitrary_state_is_reported_and_recovers(tsq, oracle):
+    """A workspace of all-ones bytes behind a control block that carries the right shape: the error word is
+    set, the table words carry no valid tag and the ticket counters wrap around.  Every token index the kernel
+    forms from them is still checked against the token count, and every store against its section, so the
+    call runs to its end and says TSQ_ERR_INTERNAL; after a reset the same buffers give the oracle's blob."""
     import torch
     x = synth.make_c2(tokens=3000)                         # more tokens than workgroups: tickets are drawn
     T, H = x.shape
@@ -33,9 +117,11 @@ def test_a_workspace_that_was_never_reset_is_reported_and_recovers(tsq, oracle):
     xd = torch.from_numpy(x.view(np.int16)).cuda()
     ws = torch.empty(int(plan.layout.workspace_bytes), dtype=torch.uint8, device="cuda")
     ws.fill_(0xFF)
+    ws.view(torch.int32)[CTL_TOKENS] = T
+    ws.view(torch.int32)[CTL_HIDDEN] = H
     blob = plan.new_blob()
     blob.zero_()
-    print("compress on a workspace of all-ones bytes", flush=True)
+    print("compress on a workspace of all-ones bytes with the right shape in it", flush=True)
     plan.compress(xd, blob, ws)
     info = plan.info(blob, check=False)
     assert info.return_status == tsq.TSQ_ERR_INTERNAL

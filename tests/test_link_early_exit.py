@@ -73,6 +73,63 @@ def test_ladder_by_hand():
     assert LO.early_exit(deadline=10.0, **args) == (LO.FEWER_TOKENS, 0, 0, 0.0)
 
 
+def walk_case(deadline):
+    """Two tokens at most, two layers, a link of 16 s per bit (see test_ladder_by_hand).  Raw output: 10 bits
+    per token and layer with the cache, 4 without; compressed: 5 / 2 per token kept and layer.  L_c = w + layer / 10."""
+    def bits(w, layer, with_kv, compressed, keep):
+        per = (5 if with_kv else 2) if compressed else (10 if with_kv else 4)
+        return float(per * keep * layer)
+    return LO.early_exit_walk(1.0, 1.0, 1e-3, 1.0, deadline, 2, 2, lambda w, layer: w + layer / 10.0, bits)
+
+
+def test_walk_by_hand():
+    # raw latencies at (w, layer) with the cache: (1,1) 1.1+160, (1,2) 1.2+320, (2,1) 2.1+320, (2,2) 2.2+640
+    # no step exceeds the deadline: every step runs, the whole output goes out compressed (5*2*2 = 20 bits)
+    assert walk_case(700.0) == (LO.COMPLETED, 1, 2, 2, 2, 2.2 + 320.0)
+    # (2,2) is the first step above 400: compressed it takes 2.2 + 320 <= 400
+    assert walk_case(400.0) == (LO.COMPRESSED, 1, 2, 2, 2, 322.2)
+    # (1,2) 321.2 > 200: compressed 1.2 + 160 fits
+    assert walk_case(200.0) == (LO.COMPRESSED, 1, 1, 2, 1, 161.2)
+    # (1,1) 161.1 > 100: compressed 81.1 fits
+    assert walk_case(100.0) == (LO.COMPRESSED, 1, 1, 1, 1, 81.1)
+    # (1,1): compressed 81.1 > 50; without the cache 1.1 + 32 fits, and the printed steps go on with I_kv = 0:
+    # raw without the cache (1,2) 1.2+128 > 50 -> compressed 1.2 + 64 > 50 -> one token less: nothing left
+    assert walk_case(50.0) == (LO.FEWER_TOKENS, 0, 1, 2, 0, 0.0 + 0.2)
+    # the same with more room: (1,2) compressed without the cache 65.2 fits
+    assert walk_case(70.0) == (LO.COMPRESSED, 0, 1, 2, 1, 65.2)
+    # nothing fits at the first step: 161.1, 81.1, 33.1 all above 20 -> no tokens, L_c(0, 1) = 0.1
+    assert walk_case(20.0) == (LO.FEWER_TOKENS, 0, 1, 1, 0, 0.1)
+
+
+def test_walk_agrees_with_the_single_step_ladder():
+    """With one layer, at the (w, 1) where the walk stops, the one-step ladder fed with the same sizes
+    decides the same (whenever the walk has not dropped the cache at an earlier step)."""
+    g = np.random.Generator(np.random.PCG64(21))
+    W, gamma, eps = PAPER["W"], PAPER["gamma"], PAPER["eps"]
+    R = LO.best_rate(W, gamma, 1e5, 1e8, 500)
+    hits = 0
+    for _ in range(300):
+        wmax = int(g.integers(1, 12))
+        hid = np.concatenate([[0], np.cumsum(g.integers(2000, 40000, wmax))]).tolist()     # compressed hidden state, by tokens
+        kvc = float(g.uniform(1.0, 30.0))
+        lcs = np.concatenate([[0.0], np.cumsum(g.uniform(1e-4, 3e-3, wmax))]).tolist()
+        D = 10 ** g.uniform(-4, 0)
+
+        def bits(w, layer, with_kv, compressed, keep):
+            b = hid[keep] * (1.0 + (kvc if with_kv else 0.0))
+            return b if compressed else 3.0 * b
+        got = LO.early_exit_walk(W, gamma, eps, R, D, wmax, 1, lambda w, layer: lcs[w], bits)
+        w = got[2]
+        one = LO.early_exit(W, gamma, eps, R, D, lcs[: w + 1], bits(w, 1, 1, 0, w), bits(w, 1, 1, 1, w), hid[: w + 1])
+        if got[0] == LO.COMPRESSED and got[1] == 1:
+            assert one[:3] == (LO.COMPRESSED, 1, w) and one[3] == got[5]
+            hits += 1
+        elif got[0] == LO.FEWER_TOKENS and one[0] == LO.FEWER_TOKENS:
+            assert (one[2], one[3]) == (got[4], got[5])
+            hits += 1
+    assert hits > 100
+
+
 # ---------------------------------------------------------------- the library against the oracle
 
 def link(W, gamma, eps):
@@ -128,3 +185,35 @@ def test_library_ladder_matches():
         assert got.latency == pytest.approx(want[3], rel=1e-12)
         seen.add(got.action)
     assert seen == {0, 1, 2, 3}
+
+
+def test_library_walk_matches():
+    g = np.random.Generator(np.random.PCG64(33))
+    W, gamma, eps = PAPER["W"], PAPER["gamma"], PAPER["eps"]
+    L = link(W, gamma, eps)
+    R = LO.best_rate(W, gamma, 1e5, 1e8, 500)
+    seen = set()
+    for _ in range(300):
+        wmax, layers = int(g.integers(1, 10)), int(g.integers(1, 6))
+        per_tok = g.integers(2000, 40000, wmax + 1).astype(np.float64)
+        kvc, c0, c1 = float(g.uniform(0.5, 20.0)), float(g.uniform(1e-5, 1e-3)), float(g.uniform(1e-5, 1e-3))
+        D = 10 ** g.uniform(-4, 0.5)
+
+        def bits(w, layer, with_kv, compressed, keep):
+            b = per_tok[:keep].sum() * (1.0 + (kvc * layer if with_kv else 0.0))
+            return b if compressed else 3.5 * b
+
+        def lc(w, layer):
+            return c0 * w + c1 * w * layer
+        want = LO.early_exit_walk(W, gamma, eps, R, D, wmax, layers, lc, bits)
+        got = tsq.tsq_early_exit_walk(L, R, D, wmax, layers, lc, bits)
+        assert (got.action, got.with_kv, got.tokens, got.layer, got.sent_tokens) == want[:5]
+        assert got.latency == pytest.approx(want[5], rel=1e-12)
+        seen.add((got.action, got.with_kv))
+    assert {(1, 1), (1, 0), (3, 0), (4, 1)} <= seen
+    # a callback that fails ends the walk
+    with pytest.raises(ZeroDivisionError):
+        tsq.tsq_early_exit_walk(L, R, 1.0, 2, 2, lambda w, layer: 1 / 0, lambda *a: 1.0)
+    with pytest.raises(tsq.TsqError):
+        tsq.tsq_early_exit_walk(L, R, 1.0, 2, 2, lambda w, layer: -1.0, lambda *a: 1.0)
+    assert tsq.lib().tsq_early_exit_walk(None, None) == tsq.TSQ_ERR_INVALID_ARG
