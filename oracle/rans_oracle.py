@@ -157,3 +157,62 @@ def encode(c, hist: np.ndarray):
 
 def decode_codes(tables, off, streams: bytes, bits, hidden: int, t: int) -> np.ndarray:
     return decode_token(streams[int(off[t]):int(off[t + 1])], hidden, tables[int(bits[t]) - 2])
+
+
+# ---------------------------------------------------------------- the same coder compiled (rans_oracle.c)
+
+_C_SRC = __import__("os").path.join(__import__("os").path.dirname(__import__("os").path.abspath(__file__)), "rans_oracle.c")
+_C_LIB = _C_SRC[:-2] + "_c.so"
+_clib = None
+
+
+def build_c(force: bool = False) -> str:
+    """Compile rans_oracle.c with gcc."""
+    import os
+    import subprocess
+    if force or not os.path.exists(_C_LIB) or os.path.getmtime(_C_LIB) < os.path.getmtime(_C_SRC):
+        tmp = _C_LIB + ".tmp.%d" % os.getpid()
+        subprocess.run(["gcc", "-std=c11", "-O2", "-fopenmp", "-fPIC", "-shared", "-Wall", "-Wextra", "-o", tmp, _C_SRC],
+                       check=True)
+        os.replace(tmp, _C_LIB)
+    return _C_LIB
+
+
+def _c():
+    global _clib
+    if _clib is None:
+        import ctypes as C
+        L = C.CDLL(build_c())
+        L.ranso_encode_token.restype = C.c_uint32
+        L.ranso_encode_token.argtypes = [C.c_void_p, C.c_uint32, C.c_void_p, C.c_void_p]
+        L.ranso_encode.restype = C.c_uint64
+        L.ranso_encode.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_uint32, C.c_uint32, C.c_void_p, C.c_void_p,
+                                   C.c_uint64]
+        _clib = L
+    return _clib
+
+
+def encode_token_c(codes, freq) -> bytes:
+    """encode_token through the compiled coder."""
+    codes = np.ascontiguousarray(codes, np.uint8)
+    f = np.zeros(256, np.uint16)
+    f[: len(freq)] = freq
+    out = np.zeros(4 * CODERS + 2 * len(codes) + 4, np.uint8)
+    n = _c().ranso_encode_token(codes.ctypes.data, len(codes), f.ctypes.data, out.ctypes.data)
+    assert n > 0, "a code that the table does not know"
+    return out[:n].tobytes()
+
+
+def encode_codes_c(codes, bits, tables):
+    """codes: u8 [T, H]; bits: u8 [T]; tables: u16 [7, 256] -> (stream offsets u64 [T+1], streams u8)."""
+    codes = np.ascontiguousarray(codes, np.uint8)
+    bits = np.ascontiguousarray(bits, np.uint8)
+    tables = np.ascontiguousarray(tables, np.uint16)
+    T, H = codes.shape
+    cap = T * (4 * CODERS + 2 * H + 4)
+    off = np.zeros(T + 1, np.uint64)
+    streams = np.zeros(cap, np.uint8)
+    n = _c().ranso_encode(codes.ctypes.data, bits.ctypes.data, tables.ctypes.data, T, H, off.ctypes.data,
+                          streams.ctypes.data, cap)
+    assert n > 0 or T == 0
+    return off, streams[: int(n)].copy()

@@ -135,6 +135,12 @@ void tsqo_aiq_row(const float *a, uint32_t H, float amax, int b,
 void tsqo_select_row(const float *a, uint32_t H, float amax, uint32_t bit_mask,
                      float budget, int32_t mode, tsqo_token_info *info)
 {
+    tsqo_select_row_rule(a, H, amax, bit_mask, budget, mode, TSQO_RETURN_LAST_PASSING, info);
+}
+
+void tsqo_select_row_rule(const float *a, uint32_t H, float amax, uint32_t bit_mask,
+                          float budget, int32_t mode, int32_t rule, tsqo_token_info *info)
+{
     int widths[8], k = 0;
     for (int b = 8; b >= 2; --b)                 /* allowed widths, descending */
         if (bit_mask & (1u << b)) widths[k++] = b;
@@ -185,9 +191,11 @@ void tsqo_select_row(const float *a, uint32_t H, float amax, uint32_t bit_mask,
             R *= (double)ss0;
             viol = L > R;
         }
-        if (viol) break;                         /* keep the last width that passed */
+        if (viol && rule == TSQO_RETURN_LAST_PASSING)
+            break;                               /* keep the last width that passed */
         sel   = bi;
         sel_s = s;
+        if (viol) break;                         /* as printed: the failing width is what is returned */
     }
 
     info->amax   = amax;
@@ -276,7 +284,7 @@ int tsqo_compress(const tsqo_config *cfg, const uint16_t *x,
         float   *a   = (float *)malloc(sizeof(float) * (size_t)H);
         uint32_t cnt; float amax;
         tsqo_ts_row(x + (size_t)t * H, H, cfg->dtype, cfg->tau, out, a, &cnt, &amax);
-        tsqo_select_row(a, H, amax, cfg->bit_mask, cfg->budget, cfg->mode, &ti[t]);
+        tsqo_select_row_rule(a, H, amax, cfg->bit_mask, cfg->budget, cfg->mode, cfg->rule, &ti[t]);
         ti[t].cnt = cnt;
         bits[t]   = (uint8_t)ti[t].bits;
         scale[t]  = ti[t].scale;

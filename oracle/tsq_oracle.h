@@ -41,6 +41,14 @@ extern "C" {
 #define TSQO_BUDGET_LSB     0   /* Algorithm 1's delta > Delta, in code LSBs        */
 #define TSQO_BUDGET_REL_RMS 1   /* mean deviation vs budget * (row RMS), see .c    */
 
+/* What Algorithm 1 returns when a candidate width exceeds the budget.  The steps as printed
+ * quantize at the candidate, test, and on failure return THAT quantization ("break" comes after the
+ * assignment of the result); the prose says the descent avoids excessive distortion, which fits the
+ * last width that still passed.  LAST_PASSING is the reading the library defaults to; AS_PRINTED is
+ * the printed order of steps.  If no candidate fails both give the smallest allowed width. */
+#define TSQO_RETURN_LAST_PASSING 0
+#define TSQO_RETURN_AS_PRINTED   1
+
 /* Rows whose inlier absmax is below this are quantized as all-zero rows
  * (r = s = 0): below it Q_b/amax can overflow binary32. */
 #define TSQO_AMAX_FLOOR 0x1p-100f
@@ -53,6 +61,7 @@ typedef struct {
     uint32_t bit_mask;   /* bit b set <=> width b allowed, 2 <= b <= 8       */
     float    budget;     /* Delta (LSB mode) or epsilon (REL_RMS mode), >= 0 */
     int32_t  mode;       /* TSQO_BUDGET_*                                    */
+    int32_t  rule;       /* TSQO_RETURN_*: which width Algorithm 1 returns   */
 } tsqo_config;
 
 typedef struct {
@@ -82,9 +91,12 @@ void tsqo_ts_row(const uint16_t *x, uint32_t H, int32_t dtype, float tau,
 void tsqo_aiq_row(const float *a, uint32_t H, float amax, int b,
                   int32_t *m, float *r, float *s);
 
-/* Algorithm 1's descent over the allowed widths for one token. */
+/* Algorithm 1's descent over the allowed widths for one token (TSQO_RETURN_LAST_PASSING). */
 void tsqo_select_row(const float *a, uint32_t H, float amax, uint32_t bit_mask,
                      float budget, int32_t mode, tsqo_token_info *info);
+/* The same with the return rule chosen by the caller (TSQO_RETURN_*). */
+void tsqo_select_row_rule(const float *a, uint32_t H, float amax, uint32_t bit_mask,
+                          float budget, int32_t mode, int32_t rule, tsqo_token_info *info);
 
 /* Dense LSB-first bit stream of b-bit sign|magnitude codes, zero padded to a
  * 4-byte multiple.  dst must hold 4*ceil(H*b/32) bytes. */

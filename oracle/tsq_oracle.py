@@ -23,6 +23,7 @@ _LIB = os.path.join(_HERE, "libtsq_oracle.so")
 
 F16, BF16 = 0, 1
 BUDGET_LSB, BUDGET_REL_RMS = 0, 1
+RETURN_LAST_PASSING, RETURN_AS_PRINTED = 0, 1
 
 
 def build(force: bool = False) -> str:
@@ -41,7 +42,7 @@ def build(force: bool = False) -> str:
 class _Config(C.Structure):
     _fields_ = [("tokens", C.c_uint32), ("hidden", C.c_uint32), ("dtype", C.c_int32),
                 ("tau", C.c_float), ("bit_mask", C.c_uint32), ("budget", C.c_float),
-                ("mode", C.c_int32)]
+                ("mode", C.c_int32), ("rule", C.c_int32)]
 
 
 class _TokenInfo(C.Structure):
@@ -71,6 +72,8 @@ def lib():
         L.tsqo_ts_row.argtypes = [vp, C.c_uint32, C.c_int32, C.c_float, vp, vp, vp, vp]
         L.tsqo_aiq_row.restype = None
         L.tsqo_aiq_row.argtypes = [vp, C.c_uint32, C.c_float, C.c_int, vp, vp, vp]
+        L.tsqo_select_row_rule.restype = None
+        L.tsqo_select_row_rule.argtypes = [vp, C.c_uint32, C.c_float, C.c_uint32, C.c_float, C.c_int32, C.c_int32, vp]
         L.tsqo_select_row.restype = None
         L.tsqo_select_row.argtypes = [vp, C.c_uint32, C.c_float, C.c_uint32, C.c_float,
                                       C.c_int32, vp]
@@ -142,12 +145,13 @@ def aiq_row(a: np.ndarray, amax, b: int):
     return m, np.float32(r[0]), np.float32(s[0])
 
 
-def select_row(a: np.ndarray, amax, bit_set, budget: float, mode: int):
-    """Algorithm 1 on one token -> numpy record (TOKEN_INFO_DTYPE)."""
+def select_row(a: np.ndarray, amax, bit_set, budget: float, mode: int, rule: int = 0):
+    """Algorithm 1 on one token -> numpy record (TOKEN_INFO_DTYPE).  rule: RETURN_LAST_PASSING (the
+    default reading) or RETURN_AS_PRINTED (the width that failed the test is returned)."""
     a = np.ascontiguousarray(a, dtype=np.float32)
     info = np.zeros(1, TOKEN_INFO_DTYPE)
-    lib().tsqo_select_row(_p(a), a.size, np.float32(amax), bit_mask(bit_set),
-                          np.float32(budget), int(mode), _p(info))
+    lib().tsqo_select_row_rule(_p(a), a.size, np.float32(amax), bit_mask(bit_set),
+                               np.float32(budget), int(mode), int(rule), _p(info))
     return info[0]
 
 
@@ -198,11 +202,11 @@ class Compressed:
 
 
 def compress(x: np.ndarray, dtype: int, tau: float, bit_set, budget: float, mode: int,
-             nthreads: int = 1) -> Compressed:
+             nthreads: int = 1, rule: int = 0) -> Compressed:
     """TS + TAB-Q of a [T, H] array of raw 16-bit values."""
     x = np.ascontiguousarray(x, dtype=np.uint16)
     T, H = x.shape
-    cfg = _Config(T, H, dtype, tau, bit_mask(bit_set), budget, mode)
+    cfg = _Config(T, H, dtype, tau, bit_mask(bit_set), budget, mode, rule)
     bmax = max(bit_set)
     bits = np.zeros(T, np.uint8)
     scale = np.zeros(T, np.float32)
@@ -233,7 +237,7 @@ def compress(x: np.ndarray, dtype: int, tau: float, bit_set, budget: float, mode
 
 def decompress(c: Compressed, nthreads: int = 1) -> np.ndarray:
     """Eq. (dequnt): -> [T, H] raw 16-bit values."""
-    cfg = _Config(c.tokens, c.hidden, c.dtype, 1.0, 0, 0.0, 0)
+    cfg = _Config(c.tokens, c.hidden, c.dtype, 1.0, 0, 0.0, 0, 0)
     out = np.zeros((c.tokens, c.hidden), np.uint16)
     payload = np.ascontiguousarray(c.payload)
     if payload.size == 0:

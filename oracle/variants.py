@@ -77,7 +77,9 @@ def baseline(x, dtype, tau, bit_set, budget, mode) -> Outcome:
 
 
 def literal_break(x, dtype, tau, bit_set, budget, mode) -> Outcome:
-    """The width at which the test first fails (the smallest allowed width if it never fails)."""
+    """The width at which the test first fails (the smallest allowed width if it never fails).  Derived
+    here from the default descent's record (how many candidates it evaluated); the C file's own switch
+    (TSQO_RETURN_AS_PRINTED) must give the same widths, which tests check."""
     a, amax, sign = _split(x, dtype, tau)
     W = _widths(bit_set)
     T = x.shape[0]

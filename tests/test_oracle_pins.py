@@ -47,8 +47,9 @@ def rhe(fr: Fraction) -> int:
     return fl
 
 
-def brute_select(a_fr, amax_fr, bit_set, budget_fr, mode):
-    """Algorithm 1 in exact rationals, for rows where binary32 is exact."""
+def brute_select(a_fr, amax_fr, bit_set, budget_fr, mode, as_printed=False):
+    """Algorithm 1 in exact rationals, for rows where binary32 is exact.  as_printed: the width that
+    fails the test is the one returned (the printed order of steps) instead of the last that passed."""
     H = len(a_fr)
     ws = sorted(bit_set, reverse=True)
     Q = {b: 2 ** (b - 1) - 1 for b in ws}
@@ -70,6 +71,8 @@ def brute_select(a_fr, amax_fr, bit_set, budget_fr, mode):
         else:
             viol = Fraction(Q[ws[0]] * sad) ** 2 > (budget_fr * Q[b]) ** 2 * H * ss0
         if viol:
+            if as_printed:
+                sel = b
             break
         sel = b
     return sel, ss0, sads
@@ -321,6 +324,69 @@ def test_selection_returns_last_passing_width_not_the_violating_one(oracle):
     assert int(i1["bits"]) == 2 and int(i1["n_eval"]) == 2
     i2 = oracle.select_row(a, 1.0, (4, 8), 0.875, LSB)
     assert int(i2["bits"]) == 4 and float(i2["scale"]) == float(np.float32(1.0) / np.float32(7.0))
+
+
+@pytest.mark.parametrize("mode", [LSB, REL])
+def test_printed_return_rule_matches_exact_rational_brute_force(oracle, mode):
+    """Algorithm 1 with the return as printed (the quantization at the width that failed): the same
+    statistics, and the width one candidate further down wherever the descent stopped."""
+    g = np.random.Generator(np.random.PCG64(142 + mode))
+    subsets = [s for n in (1, 2, 3, 4) for s in itertools.combinations(range(2, 9), n)][::2]
+    budgets = ([Fraction(0), Fraction(1, 8), Fraction(1, 2), Fraction(2)] if mode == LSB
+               else [Fraction(0), Fraction(1, 32), Fraction(1, 8), Fraction(1, 2)])
+    checked, moved = 0, 0
+    for H in (8, 33):
+        for row in _dyadic_rows(g, 5, H):
+            a = np.array([float(v) for v in row], np.float32)
+            amax_fr = max(row)
+            for bs in subsets:
+                ws = sorted(bs, reverse=True)
+                for bud in budgets:
+                    sel, ss0, sads = brute_select(row, amax_fr, bs, bud, mode, as_printed=True)
+                    keep, _, _ = brute_select(row, amax_fr, bs, bud, mode)
+                    info = oracle.select_row(a, float(amax_fr), bs, float(bud), mode, oracle.RETURN_AS_PRINTED)
+                    assert int(info["bits"]) == sel, (H, bs, bud)
+                    assert int(info["ss0"]) == ss0 and info["sad"][1:1 + len(sads)].tolist() == sads
+                    assert int(info["n_eval"]) == len(sads)
+                    assert float(info["scale"]) == float(np.float32(float(amax_fr)) / np.float32(2 ** (sel - 1) - 1))
+                    # either the same width (nothing failed) or the next allowed width below the kept one
+                    assert sel == keep or sel == ws[ws.index(keep) + 1]
+                    moved += sel != keep
+                    checked += 1
+    assert checked > 1500 and moved > 200
+
+
+def test_printed_return_rule_by_hand_and_as_a_blob(oracle):
+    # the row of the test above: one full-scale element, seven at 0.22; B = {8, 4, 2}; SAD_4 = 7
+    a = np.array([1.0] + [0.22] * 7, np.float32)
+    i0 = oracle.select_row(a, 1.0, (2, 4, 8), 0.5, LSB, oracle.RETURN_AS_PRINTED)     # 7 > 4: fails at 4 -> 4 is returned
+    assert int(i0["bits"]) == 4 and int(i0["n_eval"]) == 1 and float(i0["scale"]) == float(np.float32(1.0) / np.float32(7.0))
+    i1 = oracle.select_row(a, 1.0, (2, 4, 8), 0.875, LSB, oracle.RETURN_AS_PRINTED)   # nothing fails -> 2, as before
+    assert int(i1["bits"]) == 2 and int(i1["n_eval"]) == 2
+    i2 = oracle.select_row(a, 1.0, (8,), 0.0, LSB, oracle.RETURN_AS_PRINTED)          # no candidate at all
+    assert int(i2["bits"]) == 8
+    # whole tensors: widths per token from select_row, everything else follows from the widths exactly as
+    # in the default reading (codes, offsets, sizes, round trip within half a step of the returned width)
+    x = synth.make_c2(tokens=48)
+    for eps in (0.05, 0.2):
+        c0 = oracle.compress(x, F16, 8.0, (2, 3, 4, 6, 8), eps, REL)
+        c1 = oracle.compress(x, F16, 8.0, (2, 3, 4, 6, 8), eps, REL, rule=oracle.RETURN_AS_PRINTED)
+        assert np.all(c1.bits <= c0.bits) and np.any(c1.bits < c0.bits)
+        assert np.array_equal(c1.row_ptr, c0.row_ptr) and np.array_equal(c1.out_col, c0.out_col)
+        sizes = np.array([oracle.row_bytes(x.shape[1], int(b)) for b in c1.bits], np.uint64)
+        assert np.array_equal(c1.pay_off, np.concatenate([[0], np.cumsum(sizes)]).astype(np.uint64))
+        for t in (0, 7, 47):
+            _, at, _, amax = oracle.ts_row(x[t], F16, 8.0)
+            info = oracle.select_row(at, amax, (2, 3, 4, 6, 8), eps, REL, oracle.RETURN_AS_PRINTED)
+            assert int(c1.bits[t]) == int(info["bits"]) and float(c1.scale[t]) == float(info["scale"])
+            m, _, s = oracle.aiq_row(at, amax, int(c1.bits[t]))
+            got_m, _ = oracle.unpack_row(c1.payload[int(c1.pay_off[t]): int(c1.pay_off[t + 1])], x.shape[1], int(c1.bits[t]))
+            assert np.array_equal(got_m, m)
+        out = oracle.widen(oracle.decompress(c1), F16)
+        v = oracle.widen(x, F16)
+        inl = np.abs(v) < 8.0
+        step = np.repeat(c1.scale[:, None], x.shape[1], axis=1)
+        assert np.all(np.abs(out[inl] - v[inl]) <= 0.5001 * step[inl] + 1e-3 * np.abs(v[inl]))
 
 
 def test_selection_limit_cases_and_monotonicity(oracle):

@@ -66,3 +66,15 @@ def test_whole_tensor_uses_one_width_and_the_largest_magnitude(oracle, V):
     b = int(o.bits[0])
     per = V.baseline(x, oracle.F16, 8.0, (b,), 0.05, 1)
     assert o.rel_rmse() > per.rel_rmse()
+
+
+def test_the_c_switch_gives_the_widths_of_the_python_variant(oracle, V):
+    """The printed return rule twice: derived in variants.py from the default descent's record, and as the
+    switch of the C descent itself, which is what the GPU path is compared with."""
+    for x, dt, tau, bs in ((synth.make_c1(), oracle.F16, 6.0, (2, 4, 8)),
+                           (synth.make_c2(tokens=64), oracle.F16, 8.0, (2, 3, 4, 6, 8)),
+                           (synth.make_c4(tokens=32), oracle.BF16, 10.0, (2, 3, 4, 5, 6, 8))):
+        for eps in (0.0, 0.05, 0.1, 0.2, 0.5):
+            want = V.literal_break(x, dt, tau, bs, eps, oracle.BUDGET_REL_RMS).bits
+            got = oracle.compress(x, dt, tau, bs, eps, oracle.BUDGET_REL_RMS, rule=oracle.RETURN_AS_PRINTED).bits
+            assert np.array_equal(got, want), eps

@@ -104,3 +104,31 @@ def test_whole_tensor_round_trip_and_size(oracle, R, E):
     # and the tables promise close to the pooled entropy of the report
     pooled = E.report(hist, c.bits, c.hidden)["per_width_table"] * c.tokens * c.hidden
     assert total <= pooled * 1.01 + 4096
+
+
+@pytest.mark.parametrize("H", [1, 2, 31, 32, 33, 2047, 2048, 2049, 5000])
+def test_compiled_coder_is_the_python_coder(R, H):
+    """rans_oracle.c against encode_token (which the hand-worked streams above pin), token by token and as a
+    whole tensor."""
+    # the hand-worked streams once more
+    assert R.encode_token_c([1], np.array([1024, 3072], np.uint16)) == np.array([21 * 4096 + 2048], "<u4").tobytes()
+    s = R.encode_token_c([0, 0], np.array([1, 4095], np.uint16))
+    assert np.frombuffer(s[:4], "<u4")[0] == 1 << 24 and np.frombuffer(s[4:6], "<u2")[0] == 0 and len(s) == 8
+    g = np.random.Generator(np.random.PCG64(H))
+    T = 7
+    bits = g.choice([2, 3, 5, 8], size=T).astype(np.uint8)
+    codes = np.zeros((T, H), np.uint8)
+    tables = np.zeros((7, 256), np.uint16)
+    for b in set(bits.tolist()):
+        p = g.dirichlet(np.full(1 << b, 0.3))
+        rows = np.flatnonzero(bits == b)
+        codes[rows] = g.choice(1 << b, size=(len(rows), H), p=p)
+        tables[b - 2] = R.normalize(np.bincount(codes[rows].ravel(), minlength=256))
+    off, streams = R.encode_codes_c(codes, bits, tables)
+    at = 0
+    for t in range(T):
+        want = R.encode_token(codes[t], tables[int(bits[t]) - 2])
+        assert R.encode_token_c(codes[t], tables[int(bits[t]) - 2]) == want
+        assert int(off[t]) == at and streams[at: at + len(want)].tobytes() == want
+        at += len(want)
+    assert int(off[T]) == at == len(streams)
