@@ -52,6 +52,13 @@ typedef enum {
 } tsq_budget_mode;
 
 typedef enum {
+    TSQ_RETURN_LAST_PASSING = 0, /* the last width whose statistic stayed within the budget (the largest
+                                    allowed width if the first candidate already exceeds it)      */
+    TSQ_RETURN_AS_PRINTED   = 1  /* Algorithm 1's steps in their printed order: the candidate is
+                                    quantized, tested, and on failure THAT quantization is returned */
+} tsq_return_rule;
+
+typedef enum {
     TSQ_PIPE_AUTO   = 0,      /* the library picks: TSQ_PIPE_FUSED wherever the device can hold
                                  two workgroups of its kernel at once, else TSQ_PIPE_STAGED     */
     TSQ_PIPE_STAGED = 1,      /* row statistics -> device-wide scan -> pack: three launches,
@@ -79,6 +86,9 @@ typedef struct {
     int32_t  mode;          /* tsq_budget_mode                                                  */
     int32_t  pipeline;      /* tsq_pipeline                                                     */
     uint64_t max_outliers;  /* capacity of the side stream in elements; 0 = tokens*hidden       */
+    int32_t  return_rule;   /* tsq_return_rule: which width the descent returns when a candidate
+                               exceeds the budget (both give the smallest width if none does)   */
+    int32_t  reserved;      /* 0                                                                */
 } tsq_config;
 
 typedef struct tsq_plan tsq_plan;   /* opaque, host memory, never written after tsq_plan_create,

@@ -89,6 +89,8 @@ tsq_status tsq_plan_create(const tsq_config *cfg, tsq_plan **out) {
     if (!(cfg->budget >= 0.0f)) return TSQ_ERR_INVALID_ARG;  // rejects NaN too
     if (cfg->mode != TSQ_BUDGET_LSB && cfg->mode != TSQ_BUDGET_REL_RMS) return TSQ_ERR_INVALID_ARG;
     if (cfg->pipeline < TSQ_PIPE_AUTO || cfg->pipeline > TSQ_PIPE_FUSED) return TSQ_ERR_INVALID_ARG;
+    if (cfg->return_rule != TSQ_RETURN_LAST_PASSING && cfg->return_rule != TSQ_RETURN_AS_PRINTED) return TSQ_ERR_INVALID_ARG;
+    if (cfg->reserved != 0) return TSQ_ERR_INVALID_ARG;
     if ((uint64_t)cfg->tokens * cfg->hidden >= (1ull << 32)) return TSQ_ERR_INVALID_ARG;
     if (cfg->hidden % 8 != 0 || cfg->hidden > kMaxHidden) return TSQ_ERR_UNSUPPORTED;
 
@@ -117,6 +119,7 @@ tsq_status tsq_plan_create(const tsq_config *cfg, tsq_plan **out) {
     p.tau = cfg->tau;
     p.budget = cfg->budget;
     p.mode = cfg->mode;
+    p.return_failing = cfg->return_rule == TSQ_RETURN_AS_PRINTED ? 1u : 0u;
     p.spin_limit = 1u << 20;
 
     tsq_layout &L = pl->layout;

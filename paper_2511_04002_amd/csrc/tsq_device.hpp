@@ -631,11 +631,15 @@ __device__ __forceinline__ Choice search_width(const Params &p, const Mags<DT> &
             uint32_t sad = live ? sad_run(m0, mi, b0 - bi) : 0u;
             uint32_t *red = ring + (turn++ & 3u) * 2 * kMaxWaves;
             if (i == 1) block_sum2_nw<NW>(sad, ss0, red); else block_sum1_nw<NW>(sad, red);
-            if (violates(p.mode, p.budget, p.hidden, Q0, (1u << (bi - 1)) - 1u, sad, ss0)) break;
+            // (Algorithm 1 as printed returns the quantization that failed the test; the default keeps
+            // the last one that passed)
+            const bool failed = violates(p.mode, p.budget, p.hidden, Q0, (1u << (bi - 1)) - 1u, sad, ss0);
+            if (failed && !p.return_failing) break;
             sel = bi;
             sel_i = i;
 #pragma unroll
             for (int g = 0; g < 8; ++g) m[g] = mi[g];
+            if (failed) break;
         }
     }
     Choice c;

@@ -74,7 +74,7 @@ struct Params {
     uint32_t thr_pk;        // smallest 16-bit magnitude pattern with value >= tau, in both halves
     uint32_t bit_mask;
     uint32_t n_widths;      // number of allowed widths
-    uint32_t pad0;
+    uint32_t return_failing;  // Algorithm 1 returns the width that failed the test (1) or the last that passed (0)
     uint64_t widths_pk;     // allowed widths, descending, one per byte (byte 0 = largest)
     float    tau;
     float    budget;

@@ -19,6 +19,7 @@ TSQ_ERR_HIP, TSQ_ERR_FORMAT, TSQ_ERR_INTERNAL, TSQ_ERR_NO_MEMORY = 4, 5, 6, 7
 TSQ_F16, TSQ_BF16 = 0, 1
 TSQ_BUDGET_LSB, TSQ_BUDGET_REL_RMS = 0, 1
 TSQ_PIPE_AUTO, TSQ_PIPE_STAGED, TSQ_PIPE_FUSED = 0, 1, 2
+TSQ_RETURN_LAST_PASSING, TSQ_RETURN_AS_PRINTED = 0, 1
 
 EXPORTS = ("tsq_plan_create", "tsq_plan_destroy", "tsq_plan_layout", "tsq_plan_blob_bytes",
            "tsq_plan_workspace_bytes", "tsq_workspace_reset", "tsq_compress", "tsq_compress_blocking",
@@ -39,7 +40,8 @@ TSQ_EXIT_CONTINUE, TSQ_EXIT_COMPRESSED, TSQ_EXIT_WITHOUT_KV, TSQ_EXIT_FEWER_TOKE
 class tsq_config(C.Structure):
     _fields_ = [("tokens", C.c_uint32), ("hidden", C.c_uint32), ("dtype", C.c_int32),
                 ("tau", C.c_float), ("bit_mask", C.c_uint32), ("budget", C.c_float),
-                ("mode", C.c_int32), ("pipeline", C.c_int32), ("max_outliers", C.c_uint64)]
+                ("mode", C.c_int32), ("pipeline", C.c_int32), ("max_outliers", C.c_uint64),
+                ("return_rule", C.c_int32), ("reserved", C.c_int32)]
 
 
 class tsq_layout(C.Structure):
@@ -417,15 +419,17 @@ def bit_mask(bit_set: Iterable[int]) -> int:
 _DTYPES = {"f16": TSQ_F16, "bf16": TSQ_BF16}
 _MODES = {"lsb": TSQ_BUDGET_LSB, "rel_rms": TSQ_BUDGET_REL_RMS}
 _PIPES = {"auto": TSQ_PIPE_AUTO, "staged": TSQ_PIPE_STAGED, "fused": TSQ_PIPE_FUSED}
+_RULES = {"last_passing": TSQ_RETURN_LAST_PASSING, "as_printed": TSQ_RETURN_AS_PRINTED}
 
 
 class Plan:
     """Owns one tsq_plan plus helpers that allocate torch buffers and pass their pointers."""
 
     def __init__(self, tokens: int, hidden: int, dtype: str, tau: float, bit_set: Iterable[int],
-                 budget: float, mode: str = "rel_rms", pipeline: str = "auto", max_outliers: int = 0):
+                 budget: float, mode: str = "rel_rms", pipeline: str = "auto", max_outliers: int = 0,
+                 return_rule: str = "last_passing"):
         self.cfg = tsq_config(tokens, hidden, _DTYPES[dtype], tau, bit_mask(bit_set), budget,
-                              _MODES[mode], _PIPES[pipeline], max_outliers)
+                              _MODES[mode], _PIPES[pipeline], max_outliers, _RULES[return_rule], 0)
         self.handle = tsq_plan_create(self.cfg)
         self.layout = tsq_plan_layout(self.handle)
         self.tokens, self.hidden, self.dtype = tokens, hidden, dtype

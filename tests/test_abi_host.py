@@ -58,6 +58,9 @@ def cfg(**kw):
     (dict(budget=float("nan")), tsq.TSQ_ERR_INVALID_ARG),
     (dict(mode=5), tsq.TSQ_ERR_INVALID_ARG),
     (dict(pipeline=9), tsq.TSQ_ERR_INVALID_ARG),
+    (dict(return_rule=2), tsq.TSQ_ERR_INVALID_ARG),
+    (dict(return_rule=-1), tsq.TSQ_ERR_INVALID_ARG),
+    (dict(reserved=1), tsq.TSQ_ERR_INVALID_ARG),
     (dict(tokens=1 << 20, hidden=4096), tsq.TSQ_ERR_INVALID_ARG),       # tokens*hidden >= 2^32
     (dict(hidden=772), tsq.TSQ_ERR_UNSUPPORTED),                        # not a multiple of 8
     (dict(hidden=65536), tsq.TSQ_ERR_UNSUPPORTED),

@@ -35,15 +35,16 @@ def widen(raw, dt):
 
 
 def check_parity(tsq, oracle, x, dtype, tau, bit_set, budget, mode="rel_rms", pipeline="staged",
-                 max_outliers=0, label=""):
+                 max_outliers=0, label="", rule="last_passing"):
     import torch
-    print("case", label, x.shape, dtype, tau, bit_set, budget, mode, pipeline, flush=True)
+    print("case", label, x.shape, dtype, tau, bit_set, budget, mode, pipeline, rule, flush=True)
     T, H = x.shape
-    ref = oracle.compress(x, DT[dtype], tau, bit_set, budget, MODE[mode], nthreads=8)
+    ref = oracle.compress(x, DT[dtype], tau, bit_set, budget, MODE[mode], nthreads=8,
+                          rule=oracle.RETURN_AS_PRINTED if rule == "as_printed" else oracle.RETURN_LAST_PASSING)
     ref_out = oracle.decompress(ref, nthreads=8)
 
     plan = tsq.Plan(T, H, dtype, tau, bit_set, budget, mode=mode, pipeline=pipeline,
-                    max_outliers=max_outliers or max(ref.nnz, 1))
+                    max_outliers=max_outliers or max(ref.nnz, 1), return_rule=rule)
     xd = torch.from_numpy(x.view(np.int16)).cuda()
     ws = plan.new_workspace()
     blob = plan.new_blob()
@@ -114,6 +115,29 @@ def test_c4_prefill_70b_full_size(tsq, oracle, pipeline, eps):
     ref, _ = check_parity(tsq, oracle, synth.make_c4(), "bf16", 10.0, (2, 3, 4, 5, 6, 8), eps, "rel_rms", pipeline,
                           label="C4")
     assert len(set(ref.bits.tolist())) >= 3
+
+
+@pytest.mark.parametrize("pipeline", PIPELINES)
+def test_algorithm_1_with_its_return_as_printed(tsq, oracle, pipeline):
+    """The descent that returns the quantization at the width that failed the test (tsq_config.return_rule =
+    TSQ_RETURN_AS_PRINTED) against the oracle's switch of the same name: whole blobs and decoded bits, on the
+    five workload shapes, in both budget modes, and on the width sets where the next candidate is far below."""
+    changed = 0
+    for name, x, dt, tau, bs in (("C1", synth.make_c1(), "f16", 6.0, (2, 4, 8)),
+                                 ("C2", synth.make_c2(tokens=700), "f16", 8.0, (2, 3, 4, 6, 8)),
+                                 ("C3", synth.make_c3(5), "f16", 8.0, (2, 4, 8)),
+                                 ("C4", synth.make_c4(tokens=1100), "bf16", 10.0, (2, 3, 4, 5, 6, 8)),
+                                 ("C5", synth.make_c5_seq(3, 300), "bf16", 8.0, (2, 3, 4, 5, 6, 7, 8))):
+        for budget, mode in ((0.05, "rel_rms"), (0.2, "rel_rms"), (0.0, "rel_rms"), (0.2, "lsb"), (float("inf"), "lsb")):
+            ref, _ = check_parity(tsq, oracle, x, dt, tau, bs, budget, mode, pipeline, label=name + " as printed",
+                                  rule="as_printed")
+            base = oracle.compress(x, DT[dt], tau, bs, budget, MODE[mode], nthreads=8)
+            assert np.all(ref.bits <= base.bits)
+            changed += int((ref.bits < base.bits).sum())
+    assert changed > 1000
+    x = synth.edge_rows(2056, "bf16", 6.0)
+    for bs in ((8,), (2, 8), (7, 8), (2, 3, 4, 5, 6, 7, 8)):
+        check_parity(tsq, oracle, x, "bf16", 6.0, bs, 0.1, "rel_rms", pipeline, label="edge as printed", rule="as_printed")
 
 
 @pytest.mark.parametrize("pipeline", PIPELINES)
