@@ -251,6 +251,16 @@ k_unpack(const Params p, const uint8_t *__restrict__ blob, uint16_t *__restrict_
     if (!token_in_range(p, width, po) || !csr_slice_ok(rp0, rp1, p.outlier_capacity))
         return;
 
+    // the token's first outliers (one per thread) are asked for together with its codes, not behind them
+    const uint16_t *col = reinterpret_cast<const uint16_t *>(blob + p.off_out_col);
+    const uint16_t *val = reinterpret_cast<const uint16_t *>(blob + p.off_out_val);
+    const bool has_first = rp0 + threadIdx.x < rp1;
+    uint32_t first_col = 0, first_val = 0;
+    if (has_first) {
+        first_col = col[rp0 + threadIdx.x];
+        first_val = val[rp0 + threadIdx.x];
+    }
+
     if (run < p.runs) {
         const uint32_t left = p.pieces - 4 * run;
         const uint32_t vp = left < 4 ? left : 4;
@@ -269,10 +279,10 @@ k_unpack(const Params p, const uint8_t *__restrict__ blob, uint16_t *__restrict_
     __syncthreads();
     // + T_above: outliers overwrite their slots with the stored bits
     {
-        const uint16_t *col = reinterpret_cast<const uint16_t *>(blob + p.off_out_col);
-        const uint16_t *val = reinterpret_cast<const uint16_t *>(blob + p.off_out_val);
         uint16_t *lrow16 = reinterpret_cast<uint16_t *>(lrow);
-        for (uint64_t k = rp0 + threadIdx.x; k < rp1; k += blockDim.x) {
+        if (has_first && column_ok(first_col, p.hidden))
+            lrow16[(first_col >> 5) * (2 * kRunLdsDw) + (first_col & 31u)] = (uint16_t)first_val;
+        for (uint64_t k = rp0 + threadIdx.x + blockDim.x; k < rp1; k += blockDim.x) {
             const uint32_t c = col[k];
             if (column_ok(c, p.hidden)) lrow16[(c >> 5) * (2 * kRunLdsDw) + (c & 31u)] = val[k];
         }
