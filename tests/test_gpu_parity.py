@@ -302,19 +302,20 @@ def test_token_counts_around_the_grid_size(tsq, oracle, pipeline, T, H):
 
 @pytest.mark.parametrize("pipeline", PIPELINES)
 def test_tokens_with_more_outliers_than_the_stash_holds(tsq, oracle, pipeline):
-    # rows whose outlier count exceeds what the single-pass kernel keeps in LDS (512) are placed
-    # by its direct path; mix them with ordinary rows and with rows that are all outliers
+    # rows with more outliers per wave than the single-pass kernel keeps in LDS (232 per wave of 2048 elements
+    # for this row length) take its re-read path; counts on both sides of that limit, mixed with ordinary
+    # rows and with rows that are all outliers
     g = np.random.Generator(np.random.PCG64(5))
     T, H = 300, 4096
     v = g.standard_normal((T, H))
     heavy = g.choice(T, 40, replace=False)
     for i, t in enumerate(heavy):
-        n = (513, 600, 1024, 2048, 4096)[i % 5]
+        n = (420, 460, 500, 513, 600, 1024, 2048, 4096)[i % 8]
         v[t, g.choice(H, n, replace=False)] = 50.0 * g.choice([-1.0, 1.0], n)
     x = synth.to_bf16_bits(v)
     ref, _ = check_parity(tsq, oracle, x, "bf16", 6.0, (2, 4, 8), 0.05, "rel_rms", pipeline, label="heavy rows")
     cnt = np.diff(ref.row_ptr.astype(np.int64))
-    assert (cnt > 512).sum() >= 40 and cnt.max() == H
+    assert (cnt > 512).sum() >= 20 and (cnt > 410).sum() >= 40 and cnt.max() == H
 
 
 @pytest.mark.parametrize("pipeline", PIPELINES)
