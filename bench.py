@@ -266,34 +266,6 @@ def main():
     ms_per_step, wall = (ms_graph, wall_graph) if args.graph else (ms_stream, wall_stream)
     assert plan.info(blobs[0]).status == 0
 
-    # for information, not the headline: the same K steps with consecutive steps on two streams (each its own
-    # workspace), as a server that handles independent tensors would enqueue them; the end of one step's
-    # kernels then overlaps the start of the next step's
-    ws2 = plan.new_workspace()
-    lanes = [(torch.cuda.Stream(), ws), (torch.cuda.Stream(), ws2)]
-    torch.cuda.synchronize()
-
-    def two_stream_pass(count):
-        for i in range(count):
-            k = (args.warmup + i) % nbuf
-            stream, w_i = lanes[i % 2]
-            with torch.cuda.stream(stream):
-                if parts:
-                    plan.compress_batch(xs[k], blobs[k], w_i, table=tin[k])
-                    plan.decompress_batch(blobs[k], outs[k], table=tout[k])
-                else:
-                    plan.compress(xs[k], blobs[k], w_i)
-                    plan.decompress(blobs[k], outs[k])
-    ms_two = None
-    if nbuf >= 2:               # with one buffer set consecutive steps would write the same blob
-        two_stream_pass(args.warmup)
-        torch.cuda.synchronize()
-        t0 = time.perf_counter()
-        two_stream_pass(args.steps)
-        torch.cuda.synchronize()
-        ms_two = (time.perf_counter() - t0) * 1e3 / args.steps
-        assert all(plan.info(b).status == 0 for b in blobs)
-
     # compress / decompress split of the same steps (events between the two calls: not the headline)
     n_split = min(args.steps, 200)
     evs = [[torch.cuda.Event(enable_timing=True) for _ in range(3)] for _ in range(n_split)]
@@ -349,7 +321,7 @@ def main():
                     "frac": ops / VALU_PEAK_LANE_OPS, "source": "profiles/" + rec["source"]}
     # what kernels that only move bytes reach here, over the same buffers
     if parts:
-        ceil = copy_ceilings(tsq, torch, [v[0] for v in xs], [v[0] for v in outs], parts[0].size * 2, plan._stream())
+        ceil = copy_ceilings(tsq, torch, xs[0], outs[0], parts[0].size * 2, plan._stream(), reps=2 * len(parts))
     else:
         ceil = copy_ceilings(tsq, torch, xs, outs, 2 * n, plan._stream())
     copy_pair_ms = (alg_c + alg_d) / (ceil["copy_GBps"] * 1e6)      # the pair's bytes at the copy kernel's rate
@@ -372,11 +344,7 @@ def main():
                    "outlier_fraction": round(rho, 6), "width_hist": list(info.width_hist),
                    "compression_ratio": round(2.0 * n / info.compressed_bytes, 3)},
         "launch_modes": {"stream_ms_per_step": ms_stream, "hip_graph_ms_per_step": ms_graph,
-                         "graph_holds_steps": graph_steps,
-                         "two_streams_ms_per_step": ms_two,
-                         "two_streams_pair_frac": (alg_c + alg_d) / ms_two / 1e6 / HBM_PEAK_GBS if ms_two else None,
-                         "two_streams_is": "host wall clock over the same K steps, consecutive steps alternating between two "
-                                           "streams (independent tensors): not the headline, which is one stream"},
+                         "graph_holds_steps": graph_steps},
         # the bar: algorithmic bytes of compress + decompress over the timed step, against the 8 TB/s peak
         "target": {"quantity": "roofline.pair_frac", "bar": 0.6, "met": pair_gbps / HBM_PEAK_GBS >= 0.6},
         "roofline": {"bound": "hbm", "kernel": dom, "achieved": achieved, "peak": HBM_PEAK_GBS,

@@ -12,9 +12,15 @@
  *   restore — Eq. (dequnt): unpack, dequantize, put the outliers back.
  *
  * All pointers named d_* are DEVICE pointers on the current HIP device; every
- * other pointer is a HOST pointer.  The library allocates no device memory,
- * keeps no global state (apart from the static workspace of tsq_compress_static),
- * and never synchronizes except where stated.
+ * other pointer is a HOST pointer.  The library allocates no device memory and never
+ * synchronizes the host except where stated.  The state it keeps per device is small: the static
+ * workspace of tsq_compress_static, and which stream the last single-pass compress call used.  Two
+ * such calls on different streams of one device are ordered one after the other (the later one's
+ * stream is made to wait for what the earlier one's stream holds at that moment; an event, no
+ * host synchronization): their kernels' workgroups wait for one another and would, sharing the
+ * device, keep each other from starting.  Calls on one stream, restore calls and the staged
+ * pipeline are not affected.  Calls recorded into a HIP graph are ordered by the graph only: do
+ * not replay two graphs that hold single-pass compress calls at the same time on one device.
  * `stream` is a hipStream_t passed as void* (NULL = the default stream).
  *
  * Errors are return codes only (no exceptions, no abort).

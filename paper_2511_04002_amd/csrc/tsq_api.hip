@@ -28,6 +28,8 @@ struct tsq_plan {
 
 namespace {
 
+constexpr int kStaticMaxDevicesForOrder = 64;
+
 uint64_t align_up(uint64_t v, uint64_t a) { return (v + a - 1) / a * a; }
 
 // value of a non-negative 16-bit pattern (sign bit clear), exact in double
@@ -218,6 +220,51 @@ tsq_status tsq_workspace_reset(const tsq_plan *plan, void *d_ws, void *stream) {
     return hip_rc(launch_ws_reset(plan->p, d_ws, stream));
 }
 
+// Single-pass compress kernels of different streams must not share the device.  Such a kernel's workgroups
+// wait for one another (for a token's place, which needs every token before it); one kernel alone always gets
+// all the workgroups it needs to run, but two of them, each holding compute-unit slots that the other one's
+// not yet started workgroups need, can keep each other waiting until the bounded waits expire.  So the
+// library orders them: a call on another stream than the previous call's (on the same device) first makes its
+// stream wait for what the previous call's stream holds at that moment (an event recorded at its end).  Calls
+// that stay on one stream pay nothing for this.  Under stream capture nothing is recorded: the calls of one
+// captured graph are ordered by the graph.
+struct FusedOrder {
+    hipEvent_t tail = nullptr;          // recorded at the end of last_stream when the stream changes
+    hipStream_t last_stream = nullptr;
+    bool any = false;
+};
+static std::mutex g_order_mutex;
+static FusedOrder g_order[kStaticMaxDevicesForOrder];
+
+static bool is_capturing(hipStream_t s) {
+    hipStreamCaptureStatus st = hipStreamCaptureStatusNone;
+    if (hipStreamIsCapturing(s, &st) != hipSuccess) { (void)hipGetLastError(); return false; }
+    return st != hipStreamCaptureStatusNone;
+}
+
+static int launch_fused_ordered(const Params &p, const Geometry &g, uint32_t grid, const void *d_in, void *d_blob,
+                                void *d_ws, void *stream) {
+    hipStream_t s = reinterpret_cast<hipStream_t>(stream);
+    int dev = -1;
+    if (is_capturing(s) || hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kStaticMaxDevicesForOrder)
+        return launch_fused(p, g, grid, d_in, d_blob, d_ws, stream);
+    std::lock_guard<std::mutex> lock(g_order_mutex);
+    FusedOrder &o = g_order[dev];
+    if (o.any && o.last_stream != s && !is_capturing(o.last_stream)) {
+        if (!o.tail && hipEventCreateWithFlags(&o.tail, hipEventDisableTiming) != hipSuccess) return (int)hipGetLastError();
+        // (a stream that its owner has destroyed in the meantime cannot hold unfinished work: errors are dropped)
+        if (hipEventRecord(o.tail, o.last_stream) == hipSuccess) {
+            const hipError_t e = hipStreamWaitEvent(s, o.tail, 0);
+            if (e != hipSuccess) return (int)e;
+        } else {
+            (void)hipGetLastError();
+        }
+    }
+    const int rc = launch_fused(p, g, grid, d_in, d_blob, d_ws, stream);
+    if (rc == 0) { o.last_stream = s; o.any = true; }
+    return rc;
+}
+
 // One compress call.  rows_per_tensor == 0: d_in is the tensor; otherwise d_in is a device table of
 // tensor pointers (the kernels pick the row's tensor from it).
 static tsq_status compress_call(const tsq_plan *plan, const void *d_in, uint32_t rows_per_tensor, void *d_blob,
@@ -235,7 +282,7 @@ static tsq_status compress_call(const tsq_plan *plan, const void *d_in, uint32_t
         if (!fits && plan->cfg.pipeline != TSQ_PIPE_AUTO) return st != TSQ_OK ? st : TSQ_ERR_UNSUPPORTED;
         if (fits) {
             p.fused_classes = grid < kTicketClasses ? grid : kTicketClasses;
-            return hip_rc(launch_fused(p, plan->g, grid, d_in, d_blob, d_ws, stream));
+            return hip_rc(launch_fused_ordered(p, plan->g, grid, d_in, d_blob, d_ws, stream));
         }
     }
     int e = launch_row_stats(p, plan->g, d_in, d_blob, d_ws, stream);

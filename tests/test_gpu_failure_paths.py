@@ -230,3 +230,32 @@ def test_a_damaged_blob_is_decompressed_without_leaving_its_sections(tsq, oracle
     rp[T // 2:] = g.integers(0, 2 ** 63, T + 1 - T // 2, dtype=np.uint64)
     run("row pointers (noise)", int(L.off_row_ptr), rp.view(np.uint8), list(range(0, T // 2 - 1)))
     run("columns (noise)", int(L.off_out_col), g.integers(0, 256, 2 * max(ref.nnz, 1), dtype=np.uint8), [])
+
+
+def test_calls_that_alternate_between_two_streams_do_not_stall_each_other(tsq, oracle):
+    """Two single-pass kernels that shared the device could hold the compute units that the other one's
+    workgroups still needed, until their bounded waits expired; the library therefore orders such calls.
+    Many short calls, alternating between two streams with a workspace each: every blob complete and
+    equal to the oracle's."""
+    import torch
+    x = synth.make_c2(tokens=2048)
+    T, H = x.shape
+    ref = oracle.compress(x, oracle.F16, 8.0, (2, 3, 4, 6, 8), 0.05, 1, nthreads=8)
+    plan = tsq.Plan(T, H, "f16", 8.0, (2, 3, 4, 6, 8), 0.05, pipeline="fused", max_outliers=max(ref.nnz, 1))
+    xd = torch.from_numpy(x.view(np.int16)).cuda()
+    lanes = [(torch.cuda.Stream(), plan.new_workspace(), [plan.new_blob() for _ in range(2)], plan.new_output())
+             for _ in range(2)]
+    torch.cuda.synchronize()
+    for i in range(600):
+        stream, ws, blobs, out = lanes[i % 2]
+        with torch.cuda.stream(stream):
+            plan.compress(xd, blobs[(i // 2) % 2], ws)
+            plan.decompress(blobs[(i // 2) % 2], out)
+        if i % 100 == 99:
+            print("step", i, flush=True)
+    torch.cuda.synchronize()
+    for _, _, blobs, out in lanes:
+        for b in blobs:
+            assert plan.info(b).status == 0
+            assert np.array_equal(plan.sections(b)["payload"], ref.payload)
+        assert np.array_equal(out.cpu().numpy().view(np.uint16), oracle.decompress(ref, nthreads=8))
