@@ -163,15 +163,18 @@ __device__ __forceinline__ void pack_to_image(const uint32_t (&m)[8], const Mags
 // ---------------------------------------------------------------- the scanner (workgroup 0, one wave)
 
 constexpr uint32_t kScanWavesMax = 4;   // waves of workgroup 0 that scan
-constexpr int kScanGroups = 16;         // groups of 64 table words per round: up to 1024 tokens, whatever the number of
-                                        // waves (a narrower window would cap the tokens per second of short rows)
+// Groups of 64 table words per round.  A round takes about 1.8 us, so the window caps the tokens per second:
+// 1024 tokens for the scanners of one to three waves (short rows, up to 300 tokens per us), 512 for four waves
+// (rows of 8192 elements and more: at most 160 tokens per us; the smaller window polls fewer lines that the
+// computing workgroups are writing to, which they notice)
+constexpr int scan_groups(int waves) { return waves >= 4 ? 8 : 16; }
 
 __device__ __forceinline__ uint64_t prefix_word(uint32_t tag, uint32_t ew, uint32_t ec) {
     return ((uint64_t)((tag << 30) | ew) << 32) | ec;
 }
 
 // The scanner: R waves of workgroup 0 (this one has index wv) work in rounds.  A round looks at
-// the next 64 * kScanGroups tokens from the frontier on, cut into groups of 64 that are dealt out to
+// the next 64 * scan_groups(R) tokens from the frontier on, cut into groups of 64 that are dealt out to
 // the waves in turn (group k to wave k % R).  Every wave sums up its groups' leading runs of
 // published tokens (lane l of a group is its l-th token: loads and stores are contiguous over
 // the wave) and leaves their lengths and totals in LDS; after a barrier every wave knows, from
@@ -183,7 +186,7 @@ __device__ __forceinline__ uint64_t prefix_word(uint32_t tag, uint32_t ew, uint3
 template <int R>
 __device__ void scan_tokens(const Params &p, uint8_t *blob, uint8_t *ws, uint32_t waves_total, uint32_t *lds,
                             uint32_t wv) {
-    constexpr int kScanPerWave = kScanGroups / R;
+    constexpr int kScanPerWave = scan_groups(R) / R;
     constexpr int kGroups = kScanPerWave * R;
     const uint32_t lane = threadIdx.x & 63u;
     const uint32_t T = p.tokens, C = p.fused_classes;
