@@ -124,8 +124,11 @@ struct RowPart { uint32_t w[16]; };   // the four 16-byte pieces a lane moves, a
 // that from the compiler): the loads name the global address space, so that they are ordinary
 // vector memory loads and not loads that might also hit LDS or scratch.
 typedef const __attribute__((address_space(1))) uint8_t *GlobalBytes;
+// spread: 16 to fetch the row; 0 makes every lane fetch the row's first piece (for a caller that must issue
+// the loads but has no row to fetch: one cache line instead of a whole row)
 template <bool FULL = false>
-__device__ __forceinline__ void fetch_row_part(const uint4 *__restrict__ src, uint32_t pieces, RowPart &pre) {
+__device__ __forceinline__ void fetch_row_part(const uint4 *__restrict__ src, uint32_t pieces, RowPart &pre,
+                                               uint32_t spread = 16u) {
     const uint32_t lane = threadIdx.x & 63u, wv = threadIdx.x >> 6;
     const GlobalBytes base = (GlobalBytes)src;
 #pragma unroll
@@ -134,7 +137,7 @@ __device__ __forceinline__ void fetch_row_part(const uint4 *__restrict__ src, ui
         uint32_t x = 0, y = 0, z = 0, w = 0;
         if (FULL || q < pieces) {
             // the input is read once: streaming load
-            const u32x4 v = __builtin_nontemporal_load((const __attribute__((address_space(1))) u32x4 *)(base + 16u * q));
+            const u32x4 v = __builtin_nontemporal_load((const __attribute__((address_space(1))) u32x4 *)(base + spread * q));
             x = v.x; y = v.y; z = v.z; w = v.w;
         }
         pre.w[4 * k] = x; pre.w[4 * k + 1] = y; pre.w[4 * k + 2] = z; pre.w[4 * k + 3] = w;

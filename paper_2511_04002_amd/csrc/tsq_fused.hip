@@ -629,11 +629,11 @@ k_fused(const Params p, const uint16_t *__restrict__ in, uint8_t *__restrict__ b
         uint64_t early = 0;
         if (have_old) early = prefix_load(pre + old.token + opaque_zero());
         // The next row starts its way from HBM (into registers; it goes to LDS at the end of the
-        // iteration).  The loads are issued on every path (without a next token the current row is read
-        // again), so that the number of loads younger than the prefix load is fixed and waiting for the
-        // prefix below does not wait for the row.
+        // iteration).  The loads are issued on every path (without a next token every lane reads the first
+        // piece of the current row, which costs one cache line), so that the number of loads younger than
+        // the prefix load is fixed and waiting for the prefix below does not wait for the row.
         fetch_row_part<FULL>(reinterpret_cast<const uint4 *>(input_row<BATCH>(p, in, tn != kNoToken ? tn : t, hidden)),
-                             pieces, pre_row);
+                             pieces, pre_row, tn != kNoToken ? 16u : 0u);
         uint32_t m[8];
         const Choice c = search_width<DT, NW>(p, mg, st.amax, owns, ring, turn, m);
         __builtin_amdgcn_s_setprio(0);
