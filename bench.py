@@ -247,23 +247,10 @@ def main():
         return e0.elapsed_time(e1) / args.steps, (time.perf_counter() - t0) * 1e3 / args.steps
 
     # both launch modes: the steps enqueued one by one, and replayed from a HIP graph that holds a block of
-    # them (K is a multiple of the block); the headline is the one asked for
-    graph_steps = max(d for d in range(1, min(args.steps, 100) + 1) if args.steps % d == 0)
-    side = torch.cuda.Stream()
-    side.wait_stream(torch.cuda.current_stream())
-    with torch.cuda.stream(side):
-        graph = torch.cuda.CUDAGraph()
-        with torch.cuda.graph(graph, stream=side):
-            for i in range(graph_steps):
-                step(args.warmup + i)
-    torch.cuda.current_stream().wait_stream(side)
-    for _ in range(max(1, args.warmup // graph_steps)):
-        graph.replay()                     # untimed
-    ms_graph, wall_graph = timed_region(graph)
-    for i in range(args.warmup):
-        step(i)
+    # them (K is a multiple of the block); the headline is the one asked for.  The stream pass comes first:
+    # once a graph has been captured and instantiated in the process, the same kernels enqueued on a stream
+    # take about 1.3 us longer each on this stack (measured: 84.4 -> 87.1 us per step), as they do in the graph
     ms_stream, wall_stream = timed_region(None)
-    ms_per_step, wall = (ms_graph, wall_graph) if args.graph else (ms_stream, wall_stream)
     assert plan.info(blobs[0]).status == 0
 
     # compress / decompress split of the same steps (events between the two calls: not the headline)
@@ -306,7 +293,6 @@ def main():
         v["GBps"] = v["alg_bytes"] / v["ms"] / 1e6
     dom = max(kern, key=lambda nm: kern[nm]["ms"])
     achieved = kern[dom]["GBps"]
-    pair_gbps = (alg_c + alg_d) / ms_per_step / 1e6
     pair_split_gbps = (alg_c + alg_d) / (ms_c + ms_d) / 1e6
     # counter figures: from the committed rocprofv3 summaries, and only while the kernels are the ones profiled
     rec = profile_records().get((w.name, pipe, args.eps, dom))
@@ -324,6 +310,22 @@ def main():
         ceil = copy_ceilings(tsq, torch, xs[0], outs[0], parts[0].size * 2, plan._stream(), reps=2 * len(parts))
     else:
         ceil = copy_ceilings(tsq, torch, xs, outs, 2 * n, plan._stream())
+    # the graph pass, last (see above)
+    graph_steps = max(d for d in range(1, min(args.steps, 100) + 1) if args.steps % d == 0)
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph, stream=side):
+            for i in range(graph_steps):
+                step(args.warmup + i)
+    torch.cuda.current_stream().wait_stream(side)
+    for _ in range(max(1, args.warmup // graph_steps)):
+        graph.replay()                     # untimed
+    ms_graph, wall_graph = timed_region(graph)
+    ms_per_step, wall = (ms_graph, wall_graph) if args.graph else (ms_stream, wall_stream)
+    assert plan.info(blobs[0]).status == 0
+    pair_gbps = (alg_c + alg_d) / ms_per_step / 1e6
     copy_pair_ms = (alg_c + alg_d) / (ceil["copy_GBps"] * 1e6)      # the pair's bytes at the copy kernel's rate
 
     res = {
