@@ -5,8 +5,7 @@
 // published, into the device-wide exclusive prefix (the exclusive scan that places the
 // variable-length outputs).  Every other workgroup computes tokens.  All tokens are handed
 // out by ticket counters, so a workgroup that has not started yet holds nothing that anybody
-// waits for: any set of resident workgroups that contains workgroup 0 runs the call to its
-// end (workgroups are dispatched in index order, so workgroup 0 is the first to start).
+// waits for (workgroups are dispatched in index order, so workgroup 0 is the first to start).
 //
 // Tickets: the computing workgroups are spread over C classes (g % C), class c owns the
 // tokens t with t % C == c and hands them out in ascending order from its own counter, so no
@@ -16,7 +15,7 @@
 // workgroup which tag the tables of this call use.
 //
 // Per token a workgroup publishes one 32-bit word (tag, payload words, outliers) in a table.
-// The scanner reads the table in order, up to 1024 words per round, and for the leading run of
+// The scanner reads the table in order, 512 or 1024 words per round, and for the leading run of
 // published tokens writes (tag, words before, outliers before) into a second table, and the
 // blob's pay_off / row_ptr entries on the way.  Nobody else adds anything up.  (One wave alone
 // does not keep up with 200 tokens per microsecond: its rounds are chains of dependent steps.)
@@ -30,9 +29,14 @@
 // outliers than its stash holds (rare) keeps none of them and takes them from the row again
 // when the token is stored.
 //
-// Progress: a workgroup waits (for a prefix) only after it has published its current token,
-// so the smallest unpublished token is always being computed by somebody who is not waiting;
-// the scanner waits for publications only.  Every wait is bounded by p.spin_limit anyway; an
+// Progress: a workgroup's tokens ascend, and what it waits for is the prefix of a token older
+// than the one it is computing.  So the smallest unpublished token is either being computed
+// (if its workgroup waits, then for a prefix that depends on published tokens only, and the
+// scanner waits for publications only), or not yet drawn, and then the workgroups of its class
+// hold older tokens only and one of them draws it.  That holds for one such kernel on the
+// device, with at least one workgroup of every class running; two of these kernels at once, each
+// with workgroups that have not started, can hold the slots that the other one's workgroups
+// need (the host side orders such launches).  Every wait is bounded by p.spin_limit anyway; an
 // expired wait raises the workspace's error word, which ends every other wait quickly, and the
 // scanner then writes status TSQ_ERR_INTERNAL.  The scanner alone writes the header.
 //
