@@ -338,10 +338,22 @@ __device__ __forceinline__ uint32_t draw_ticket(uint32_t *counter) {
 }
 
 // What a wave keeps of a token between computing it and storing it (all uniform in the wave).
+// Three words, not seven: the kernel is short of scalar registers, and what does not fit them is kept in lanes
+// of a vector register and fetched back with a vector instruction at every use.
 struct Pending {
-    uint32_t width, cnt, words, token;
-    uint32_t parity;     // which payload image and which stash hold it
-    uint32_t cb, nw;     // outliers of the token in the waves before this one / in this wave
+    uint32_t token;
+    uint32_t wpc;        // width | parity << 4 | outliers of the token << 8
+    uint32_t split;      // outliers of the token in the waves before this one | those in this wave << 16
+    __device__ __forceinline__ uint32_t width() const { return wpc & 15u; }
+    __device__ __forceinline__ uint32_t parity() const { return (wpc >> 4) & 1u; }   // which payload image and stash hold it
+    __device__ __forceinline__ uint32_t cnt() const { return wpc >> 8; }
+    __device__ __forceinline__ uint32_t cb() const { return split & 0xFFFFu; }
+    __device__ __forceinline__ uint32_t nw() const { return split >> 16; }
+    __device__ __forceinline__ void set(uint32_t t, uint32_t width, uint32_t parity, uint32_t cnt, uint32_t cb, uint32_t nw) {
+        token = t;
+        wpc = width | (parity << 4) | (cnt << 8);
+        split = cb | (nw << 16);
+    }
 };
 struct Prefix {
     uint32_t ew, ec;     // payload words / outliers of all tokens before the token
@@ -371,7 +383,7 @@ struct StoreTargets {
     uint16_t *out_col, *out_val;
     const uint32_t *images, *stashes;
     uint32_t runs, pieces;
-    uint64_t payload_words, outlier_capacity;
+    uint32_t payload_words, outlier_capacity;      // both below 2^32: tokens * hidden is
 };
 
 // The lane's run of a token's row, read from memory again (see the rare case in store_wave_part).
@@ -403,14 +415,15 @@ __device__ __forceinline__ bool store_wave_part(const StoreTargets &o, const Pen
     uint32_t lane = threadIdx.x & 63u;
     asm volatile("" : "+v"(lane));
     const uint32_t wv = uniform(threadIdx.x >> 6);
-    if ((uint64_t)x.ew + q.words > o.payload_words) return false;
-    const uint32_t first = 64u * wv * q.width;                        // the wave's first dword of the image
-    const uint32_t n = q.words > first ? (q.words - first < 64u * q.width ? q.words - first : 64u * q.width) : 0u;
+    const uint32_t width = q.width(), words = row_bytes(o.p.hidden, width) >> 2, nw = q.nw();
+    if ((uint64_t)x.ew + words > (uint64_t)o.payload_words) return false;
+    const uint32_t first = 64u * wv * width;                          // the wave's first dword of the image
+    const uint32_t n = words > first ? (words - first < 64u * width ? words - first : 64u * width) : 0u;
     // Every address below is a uniform base (x is uniform) plus a byte offset of 32 bits: the base
     // stays in scalar registers and no lane holds a 64-bit pointer of its own.
     // (in the image every wave's codes start at its own fixed place, whatever the width: the regions
     // of two tokens of different widths never overlap between waves)
-    const uint32_t *img = o.images + q.parity * o.runs * 8u + wv * (64u * 8u);
+    const uint32_t *img = o.images + q.parity() * o.runs * 8u + wv * (64u * 8u);
     uint8_t *dst = reinterpret_cast<uint8_t *>(o.payload + x.ew + first);
     const uint32_t quads = n >> 2;            // at most 128: 8 bits x 32 elements per lane = 32 bytes
     const __amdgpu_buffer_rsrc_t window = raw_window(dst, n << 2);
@@ -427,12 +440,12 @@ __device__ __forceinline__ bool store_wave_part(const StoreTargets &o, const Pen
     }
     const uint32_t rest = n & 3u;
     if (lane < rest) *reinterpret_cast<uint32_t *>(dst + 4u * (4u * quads + lane)) = img[4u * quads + lane];
-    if (q.nw > 0 && (uint64_t)x.ec + q.cnt <= o.outlier_capacity) {
-        uint8_t *col = reinterpret_cast<uint8_t *>(o.out_col + x.ec + q.cb);
-        uint8_t *val = reinterpret_cast<uint8_t *>(o.out_val + x.ec + q.cb);
-        if (q.nw <= kStashWave) {
-            const uint32_t *stash = o.stashes + (q.parity * NW + wv) * kStashWave;
-            for (uint32_t k = lane; k < q.nw; k += 64u) {
+    if (nw > 0 && (uint64_t)x.ec + q.cnt() <= (uint64_t)o.outlier_capacity) {
+        uint8_t *col = reinterpret_cast<uint8_t *>(o.out_col + x.ec + q.cb());
+        uint8_t *val = reinterpret_cast<uint8_t *>(o.out_val + x.ec + q.cb());
+        if (nw <= kStashWave) {
+            const uint32_t *stash = o.stashes + (q.parity() * NW + wv) * kStashWave;
+            for (uint32_t k = lane; k < nw; k += 64u) {
                 const uint32_t e = stash[k];
                 *reinterpret_cast<uint16_t *>(col + 2u * k) = (uint16_t)(e >> 16);
                 *reinterpret_cast<uint16_t *>(val + 2u * k) = (uint16_t)e;
@@ -568,12 +581,11 @@ k_fused(const Params p, const uint16_t *__restrict__ in, uint8_t *__restrict__ b
     // to leave before the current token's codes are packed into the same image.
     Pending young, old;
     bool have_young = false, have_old = false;
-    young.width = 8; young.cnt = 0; young.words = 0; young.token = 0; young.parity = 0;
-    young.cb = 0; young.nw = 0;
+    young.set(0, 8, 0, 0, 0, 0);
     old = young;
 
     const StoreTargets out{p, in, reinterpret_cast<uint32_t *>(blob + p.off_payload), out_col, out_val, images, stashes,
-                           runs, pieces, p.payload_capacity >> 2, p.outlier_capacity};
+                           runs, pieces, (uint32_t)(p.payload_capacity >> 2), (uint32_t)p.outlier_capacity};
 
     // The end of a call: workgroups that were dispatched later run slower (the instruction arbiter of
     // a SIMD prefers its older waves), and whoever starts a token among the last ones keeps everybody
@@ -641,7 +653,6 @@ k_fused(const Params p, const uint16_t *__restrict__ in, uint8_t *__restrict__ b
         uint32_t m[8];
         const Choice c = search_width<DT, NW>(p, mg, st.amax, owns, ring, turn, m);
         __builtin_amdgcn_s_setprio(0);
-        const uint32_t words = row_bytes(p.hidden, c.width) >> 2;
         // the prefix asked for at the top: taken as late as the stores allow
         Prefix xo;
         xo.ew = xo.ec = xo.bad = 0;
@@ -660,10 +671,9 @@ k_fused(const Params p, const uint16_t *__restrict__ in, uint8_t *__restrict__ b
 
         // ---- codes of the lane's run at the chosen width, into this iteration's payload image
         Pending cur;
-        cur.width = c.width; cur.cnt = st.cnt; cur.words = words; cur.token = t; cur.parity = it & 1u;
-        cur.cb = st.cnt_before; cur.nw = cnt_wave;
+        cur.set(t, c.width, it & 1u, st.cnt, st.cnt_before, cnt_wave);
         if (owns) {
-            uint32_t *dst = images + cur.parity * runs * 8u + wv * (64u * 8u) + (run & 63u) * c.width;
+            uint32_t *dst = images + (it & 1u) * runs * 8u + wv * (64u * 8u) + (run & 63u) * c.width;
             const uint32_t nd = (FULL || left >= 4) ? c.width : ((left * c.width + 3u) >> 2);
             switch (c.width) {
                 case 2: pack_to_image<2, DT, FULL>(m, mg, dst, nd); break;
@@ -699,7 +709,7 @@ k_fused(const Params p, const uint16_t *__restrict__ in, uint8_t *__restrict__ b
     // (a wave that kept none of the older token's outliers asks for its part of that row now, not
     // when the prefix has arrived)
     uint32_t again[16];
-    const bool old_reread = have_old && old.nw > kStashWave;
+    const bool old_reread = have_old && old.nw() > kStashWave;
     if (old_reread) reread_run(out, old.token, again);
     if (have_old) {
         const Prefix x = prefix_finish(p, pre, tag, old.token, last_old, error_flag);
