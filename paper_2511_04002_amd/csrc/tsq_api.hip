@@ -118,6 +118,17 @@ tsq_status tsq_plan_create(const tsq_config *cfg, tsq_plan **out) {
             p.widths_pk |= (uint64_t)b << (8 * p.n_widths);
             ++p.n_widths;
         }
+    for (uint32_t i = 0; i < p.n_widths; ++i) {
+        const uint32_t Qi = (1u << (width_at(p, i) - 1u)) - 1u;
+        if (cfg->mode == TSQ_BUDGET_LSB) {
+            p.test_rhs[i] = (double)cfg->budget * (double)H;
+        } else {
+            double R = (double)cfg->budget * (double)Qi;
+            R *= R;
+            R *= (double)H;
+            p.test_rhs[i] = R;
+        }
+    }
     p.tau = cfg->tau;
     p.budget = cfg->budget;
     p.mode = cfg->mode;

@@ -369,16 +369,17 @@ __device__ __forceinline__ uint32_t sad_run(const uint32_t (&m0)[8], const uint3
     return s;
 }
 
-// Algorithm 1's stopping test, the same fixed sequence of fp64 operations on every lane.
-__device__ __forceinline__ bool violates(int mode, float budget, uint32_t H, uint32_t Q0, uint32_t Qi,
-                                         uint32_t sad, uint32_t ss0) {
-    if (mode == kModeLsb) return (double)sad > (double)budget * (double)H;
+// Algorithm 1's stopping test, the same fixed sequence of fp64 operations on every lane:
+//   LSB:      (double)sad > (double)budget * (double)H
+//   REL_RMS:  L = (double)Q0 * (double)sad; L *= L; R = (double)budget * (double)Qi; R *= R; R *= (double)H;
+//             R *= (double)ss0; L > R
+// rhs is the part of the right-hand side that the host computed in that sequence (Params::test_rhs): all of it
+// (LSB), or R before its last factor (REL_RMS).
+__device__ __forceinline__ bool violates(int mode, double rhs, uint32_t Q0, uint32_t sad, uint32_t ss0) {
+    if (mode == kModeLsb) return (double)sad > rhs;
     double L = (double)Q0 * (double)sad;
     L *= L;
-    double R = (double)budget * (double)Qi;
-    R *= R;
-    R *= (double)H;
-    R *= (double)ss0;
+    const double R = rhs * (double)ss0;
     return L > R;
 }
 
@@ -636,7 +637,7 @@ __device__ __forceinline__ Choice search_width(const Params &p, const Mags<DT> &
             if (i == 1) block_sum2_nw<NW>(sad, ss0, red); else block_sum1_nw<NW>(sad, red);
             // (Algorithm 1 as printed returns the quantization that failed the test; the default keeps
             // the last one that passed)
-            const bool failed = violates(p.mode, p.budget, p.hidden, Q0, (1u << (bi - 1)) - 1u, sad, ss0);
+            const bool failed = violates(p.mode, p.test_rhs[i], Q0, sad, ss0);
             if (failed && !p.return_failing) break;
             sel = bi;
             sel_i = i;

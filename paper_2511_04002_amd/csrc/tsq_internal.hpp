@@ -76,6 +76,10 @@ struct Params {
     uint32_t n_widths;      // number of allowed widths
     uint32_t return_failing;  // Algorithm 1 returns the width that failed the test (1) or the last that passed (0)
     uint64_t widths_pk;     // allowed widths, descending, one per byte (byte 0 = largest)
+    double   test_rhs[8];   // Algorithm 1's test for candidate i (descending widths): everything of its right-hand side
+                            // that does not depend on the token, computed on the host in the very sequence of binary64
+                            // operations that defines the test.  REL_RMS: ((double)budget * (double)Q_i)^2 * (double)H, to be
+                            // multiplied by (double)SS0; LSB: (double)budget * (double)H
     float    tau;
     float    budget;
     int32_t  mode;
