@@ -95,6 +95,31 @@ def test_null_arguments(L):
         # misaligned device pointers are refused before any launch
         assert L.tsq_compress(plan, 0x1008, 0x2000, 0x3000, None) == tsq.TSQ_ERR_INVALID_ARG
         assert L.tsq_compress(plan, 0x1000, 0x2010, 0x3000, None) == tsq.TSQ_ERR_INVALID_ARG
+        # the calls that synchronize check their host pointers first
+        info = tsq.tsq_info()
+        assert L.tsq_compress_blocking(plan, 0x1000, 0x2000, 0x3000, None, None) == tsq.TSQ_ERR_INVALID_ARG
+        assert L.tsq_compress_blocking(plan, None, 0x2000, 0x3000, None, C.byref(info)) == tsq.TSQ_ERR_INVALID_ARG
+        out = (C.c_uint64 * 2)()
+        ks = (C.c_uint32 * 2)(0, c.tokens + 1)
+        assert L.tsq_prefix_bytes(plan, None, None, 2, out, None) == tsq.TSQ_ERR_INVALID_ARG
+        assert L.tsq_prefix_bytes(plan, 0x2000, None, 0, out, None) == tsq.TSQ_ERR_INVALID_ARG
+        assert L.tsq_prefix_bytes(plan, 0x2000, None, 2, None, None) == tsq.TSQ_ERR_INVALID_ARG
+        assert L.tsq_prefix_bytes(plan, 0x2000, None, c.tokens + 2, out, None) == tsq.TSQ_ERR_INVALID_ARG
+        assert L.tsq_prefix_bytes(plan, 0x2000, ks, 2, out, None) == tsq.TSQ_ERR_INVALID_ARG      # a count beyond the tokens
+        assert L.tsq_compress_static(plan, None, 0x2000, None) == tsq.TSQ_ERR_INVALID_ARG
+    finally:
+        tsq.tsq_plan_destroy(plan)
+    # the measurement calls: sizes are multiples of 16 bytes, pointers 16-byte aligned
+    assert L.tsq_measure_copy(None, 0x1000, 64, None) == tsq.TSQ_ERR_INVALID_ARG
+    assert L.tsq_measure_copy(0x2000, 0x1000, 0, None) == tsq.TSQ_ERR_INVALID_ARG
+    assert L.tsq_measure_copy(0x2000, 0x1000, 72, None) == tsq.TSQ_ERR_INVALID_ARG
+    assert L.tsq_measure_copy(0x2008, 0x1000, 64, None) == tsq.TSQ_ERR_INVALID_ARG
+    assert L.tsq_measure_read(0x1000, 64, None, None) == tsq.TSQ_ERR_INVALID_ARG
+    assert L.tsq_measure_read(0x1004, 64, 0x3000, None) == tsq.TSQ_ERR_INVALID_ARG
+    assert tsq.tsq_status_string(tsq.TSQ_ERR_NO_MEMORY) == "host allocation failed"
+    plan = tsq.tsq_plan_create(c)
+    try:
+        pass
     finally:
         tsq.tsq_plan_destroy(plan)
     assert L.tsq_plan_blob_bytes(None) == 0 and L.tsq_plan_workspace_bytes(None) == 0
