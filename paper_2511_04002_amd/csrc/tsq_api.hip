@@ -176,10 +176,10 @@ tsq_status tsq_plan_create(const tsq_config *cfg, tsq_plan **out) {
     E.eblob_bytes = eo;
     uint64_t ew = 0;
     E.pool_tokens = (T + kMaxPoolGroups - 1u) / kMaxPoolGroups;
-    if (E.pool_tokens < 4u) E.pool_tokens = 4u;
+    if (E.pool_tokens < 16u) E.pool_tokens = 16u;    // a token per wave of a counting workgroup
     E.pool_groups = (T + E.pool_tokens - 1u) / E.pool_tokens;
     E.ws_pooled = ew;  ew = align_up(ew + (uint64_t)kPoolCopies * 7ull * 256 * 4, 256);
-    E.ws_block = ew;   ew = align_up(ew + 4ull * ((T + kLenBlock - 1u) / kLenBlock), 256);
+    E.ws_block = ew;   ew = align_up(ew + 4ull * kBlockStride * ((T + kLenBlock - 1u) / kLenBlock), 256);
     E.ws_len = ew;     ew = align_up(ew + 4ull * T, 256);
     E.ws_slots = ew;   ew = align_up(ew + (uint64_t)T * E.slot_bytes, 256);
     E.ws_bytes = ew;

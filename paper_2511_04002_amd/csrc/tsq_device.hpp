@@ -55,6 +55,42 @@ __device__ __forceinline__ uint32_t lane_value(uint32_t v, int lane) {
 // lets the arithmetic that follows run on the scalar unit).
 __device__ __forceinline__ uint32_t uniform(uint32_t v) { return (uint32_t)__builtin_amdgcn_readfirstlane((int)v); }
 
+// The B payload words of a run of 32 b-bit codes, as few memory instructions as B allows (16, 8 and 4
+// bytes; a payload row is only 4-byte aligned, which is all that these need on this hardware).  A lane that
+// takes one word at a time makes the memory pipeline walk the cache lines under a wave's runs B times.
+typedef uint32_t Words4 __attribute__((ext_vector_type(4), aligned(4)));
+typedef uint32_t Words2 __attribute__((ext_vector_type(2), aligned(4)));
+template <int B>
+__device__ __forceinline__ void load_run_words(const uint32_t *src, uint32_t (&d)[B]) {
+    int k = 0;
+#pragma unroll
+    for (; k + 4 <= B; k += 4) {
+        const Words4 v = *reinterpret_cast<const Words4 *>(src + k);
+        d[k] = v.x; d[k + 1] = v.y; d[k + 2] = v.z; d[k + 3] = v.w;
+    }
+    if (k + 2 <= B) {
+        const Words2 v = *reinterpret_cast<const Words2 *>(src + k);
+        d[k] = v.x; d[k + 1] = v.y;
+        k += 2;
+    }
+    if (k < B) d[k] = src[k];
+}
+template <int B>
+__device__ __forceinline__ void store_run_words(uint32_t *dst, const uint32_t (&d)[B]) {
+    int k = 0;
+#pragma unroll
+    for (; k + 4 <= B; k += 4) {
+        Words4 v; v.x = d[k]; v.y = d[k + 1]; v.z = d[k + 2]; v.w = d[k + 3];
+        *reinterpret_cast<Words4 *>(dst + k) = v;
+    }
+    if (k + 2 <= B) {
+        Words2 v; v.x = d[k]; v.y = d[k + 1];
+        *reinterpret_cast<Words2 *>(dst + k) = v;
+        k += 2;
+    }
+    if (k < B) dst[k] = d[k];
+}
+
 // Reductions over the 64 lanes of a wave; the result is uniform.  Four DPP steps leave the
 // total of each row of 16 lanes in all of its lanes; the four row totals are combined as scalars.
 __device__ __forceinline__ uint32_t wave_max_u32(uint32_t v) {

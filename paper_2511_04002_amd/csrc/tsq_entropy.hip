@@ -24,8 +24,12 @@ __device__ __forceinline__ void count_run(const uint32_t *src_row, uint32_t run,
     uint32_t d[B];
     const uint32_t *src = src_row + run * B;
     const uint32_t nd = (!RAGGED || valid_elems >= 32u) ? (uint32_t)B : (valid_elems * B + 31u) >> 5;
+    if (!RAGGED) {
+        load_run_words<B>(src, d);
+    } else {
 #pragma unroll
-    for (int k = 0; k < B; ++k) d[k] = (!RAGGED || (uint32_t)k < nd) ? src[k] : 0u;
+        for (int k = 0; k < B; ++k) d[k] = (uint32_t)k < nd ? src[k] : 0u;
+    }
 #pragma unroll
     for (int j = 0; j < 32; ++j) {
         const int off = j * B, k = off >> 5, sh = off & 31;
@@ -85,69 +89,94 @@ k_code_hist(const Params p, const uint8_t *__restrict__ blob, uint32_t *__restri
 }
 
 // The same counts pooled per width class (what the frequency tables of the entropy coder are built
-// from).  A workgroup counts `per` consecutive tokens, class by class: all its tokens of one width
-// go into the bins before the copies are added up, so the adding up happens once per width that
-// occurs, not once per token.  The sums are added to one of kPoolCopies sets counts[set][7][256]
-// (row b - 2: width b; zeroed by the caller), which k_rans_tables adds up: atomic adds on one
-// address from all over the chip take about 30 ns each, one after the other, so both the number
-// of counting workgroups and the number of them that share a set are kept small.
-constexpr uint32_t kPoolMaxTokens = 64;   // widths held in LDS at a time
-__global__ void __launch_bounds__(1024)
+// from).  A workgroup of sixteen waves counts `per` consecutive tokens, a wave a token at a time (lane l
+// takes the runs l, l + 64, ... as the coder does, four runs on their way at a time), into bins that
+// stay in LDS until all its tokens are counted: one bin per (width, code) pair and lane % 16, word
+// (2^b - 4 + code) * 16 + lane % 16.  That is 508 pairs, and a spare one for what lies beyond the end
+// of a row.  At the end thread k adds up the 16 words of pair k and adds the sum to one of
+// kPoolCopies sets counts[set][7][256] (row b - 2: width b; zeroed by the caller), which
+// k_rans_tables adds up: atomic adds on one address from all over the chip take about 30 ns each,
+// one after the other, so both the number of counting workgroups and the number of them that share
+// a set are kept small.
+constexpr uint32_t kPoolPairs = 508, kPoolLanes = 16, kPoolWords = (kPoolPairs + 1u) * kPoolLanes;
+constexpr uint32_t kPoolAhead = 4;       // runs of a lane that are loaded before the first of them is counted
+
+// The runs lane, lane + 64, ... of one token of width B.
+template <int B>
+__device__ __forceinline__ void pool_token(const Params &p, const uint32_t *row, uint32_t rounds, uint32_t *mine) {
+    const uint32_t lane = threadIdx.x & 63u;
+    for (uint32_t r0 = 0; r0 < rounds; r0 += kPoolAhead) {
+        uint32_t d[kPoolAhead][B], valid[kPoolAhead];
+#pragma unroll
+        for (uint32_t k = 0; k < kPoolAhead; ++k) {
+            const uint32_t run = lane + 64u * (r0 + k), first = run * kRun;
+            valid[k] = first < p.hidden ? (p.hidden - first < 32u ? p.hidden - first : 32u) : 0u;
+            if (valid[k] == 32u) {
+                load_run_words<B>(row + run * B, d[k]);
+            } else {
+                const uint32_t nd = (valid[k] * B + 31u) >> 5;
+#pragma unroll
+                for (uint32_t w = 0; w < (uint32_t)B; ++w) d[k][w] = w < nd ? row[run * B + w] : 0u;
+            }
+        }
+#pragma unroll
+        for (uint32_t k = 0; k < kPoolAhead; ++k) {
+            if (r0 + k >= rounds) break;                       // (its lanes loaded nothing: their runs lie beyond the row)
+            const bool ragged = __builtin_amdgcn_ballot_w64(valid[k] < 32u) != 0;
+#pragma unroll
+            for (int j = 0; j < 32; ++j) {
+                const int off = j * B, w = off >> 5, sh = off & 31;
+                uint32_t code = d[k][w] >> sh;
+                if (sh + B > 32) code |= d[k][w + 1 < B ? w + 1 : w] << (32 - sh);
+                code &= (1u << B) - 1u;
+                uint32_t pair = (1u << B) - 4u + code;
+                if (ragged && (uint32_t)j >= valid[k]) pair = kPoolPairs;
+                __hip_atomic_fetch_add(mine + pair * kPoolLanes, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+            }
+        }
+    }
+}
+
+constexpr uint32_t kPoolThreads = 1024, kPoolWaves = kPoolThreads / 64;
+__global__ void __launch_bounds__(kPoolThreads)
 k_code_pool(const Params p, const uint8_t *__restrict__ blob, uint32_t *__restrict__ counts, uint32_t per) {
-    __shared__ uint32_t bins[kCopies * kCopyStride];
-    __shared__ uint32_t acc[7 * 256];
-    __shared__ uint8_t widths[kPoolMaxTokens];
+    __shared__ uint32_t bins[kPoolWords];
     const BlobHeader *h = reinterpret_cast<const BlobHeader *>(blob);
     const bool ok = h->magic == kMagic && h->version == kVersion && h->status == 0 && h->tokens == p.tokens &&
                     h->hidden == p.hidden && h->dtype == p.dtype && h->off_payload == p.off_payload;
-    const uint32_t run = threadIdx.x;
-    uint32_t *mine_out = counts + (blockIdx.x % kPoolCopies) * 7u * 256u;
-    for (uint32_t i = threadIdx.x; i < 7u * 256u; i += blockDim.x) acc[i] = 0;
-    for (uint32_t i = threadIdx.x; i < kCopies * kCopyStride; i += blockDim.x) bins[i] = 0;
+    if (!ok) return;
+    const uint32_t lane = threadIdx.x & 63u, wv = threadIdx.x >> 6;
     const uint32_t t0 = blockIdx.x * per, t1 = t0 + per < p.tokens ? t0 + per : p.tokens;
-    for (uint32_t base = t0; ok && base < t1; base += kPoolMaxTokens) {
-        const uint32_t n = t1 - base < kPoolMaxTokens ? t1 - base : kPoolMaxTokens;
-        __syncthreads();                                   // bins and acc are zero / complete; widths[] is free
-        if (threadIdx.x < n) {
-            const uint32_t t = base + threadIdx.x;
-            const uint32_t width = blob[p.off_bits + t];
-            const uint64_t po = reinterpret_cast<const uint64_t *>(blob + p.off_pay_off)[t];
-            // a damaged token is skipped rather than read out of bounds
-            const bool good = token_in_range(p, width, po);
-            widths[threadIdx.x] = good ? (uint8_t)width : 0;
-        }
-        __syncthreads();
-        for (uint32_t b = 2; b <= 8; ++b) {
-            bool any = false;                              // uniform: depends on widths[] only
-            for (uint32_t k = 0; k < n; ++k) {
-                if (widths[k] != b) continue;
-                any = true;
-                if (run < p.runs) {
-                    const uint32_t t = base + k;
-                    const uint64_t po = reinterpret_cast<const uint64_t *>(blob + p.off_pay_off)[t];
-                    const uint32_t left = p.hidden - run * kRun;
-                    const uint32_t *src_row = reinterpret_cast<const uint32_t *>(blob + p.off_payload + po);
-                    uint32_t *mine = bins + (threadIdx.x & (kCopies - 1u)) * kCopyStride;
-                    if (__builtin_amdgcn_ballot_w64(left < 32u) == 0) count_run_any<false>(b, src_row, run, left, mine);
-                    else count_run_any<true>(b, src_row, run, left, mine);
-                }
-            }
-            if (!any) continue;
-            __syncthreads();
-            for (uint32_t c = threadIdx.x; c < 256u; c += blockDim.x) {
-                uint32_t s = 0;
-#pragma unroll
-                for (uint32_t j = 0; j < kCopies; ++j) s += bins[j * kCopyStride + c];
-                acc[(b - 2u) * 256u + c] += s;
-            }
-            __syncthreads();
-            for (uint32_t i = threadIdx.x; i < kCopies * kCopyStride; i += blockDim.x) bins[i] = 0;
-            __syncthreads();
+    const uint32_t rounds = (p.runs + 63u) / 64u;
+    for (uint32_t i = threadIdx.x; i < kPoolWords; i += kPoolThreads) bins[i] = 0;
+    __syncthreads();
+
+    uint32_t *mine = bins + (lane & (kPoolLanes - 1u));
+    for (uint32_t t = t0 + wv; t < t1; t += kPoolWaves) {
+        const uint32_t b = blob[p.off_bits + t];
+        const uint64_t po = reinterpret_cast<const uint64_t *>(blob + p.off_pay_off)[t];
+        if (!token_in_range(p, b, po)) continue;               // a damaged token is skipped rather than read out of bounds
+        const uint32_t *row = reinterpret_cast<const uint32_t *>(blob + p.off_payload + po);
+        switch (b) {                                           // uniform in the wave
+            case 2: pool_token<2>(p, row, rounds, mine); break;
+            case 3: pool_token<3>(p, row, rounds, mine); break;
+            case 4: pool_token<4>(p, row, rounds, mine); break;
+            case 5: pool_token<5>(p, row, rounds, mine); break;
+            case 6: pool_token<6>(p, row, rounds, mine); break;
+            case 7: pool_token<7>(p, row, rounds, mine); break;
+            default: pool_token<8>(p, row, rounds, mine); break;
         }
     }
     __syncthreads();
-    for (uint32_t i = threadIdx.x; i < 7u * 256u; i += blockDim.x)
-        if (acc[i]) atomicAdd(mine_out + i, acc[i]);
+    if (threadIdx.x < kPoolPairs) {
+        const uint32_t pair = threadIdx.x;
+        uint32_t n = 0;
+#pragma unroll
+        for (uint32_t k = 0; k < kPoolLanes; ++k) n += bins[pair * kPoolLanes + ((k + pair) & (kPoolLanes - 1u))];
+        // pair = 2^b - 4 + code
+        const uint32_t bw = 31u - (uint32_t)__builtin_clz(pair + 4u), code = pair + 4u - (1u << bw);
+        if (n) atomicAdd(counts + (blockIdx.x % kPoolCopies) * 7u * 256u + (bw - 2u) * 256u + code, n);
+    }
 }
 
 int launch_code_hist(const Params &p, const Geometry &g, const void *d_blob, void *d_hist, void *stream) {
@@ -158,7 +187,7 @@ int launch_code_hist(const Params &p, const Geometry &g, const void *d_blob, voi
 
 int launch_code_pool(const Params &p, const Geometry &g, const EntropyLayout &e, const void *d_blob, void *d_counts,
                      void *stream) {
-    hipLaunchKernelGGL(k_code_pool, dim3(e.pool_groups), dim3(g.block), 0, reinterpret_cast<hipStream_t>(stream), p,
+    hipLaunchKernelGGL(k_code_pool, dim3(e.pool_groups), dim3(kPoolThreads), 0, reinterpret_cast<hipStream_t>(stream), p,
                        static_cast<const uint8_t *>(d_blob), static_cast<uint32_t *>(d_counts), e.pool_tokens);
     return (int)hipGetLastError();
 }

@@ -52,7 +52,7 @@ static_assert(sizeof(EntropyHeader) == 256, "entropy header must be 256 bytes");
 struct EntropyLayout {
     uint64_t off_tables, off_stream_off, off_streams, stream_capacity, eblob_bytes;
     uint64_t ws_pooled;     // u32[kPoolCopies][7][256] code counts per width class (a counting workgroup adds to set id % kPoolCopies)
-    uint64_t ws_block;      // u32[ceil(T / kLenBlock)] padded stream bytes of each block of kLenBlock tokens
+    uint64_t ws_block;      // u32[ceil(T / kLenBlock)][kBlockStride], word 0 of each: padded stream bytes of the block of kLenBlock tokens
     uint64_t ws_len;        // u32[T] stream bytes per token
     uint64_t ws_slots;      // T slots of slot_bytes: the streams before they are moved together
     uint64_t ws_bytes;
@@ -62,7 +62,9 @@ struct EntropyLayout {
     uint32_t pad;
 };
 constexpr uint32_t kLenBlock = 256;     // tokens per partial sum of stream lengths
-constexpr uint32_t kMaxPoolGroups = 1536;   // counting workgroups: six fit a compute unit (LDS), 256 compute units: one round
+constexpr uint32_t kBlockStride = 64;   // 32-bit words from one partial sum to the next: the encoder's waves add to them, and
+                                        // adds to one 128-byte line from all over the chip hold up the stores queued behind them
+constexpr uint32_t kMaxPoolGroups = 512;    // counting workgroups: two fit a compute unit (LDS), 256 compute units: one round
 constexpr uint32_t kPoolCopies = 16;    // sets of pooled counts: 16 times fewer atomic adds per address
 
 // Kernel argument block (passed by value).

@@ -23,8 +23,7 @@ __device__ __forceinline__ void store_codes(const uint32_t (&m)[8], const Mags<D
     pack_regs<B, DT>(m, mg, out);
     uint32_t *dst = dst_row + run * B;
     if (valid_pieces >= 4) {
-#pragma unroll
-        for (int k = 0; k < B; ++k) dst[k] = out[k];
+        store_run_words<B>(dst, out);
     } else {
         const uint32_t nd = (valid_pieces * B + 3u) >> 2;  // ceil(8*valid*B / 32)
 #pragma unroll
@@ -213,8 +212,7 @@ __device__ __forceinline__ void load_and_unpack(const uint32_t *src_row, uint32_
     uint32_t d[B];
     const uint32_t *src = src_row + run * B;
     if (valid_pieces >= 4) {
-#pragma unroll
-        for (int k = 0; k < B; ++k) d[k] = src[k];
+        load_run_words<B>(src, d);
     } else {
         const uint32_t nd = (valid_pieces * B + 3u) >> 2;
 #pragma unroll

@@ -14,9 +14,9 @@
 //
 // Encode: code counts per width, added to one of 16 sets (k_code_pool) -> sets added up,
 // tables (k_rans_tables) -> one wave per token codes its stream into a slot of the workspace
-// (k_rans_encode) -> stream bytes per block of 256 tokens (k_rans_blocks) -> every token finds its
-// offset from the block sums before it and the lengths before it inside its block, and its stream
-// moves to its place (k_rans_gather).
+// (k_rans_encode) and adds its length to the stream bytes of its block of 256 tokens -> every token
+// finds its offset from the block sums before it and the lengths before it inside its block, and its
+// stream moves to its place (k_rans_gather).
 // Decode: one wave per token (k_rans_decode) rebuilds the packed payload; the words it reads
 // pass through registers (four windows of 64 words), so a token needs 5 KB of LDS for its tables
 // and nothing else, and a compute unit holds its full 32 waves.
@@ -29,6 +29,7 @@ namespace tsq {
 
 constexpr uint32_t kProbBits = 12, kProbScale = 1u << kProbBits, kRansLow = 1u << 16;
 static_assert(kProbScale == 4096, "frequency_slot() masks 12 bits");
+constexpr float kJustBelowOne = 0.999999523162841796875f;        // 1 - 2^-21 (see quotient_or_one_less)
 
 __device__ __forceinline__ bool blob_is_valid(const Params &p, const uint8_t *blob) {
     const BlobHeader *h = reinterpret_cast<const BlobHeader *>(blob);
@@ -43,11 +44,17 @@ __device__ __forceinline__ bool eblob_is_valid(const Params &p, const EntropyLay
 
 // ---------------------------------------------------------------- pooled counts and tables
 
-__global__ void k_rans_begin(const Params p, const EntropyLayout e, uint8_t *__restrict__ eblob, uint8_t *__restrict__ ews) {
-    uint32_t *counts = reinterpret_cast<uint32_t *>(ews + e.ws_pooled);
-    for (uint32_t i = threadIdx.x; i < kPoolCopies * 7u * 256u; i += blockDim.x) counts[i] = 0;
+// What the kernels of a call add to starts at zero: the pooled code counts and the stream bytes per block of
+// tokens (one thread per word).
+constexpr uint32_t kBeginThreads = 1024;
+__global__ void __launch_bounds__(kBeginThreads)
+k_rans_begin(const Params p, const EntropyLayout e, uint8_t *__restrict__ eblob, uint8_t *__restrict__ ews) {
+    const uint32_t i = blockIdx.x * kBeginThreads + threadIdx.x, n_counts = kPoolCopies * 7u * 256u;
+    const uint32_t n_blocks = (p.tokens + kLenBlock - 1u) / kLenBlock;
+    if (i < n_counts) reinterpret_cast<uint32_t *>(ews + e.ws_pooled)[i] = 0;
+    else if (i - n_counts < n_blocks) reinterpret_cast<uint32_t *>(ews + e.ws_block)[(i - n_counts) * kBlockStride] = 0;
     // the header becomes valid only when the last kernel of the call has run
-    if (threadIdx.x < sizeof(EntropyHeader) / 4) reinterpret_cast<uint32_t *>(eblob)[threadIdx.x] = 0;
+    if (blockIdx.x == 0 && threadIdx.x < sizeof(EntropyHeader) / 4) reinterpret_cast<uint32_t *>(eblob)[threadIdx.x] = 0;
 }
 
 // One workgroup per width class: counts -> 12-bit frequencies.  f_c = max(1, floor(n_c * 4096 / N))
@@ -126,7 +133,9 @@ k_rans_tables(const Params p, const EntropyLayout e, const uint8_t *__restrict__
 }
 
 // The table of a token's class into LDS, by one wave (lane l owns the codes 4l .. 4l+3): per code
-// x = f | cum << 16 (cum = exclusive running sum, < 4096) and y = the binary32 pattern of 1 / f.
+// x = f | cum << 16 (cum = exclusive running sum, < 4096) and y = the binary32 pattern of a value a
+// little below 1 / f (see quotient_or_one_less).  Eight bytes per code: wider entries cost more LDS
+// time than the instructions they save.
 // A code the table does not know (f = 0; cannot happen for a table built from the blob that is
 // coded) is entered with f = 1, which keeps the division defined.
 __device__ __forceinline__ void load_table(const uint16_t *table, uint2 *ftab) {
@@ -138,7 +147,8 @@ __device__ __forceinline__ void load_table(const uint16_t *table, uint2 *ftab) {
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
         const uint32_t fi = f[i] ? f[i] : 1u;
-        ftab[4u * lane + i] = make_uint2(fi | (cum << 16), __float_as_uint(1.0f / (float)fi));
+        const float below = (1.0f / (float)fi) * kJustBelowOne;
+        ftab[4u * lane + i] = make_uint2(fi | (cum << 16), __float_as_uint(below));
         cum += f[i];
     }
 }
@@ -158,17 +168,14 @@ __device__ __forceinline__ void load_table_decode(const uint16_t *table, uint32_
     }
 }
 
-// x / f and x % f for x < f << 20 (so the quotient is below 2^20) and f <= 4096: the binary32
-// product of x and 1/f is within 0.2 of the true quotient (three roundings of relative size
-// 2^-24 on a value below 2^20), so its integer part is off by at most one, which the sign and
-// size of the remainder tell.  All multiplications fit 24 bits.
-__device__ __forceinline__ void divide_small(uint32_t x, uint32_t f, float rcp, uint32_t &q, uint32_t &r) {
-    uint32_t qq = (uint32_t)((float)x * rcp);
-    int32_t rr = (int32_t)(x - __umul24(qq, f));
-    if (rr < 0) { --qq; rr += (int32_t)f; }
-    else if ((uint32_t)rr >= f) { ++qq; rr -= (int32_t)f; }
-    q = qq;
-    r = (uint32_t)rr;
+// floor(x / f) or one less, for x < f << 20 (so the quotient is below 2^20) and f <= 4096, from `below`, the
+// binary32 quotient 1 / f times (1 - 2^-21), rounded.  With e = 2^-24 the unit roundoff: below lies in
+// [(1 - 2^-21)(1 - e)^2 / f, (1 - 2^-21)(1 + e)^2 / f], and the product of (float)x and below carries two
+// more roundings, so it lies in [x/f * (1 - 2^-21)(1 - e)^4, x/f * (1 - 2^-21)(1 + e)^4]: never above x/f
+// (4e < 2^-21), and less than x/f * 12e < 0.75 below it.  Its integer part is therefore
+// floor(x/f) or floor(x/f) - 1, which the size of the remainder tells.  The products fit 24 x 24 bits.
+__device__ __forceinline__ uint32_t quotient_or_one_less(uint32_t x, float below) {
+    return (uint32_t)((float)x * below);
 }
 
 // How many of the lanes before this one are set in `who`.
@@ -187,8 +194,12 @@ __device__ __forceinline__ void encode_round(const uint32_t *src_row, uint32_t r
                                              uint16_t *out, uint32_t &ptr, uint32_t &x) {
     uint32_t d[B];
     const uint32_t nd = (WHOLE || valid >= 32) ? (uint32_t)B : (valid > 0 ? ((uint32_t)valid * B + 31u) >> 5 : 0u);
+    if (WHOLE) {
+        load_run_words<B>(src_row + run * B, d);
+    } else {
 #pragma unroll
-    for (int k = 0; k < B; ++k) d[k] = (WHOLE || (uint32_t)k < nd) ? src_row[run * B + k] : 0u;
+        for (int k = 0; k < B; ++k) d[k] = (uint32_t)k < nd ? src_row[run * B + k] : 0u;
+    }
 #pragma unroll
     for (int j = 31; j >= 0; --j) {
         const int off = j * B, k = off >> 5, sh = off & 31;
@@ -198,7 +209,6 @@ __device__ __forceinline__ void encode_round(const uint32_t *src_row, uint32_t r
         const bool active = WHOLE || j < valid;
         const uint2 entry = ftab[code];
         const uint32_t f = entry.x & 0xFFFFu;
-        const uint32_t c = entry.x >> 16;
         const bool shed = active && (x >> 20) >= f;            // x >= f << 20, without overflow for f = 4096
         const uint64_t who = __builtin_amdgcn_ballot_w64(shed);
         ptr -= (uint32_t)__builtin_popcountll(who);
@@ -207,9 +217,11 @@ __device__ __forceinline__ void encode_round(const uint32_t *src_row, uint32_t r
             x >>= 16;
         }
         if (active) {
-            uint32_t q, r;
-            divide_small(x, f, __uint_as_float(entry.y), q, r);
-            x = (q << kProbBits) + r + c;
+            // x -> (q << 12) + (x - q f) + cum with q = floor(x / f) = q1 or q1 + 1
+            const uint32_t q1 = quotient_or_one_less(x, __uint_as_float(entry.y));
+            const uint32_t r1 = x - __umul24(q1, f);           // x - q1 f: the remainder, or f more
+            const uint32_t more = r1 >= f ? kProbScale - f : 0u;
+            x = (q1 << kProbBits) + r1 + (entry.x >> 16) + more;
         }
     }
 }
@@ -264,55 +276,88 @@ k_rans_encode(const Params p, const EntropyLayout e, const uint8_t *__restrict__
     const uint32_t coders = p.runs < 64u ? p.runs : 64u;  // coders that own a run; the others still hold 2^16
     if (lane < coders) reinterpret_cast<uint32_t *>(slot)[lane] = x;
     if (lane == 0) {
-        len[t] = 4u * coders + 2u * (cap - ptr);           // unpadded; the stream is padded to 4 bytes when it is placed
+        const uint32_t bytes = 4u * coders + 2u * (cap - ptr);
+        len[t] = bytes;                                     // unpadded; the stream is padded to 4 bytes when it is placed
+        // padded stream bytes of the token's block of kLenBlock tokens (kLenBlock slots of at most 64 KiB + 256
+        // bytes: the sum fits 32 bits)
+        atomicAdd(reinterpret_cast<uint32_t *>(ews + e.ws_block) + (t / kLenBlock) * kBlockStride, (bytes + 3u) & ~3u);
     }
 }
 
-// Padded stream bytes of every block of kLenBlock tokens: one workgroup per block, one thread per
-// token.  kLenBlock slots of at most 64 KiB + 256 bytes: the sum fits 32 bits.
-__global__ void __launch_bounds__(256)
-k_rans_blocks(const Params p, const EntropyLayout e, const uint8_t *__restrict__ blob, uint8_t *__restrict__ ews) {
-    __shared__ uint32_t part[4];
-    static_assert(kLenBlock == 256, "one thread per token of a block");
-    if (!blob_is_valid(p, blob)) return;
-    const uint32_t *len = reinterpret_cast<const uint32_t *>(ews + e.ws_len);
-    const uint32_t t = blockIdx.x * kLenBlock + threadIdx.x;
-    const uint32_t w = wave_sum_u32(t < p.tokens ? (len[t] + 3u) & ~3u : 0u);
-    if ((threadIdx.x & 63u) == 0) part[threadIdx.x >> 6] = w;
-    __syncthreads();
-    if (threadIdx.x == 0) reinterpret_cast<uint32_t *>(ews + e.ws_block)[blockIdx.x] = part[0] + part[1] + part[2] + part[3];
+// A token's stream moves from its slot to its place, by one wave: the (padded) lengths of all streams
+// before it are the sums of the blocks before its block plus the lengths before it inside its block
+// (64-bit: tokens * slot size may exceed 32 bits; a lane's share stays below 2^40, so it is split at bit
+// 24 into two parts whose sums over 64 lanes fit 32 bits).  The first words of the stream are asked for
+// together with those lengths: where they come from depends on the token's own length only.  The wave
+// of the last token also writes the end offset and the header.
+//
+// The words stand at the end of the slot's room, which holds an even number of them: they start at an
+// odd word exactly when their number is odd.  They move eight at a time (16 bytes; the last ones two at a
+// time); in the odd case a pair is the high half of one 32-bit word of the room and the low half of the
+// next, and the pair after the last word of the room is the padding to 4 bytes.
+struct StreamSource {
+    const uint32_t *src;      // the 32-bit word of the room that holds the first word of the stream
+    uint32_t left;            // 32-bit words from there to the end of the room
+    uint32_t odd;             // the stream starts in the high half of *src
+};
+__device__ __forceinline__ uint32_t stream_pair(const StreamSource &q, uint32_t i) {
+    uint32_t v = q.src[i];
+    if (q.odd) v = (v >> 16) | ((i + 1u < q.left ? q.src[i + 1u] : 0u) << 16);
+    return v;
+}
+// pairs 4c .. 4c+3 (all of them exist)
+__device__ __forceinline__ Words4 stream_pairs4(const StreamSource &q, uint32_t c) {
+    const Words4 a = *reinterpret_cast<const Words4 *>(q.src + 4u * c);
+    if (!q.odd) return a;
+    const uint32_t next = 4u * c + 4u < q.left ? q.src[4u * c + 4u] : 0u;
+    Words4 v;
+    v.x = (a.x >> 16) | (a.y << 16); v.y = (a.y >> 16) | (a.z << 16);
+    v.z = (a.z >> 16) | (a.w << 16); v.w = (a.w >> 16) | (next << 16);
+    return v;
 }
 
-// A token's stream moves from its slot to its place: the (padded) lengths of all streams before it
-// are the sums of the blocks before its block plus the lengths before it inside its block, added up
-// by the workgroup (64-bit: tokens * slot size may exceed 32 bits; a thread's share stays below
-// 2^34, so it is split at bit 24 into two parts whose sums over 256 threads fit 32 bits).  The
-// workgroup of the last token also writes the end offset and the header.
-__global__ void __launch_bounds__(256)
+constexpr uint32_t kGatherEarly = 2;     // 16-byte pieces per lane that are loaded before the offset is known
+__global__ void __launch_bounds__(64)
 k_rans_gather(const Params p, const EntropyLayout e, const uint8_t *__restrict__ blob, uint8_t *__restrict__ eblob,
               const uint8_t *__restrict__ ews) {
-    __shared__ uint32_t part[2][4];
-    static_assert(kLenBlock == 256, "one thread per token of a block");
+    static_assert(kLenBlock == 256, "four lengths per lane inside a block");
     if (!blob_is_valid(p, blob)) return;
-    const uint32_t t = blockIdx.x;
+    const uint32_t t = blockIdx.x, lane = threadIdx.x;
     const uint32_t *len = reinterpret_cast<const uint32_t *>(ews + e.ws_len);
     const uint32_t *block = reinterpret_cast<const uint32_t *>(ews + e.ws_block);
     const uint32_t blk = t / kLenBlock;
-    uint64_t s = 0;
-    for (uint32_t b = threadIdx.x; b < blk; b += 256u) s += block[b];
-    const uint32_t u = blk * kLenBlock + threadIdx.x;       // kLenBlock == threads of this workgroup
-    if (u < t) s += (len[u] + 3u) & ~3u;
-    const uint32_t lo = wave_sum_u32((uint32_t)s & 0xFFFFFFu), hi = wave_sum_u32((uint32_t)(s >> 24));
-    if ((threadIdx.x & 63u) == 0) { part[0][threadIdx.x >> 6] = lo; part[1][threadIdx.x >> 6] = hi; }
-    __syncthreads();
-    uint64_t at = 0;
-#pragma unroll
-    for (int w = 0; w < 4; ++w) at += (uint64_t)part[0][w] + ((uint64_t)part[1][w] << 24);
-
+    const uint32_t coders = p.runs < 64u ? p.runs : 64u;
     const uint32_t bytes = len[t];                          // states + words, unpadded
     const uint32_t padded = (bytes + 3u) & ~3u;
+    const uint32_t room = (e.slot_bytes - 256u) >> 1;
+    const uint8_t *slot = ews + e.ws_slots + (size_t)t * e.slot_bytes;
+    // (a length that k_rans_encode wrote passes; anything else moves nothing)
+    const bool sane = bytes >= 4u * coders && bytes <= e.slot_bytes && ((bytes - 4u * coders) >> 1) <= room;
+    const uint32_t nwords = sane ? (bytes - 4u * coders) >> 1 : 0u;
+    const uint32_t first = room - nwords, pairs = (nwords + 1u) >> 1, pieces = pairs >> 2;
+    StreamSource q;
+    q.src = reinterpret_cast<const uint32_t *>(slot + 256) + (first >> 1);
+    q.left = (room >> 1) - (first >> 1);
+    q.odd = first & 1u;
+    Words4 early[kGatherEarly];
+#pragma unroll
+    for (uint32_t k = 0; k < kGatherEarly; ++k) {
+        const uint32_t c = lane + 64u * k;
+        early[k] = c < pieces ? stream_pairs4(q, c) : Words4{0u, 0u, 0u, 0u};
+    }
+    const uint32_t state = lane < coders && sane ? reinterpret_cast<const uint32_t *>(slot)[lane] : 0u;
+
+    uint64_t s = 0;
+    for (uint32_t b = lane; b < blk; b += 64u) s += block[b * kBlockStride];
+#pragma unroll
+    for (uint32_t k = 0; k < kLenBlock / 64u; ++k) {
+        const uint32_t u = blk * kLenBlock + lane + 64u * k;
+        if (u < t) s += (len[u] + 3u) & ~3u;
+    }
+    const uint64_t at = (uint64_t)wave_sum_u32((uint32_t)s & 0xFFFFFFu) + ((uint64_t)wave_sum_u32((uint32_t)(s >> 24)) << 24);
+
     uint64_t *off = reinterpret_cast<uint64_t *>(eblob + e.off_stream_off);
-    if (threadIdx.x == 0) {
+    if (lane == 0) {
         off[t] = at;
         if (t == p.tokens - 1u) {
             off[p.tokens] = at + padded;
@@ -324,17 +369,18 @@ k_rans_gather(const Params p, const EntropyLayout e, const uint8_t *__restrict__
             *reinterpret_cast<EntropyHeader *>(eblob) = h;
         }
     }
-    const uint32_t coders = p.runs < 64u ? p.runs : 64u;
-    if (!stream_move_ok(bytes, coders, e.slot_bytes, at, e.stream_capacity)) return;
-    const uint8_t *slot = ews + e.ws_slots + (size_t)t * e.slot_bytes;
+    if (!sane || !stream_move_ok(bytes, coders, e.slot_bytes, at, e.stream_capacity)) return;
     uint8_t *dst = eblob + e.off_streams + at;
-    if (threadIdx.x < coders) reinterpret_cast<uint32_t *>(dst)[threadIdx.x] = reinterpret_cast<const uint32_t *>(slot)[threadIdx.x];
-    // the words stand at the end of the slot
-    const uint32_t nwords = (bytes - 4u * coders) >> 1, room = (e.slot_bytes - 256u) >> 1;
-    const uint16_t *src = reinterpret_cast<const uint16_t *>(slot + 256) + (room - nwords);
-    uint16_t *words = reinterpret_cast<uint16_t *>(dst + 4u * coders);
-    for (uint32_t i = threadIdx.x; i < nwords; i += 256u) words[i] = src[i];
-    if ((nwords & 1u) && threadIdx.x == 0) words[nwords] = 0;                          // padding to 4 bytes
+    if (lane < coders) reinterpret_cast<uint32_t *>(dst)[lane] = state;
+    uint32_t *out = reinterpret_cast<uint32_t *>(dst + 4u * coders);
+#pragma unroll
+    for (uint32_t k = 0; k < kGatherEarly; ++k) {
+        const uint32_t c = lane + 64u * k;
+        if (c < pieces) *reinterpret_cast<Words4 *>(out + 4u * c) = early[k];
+    }
+    for (uint32_t c = lane + 64u * kGatherEarly; c < pieces; c += 64u) *reinterpret_cast<Words4 *>(out + 4u * c) = stream_pairs4(q, c);
+    const uint32_t i = 4u * pieces + lane;                  // the last pairs, fewer than four
+    if (i < pairs) out[i] = stream_pair(q, i);
 }
 
 // ---------------------------------------------------------------- decode
@@ -448,9 +494,13 @@ __device__ __forceinline__ void decode_round(uint32_t *dst_row, uint32_t run, in
         }
     }
     const uint32_t nd = (WHOLE || valid >= 32) ? (uint32_t)B : (valid > 0 ? ((uint32_t)valid * B + 31u) >> 5 : 0u);
+    if (WHOLE) {
+        store_run_words<B>(dst_row + run * B, d);
+    } else {
 #pragma unroll
-    for (int k = 0; k < B; ++k)
-        if (WHOLE || (uint32_t)k < nd) dst_row[run * B + k] = d[k];
+        for (int k = 0; k < B; ++k)
+            if ((uint32_t)k < nd) dst_row[run * B + k] = d[k];
+    }
 }
 
 __global__ void __launch_bounds__(64, 8)    // 8 waves per SIMD: all 32 tokens of a compute unit's share run at once
@@ -512,13 +562,13 @@ int launch_rans_encode(const Params &p, const Geometry &g, const EntropyLayout &
     const uint8_t *blob = static_cast<const uint8_t *>(d_blob);
     uint8_t *eblob = static_cast<uint8_t *>(d_eblob), *ews = static_cast<uint8_t *>(d_ews);
     hipStream_t s = as_stream(stream);
-    hipLaunchKernelGGL(k_rans_begin, dim3(1), dim3(1024), 0, s, p, e, eblob, ews);
+    const uint32_t to_zero = kPoolCopies * 7u * 256u + (p.tokens + kLenBlock - 1u) / kLenBlock;
+    hipLaunchKernelGGL(k_rans_begin, dim3((to_zero + kBeginThreads - 1u) / kBeginThreads), dim3(kBeginThreads), 0, s, p, e, eblob, ews);
     int rc = launch_code_pool(p, g, e, d_blob, ews + e.ws_pooled, stream);
     if (rc != 0) return rc;
     hipLaunchKernelGGL(k_rans_tables, dim3(7), dim3(256), 0, s, p, e, blob, eblob, ews);
     hipLaunchKernelGGL(k_rans_encode, dim3(p.tokens), dim3(64), 0, s, p, e, blob, eblob, ews);
-    hipLaunchKernelGGL(k_rans_blocks, dim3((p.tokens + kLenBlock - 1u) / kLenBlock), dim3(256), 0, s, p, e, blob, ews);
-    hipLaunchKernelGGL(k_rans_gather, dim3(p.tokens), dim3(256), 0, s, p, e, blob, eblob, ews);
+    hipLaunchKernelGGL(k_rans_gather, dim3(p.tokens), dim3(64), 0, s, p, e, blob, eblob, ews);
     return (int)hipGetLastError();
 }
 
