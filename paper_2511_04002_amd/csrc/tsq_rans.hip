@@ -213,7 +213,9 @@ __device__ __forceinline__ void encode_round(const uint32_t *src_row, uint32_t r
         const uint64_t who = __builtin_amdgcn_ballot_w64(shed);
         ptr -= (uint32_t)__builtin_popcountll(who);
         if (shed) {
-            out[ptr + rank_in(who)] = (uint16_t)x;
+            // (a 32-bit byte offset from a uniform base: one instruction for the address)
+            const uint32_t at = (ptr + rank_in(who)) << 1;
+            *reinterpret_cast<uint16_t *>(reinterpret_cast<uint8_t *>(out) + at) = (uint16_t)x;
             x >>= 16;
         }
         if (active) {
