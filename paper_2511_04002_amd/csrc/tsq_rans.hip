@@ -18,7 +18,7 @@
 // finds its offset from the block sums before it and the lengths before it inside its block, and its
 // stream moves to its place (k_rans_gather).
 // Decode: one wave per token (k_rans_decode) rebuilds the packed payload; the words it reads
-// pass through registers (four windows of 64 words), so a token needs 5 KB of LDS for its tables
+// pass through registers (windows of 64 words), so a token needs 5 KB of LDS for its tables
 // and nothing else, and a compute unit holds its full 32 waves.
 #include <hip/hip_runtime.h>
 
@@ -446,21 +446,48 @@ __device__ __forceinline__ void build_slot_table(const uint32_t *ftab, uint32_t 
     __syncthreads();
 }
 
-// The token's words as the decoder consumes them: four windows of 64 words in registers (lane l
-// of window k holds word base + 64k + l); a step reads at most 64 words from the first two, and
-// when the first is used up the windows move on and the fourth is fetched from memory again.
+// The token's words as the decoder consumes them: windows of 64 words in registers (lane l of window k
+// holds word base + 64k + l).  A step reads at most 64 words from the first two windows, which share a
+// register (low / high half: one permute reads both); when the first is used up the windows move on by
+// one.  Behind them: two registers of two windows each (pair, next) and two of one window each (far),
+// which move on by two windows at every second move, when two new windows are asked for.  So a window is
+// not touched until two moves after it was asked for: by then it has arrived (a window is a cache line of
+// its own, fetched from memory for the first time), and no step waits for memory.
+// Past the end of the stream a window repeats the stream's last word: a stream that is not damaged is never
+// read there.
 struct Words {
     const uint16_t *src;
-    uint32_t count, base;
-    uint32_t w01, w2, w3;      // the first two windows share a register (low / high half): one permute reads both
+    uint32_t last, base;       // index of the last word; first word of the first window
+    uint32_t cur;              // the first two windows
+    uint32_t pair, next;       // windows 0, 1 and 2, 3 (odd = 0) or -1, 0 and 1, 2 (odd = 1)
+    uint32_t far0, far1;       // the two windows after those
+    uint32_t odd;              // one window of `pair` is used up
 };
 __device__ __forceinline__ uint32_t word_at(const Words &q, uint32_t k) {
     const uint32_t i = k + (threadIdx.x & 63u);
-    return i < q.count ? (uint32_t)q.src[i] : 0u;               // past the end: a damaged stream is read as zeros
+    return (uint32_t)q.src[i < q.last ? i : q.last];
 }
-__device__ __forceinline__ void words_open(Words &q, const uint16_t *src, uint32_t count) {
-    q.src = src; q.count = count; q.base = 0;
-    q.w01 = word_at(q, 0) | (word_at(q, 64) << 16); q.w2 = word_at(q, 128); q.w3 = word_at(q, 192);
+// count words at src; `fallback` is readable memory for the case of no words at all
+__device__ __forceinline__ void words_open(Words &q, const uint16_t *src, uint32_t count, const uint16_t *fallback) {
+    q.src = count ? src : fallback; q.last = count ? count - 1u : 0u; q.base = 0; q.odd = 0;
+    q.pair = word_at(q, 0) | (word_at(q, 64) << 16); q.next = word_at(q, 128) | (word_at(q, 192) << 16);
+    q.far0 = word_at(q, 256); q.far1 = word_at(q, 320);
+    q.cur = q.pair;
+}
+// the first window is used up
+__device__ __forceinline__ void words_move_on(Words &q) {
+    q.base += 64u;
+    if (q.odd) {                                              // (uniform)
+        q.pair = q.next;
+        q.next = q.far0 | (q.far1 << 16);
+        // (the loads stay behind the last use of the registers they fill: moved ahead of it, they would need
+        // other registers and copies, which would wait for them)
+        asm volatile("; the far windows have moved, their registers are asked for again" : "+v"(q.pair), "+v"(q.next) : : "memory");
+        q.far0 = word_at(q, q.base + 256u);
+        q.far1 = word_at(q, q.base + 320u);
+    }
+    q.odd ^= 1u;
+    q.cur = q.odd ? (q.pair >> 16) | (q.next << 16) : q.pair;
 }
 
 template <int B, bool WHOLE>
@@ -485,14 +512,10 @@ __device__ __forceinline__ void decode_round(uint32_t *dst_row, uint32_t run, in
         const uint64_t who = __builtin_amdgcn_ballot_w64(need);
         if (who) {
             const uint32_t at = pos - q.base + rank_in(who);   // < 128
-            const uint32_t both = (uint32_t)__builtin_amdgcn_ds_bpermute((int)((at & 63u) << 2), (int)q.w01);
+            const uint32_t both = (uint32_t)__builtin_amdgcn_ds_bpermute((int)((at & 63u) << 2), (int)q.cur);
             if (need) x = (x << 16) | ((both >> ((at & 64u) >> 2)) & 0xFFFFu);
             pos += (uint32_t)__builtin_popcountll(who);
-            if (pos - q.base >= 64u) {
-                q.base += 64u;
-                q.w01 = (q.w01 >> 16) | (q.w2 << 16); q.w2 = q.w3;
-                q.w3 = word_at(q, q.base + 192u);
-            }
+            if (pos - q.base >= 64u) words_move_on(q);
         }
     }
     const uint32_t nd = (WHOLE || valid >= 32) ? (uint32_t)B : (valid > 0 ? ((uint32_t)valid * B + 31u) >> 5 : 0u);
@@ -524,7 +547,8 @@ k_rans_decode(const Params p, const EntropyLayout e, const uint8_t *__restrict__
     const uint8_t *sym = reinterpret_cast<const uint8_t *>(sym32);
     const uint8_t *stream = eblob + e.off_streams + a;
     Words q;
-    words_open(q, reinterpret_cast<const uint16_t *>(stream + 4u * coders), (uint32_t)(b - a - 4u * coders) >> 1);
+    words_open(q, reinterpret_cast<const uint16_t *>(stream + 4u * coders), (uint32_t)(b - a - 4u * coders) >> 1,
+               reinterpret_cast<const uint16_t *>(stream));
     uint32_t x = lane < coders ? reinterpret_cast<const uint32_t *>(stream)[lane] : kRansLow, pos = 0;
     uint32_t *dst_row = reinterpret_cast<uint32_t *>(blob + p.off_payload + po);
     const uint32_t rounds = (p.runs + 63u) / 64u;
