@@ -3,7 +3,8 @@
  * read from a blob, an entropy-coded blob or a workspace before using them as addresses, evaluated
  * on the HOST.  Each call runs the very predicate the kernels compile (one source, built for both
  * sides), so that a test without a GPU can drive it with wrapping offsets and noise.  Plain values
- * in, 1 (admissible) or 0 out; no pointers, no device, no errors.
+ * in, 1 (admissible) or 0 out; no device, no errors.  tsq_check_quotients does the same for the one step of
+ * the entropy coder's arithmetic that rests on a rounding argument.
  */
 #ifndef TSQ_RANGES_H
 #define TSQ_RANGES_H
@@ -30,6 +31,10 @@ int tsq_check_stream_span(uint64_t begin, uint64_t end, uint64_t capacity, uint3
 int tsq_check_stream_move(uint32_t bytes, uint32_t coders, uint32_t slot_bytes, uint64_t at, uint64_t capacity);
 /* Index into the 4096-entry frequency table from a coder state (always below 4096). */
 uint32_t tsq_check_frequency_slot(uint32_t state);
+/* The entropy encoder's division step, for n pairs (HOST arrays): q[i] = the encoder's first estimate of
+ * floor(x[i] / f[i]), which is that quotient or one less whenever 1 <= f[i] <= 4096 and x[i] < f[i] << 20
+ * (the encoder then corrects it by the size of the remainder). */
+void tsq_check_quotients(const uint32_t *x, const uint32_t *f, uint32_t *q, uint64_t n);
 /* The shape recorded in a workspace against the plan's. */
 int tsq_check_workspace_shape(uint32_t ws_tokens, uint32_t ws_hidden, uint32_t tokens, uint32_t hidden);
 

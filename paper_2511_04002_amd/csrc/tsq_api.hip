@@ -559,6 +559,9 @@ int tsq_check_column(uint32_t column, uint32_t hidden) { return column_ok(column
 int tsq_check_stream_span(uint64_t begin, uint64_t end, uint64_t capacity, uint32_t coders, uint32_t slot_bytes) {
     return stream_span_ok(begin, end, capacity, coders, slot_bytes) ? 1 : 0;
 }
+void tsq_check_quotients(const uint32_t *x, const uint32_t *f, uint32_t *q, uint64_t n) {
+    for (uint64_t i = 0; i < n; ++i) q[i] = quotient_or_one_less(x[i], reciprocal_just_below(f[i]));
+}
 int tsq_check_stream_move(uint32_t bytes, uint32_t coders, uint32_t slot_bytes, uint64_t at, uint64_t capacity) {
     return stream_move_ok(bytes, coders, slot_bytes, at, capacity) ? 1 : 0;
 }

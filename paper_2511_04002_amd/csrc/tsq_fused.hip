@@ -82,16 +82,6 @@ __device__ __forceinline__ uint32_t opaque_zero() {
     return zero;
 }
 
-// The same pointer, held in vector registers from here on.  The kernel's loop needs more uniform values than
-// there are scalar registers; what does not fit is parked in lanes of a vector register and fetched back with a
-// vector instruction at every use.  A pointer that only one thread uses is cheaper as a plain vector value.
-template <typename T>
-__device__ __forceinline__ T *in_vector_registers(T *ptr) {
-    uint32_t lo = (uint32_t)reinterpret_cast<uintptr_t>(ptr), hi = (uint32_t)(reinterpret_cast<uintptr_t>(ptr) >> 32);
-    asm volatile("" : "+v"(lo), "+v"(hi));
-    return reinterpret_cast<T *>(((uintptr_t)hi << 32) | lo);
-}
-
 // A uniform value that the compiler is to keep as it is now, instead of deriving it again from its (wider)
 // sources wherever it is used.
 __device__ __forceinline__ uint32_t as_computed(uint32_t v) {
@@ -548,7 +538,7 @@ k_fused(const Params p, const uint16_t *__restrict__ in, uint8_t *__restrict__ b
 
     uint32_t *ctrl = reinterpret_cast<uint32_t *>(ws + p.ws_ctrl);
     uint32_t *error_flag = ctrl + kCtlError;
-    uint32_t *sizes = in_vector_registers(reinterpret_cast<uint32_t *>(ws + p.ws_sizes));
+    uint32_t *sizes = reinterpret_cast<uint32_t *>(ws + p.ws_sizes);
     const uint64_t *pre = reinterpret_cast<const uint64_t *>(ws + p.ws_prefix);
 
     // ticket class of this workgroup: class c owns the tokens t % C == c
@@ -556,9 +546,8 @@ k_fused(const Params p, const uint16_t *__restrict__ in, uint8_t *__restrict__ b
     const uint32_t n_cls = (p.tokens - cls + C - 1u) / C;   // tokens of the class (cls < C <= G <= tokens)
     uint32_t *counter = reinterpret_cast<uint32_t *>(ws + p.ws_tickets) + cls * kTicketStride;
 
-    // (used by thread 0 only, once per token)
-    uint8_t *bits = in_vector_registers(blob + p.off_bits);
-    float *scale = in_vector_registers(reinterpret_cast<float *>(blob + p.off_scale));
+    uint8_t *bits = blob + p.off_bits;
+    float *scale = reinterpret_cast<float *>(blob + p.off_scale);
     uint16_t *out_col = reinterpret_cast<uint16_t *>(blob + p.off_out_col);
     uint16_t *out_val = reinterpret_cast<uint16_t *>(blob + p.off_out_val);
     const uint32_t hidden = FULL ? 2048u * NW : p.hidden;

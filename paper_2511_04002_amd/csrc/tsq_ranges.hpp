@@ -2,7 +2,8 @@
 // entropy-coded blob, a workspace) before it uses them as addresses.  Plain integer predicates on
 // plain values, written without sums of untrusted values (which could wrap), compiled for the
 // device (the kernels call them) and for the host (tsq_check_* in tsq_api.hip evaluates them
-// for tests that need no GPU).
+// for tests that need no GPU).  Also here, for the same reason: the one piece of the entropy coder's
+// arithmetic whose exactness rests on a rounding argument.
 #pragma once
 
 #include <stdint.h>
@@ -52,6 +53,15 @@ TSQ_HD bool stream_move_ok(uint32_t bytes, uint32_t coders, uint32_t slot_bytes,
 
 // Index into the 4096-entry cumulative-frequency table from a coder state.
 TSQ_HD uint32_t frequency_slot(uint32_t state) { return state & 4095u; }
+
+// The entropy coder's division.  floor(x / f) or one less, for x < f << 20 (so the quotient is below 2^20)
+// and 1 <= f <= 4096, from `below` = the binary32 quotient 1 / f times (1 - 2^-21), rounded.  With e = 2^-24
+// the unit roundoff: below lies in [(1 - 2^-21)(1 - e)^2 / f, (1 - 2^-21)(1 + e)^2 / f], and the product of
+// (float)x and below carries two more roundings, so it lies in [x/f * (1 - 2^-21)(1 - e)^4,
+// x/f * (1 - 2^-21)(1 + e)^4]: never above x/f (4e < 2^-21), and less than x/f * 12e < 0.75 below it.  Its
+// integer part is therefore floor(x/f) or floor(x/f) - 1, which the size of the remainder tells.
+TSQ_HD float reciprocal_just_below(uint32_t f) { return (1.0f / (float)f) * 0.999999523162841796875f; }   // 1 - 2^-21
+TSQ_HD uint32_t quotient_or_one_less(uint32_t x, float below) { return (uint32_t)((float)x * below); }
 
 // A workspace's recorded shape against the plan's.
 TSQ_HD bool workspace_shape_ok(uint32_t ws_tokens, uint32_t ws_hidden, uint32_t tokens, uint32_t hidden) {

@@ -29,7 +29,6 @@ namespace tsq {
 
 constexpr uint32_t kProbBits = 12, kProbScale = 1u << kProbBits, kRansLow = 1u << 16;
 static_assert(kProbScale == 4096, "frequency_slot() masks 12 bits");
-constexpr float kJustBelowOne = 0.999999523162841796875f;        // 1 - 2^-21 (see quotient_or_one_less)
 
 __device__ __forceinline__ bool blob_is_valid(const Params &p, const uint8_t *blob) {
     const BlobHeader *h = reinterpret_cast<const BlobHeader *>(blob);
@@ -147,8 +146,7 @@ __device__ __forceinline__ void load_table(const uint16_t *table, uint2 *ftab) {
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
         const uint32_t fi = f[i] ? f[i] : 1u;
-        const float below = (1.0f / (float)fi) * kJustBelowOne;
-        ftab[4u * lane + i] = make_uint2(fi | (cum << 16), __float_as_uint(below));
+        ftab[4u * lane + i] = make_uint2(fi | (cum << 16), __float_as_uint(reciprocal_just_below(fi)));
         cum += f[i];
     }
 }
@@ -166,16 +164,6 @@ __device__ __forceinline__ void load_table_decode(const uint16_t *table, uint32_
         ftab[4u * lane + i] = f[i] | (cum << 16);
         cum += f[i];
     }
-}
-
-// floor(x / f) or one less, for x < f << 20 (so the quotient is below 2^20) and f <= 4096, from `below`, the
-// binary32 quotient 1 / f times (1 - 2^-21), rounded.  With e = 2^-24 the unit roundoff: below lies in
-// [(1 - 2^-21)(1 - e)^2 / f, (1 - 2^-21)(1 + e)^2 / f], and the product of (float)x and below carries two
-// more roundings, so it lies in [x/f * (1 - 2^-21)(1 - e)^4, x/f * (1 - 2^-21)(1 + e)^4]: never above x/f
-// (4e < 2^-21), and less than x/f * 12e < 0.75 below it.  Its integer part is therefore
-// floor(x/f) or floor(x/f) - 1, which the size of the remainder tells.  The products fit 24 x 24 bits.
-__device__ __forceinline__ uint32_t quotient_or_one_less(uint32_t x, float below) {
-    return (uint32_t)((float)x * below);
 }
 
 // How many of the lanes before this one are set in `who`.

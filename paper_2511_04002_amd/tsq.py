@@ -31,6 +31,7 @@ EXPORTS = ("tsq_plan_create", "tsq_plan_destroy", "tsq_plan_layout", "tsq_plan_b
            # tsq_ranges.h
            "tsq_check_payload_span", "tsq_check_csr_slice", "tsq_check_csr_slice_holds", "tsq_check_column",
            "tsq_check_stream_span", "tsq_check_stream_move", "tsq_check_frequency_slot", "tsq_check_workspace_shape",
+           "tsq_check_quotients",
            "tsq_entropy_blob_bytes", "tsq_entropy_workspace_bytes", "tsq_entropy_encode", "tsq_entropy_decode",
            "tsq_entropy_info", "tsq_link_outage_probability", "tsq_link_latency", "tsq_link_best_rate", "tsq_early_exit_decide",
            "tsq_early_exit_walk")
@@ -146,6 +147,8 @@ def lib():
                            ("tsq_check_workspace_shape", [u32, u32, u32, u32])):
             getattr(L, name).restype = C.c_int
             getattr(L, name).argtypes = args
+        L.tsq_check_quotients.restype = None
+        L.tsq_check_quotients.argtypes = [vp, vp, vp, u64]
         L.tsq_check_frequency_slot.restype = u32
         L.tsq_check_frequency_slot.argtypes = [u32]
         L.tsq_decompress.restype = u

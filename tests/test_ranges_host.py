@@ -78,3 +78,42 @@ def test_slot_and_shape(L):
     for a in (0, 1, 600, U32):
         for b in (0, 8, 4096, U32):
             assert L.tsq_check_workspace_shape(a, b, 600, 4096) == int((a, b) == (600, 4096))
+
+
+def test_encoder_quotient_is_exact_or_one_less(L):
+    """The entropy encoder divides a state x < f << 20 by a frequency 1 <= f <= 4096 through a binary32 product
+    with a reciprocal rounded down a little, and repairs the result by the size of the remainder.  That is
+    exact only if the product's integer part is floor(x / f) or one less, for EVERY admissible pair; here the
+    very routine the kernel compiles is run on the host for every f, on the pairs where a rounding could
+    hurt (just below, at and just above multiples of f; the largest quotients, where the product has the
+    fewest spare bits; states with all mantissa bits set) and on noise."""
+    g = np.random.Generator(np.random.PCG64(7))
+    xs, fs = [], []
+    for f in range(1, 4097):
+        top = (f << 20) - 1                                   # the largest admissible state
+        qs = np.concatenate([
+            np.array([1, 2, 3, 255, 256, 4095, 4096, 65535, 65536, (1 << 19) - 1, 1 << 19, (1 << 20) - 2, (1 << 20) - 1], np.int64),
+            g.integers(1, 1 << 20, 40)])
+        for r in (-1, 0, 1, f // 2, f - 1):
+            x = qs * f + r
+            x = x[(x >= 0) & (x <= top)]
+            xs.append(x); fs.append(np.full(x.size, f, np.int64))
+        x = g.integers(0, top + 1, 60)
+        xs.append(x); fs.append(np.full(x.size, f, np.int64))
+        # states whose binary32 conversion rounds up: low bits all ones
+        x = np.minimum(top, (g.integers(1 << 24, 1 << 32, 20) | 0xFF))
+        xs.append(x); fs.append(np.full(x.size, f, np.int64))
+        xs.append(np.array([top, top - 1, 0, f - 1, f], np.int64)); fs.append(np.full(5, f, np.int64))
+    x = np.concatenate(xs).astype(np.uint32); f = np.concatenate(fs).astype(np.uint32)
+    assert np.all(x.astype(np.int64) < (f.astype(np.int64) << 20))
+    q = np.zeros(x.size, np.uint32)
+    L.tsq_check_quotients(x.ctypes.data, f.ctypes.data, q.ctypes.data, x.size)
+    true = x.astype(np.int64) // f.astype(np.int64)
+    d = true - q.astype(np.int64)
+    assert d.min() >= 0 and d.max() <= 1, (x[d.argmax()], f[d.argmax()], x[d.argmin()], f[d.argmin()])
+    # both cases occur, so the test exercises the correction
+    assert (d == 0).any() and (d == 1).any()
+    # what the encoder makes of it: remainder below 2f, and the repaired pair is the true one
+    r1 = x.astype(np.int64) - q.astype(np.int64) * f.astype(np.int64)
+    assert np.all((r1 >= 0) & (r1 < 2 * f.astype(np.int64)))
+    assert np.array_equal(np.where(r1 >= f, q.astype(np.int64) + 1, q.astype(np.int64)), true)
