@@ -88,6 +88,17 @@ def test_edge_rows_and_ragged_hidden(tsq, oracle, RE, dtype, H):
         check(tsq, oracle, RE, x, dtype, 6.0, bs, bud, mode, label="edge H=%d" % H)
 
 
+@pytest.mark.parametrize("H", [8192 + 264, 16384 + 24, 32768])
+def test_rows_of_more_than_four_runs_per_lane(tsq, oracle, RE, H):
+    """Rows beyond 8192 elements: the counting kernel takes a lane's runs four at a time and goes round more
+    than once, the coders and the gather loop further than on any benchmarked shape; the longest row the
+    library takes is among them."""
+    g = np.random.Generator(np.random.PCG64(H))
+    v = g.standard_t(4, size=(5, H)) * g.lognormal(0.0, 0.6, (5, 1)) * 2.0
+    check(tsq, oracle, RE, synth.to_bf16_bits(v), "bf16", 10.0, (2, 3, 5, 8), 0.1, label="long rows H=%d" % H)
+    check(tsq, oracle, RE, synth.to_f16_bits(v), "f16", 6.0, (4, 7), 0.3, 0, label="long rows H=%d" % H)
+
+
 @pytest.mark.parametrize("seed", range(3))
 def test_random_configurations(tsq, oracle, RE, seed):
     g = np.random.Generator(np.random.PCG64(2000 + seed))
