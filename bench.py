@@ -69,8 +69,13 @@ def parse():
     ap.add_argument("--nbuf", type=int, default=0,
                     help="buffer sets rotated through (default 4; 1 for C5 and the KV workloads, whose "
                          "single set is beyond the last-level cache already)")
-    ap.add_argument("--graph", action="store_true",
-                    help="replay the timed steps as one HIP graph (the line reports both launch modes either way)")
+    ap.add_argument("--launch", default="auto", choices=["auto", "stream", "graph", "two-streams"],
+                    help="how the timed steps that give the headline are enqueued (the line reports all three either "
+                         "way): one by one on one stream; replayed from a HIP graph; compress calls on one stream and "
+                         "decompress calls on a second one, each decompress behind its compress by an event, so that "
+                         "a step's decompress overlaps the next step's compress.  auto: the faster of stream and "
+                         "two-streams")
+    ap.add_argument("--graph", action="store_true", help="the same as --launch graph")
     ap.add_argument("--bits", default="", help="allowed widths, e.g. 2,4,8 (default: the workload's set)")
     ap.add_argument("--tau", type=float, default=0.0, help="outlier threshold (default: the workload's)")
     ap.add_argument("--c5-seqs", type=int, default=32)
@@ -196,25 +201,54 @@ def main():
         x0 = torch.from_numpy(x.view(np.int16)).cuda()
         xs = [x0] + [x0.clone() for _ in range(nbuf - 1)]
         outs = [plan.new_output() for _ in range(nbuf)]
-    blobs = [plan.new_blob() for _ in range(nbuf)]
+    nblob = max(nbuf, 2)                   # (two streams: a blob is read while the next one is written)
+    blobs = [plan.new_blob() for _ in range(nblob)]
     ws = plan.new_workspace()
+
+    def compress(k, kb):
+        if parts:
+            plan.compress_batch(xs[k], blobs[kb], ws, table=tin[k])
+        else:
+            plan.compress(xs[k], blobs[kb], ws)
+
+    def decompress(k, kb):
+        if parts:
+            plan.decompress_batch(blobs[kb], outs[k], table=tout[k])
+        else:
+            plan.decompress(blobs[kb], outs[k])
 
     def step(i, ev=None):
         k = i % nbuf
         if ev:
             ev[0].record()
-        if parts:
-            plan.compress_batch(xs[k], blobs[k], ws, table=tin[k])
-        else:
-            plan.compress(xs[k], blobs[k], ws)
+        compress(k, k)
         if ev:
             ev[1].record()
-        if parts:
-            plan.decompress_batch(blobs[k], outs[k], table=tout[k])
-        else:
-            plan.decompress(blobs[k], outs[k])
+        decompress(k, k)
         if ev:
             ev[2].record()
+
+    # The same steps on two streams: every compress call on the current stream, every decompress call on a second
+    # one, behind its compress call by an event; a blob is written again only when the decompress call that read it
+    # has finished (another event).  Step i's decompress then overlaps step i+1's compress; every step still does
+    # all of its work, in order.  (All compress calls share a stream, so no two single-pass kernels meet.)
+    second = torch.cuda.Stream()
+    written = [torch.cuda.Event() for _ in range(nblob)]
+    read = [torch.cuda.Event() for _ in range(nblob)]
+
+    def steps_on_two_streams(first, count):
+        main_stream = torch.cuda.current_stream()
+        for i in range(first, first + count):
+            k, kb = i % nbuf, i % nblob
+            if i - first >= nblob:
+                main_stream.wait_event(read[kb])
+            compress(k, kb)
+            written[kb].record(main_stream)
+            with torch.cuda.stream(second):
+                second.wait_event(written[kb])
+                decompress(k, kb)
+                read[kb].record(second)
+        main_stream.wait_stream(second)
 
     for i in range(args.warmup):
         step(i)
@@ -230,8 +264,9 @@ def main():
             step(i)
         torch.cuda.synchronize()
 
-    def timed_region(graph):
-        """Exactly K steps between two events on the stream (nothing else is enqueued in between)."""
+    def timed_region(graph, two_streams=False):
+        """Exactly K steps between two events on the stream (nothing else is enqueued in between; with two
+        streams the second event waits for the second stream's last call)."""
         e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
         torch.cuda.synchronize()
         t0 = time.perf_counter()
@@ -239,6 +274,8 @@ def main():
         if graph is not None:
             for _ in range(args.steps // graph_steps):
                 graph.replay()
+        elif two_streams:
+            steps_on_two_streams(args.warmup, args.steps)
         else:
             for i in range(args.steps):
                 step(args.warmup + i)
@@ -252,7 +289,6 @@ def main():
     # take about 1.3 us longer each on this stack (measured: 84.4 -> 87.1 us per step), as they do in the graph
     ms_stream, wall_stream = timed_region(None)
     assert plan.info(blobs[0]).status == 0
-
     # compress / decompress split of the same steps (events between the two calls: not the headline)
     n_split = min(args.steps, 200)
     evs = [[torch.cuda.Event(enable_timing=True) for _ in range(3)] for _ in range(n_split)]
@@ -332,6 +368,29 @@ def main():
         ceil = copy_ceilings(tsq, torch, xs[0], outs[0], parts[0].size * 2, plan._stream(), reps=2 * len(parts))
     else:
         ceil = copy_ceilings(tsq, torch, xs, outs, 2 * n, plan._stream())
+    # the two-stream pass: warm-up steps of its own, then K steps; its outputs must be those of the steps on one stream.
+    # (It comes after the per-call timings: once a second stream has been used, an event pair around a single
+    # call reads about 2 us more.)
+    # (Left out when one stream or the graph is asked for by name: a kernel trace of such a run then holds no
+    # kernels that ran side by side.)
+    ms_two, wall_two = None, None
+    if not args.graph and args.launch in ("auto", "two-streams"):
+        step(0)                            # (the copy kernels above wrote to the outputs)
+        torch.cuda.synchronize()
+        if parts:
+            want_out = [t.clone() for t in outs[0]]
+            for t in outs[0]:
+                t.zero_()
+        else:
+            want_out = outs[0].clone()
+            outs[0].zero_()
+        steps_on_two_streams(0, args.warmup)
+        ms_two, wall_two = timed_region(None, two_streams=True)
+        assert all(plan.info(b).status == 0 for b in blobs)
+        same = all(torch.equal(a, b) for a, b in zip(want_out, outs[0])) if parts else torch.equal(want_out, outs[0])
+        assert same, "the steps on two streams restored something else than the steps on one"
+        del want_out
+
     # the graph pass, last (see above)
     graph_steps = max(d for d in range(1, min(args.steps, 100) + 1) if args.steps % d == 0)
     side = torch.cuda.Stream()
@@ -345,7 +404,14 @@ def main():
     for _ in range(max(1, args.warmup // graph_steps)):
         graph.replay()                     # untimed
     ms_graph, wall_graph = timed_region(graph)
-    ms_per_step, wall = (ms_graph, wall_graph) if args.graph else (ms_stream, wall_stream)
+    launch = "graph" if args.graph else args.launch
+    if launch == "auto":
+        launch = "two-streams" if ms_two < ms_stream else "stream"
+    ms_per_step, wall = {"stream": (ms_stream, wall_stream), "graph": (ms_graph, wall_graph),
+                         "two-streams": (ms_two, wall_two)}[launch]
+    launch_name = {"stream": "stream", "graph": "hip graph",
+                   "two-streams": "two streams: compress calls on one, decompress calls on the other, each behind its "
+                                  "compress call by an event"}[launch]
     assert plan.info(blobs[0]).status == 0
     pair_gbps = (alg_c + alg_d) / ms_per_step / 1e6
     copy_pair_ms = (alg_c + alg_d) / (ceil["copy_GBps"] * 1e6)      # the pair's bytes at the copy kernel's rate
@@ -364,11 +430,15 @@ def main():
                                (" as %d tensors of %d rows" % (len(parts), parts[0].shape[0]) if parts else ""),
                    "tau": tau,
                    "bit_set": list(bit_set), "budget": "%.3g x row RMS" % args.eps,
-                   "pipeline": pipe, "launch": "hip graph" if args.graph else "stream", "buffer_sets": nbuf, "mean_width": round(bbar, 3),
+                   "pipeline": pipe, "launch": launch_name, "buffer_sets": nbuf, "mean_width": round(bbar, 3),
                    "outlier_fraction": round(rho, 6), "width_hist": list(info.width_hist),
                    "compression_ratio": round(2.0 * n / info.compressed_bytes, 3)},
         "launch_modes": {"stream_ms_per_step": ms_stream, "hip_graph_ms_per_step": ms_graph,
-                         "graph_holds_steps": graph_steps},
+                         "two_streams_ms_per_step": ms_two, "graph_holds_steps": graph_steps,
+                         "pair_frac": {"stream": (alg_c + alg_d) / ms_stream / 1e6 / HBM_PEAK_GBS,
+                                       "hip_graph": (alg_c + alg_d) / ms_graph / 1e6 / HBM_PEAK_GBS,
+                                       "two_streams": (alg_c + alg_d) / ms_two / 1e6 / HBM_PEAK_GBS if ms_two else None},
+                         "headline": launch},
         # the bar: algorithmic bytes of compress + decompress over the timed step, against the 8 TB/s peak
         "target": {"quantity": "roofline.pair_frac", "bar": 0.6, "met": pair_gbps / HBM_PEAK_GBS >= 0.6},
         "roofline": {"bound": "hbm", "kernel": dom, "achieved": achieved, "peak": HBM_PEAK_GBS,

@@ -259,3 +259,46 @@ def test_calls_that_alternate_between_two_streams_do_not_stall_each_other(tsq, o
             assert plan.info(b).status == 0
             assert np.array_equal(plan.sections(b)["payload"], ref.payload)
         assert np.array_equal(out.cpu().numpy().view(np.uint16), oracle.decompress(ref, nthreads=8))
+
+
+@pytest.mark.parametrize("shape", ["C2", "C4 rows"])
+def test_a_decompress_stream_behind_a_compress_stream(tsq, oracle, shape):
+    """The launch pattern that bench.py calls two streams: every compress call on one stream, every decompress
+    call on a second one, behind its compress call by an event, a blob written again only after the call that
+    read it.  A step's restore kernel then runs beside the next step's single-pass kernel, whose workgroups
+    wait for one another; many steps, different inputs per buffer set, every output equal to the oracle's."""
+    import torch
+    if shape == "C2":
+        base, dtype, tau, bits, odt = synth.make_c2(tokens=2048), "f16", 8.0, (2, 3, 4, 6, 8), oracle.F16
+    else:
+        base, dtype, tau, bits, odt = synth.make_c4(tokens=1536), "bf16", 10.0, (2, 3, 4, 5, 6, 8), oracle.BF16
+    T, H = base.shape
+    nset = 3
+    xs = [np.ascontiguousarray(np.roll(base, 7 * k, axis=0)) for k in range(nset)]     # a tensor of its own per set
+    refs = [oracle.compress(x, odt, tau, bits, 0.05, 1, nthreads=8) for x in xs]
+    plan = tsq.Plan(T, H, dtype, tau, bits, 0.05, pipeline="fused", max_outliers=max(max(r.nnz for r in refs), 1))
+    xd = [torch.from_numpy(x.view(np.int16)).cuda() for x in xs]
+    blobs, outs, ws = [plan.new_blob() for _ in range(nset)], [plan.new_output() for _ in range(nset)], plan.new_workspace()
+    first, second = torch.cuda.Stream(), torch.cuda.Stream()
+    written, read = [torch.cuda.Event() for _ in range(nset)], [torch.cuda.Event() for _ in range(nset)]
+    torch.cuda.synchronize()
+    steps = 300
+    for i in range(steps):
+        k = i % nset
+        with torch.cuda.stream(first):
+            if i >= nset:
+                first.wait_event(read[k])
+            plan.compress(xd[k], blobs[k], ws)
+            written[k].record(first)
+        with torch.cuda.stream(second):
+            second.wait_event(written[k])
+            plan.decompress(blobs[k], outs[k])
+            read[k].record(second)
+        if i % 100 == 99:
+            print("step", i, flush=True)
+    torch.cuda.synchronize()
+    for k in range(nset):
+        assert plan.info(blobs[k]).status == 0
+        sec = plan.sections(blobs[k])
+        assert np.array_equal(sec["payload"], refs[k].payload) and np.array_equal(sec["out_col"], refs[k].out_col)
+        assert np.array_equal(outs[k].cpu().numpy().view(np.uint16), oracle.decompress(refs[k], nthreads=8))
