@@ -439,7 +439,8 @@ class Plan:
 
     def __del__(self):
         h = getattr(self, "handle", None)
-        if h:
+        # (at interpreter shutdown the module's globals may be gone before the last plan is)
+        if h and tsq_plan_destroy is not None:
             tsq_plan_destroy(h)
             self.handle = None
 
