@@ -64,7 +64,7 @@ struct EntropyLayout {
 constexpr uint32_t kLenBlock = 256;     // tokens per partial sum of stream lengths
 constexpr uint32_t kBlockStride = 64;   // 32-bit words from one partial sum to the next: the encoder's waves add to them, and
                                         // adds to one 128-byte line from all over the chip hold up the stores queued behind them
-constexpr uint32_t kMaxPoolGroups = 512;    // counting workgroups: two fit a compute unit (LDS), 256 compute units: one round
+constexpr uint32_t kMaxPoolGroups = 512;    // counting workgroups of 1024 threads: two fit a compute unit, 256 compute units: one round
 constexpr uint32_t kPoolCopies = 16;    // sets of pooled counts: 16 times fewer atomic adds per address
 
 // Kernel argument block (passed by value).
