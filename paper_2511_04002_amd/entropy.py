@@ -27,19 +27,27 @@ def shannon_bits(counts: np.ndarray) -> float:
 
 def main():
     ap = argparse.ArgumentParser()
-    ap.add_argument("--workload", default="C4", choices=["C1", "C2", "C3", "C4"])
+    ap.add_argument("--workload", default="C4", choices=["C1", "C2", "C3", "C4", "KV7", "KV13"],
+                    help="KV7 / KV13: the cache of the batch form (one blob for all the per-layer key and value tensors)")
     ap.add_argument("--eps", type=float, default=0.05)
     ap.add_argument("--steps", type=int, default=20)
     args = ap.parse_args()
     from . import synth
     w = synth.WORKLOADS[args.workload]
-    x = synth.make_c3(0) if args.workload == "C3" else synth.make(args.workload)
+    kv = args.workload.startswith("KV")
+    parts = synth.make_kv(args.workload) if kv else None
+    x = None if kv else (synth.make_c3(0) if args.workload == "C3" else synth.make(args.workload))
     import torch
     from . import tsq
     tsq.lib()
-    T, H = x.shape
+    T, H = (len(parts) * parts[0].shape[0], parts[0].shape[1]) if kv else x.shape
     plan = tsq.Plan(T, H, w.dtype, w.tau, w.bit_set, args.eps, max_outliers=max(1, T * H // 8))
-    blob = plan.compress(torch.from_numpy(x.view(np.int16)).cuda())
+    if kv:
+        tensors = [torch.from_numpy(t.view(np.int16)).cuda() for t in parts]
+        blob, _table = plan.compress_batch(tensors)
+        torch.cuda.synchronize()
+    else:
+        blob = plan.compress(torch.from_numpy(x.view(np.int16)).cuda())
     info = plan.info(blob)
     hist = plan.code_histogram(blob)
     e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)

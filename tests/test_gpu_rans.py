@@ -158,6 +158,36 @@ def test_more_tokens_than_the_counting_kernel_takes_in_one_go(tsq, oracle, RE):
     assert np.array_equal(plan.sections(blob2)["payload"], ref.payload)
 
 
+def test_the_blob_of_a_batch_call(tsq, oracle, RE):
+    """The stage takes any blob of the plan: here the one that the batch form writes for the key and value
+    tensors of a KV cache (one blob for all of them), against the oracle on the concatenated tensor."""
+    import torch
+    R, E = RE
+    parts = synth.make_kv("KV7", layers=3, rows=40)
+    w = synth.WORKLOADS["KV7"]
+    x = np.concatenate(parts)
+    T, H = x.shape
+    ref = oracle.compress(x, DT[w.dtype], w.tau, w.bit_set, 0.1, 1, nthreads=8)
+    tables, off, streams = R.encode(ref, E.code_histogram(ref))
+    plan = tsq.Plan(T, H, w.dtype, w.tau, w.bit_set, 0.1, max_outliers=max(ref.nnz, 1))
+    tensors = [torch.from_numpy(p.view(np.int16)).cuda() for p in parts]
+    blob, _table = plan.compress_batch(tensors)
+    assert plan.info(blob).status == 0
+    eblob = plan.entropy_encode(blob)
+    sec = plan.entropy_sections(eblob)
+    assert np.array_equal(sec["tables"], tables) and np.array_equal(sec["stream_off"], off)
+    assert sec["streams"].tobytes() == streams
+    L = plan.layout
+    blob2 = blob.clone()
+    blob2[int(L.off_payload): int(L.off_payload) + int(L.payload_capacity)] = 0x5A
+    plan.entropy_decode(eblob, blob2)
+    outs = [torch.empty_like(t) for t in tensors]
+    plan.decompress_batch(blob2, outs)
+    want = oracle.decompress(ref, nthreads=8)
+    got = np.concatenate([o.cpu().numpy().view(np.uint16) for o in outs])
+    assert np.array_equal(got, want)
+
+
 def test_a_foreign_blob_gives_no_valid_eblob(tsq):
     import torch
     plan = tsq.Plan(16, 64, "f16", 6.0, (4, 8), 0.05)
