@@ -273,6 +273,18 @@ tsq_status tsq_entropy_decode(const tsq_plan *plan, const void *d_eblob, void *d
 tsq_status tsq_entropy_info(const tsq_plan *plan, const void *d_eblob, tsq_entropy_layout *host_out, void *stream);
 
 /*
+ * Size in bytes of what carries the first k tokens when the codes travel entropy-coded: the blob's
+ * header, per-token metadata and CSR entries as in tsq_prefix_bytes, and in place of the codes the
+ * coded blob's header, its frequency tables (those of the whole blob: a prefix is coded with them),
+ * k + 1 stream offsets and the streams of the first k tokens.  For k = tokens that is
+ * tsq_info.compressed_bytes - payload_bytes + tsq_entropy_layout.coded_bytes.  d_eblob must be the
+ * coded form of d_blob.  k, n, bytes_out, synchronization and results as for tsq_prefix_bytes
+ * (FORMAT also for an eblob that is not this plan's).
+ */
+tsq_status tsq_entropy_prefix_bytes(const tsq_plan *plan, const void *d_blob, const void *d_eblob,
+                                    const uint32_t *k, uint32_t n, uint64_t *bytes_out, void *stream);
+
+/*
  * Reads the blob's header and widths back to the host.  SYNCHRONIZES `stream`.
  * Returns the status stored in the blob (CAPACITY / FORMAT / INTERNAL), FORMAT when
  * the header is not this plan's (host_out->status is 0 then), or OK.

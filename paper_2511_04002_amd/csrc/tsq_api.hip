@@ -531,6 +531,56 @@ tsq_status tsq_prefix_bytes(const tsq_plan *plan, const void *d_blob, const uint
     return st;
 }
 
+tsq_status tsq_entropy_prefix_bytes(const tsq_plan *plan, const void *d_blob, const void *d_eblob, const uint32_t *k,
+                                    uint32_t n, uint64_t *bytes_out, void *stream) {
+    if (!plan || !d_blob || !d_eblob || n == 0 || !bytes_out) return TSQ_ERR_INVALID_ARG;
+    const Params &p = plan->p;
+    const EntropyLayout &E = plan->e;
+    if (!k && (uint64_t)n > p.tokens + 1ull) return TSQ_ERR_INVALID_ARG;
+    for (uint32_t i = 0; k && i < n; ++i)
+        if (k[i] > p.tokens) return TSQ_ERR_INVALID_ARG;
+    hipStream_t s = reinterpret_cast<hipStream_t>(stream);
+    const uint8_t *blob = static_cast<const uint8_t *>(d_blob), *eblob = static_cast<const uint8_t *>(d_eblob);
+    BlobHeader h;
+    EntropyHeader eh;
+    if (hipMemcpyAsync(&h, blob, sizeof h, hipMemcpyDeviceToHost, s) != hipSuccess) return TSQ_ERR_HIP;
+    if (hipMemcpyAsync(&eh, eblob, sizeof eh, hipMemcpyDeviceToHost, s) != hipSuccess) {
+        (void)hipStreamSynchronize(s);
+        return TSQ_ERR_HIP;
+    }
+    // bytes_out doubles as the landing place of the stream offsets; row_ptr[k] lands in a buffer of its own
+    uint64_t *rp = static_cast<uint64_t *>(std::malloc(sizeof(uint64_t) * n));
+    if (!rp) { (void)hipStreamSynchronize(s); return TSQ_ERR_NO_MEMORY; }
+    int bad = 0;
+    if (!k) {
+        bad |= hipMemcpyAsync(bytes_out, eblob + E.off_stream_off, 8ull * n, hipMemcpyDeviceToHost, s) != hipSuccess;
+        bad |= hipMemcpyAsync(rp, blob + p.off_row_ptr, 8ull * n, hipMemcpyDeviceToHost, s) != hipSuccess;
+    }
+    for (uint32_t i = 0; k && i < n && !bad; ++i) {
+        bad |= hipMemcpyAsync(&bytes_out[i], eblob + E.off_stream_off + 8ull * k[i], 8, hipMemcpyDeviceToHost, s) != hipSuccess;
+        bad |= hipMemcpyAsync(&rp[i], blob + p.off_row_ptr + 8ull * k[i], 8, hipMemcpyDeviceToHost, s) != hipSuccess;
+    }
+    if (hipStreamSynchronize(s) != hipSuccess) bad = 1;
+    tsq_status st = bad ? TSQ_ERR_HIP : TSQ_OK;
+    if (st == TSQ_OK && (h.magic != kMagic || h.version != kVersion || h.tokens != p.tokens || h.hidden != p.hidden ||
+                         h.off_row_ptr != p.off_row_ptr))
+        st = TSQ_ERR_FORMAT;
+    if (st == TSQ_OK && h.status != 0) st = h.status == TSQ_ERR_CAPACITY ? TSQ_ERR_CAPACITY : TSQ_ERR_INTERNAL;
+    if (st == TSQ_OK && (eh.magic != kEntropyMagic || eh.version != kVersion || eh.tokens != p.tokens || eh.hidden != p.hidden ||
+                         eh.off_streams != E.off_streams || eh.stream_bytes > E.stream_capacity))
+        st = TSQ_ERR_FORMAT;
+    // the blob's header and per-token metadata of k tokens and its CSR entries, as in tsq_prefix_bytes; in place of the
+    // codes: the coded blob's header, its tables, k + 1 stream offsets and the streams before offset[k]
+    for (uint32_t i = 0; i < n && st == TSQ_OK; ++i) {
+        const uint64_t ki = k ? k[i] : i;
+        if (bytes_out[i] > eh.stream_bytes) { st = TSQ_ERR_FORMAT; break; }
+        bytes_out[i] = 128ull + 5ull * ki + 16ull * (ki + 1ull) + 4ull * rp[i] +
+                       sizeof(EntropyHeader) + 7ull * 256 * 2 + 8ull * (ki + 1ull) + bytes_out[i];
+    }
+    std::free(rp);
+    return st;
+}
+
 tsq_status tsq_compress_blocking(const tsq_plan *plan, const void *d_in, void *d_blob, void *d_ws, void *stream,
                                  tsq_info *info_out) {
     if (!info_out) return TSQ_ERR_INVALID_ARG;

@@ -18,8 +18,9 @@ import json
 import numpy as np
 
 
-def measure(tokens: int, layers: int, eps: float = 0.05):
-    """-> (raw_bits, compressed_bits_with_kv, hidden_prefix_bits) from GPU compress calls."""
+def measure(tokens: int, layers: int, eps: float = 0.05, entropy: bool = False):
+    """-> (raw_bits, compressed_bits_with_kv, hidden_prefix_bits) from GPU compress calls.  entropy: the codes
+    travel through the rANS stage (tsq_entropy_encode; sizes from tsq_entropy_prefix_bytes)."""
     import torch
     from . import synth, tsq
     w2, wk = synth.WORKLOADS["C2"], synth.WORKLOADS["KV7"]
@@ -28,15 +29,26 @@ def measure(tokens: int, layers: int, eps: float = 0.05):
     plan = tsq.Plan(tokens, H, w2.dtype, w2.tau, w2.bit_set, eps, max_outliers=tokens * H // 8)
     blob = plan.compress(torch.from_numpy(hid.view(np.int16)).cuda())
     info = plan.info(blob)
-    pre = [8 * v for v in plan.prefix_bytes(blob)]          # bits, k = 0 .. tokens (tsq_prefix_bytes)
-    assert pre[-1] == 8 * info.compressed_bytes
+    if entropy:
+        eblob = plan.entropy_encode(blob)
+        pre = [8 * v for v in plan.entropy_prefix_bytes(blob, eblob)]
+        einfo = tsq.tsq_entropy_info(plan.handle, eblob.data_ptr(), plan._stream())
+        hidden_bytes = info.compressed_bytes - info.payload_bytes + einfo.coded_bytes
+    else:
+        pre = [8 * v for v in plan.prefix_bytes(blob)]      # bits, k = 0 .. tokens (tsq_prefix_bytes)
+        hidden_bytes = info.compressed_bytes
+    assert pre[-1] == 8 * hidden_bytes
     kv = [torch.from_numpy(p.view(np.int16)).cuda() for p in synth.make_kv("KV7", layers=layers, rows=tokens)]
     plan_kv = tsq.Plan(2 * layers * tokens, H, wk.dtype, wk.tau, wk.bit_set, eps,
                        max_outliers=2 * layers * tokens * H // 8)
     blob_kv, _ = plan_kv.compress_batch(kv)
     info_kv = plan_kv.info(blob_kv)
+    kv_bytes = info_kv.compressed_bytes
+    if entropy:
+        eblob_kv = plan_kv.entropy_encode(blob_kv)
+        kv_bytes += tsq.tsq_entropy_info(plan_kv.handle, eblob_kv.data_ptr(), plan_kv._stream()).coded_bytes - info_kv.payload_bytes
     raw = 16.0 * (tokens * H + 2 * layers * tokens * H)           # Eq. (if_total), I_kv = 1, 16-bit activations
-    return raw, 8.0 * (info.compressed_bytes + info_kv.compressed_bytes), pre
+    return raw, 8.0 * (hidden_bytes + kv_bytes), pre
 
 
 class StepSizes:
@@ -103,6 +115,8 @@ def main():
     ap.add_argument("--layers", type=int, default=20)
     ap.add_argument("--c0", type=float, default=0.05, help="L_c(w) = c0 + c1 * w, seconds")
     ap.add_argument("--c1", type=float, default=0.002)
+    ap.add_argument("--entropy", action="store_true",
+                    help="the codes travel through the rANS stage (one-step form only)")
     ap.add_argument("--walk", action="store_true",
                     help="run Algorithm 2's loops over w = 1..tokens and layer = 1..layers, measuring sizes at each exit")
     args = ap.parse_args()
@@ -110,7 +124,7 @@ def main():
         walk(args.tokens, args.layers, args.c0, args.c1, (10.0, 1.0, 0.3, 0.1, 0.03, 0.01, 0.003))
         return
     from . import tsq
-    raw, with_kv, pre = measure(args.tokens, args.layers)
+    raw, with_kv, pre = measure(args.tokens, args.layers, entropy=args.entropy)
     link = tsq.tsq_link(10e6, 10.0, 1e-3)
     rate = tsq.tsq_link_best_rate(link, 1e5, 1e8, 2000)
     lc = [args.c0 + args.c1 * k if k else 0.0 for k in range(args.tokens + 1)]

@@ -31,7 +31,7 @@ EXPORTS = ("tsq_plan_create", "tsq_plan_destroy", "tsq_plan_layout", "tsq_plan_b
            # tsq_ranges.h
            "tsq_check_payload_span", "tsq_check_csr_slice", "tsq_check_csr_slice_holds", "tsq_check_column",
            "tsq_check_stream_span", "tsq_check_stream_move", "tsq_check_frequency_slot", "tsq_check_workspace_shape",
-           "tsq_check_quotients",
+           "tsq_check_quotients", "tsq_entropy_prefix_bytes",
            "tsq_entropy_blob_bytes", "tsq_entropy_workspace_bytes", "tsq_entropy_encode", "tsq_entropy_decode",
            "tsq_entropy_info", "tsq_link_outage_probability", "tsq_link_latency", "tsq_link_best_rate", "tsq_early_exit_decide",
            "tsq_early_exit_walk")
@@ -135,6 +135,8 @@ def lib():
         L.tsq_compress_blocking.argtypes = [vp, vp, vp, vp, vp, C.POINTER(tsq_info)]
         L.tsq_prefix_bytes.restype = u
         L.tsq_prefix_bytes.argtypes = [vp, vp, C.POINTER(C.c_uint32), C.c_uint32, C.POINTER(C.c_uint64), vp]
+        L.tsq_entropy_prefix_bytes.restype = u
+        L.tsq_entropy_prefix_bytes.argtypes = [vp, vp, vp, C.POINTER(C.c_uint32), C.c_uint32, C.POINTER(C.c_uint64), vp]
         L.tsq_measure_copy.restype = u
         L.tsq_measure_copy.argtypes = [vp, vp, C.c_size_t, vp]
         L.tsq_measure_read.restype = u
@@ -287,6 +289,21 @@ def tsq_prefix_bytes(plan: int, d_blob: int, k=None, n: int = 0, stream: int = 0
     st = lib().tsq_prefix_bytes(plan, d_blob, ks, n, out, stream)
     if st != TSQ_OK:
         raise TsqError(st, "tsq_prefix_bytes")
+    return list(out)
+
+
+def tsq_entropy_prefix_bytes(plan: int, d_blob: int, d_eblob: int, k=None, n: int = 0, stream: int = 0):
+    """-> list of sizes in bytes of what carries the first k tokens with the codes entropy-coded, for the counts
+    in `k` (or for k = 0 .. n-1 when k is None).  Synchronizes."""
+    if k is not None:
+        n = len(k)
+        ks = (C.c_uint32 * n)(*[int(v) for v in k])
+    else:
+        ks = None
+    out = (C.c_uint64 * n)()
+    st = lib().tsq_entropy_prefix_bytes(plan, d_blob, d_eblob, ks, n, out, stream)
+    if st != TSQ_OK:
+        raise TsqError(st, "tsq_entropy_prefix_bytes")
     return list(out)
 
 
@@ -551,6 +568,11 @@ class Plan:
     def prefix_bytes(self, blob, k=None):
         """Compressed size of the first k tokens for every k in `k` (default: k = 0 .. tokens)."""
         return tsq_prefix_bytes(self.handle, blob.data_ptr(), k, self.tokens + 1 if k is None else 0, self._stream())
+
+    def entropy_prefix_bytes(self, blob, eblob, k=None):
+        """Size of what carries the first k tokens with the codes entropy-coded, for every k in `k` (default: k = 0 .. tokens)."""
+        return tsq_entropy_prefix_bytes(self.handle, blob.data_ptr(), eblob.data_ptr(), k,
+                                        self.tokens + 1 if k is None else 0, self._stream())
 
     def sections(self, blob) -> Dict[str, "object"]:
         """Host copies (numpy) of the blob's sections, cut to their actual lengths."""

@@ -106,6 +106,12 @@ def test_null_arguments(L):
         assert L.tsq_prefix_bytes(plan, 0x2000, None, 2, None, None) == tsq.TSQ_ERR_INVALID_ARG
         assert L.tsq_prefix_bytes(plan, 0x2000, None, c.tokens + 2, out, None) == tsq.TSQ_ERR_INVALID_ARG
         assert L.tsq_prefix_bytes(plan, 0x2000, ks, 2, out, None) == tsq.TSQ_ERR_INVALID_ARG      # a count beyond the tokens
+        assert L.tsq_entropy_prefix_bytes(plan, None, 0x3000, None, 2, out, None) == tsq.TSQ_ERR_INVALID_ARG
+        assert L.tsq_entropy_prefix_bytes(plan, 0x2000, None, None, 2, out, None) == tsq.TSQ_ERR_INVALID_ARG
+        assert L.tsq_entropy_prefix_bytes(plan, 0x2000, 0x3000, None, 0, out, None) == tsq.TSQ_ERR_INVALID_ARG
+        assert L.tsq_entropy_prefix_bytes(plan, 0x2000, 0x3000, None, 2, None, None) == tsq.TSQ_ERR_INVALID_ARG
+        assert L.tsq_entropy_prefix_bytes(plan, 0x2000, 0x3000, None, c.tokens + 2, out, None) == tsq.TSQ_ERR_INVALID_ARG
+        assert L.tsq_entropy_prefix_bytes(plan, 0x2000, 0x3000, ks, 2, out, None) == tsq.TSQ_ERR_INVALID_ARG
         assert L.tsq_compress_static(plan, None, 0x2000, None) == tsq.TSQ_ERR_INVALID_ARG
     finally:
         tsq.tsq_plan_destroy(plan)
