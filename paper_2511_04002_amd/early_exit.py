@@ -56,10 +56,10 @@ class StepSizes:
     tokens at the split layer and the KV cache of the `layer` layers below it, compressed with tsq_compress /
     tsq_compress_batch (one plan per shape, kept)."""
 
-    def __init__(self, max_tokens: int, layers: int, eps: float = 0.05):
+    def __init__(self, max_tokens: int, layers: int, eps: float = 0.05, entropy: bool = False):
         import torch
         from . import synth, tsq
-        self.tsq, self.torch = tsq, torch
+        self.tsq, self.torch, self.entropy = tsq, torch, entropy
         self.w2, self.wk, self.eps = synth.WORKLOADS["C2"], synth.WORKLOADS["KV7"], eps
         self.H = self.w2.hidden
         self.hid = torch.from_numpy(synth.make_c2(tokens=max_tokens).view(np.int16)).cuda()
@@ -75,7 +75,10 @@ class StepSizes:
                                  max_outliers=max(1, w * self.H // 8))
             blob = plan.compress(self.hid[:w].contiguous())
             self.compress_calls += 1
-            self.cache[key] = [8 * v for v in plan.prefix_bytes(blob)]
+            if self.entropy:
+                self.cache[key] = [8 * v for v in plan.entropy_prefix_bytes(blob, plan.entropy_encode(blob))]
+            else:
+                self.cache[key] = [8 * v for v in plan.prefix_bytes(blob)]
         return self.cache[key]
 
     def kv_bits(self, w: int, layer: int) -> float:
@@ -85,7 +88,12 @@ class StepSizes:
                                  max_outliers=max(1, 2 * layer * w * self.H // 8))
             blob, _ = plan.compress_batch([t[:w].contiguous() for t in self.kv[: 2 * layer]])
             self.compress_calls += 1
-            self.cache[key] = 8.0 * plan.info(blob).compressed_bytes
+            info = plan.info(blob)
+            nbytes = info.compressed_bytes
+            if self.entropy:
+                eblob = plan.entropy_encode(blob)
+                nbytes += self.tsq.tsq_entropy_info(plan.handle, eblob.data_ptr(), plan._stream()).coded_bytes - info.payload_bytes
+            self.cache[key] = 8.0 * nbytes
         return self.cache[key]
 
     def bits(self, w, layer, with_kv, compressed, keep):
@@ -94,10 +102,10 @@ class StepSizes:
         return float(self.hidden_prefix_bits(w)[keep]) + (self.kv_bits(w, layer) if with_kv else 0.0)
 
 
-def walk(max_tokens: int, layers: int, c0: float, c1: float, deadlines):
+def walk(max_tokens: int, layers: int, c0: float, c1: float, deadlines, entropy: bool = False):
     """Algorithm 2 with both loops (tsq_early_exit_walk); sizes are measured at the step that needs them."""
     from . import tsq
-    sizes = StepSizes(max_tokens, layers)
+    sizes = StepSizes(max_tokens, layers, entropy=entropy)
     link = tsq.tsq_link(10e6, 10.0, 1e-3)
     rate = tsq.tsq_link_best_rate(link, 1e5, 1e8, 2000)
     names = {1: "compressed", 3: "fewer_tokens", 4: "completed"}
@@ -116,12 +124,12 @@ def main():
     ap.add_argument("--c0", type=float, default=0.05, help="L_c(w) = c0 + c1 * w, seconds")
     ap.add_argument("--c1", type=float, default=0.002)
     ap.add_argument("--entropy", action="store_true",
-                    help="the codes travel through the rANS stage (one-step form only)")
+                    help="the codes travel through the rANS stage (sizes from tsq_entropy_prefix_bytes)")
     ap.add_argument("--walk", action="store_true",
                     help="run Algorithm 2's loops over w = 1..tokens and layer = 1..layers, measuring sizes at each exit")
     args = ap.parse_args()
     if args.walk:
-        walk(args.tokens, args.layers, args.c0, args.c1, (10.0, 1.0, 0.3, 0.1, 0.03, 0.01, 0.003))
+        walk(args.tokens, args.layers, args.c0, args.c1, (10.0, 1.0, 0.3, 0.1, 0.03, 0.01, 0.003), entropy=args.entropy)
         return
     from . import tsq
     raw, with_kv, pre = measure(args.tokens, args.layers, entropy=args.entropy)
