@@ -373,7 +373,7 @@ def main():
     # call reads about 2 us more.)
     # (Left out when one stream or the graph is asked for by name: a kernel trace of such a run then holds no
     # kernels that ran side by side.)
-    ms_two, wall_two = None, None
+    ms_two, wall_two, two_streams_failed = None, None, False
     if not args.graph and args.launch in ("auto", "two-streams"):
         step(0)                            # (the copy kernels above wrote to the outputs)
         torch.cuda.synchronize()
@@ -386,9 +386,19 @@ def main():
             outs[0].zero_()
         steps_on_two_streams(0, args.warmup)
         ms_two, wall_two = timed_region(None, two_streams=True)
-        assert all(plan.info(b).status == 0 for b in blobs)
-        same = all(torch.equal(a, b) for a, b in zip(want_out, outs[0])) if parts else torch.equal(want_out, outs[0])
-        assert same, "the steps on two streams restored something else than the steps on one"
+        if all(plan.info(b, check=False).status == 0 for b in blobs):
+            same = all(torch.equal(a, b) for a, b in zip(want_out, outs[0])) if parts else torch.equal(want_out, outs[0])
+            assert same, "the steps on two streams restored something else than the steps on one"
+        else:
+            # a compress call gave up (a bounded wait of the single-pass kernel expired while another kernel held
+            # the device): this pass does not count, and the workspace starts afresh for what follows
+            two_streams_failed = True
+            ms_two, wall_two = None, None
+            ws = plan.new_workspace()
+            for i in range(nblob):
+                step(i)
+            torch.cuda.synchronize()
+            assert plan.info(blobs[0]).status == 0
         del want_out
 
     # the graph pass, last (see above)
@@ -405,8 +415,8 @@ def main():
         graph.replay()                     # untimed
     ms_graph, wall_graph = timed_region(graph)
     launch = "graph" if args.graph else args.launch
-    if launch == "auto":
-        launch = "two-streams" if ms_two < ms_stream else "stream"
+    if launch == "auto" or (launch == "two-streams" and ms_two is None):
+        launch = "two-streams" if ms_two is not None and ms_two < ms_stream else "stream"
     ms_per_step, wall = {"stream": (ms_stream, wall_stream), "graph": (ms_graph, wall_graph),
                          "two-streams": (ms_two, wall_two)}[launch]
     launch_name = {"stream": "stream", "graph": "hip graph",
@@ -438,7 +448,7 @@ def main():
                          "pair_frac": {"stream": (alg_c + alg_d) / ms_stream / 1e6 / HBM_PEAK_GBS,
                                        "hip_graph": (alg_c + alg_d) / ms_graph / 1e6 / HBM_PEAK_GBS,
                                        "two_streams": (alg_c + alg_d) / ms_two / 1e6 / HBM_PEAK_GBS if ms_two else None},
-                         "headline": launch},
+                         "two_streams_gave_up": two_streams_failed, "headline": launch},
         # the bar: algorithmic bytes of compress + decompress over the timed step, against the 8 TB/s peak
         "target": {"quantity": "roofline.pair_frac", "bar": 0.6, "met": pair_gbps / HBM_PEAK_GBS >= 0.6},
         "roofline": {"bound": "hbm", "kernel": dom, "achieved": achieved, "peak": HBM_PEAK_GBS,
